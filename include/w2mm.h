@@ -1,0 +1,179 @@
+/*
+ * w2mm -- 2-bit-weight mixed-precision matmul for AMD MI355X (gfx950 / CDNA4)
+ *
+ *     Y[M,N] = X[M,K] . dequant(W2[K,N])
+ *
+ * W2 holds 2-bit weight codes with one bf16 scale per group of G consecutive K
+ * per output column.  X is either int8 (quantised per token by
+ * w2_quantize_rows; "w2a8") or bf16 ("w2a16").  Y is bf16.
+ *
+ * Naming: X = activations (M tokens), W = weights (N output features).  The
+ * paper names the weight matrix A (its M x K), the activations B (its N x K)
+ * and the output C.
+ *
+ * Conventions for every entry point
+ *   - returns a w2_status_t (0 = OK, negative = error); never throws, never
+ *     aborts, never synchronises the device;
+ *   - all work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) of the CURRENT device;
+ *   - every buffer is owned by the caller; the library keeps no device state,
+ *     allocates nothing and holds no handles, so calls from several host
+ *     threads are independent;
+ *   - "dev" pointers are device memory of the current device, "host" pointers
+ *     are ordinary host memory;
+ *   - arguments are validated before anything is launched: a call that returns
+ *     an error has written nothing;
+ *   - M == 0 is valid everywhere and does nothing.
+ *
+ * Shape rules: K > 0, K % 256 == 0, G in {64, 128}; N > 0 and N % 8 == 0
+ * (columns are padded to a multiple of 16 inside the packed blob);
+ * `packed`, `xq`, `X` and `Y` 16-byte aligned, row strides (ldx, ldy) in
+ * elements and multiples of 8.
+ */
+#ifndef W2MM_H
+#define W2MM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define W2_API __attribute__((visibility("default")))
+#else
+#define W2_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Code -> value map of the canonical (caller-side) weight codes.  The paper
+ * does not print one; these follow the benchmark configuration:
+ * INT2: q = c - 2 (values -2,-1,0,1); TERNARY: q = c - 1 (values -1,0,1),
+ * code 3 is illegal. */
+typedef enum { W2_CODEC_INT2 = 0, W2_CODEC_TERNARY = 1 } w2_codec_t;
+
+typedef enum { W2_DT_F32 = 0, W2_DT_BF16 = 1 } w2_dtype_t;
+
+typedef enum {
+    W2_OK = 0,
+    W2_ERR_INVALID_ARG = -1,       /* NULL pointer, unknown enum, negative size */
+    W2_ERR_UNSUPPORTED_SHAPE = -2, /* violates the shape rules above */
+    W2_ERR_MISALIGNED = -3,        /* pointer or stride alignment */
+    W2_ERR_BUFFER_TOO_SMALL = -4,  /* packed_bytes / workspace_bytes too small */
+    W2_ERR_HIP = -5,               /* a HIP call failed; see w2_last_error() */
+    W2_ERR_BAD_CODE = -6           /* reserved for callers that check bad_codes */
+} w2_status_t;
+
+/* Kernel families, for w2_matmul_a8_ex / w2_matmul_a16_ex and the debug export.
+ * AUTO picks by M.  DOT4: per-lane v_dot4_i32_i8 with split-K across the waves
+ * of a workgroup (M <= 4).  SMALLM: one 16-row int8 (bf16 for a16) MFMA tile
+ * per wave, split-K across waves (M <= 16).  TILED: LDS-staged MFMA tiles
+ * (any M). */
+typedef enum { W2_VARIANT_AUTO = 0, W2_VARIANT_DOT4 = 1, W2_VARIANT_SMALLM = 2,
+               W2_VARIANT_TILED = 3 } w2_variant_t;
+
+/* ------------------------------------------------------------------------
+ * Offline weight pre-formatting (Sec. II-B "packed ... off-line"; Sec. II-D
+ * "pre-format ... without any overhead during runtime").  The device layout
+ * is this library's own (the paper's VNNI4-interleaved and VNNI16 layouts are
+ * for x86 and Xe2); the principle kept from Sec. II-B is that one shift and
+ * one mask land four consecutive-K codes directly in the byte lanes the int8
+ * dot/matrix instruction consumes.
+ * ------------------------------------------------------------------------ */
+
+/* Size in bytes of the packed blob for a K x N weight with group size G.
+ * bytes: host out-pointer. */
+W2_API int w2_packed_size(int64_t K, int64_t N, int G, size_t* bytes);
+
+/* codes_KN  dev, uint8, one code per byte, row-major [K][N]
+ * scales    dev, bf16 bit patterns, row-major [K/G][N]
+ * packed    dev, caller-allocated, >= w2_packed_size bytes, 16-byte aligned;
+ *           fully overwritten (padding columns get value 0 and scale 0)
+ * bad_codes dev, int32 counter or NULL; if given it must be zero on entry and
+ *           is incremented once per code outside the codec's alphabet
+ *           (> 3, or == 3 under TERNARY).  Such a code is stored as value 0. */
+W2_API int w2_prepack(const uint8_t* codes_KN, const uint16_t* scales, int64_t K, int64_t N, int G,
+               w2_codec_t codec, void* packed, size_t packed_bytes, int32_t* bad_codes,
+               void* stream);
+
+/* ------------------------------------------------------------------------
+ * Per-token activation quantisation (Sec. II-B; Sec. II-D: abs-max per
+ * granularity gives the scale, entries are multiplied by the inverse scale
+ * and converted to int8).  Granularity: one scale per row over all K.
+ * All arithmetic in IEEE binary32, one rounding per operation:
+ *   amax = max_k |x|;  inv = 127/amax;  sx = amax/127  (both 0 if amax == 0)
+ *   xq = clamp(round_half_even(x * inv), -127, 127)
+ * X     dev, [M][K] row-major with row stride ldx, fp32 or bf16 (x_dtype)
+ * xq    dev, int8 [M][K] dense
+ * sx    dev, fp32 [M]
+ * gsum  dev, int32 [M][K/G] = per-group sums of xq, or NULL (then G is unused).
+ *       The matmul calls do not need it; it is offered to callers that fold a
+ *       weight zero-point themselves. */
+W2_API int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_t K, int64_t ldx, int G,
+                     int8_t* xq, float* sx, int32_t* gsum, void* stream);
+
+/* ------------------------------------------------------------------------
+ * w2a8 (Sec. II-C "up-convert and compute": 2-bit codes -> int8 in registers,
+ * int8 x int8 -> int32; Sec. II-D: int32 -> float, x (activation scale x
+ * weight scale), -> bf16, fused before the store):
+ *   acc[m,g,n] = sum_{k in group g} xq[m,k] * q[k,n]            (int32, exact)
+ *   Y[m,n]     = bf16( sx[m] * sum_g sw[g,n] * float(acc[m,g,n]) )   (fp32)
+ * packed  dev, from w2_prepack with the same K, N, G
+ * xq, sx  dev, as produced by w2_quantize_rows ([M][K] dense, [M])
+ * Y       dev, bf16 bit patterns [M][N], row stride ldy
+ * workspace  unused by the current kernels (split-K is reduced inside a
+ *            workgroup); pass NULL / 0.  w2_workspace_size reports 0. */
+W2_API int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
+                 const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
+                 size_t workspace_bytes, void* stream);
+
+/* Same, with the kernel family forced (tests, tuning).  Returns
+ * W2_ERR_UNSUPPORTED_SHAPE if the family does not cover M. */
+W2_API int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
+                    const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
+                    size_t workspace_bytes, int variant, void* stream);
+
+/* ------------------------------------------------------------------------
+ * w2a16 (Sec. II-D, "Alternative implementation": weights rebuilt as 16-bit
+ * values from code and group scale, activations left unquantised, 16-bit
+ * matrix instructions with fp32 accumulation, no quantise/dequantise):
+ *   Y[m,n] = bf16( sum_k x[m,k] * (sw[k/G,n] * q[k,n]) )
+ * X  dev, bf16 bit patterns [M][K], row stride ldx. */
+W2_API int w2_matmul_a16(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
+                  int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
+W2_API int w2_matmul_a16_ex(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
+                     int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
+                     size_t workspace_bytes, int variant, void* stream);
+
+/* Bytes of workspace the matmul calls need for this problem (host out-pointer).
+ * a16: 0 = w2a8, 1 = w2a16. */
+W2_API int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* bytes);
+
+/* ------------------------------------------------------------------------
+ * Test-only exports.
+ * w2_debug_group_acc_a8: the int32 group accumulators acc[M][K/G][N] (dense)
+ *   exactly as the chosen kernel family holds them before the dequant step.
+ * w2_debug_unpack: inverse of w2_prepack: canonical codes [K][N] and scales
+ *   [K/G][N] recovered from the blob (codec selects the code -> value map). */
+W2_API int w2_debug_group_acc_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
+                          int64_t M, int variant, int32_t* acc, void* stream);
+W2_API int w2_debug_unpack(const void* packed, int64_t K, int64_t N, int G, w2_codec_t codec,
+                    uint8_t* codes_KN, uint16_t* scales, void* stream);
+
+/* Streaming-read probe: 128-bit loads over `bytes` of dev memory, xor-reduced
+ * into sink[0] (dev, uint32).  Used by the benchmark as the attainable
+ * read-bandwidth ceiling the weight stream is compared with (the role the
+ * int8-weight GEMV plays in Sec. III-B/III-C). */
+W2_API int w2_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+
+W2_API const char* w2_status_string(int status);
+/* Thread-local detail of the last error on this host thread (e.g. the HIP error
+ * string or the violated rule); empty string if none. */
+W2_API const char* w2_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W2MM_H */

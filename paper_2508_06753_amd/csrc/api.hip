@@ -1,0 +1,298 @@
+// C-ABI entry points of libw2mm: argument validation, dispatch by M, error
+// reporting.  No arithmetic of the method lives here.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/w2mm.h"
+#include "w2_internal.h"
+
+namespace w2 {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+int check_launch(const char* what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("%s: %s", what, hipGetErrorString(e));
+        return W2_ERR_HIP;
+    }
+    return W2_OK;
+}
+
+int env_int(const char* name, int dflt)
+{
+    const char* v = getenv(name);
+    if (!v || !*v) return dflt;
+    return atoi(v);
+}
+
+// Streaming-read probe: grid-stride 128-bit loads, xor-reduced.
+__global__ void __launch_bounds__(256)
+stream_read_kernel(const uint4* __restrict__ src, size_t n_vec, uint32_t* __restrict__ sink)
+{
+    uint32_t x = 0;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) {
+        const uint4 v = src[i];
+        x ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x ^= __shfl_xor(x, off);
+    if ((threadIdx.x & 63) == 0 && x == 0x9e3779b9u) atomicXor(sink, x);   // practically never taken
+}
+
+int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream)
+{
+    const size_t n_vec = bytes / 16;
+    if (n_vec == 0) return W2_OK;
+    size_t blocks = (n_vec + 255) / 256;
+    const size_t cap = (size_t)env_int("W2_STREAM_BLOCKS", 256 * 16);
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       (const uint4*)src, n_vec, sink);
+    return check_launch("w2_debug_stream_read");
+}
+
+static int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+static int check_shape(const char* fn, int64_t K, int64_t N, int G)
+{
+    if (K <= 0 || N <= 0) return fail(W2_ERR_INVALID_ARG, "%s: K and N must be positive", fn);
+    if (G != 64 && G != 128) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: G must be 64 or 128", fn);
+    if (K % TILE_K) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: K must be a multiple of 256", fn);
+    if (N % 8) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: N must be a multiple of 8", fn);
+    if (K > (int64_t)1 << 24 || N > (int64_t)1 << 24)
+        return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: K and N are limited to 2^24", fn);
+    return W2_OK;
+}
+
+}  // namespace w2
+
+using namespace w2;
+
+extern "C" {
+
+int w2_packed_size(int64_t K, int64_t N, int G, size_t* bytes)
+{
+    if (!bytes) return fail(W2_ERR_INVALID_ARG, "w2_packed_size: bytes is NULL");
+    int rc = check_shape("w2_packed_size", K, N, G);
+    if (rc) return rc;
+    *bytes = make_layout(K, N, G).total_bytes;
+    return W2_OK;
+}
+
+int w2_prepack(const uint8_t* codes_KN, const uint16_t* scales, int64_t K, int64_t N, int G,
+               w2_codec_t codec, void* packed, size_t packed_bytes, int32_t* bad_codes,
+               void* stream)
+{
+    int rc = check_shape("w2_prepack", K, N, G);
+    if (rc) return rc;
+    if (!codes_KN || !scales || !packed) return fail(W2_ERR_INVALID_ARG, "w2_prepack: NULL pointer");
+    if (codec != W2_CODEC_INT2 && codec != W2_CODEC_TERNARY)
+        return fail(W2_ERR_INVALID_ARG, "w2_prepack: unknown codec %d", (int)codec);
+    if (!aligned16(packed)) return fail(W2_ERR_MISALIGNED, "w2_prepack: packed must be 16-byte aligned");
+    const Layout L = make_layout(K, N, G);
+    if (packed_bytes < L.total_bytes)
+        return fail(W2_ERR_BUFFER_TOO_SMALL, "w2_prepack: packed_bytes %zu < %zu", packed_bytes, L.total_bytes);
+    return launch_prepack(codes_KN, scales, L, (int)codec, packed, bad_codes, (hipStream_t)stream);
+}
+
+int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_t K, int64_t ldx, int G,
+                     int8_t* xq, float* sx, int32_t* gsum, void* stream)
+{
+    if (M < 0 || K <= 0) return fail(W2_ERR_INVALID_ARG, "w2_quantize_rows: bad M or K");
+    if (x_dtype != W2_DT_F32 && x_dtype != W2_DT_BF16)
+        return fail(W2_ERR_INVALID_ARG, "w2_quantize_rows: unknown dtype %d", (int)x_dtype);
+    if (K % TILE_K) return fail(W2_ERR_UNSUPPORTED_SHAPE, "w2_quantize_rows: K must be a multiple of 256");
+    if (gsum && G != 64 && G != 128)
+        return fail(W2_ERR_UNSUPPORTED_SHAPE, "w2_quantize_rows: G must be 64 or 128 when gsum is given");
+    if (M > 0x7fffffff) return fail(W2_ERR_UNSUPPORTED_SHAPE, "w2_quantize_rows: M too large");
+    if (M == 0) return W2_OK;
+    if (!X || !xq || !sx) return fail(W2_ERR_INVALID_ARG, "w2_quantize_rows: NULL pointer");
+    if (ldx < K || ldx % 8) return fail(W2_ERR_MISALIGNED, "w2_quantize_rows: ldx must be >= K and a multiple of 8");
+    if (!aligned16(X) || !aligned16(xq)) return fail(W2_ERR_MISALIGNED, "w2_quantize_rows: X and xq must be 16-byte aligned");
+    return launch_quantize(X, x_dtype == W2_DT_BF16, M, K, ldx, gsum ? G : 128, xq, sx, gsum,
+                           (hipStream_t)stream);
+}
+
+static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, int G,
+                     const int8_t* xq, const float* sx, int64_t M, uint16_t* Y, int64_t ldy,
+                     int32_t* acc_out, int variant, void* stream)
+{
+    int rc = check_shape(fn, K, N, G);
+    if (rc) return rc;
+    if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
+    if (variant < W2_VARIANT_AUTO || variant > W2_VARIANT_TILED)
+        return fail(W2_ERR_INVALID_ARG, "%s: unknown variant %d", fn, variant);
+    if (M == 0) return W2_OK;
+    if (!packed || !xq) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
+    if (!acc_out && (!sx || !Y)) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
+    if (!aligned16(packed) || !aligned16(xq) || (Y && !aligned16(Y)))
+        return fail(W2_ERR_MISALIGNED, "%s: packed, xq and Y must be 16-byte aligned", fn);
+    if (!acc_out && (ldy < N || ldy % 8))
+        return fail(W2_ERR_MISALIGNED, "%s: ldy must be >= N and a multiple of 8", fn);
+    if (M > ((int64_t)1 << 24)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: M is limited to 2^24", fn);
+    const Layout L = make_layout(K, N, G);
+    A8Args a;
+    a.codes = (const uint32_t*)packed;
+    a.scales = (const uint16_t*)((const char*)packed + L.codes_bytes);
+    a.xq = xq; a.sx = sx; a.Y = Y; a.acc_out = acc_out;
+    a.M = M; a.K = K; a.N = N; a.ldy = ldy;
+    a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
+    if (variant == W2_VARIANT_AUTO) {
+        const int dot4_max = env_int("W2_DOT4_MAX_M", 1);
+        variant = M <= dot4_max && a8_dot4_supports(a) ? W2_VARIANT_DOT4
+                : a8_smallm_supports(a)                 ? W2_VARIANT_SMALLM
+                                                        : W2_VARIANT_TILED;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    switch (variant) {
+    case W2_VARIANT_DOT4:
+        if (!a8_dot4_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: DOT4 needs M <= 4", fn);
+        return launch_a8_dot4(a, s);
+    case W2_VARIANT_SMALLM:
+        if (!a8_smallm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: SMALLM needs M <= 16", fn);
+        return launch_a8_smallm(a, s);
+    default:
+        return launch_a8_tiled(a, s);
+    }
+}
+
+int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
+                    const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
+                    size_t workspace_bytes, int variant, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    return a8_common("w2_matmul_a8", packed, K, N, G, xq, sx, M, Y, ldy, nullptr, variant, stream);
+}
+
+int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
+                 const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
+                 size_t workspace_bytes, void* stream)
+{
+    return w2_matmul_a8_ex(packed, K, N, G, xq, sx, M, Y, ldy, workspace, workspace_bytes,
+                           W2_VARIANT_AUTO, stream);
+}
+
+int w2_debug_group_acc_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
+                          int64_t M, int variant, int32_t* acc, void* stream)
+{
+    if (!acc && M > 0) return fail(W2_ERR_INVALID_ARG, "w2_debug_group_acc_a8: acc is NULL");
+    return a8_common("w2_debug_group_acc_a8", packed, K, N, G, xq, nullptr, M, nullptr, 0, acc,
+                     variant, stream);
+}
+
+static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, int G,
+                      const uint16_t* X, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                      int variant, void* stream)
+{
+    int rc = check_shape(fn, K, N, G);
+    if (rc) return rc;
+    if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
+    if (variant != W2_VARIANT_AUTO && variant != W2_VARIANT_SMALLM && variant != W2_VARIANT_TILED)
+        return fail(W2_ERR_INVALID_ARG, "%s: variant %d not available for w2a16", fn, variant);
+    if (M == 0) return W2_OK;
+    if (!packed || !X || !Y) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
+    if (!aligned16(packed) || !aligned16(X) || !aligned16(Y))
+        return fail(W2_ERR_MISALIGNED, "%s: packed, X and Y must be 16-byte aligned", fn);
+    if (ldx < K || ldx % 8 || ldy < N || ldy % 8)
+        return fail(W2_ERR_MISALIGNED, "%s: ldx >= K, ldy >= N, both multiples of 8", fn);
+    if (M > ((int64_t)1 << 24)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: M is limited to 2^24", fn);
+    const Layout L = make_layout(K, N, G);
+    A16Args a;
+    a.codes = (const uint32_t*)packed;
+    a.scales = (const uint16_t*)((const char*)packed + L.codes_bytes);
+    a.X = X; a.Y = Y; a.M = M; a.K = K; a.N = N; a.ldx = ldx; a.ldy = ldy;
+    a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
+    if (variant == W2_VARIANT_AUTO)
+        variant = a16_smallm_supports(a) ? W2_VARIANT_SMALLM : W2_VARIANT_TILED;
+    if (variant == W2_VARIANT_SMALLM) {
+        if (!a16_smallm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: SMALLM needs M <= 16", fn);
+        return launch_a16_smallm(a, (hipStream_t)stream);
+    }
+    return launch_a16_tiled(a, (hipStream_t)stream);
+}
+
+int w2_matmul_a16_ex(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
+                     int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
+                     size_t workspace_bytes, int variant, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    return a16_common("w2_matmul_a16", packed, K, N, G, X, ldx, M, Y, ldy, variant, stream);
+}
+
+int w2_matmul_a16(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
+                  int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
+                  size_t workspace_bytes, void* stream)
+{
+    return w2_matmul_a16_ex(packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes,
+                            W2_VARIANT_AUTO, stream);
+}
+
+int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* bytes)
+{
+    (void)M; (void)a16;
+    if (!bytes) return fail(W2_ERR_INVALID_ARG, "w2_workspace_size: bytes is NULL");
+    int rc = check_shape("w2_workspace_size", K, N, G);
+    if (rc) return rc;
+    *bytes = 0;
+    return W2_OK;
+}
+
+int w2_debug_unpack(const void* packed, int64_t K, int64_t N, int G, w2_codec_t codec,
+                    uint8_t* codes_KN, uint16_t* scales, void* stream)
+{
+    int rc = check_shape("w2_debug_unpack", K, N, G);
+    if (rc) return rc;
+    if (!packed || !codes_KN || !scales) return fail(W2_ERR_INVALID_ARG, "w2_debug_unpack: NULL pointer");
+    if (codec != W2_CODEC_INT2 && codec != W2_CODEC_TERNARY)
+        return fail(W2_ERR_INVALID_ARG, "w2_debug_unpack: unknown codec %d", (int)codec);
+    return launch_unpack(packed, make_layout(K, N, G), (int)codec, codes_KN, scales,
+                         (hipStream_t)stream);
+}
+
+int w2_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream)
+{
+    if (!src || !sink) return fail(W2_ERR_INVALID_ARG, "w2_debug_stream_read: NULL pointer");
+    if (!aligned16(src)) return fail(W2_ERR_MISALIGNED, "w2_debug_stream_read: src must be 16-byte aligned");
+    return launch_stream_read(src, bytes, sink, (hipStream_t)stream);
+}
+
+const char* w2_status_string(int status)
+{
+    switch (status) {
+    case W2_OK: return "ok";
+    case W2_ERR_INVALID_ARG: return "invalid argument";
+    case W2_ERR_UNSUPPORTED_SHAPE: return "unsupported shape";
+    case W2_ERR_MISALIGNED: return "misaligned pointer or stride";
+    case W2_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+    case W2_ERR_HIP: return "HIP error";
+    case W2_ERR_BAD_CODE: return "weight code outside the codec's alphabet";
+    default: return "unknown status";
+    }
+}
+
+const char* w2_last_error(void) { return g_err; }
+
+}  // extern "C"

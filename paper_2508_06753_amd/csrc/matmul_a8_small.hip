@@ -1,0 +1,366 @@
+// w2a8 for small M (decode): the memory-bound regime where time tracks the
+// bytes of weight streamed (Sec. I, II-A).  "Up-convert and compute"
+// (Sec. II-C): each lane reads 128 bits of packed 2-bit weights, turns them
+// into int8 operands in registers with one shift + one mask per four weights,
+// and feeds int8 x int8 -> int32 instructions.  Two kernel families:
+//   DOT4   v_dot4_i32_i8 per lane (the CDNA analog of the VNNI FMA microkernel
+//          of Sec. II-C), M <= 4;
+//   SMALLM one v_mfma_i32_16x16x64_i8 per 64-k step with the M rows padded to
+//          the 16-row tile, M <= 16: the up-convert cost no longer grows with M.
+// Both split K across the waves of a workgroup (Sec. II-D mentions K-splitting
+// for small shapes) and reduce through LDS in a fixed order, so results are
+// deterministic.  The dequant epilogue (Sec. II-D: int32 -> float, x scales,
+// -> bf16) is fused: per group y += sw * float(acc), at the end y * sx / 64.
+#include <hip/hip_runtime.h>
+
+#include "w2_internal.h"
+
+namespace w2 {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int XS_PAD = 16;   // bytes of padding per LDS activation row (bank spread)
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// 16 two-bit fields -> four dwords of int8 lanes holding 64*q.
+__device__ __forceinline__ void upconvert(uint32_t w, int (&u)[4])
+{
+    u[0] = (int)((w << 6) & 0xC0C0C0C0u);
+    u[1] = (int)((w << 4) & 0xC0C0C0C0u);
+    u[2] = (int)((w << 2) & 0xC0C0C0C0u);
+    u[3] = (int)(w & 0xC0C0C0C0u);
+}
+
+// One streamed tile: 16 B of codes and the tile's group scales for this lane.
+struct TileRegs {
+    uint4 w;
+    uint32_t s0, s1;   // bf16 scales: G=128 -> s0 = {g0,g1}; G=64 -> s0 = {g0,g1}, s1 = {g2,g3}
+};
+
+template <int G>
+__device__ __forceinline__ TileRegs load_tile(const uint32_t* __restrict__ codes,
+                                              const uint16_t* __restrict__ scales, int64_t tile,
+                                              int lane)
+{
+    TileRegs r;
+    r.w = *reinterpret_cast<const uint4*>(codes + (tile * 64 + lane) * 4);
+    if constexpr (G == 128) {
+        r.s0 = *reinterpret_cast<const uint32_t*>(scales + (tile * TILE_N + (lane & 15)) * 2);
+        r.s1 = 0;
+    } else {
+        const uint2 s = *reinterpret_cast<const uint2*>(scales + (tile * TILE_N + (lane & 15)) * 4);
+        r.s0 = s.x; r.s1 = s.y;
+    }
+    return r;
+}
+
+template <int G>
+__device__ __forceinline__ float tile_scale(const TileRegs& r, int gi)
+{
+    // gi = group index inside the tile
+    const uint32_t pair = (G == 128 || gi < 2) ? r.s0 : r.s1;
+    return (gi & 1) ? __uint_as_float(pair & 0xffff0000u) : __uint_as_float(pair << 16);
+}
+
+// Copies rows [0,rows) x k in [k0, k0+len) of xq into LDS rows of stride
+// len + XS_PAD.  len % 16 == 0.
+__device__ __forceinline__ void stage_activations(const int8_t* __restrict__ xq, int64_t K,
+                                                  int rows, int64_t k0, int len, int8_t* xs)
+{
+    const int vec_per_row = len >> 4;
+    const int total = rows * vec_per_row;
+    for (int i = threadIdx.x; i < total; i += blockDim.x) {
+        const int r = i / vec_per_row, v = i - r * vec_per_row;
+        *reinterpret_cast<uint4*>(xs + r * (len + XS_PAD) + v * 16) =
+            *reinterpret_cast<const uint4*>(xq + (int64_t)r * K + k0 + v * 16);
+    }
+}
+
+struct SmallCfg {
+    int cbw;        // column blocks per workgroup
+    int ks;         // k-splits inside the workgroup (waves = cbw * ks)
+    int kc;         // k per LDS chunk (multiple of 256)
+};
+
+// ---------------------------------------------------------------- DOT4
+template <int MT, int G, bool DBG>
+__global__ void __launch_bounds__(1024)
+a8_dot4_kernel(A8Args a, SmallCfg cfg)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int cbi = wave % cfg.cbw;
+    const int ks = wave / cfg.cbw;
+    const int64_t cb = (int64_t)blockIdx.x * cfg.cbw + cbi;
+    const bool cb_ok = cb < a.n_cb;
+    const int64_t cbc = cb_ok ? cb : a.n_cb - 1;           // clamp: keeps loads in bounds
+    const int q = lane >> 4;
+    const int64_t n = cb * TILE_N + (lane & 15);
+    constexpr int GPT = TILE_K / G;
+    const int tiles_per_chunk = cfg.kc / TILE_K;
+    const int row_stride = cfg.kc + XS_PAD;
+
+    float y[MT];
+    int acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) { y[m] = 0.0f; acc[m] = 0; }
+
+    int64_t kt = ks;                                        // this wave's tiles: ks, ks+KS, ...
+    TileRegs t0 = {}, t1 = {};
+    if (kt < a.n_kt) t0 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt, lane);
+    if (kt + cfg.ks < a.n_kt) t1 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt + cfg.ks, lane);
+
+    const int n_chunks = (int)((a.n_kt + tiles_per_chunk - 1) / tiles_per_chunk);
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t kt_begin = (int64_t)c * tiles_per_chunk;
+        const int64_t kt_end = min(kt_begin + tiles_per_chunk, a.n_kt);
+        if (c > 0) __syncthreads();
+        stage_activations(a.xq, a.K, MT < (int)a.M ? MT : (int)a.M, kt_begin * TILE_K,
+                          (int)(kt_end - kt_begin) * TILE_K, smem);
+        __syncthreads();
+        const int cur_stride = (int)(kt_end - kt_begin) * TILE_K + XS_PAD;
+        (void)row_stride;
+        for (; kt < kt_end; kt += cfg.ks) {
+            const TileRegs cur = t0;
+            t0 = t1;
+            if (kt + 2 * cfg.ks < a.n_kt)
+                t1 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt + 2 * cfg.ks, lane);
+            const int8_t* xrow = smem + (int)(kt - kt_begin) * TILE_K + q * 16;
+            const uint32_t wd[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                int u[4];
+                upconvert(wd[t], u);
+#pragma unroll
+                for (int m = 0; m < MT; ++m) {
+                    const int mr = m < (int)a.M ? m : (int)a.M - 1;
+                    const v4i x = *reinterpret_cast<const v4i*>(xrow + mr * cur_stride + t * 64);
+                    acc[m] = __builtin_amdgcn_sdot4(u[0], x[0], acc[m], false);
+                    acc[m] = __builtin_amdgcn_sdot4(u[1], x[1], acc[m], false);
+                    acc[m] = __builtin_amdgcn_sdot4(u[2], x[2], acc[m], false);
+                    acc[m] = __builtin_amdgcn_sdot4(u[3], x[3], acc[m], false);
+                }
+                if (G == 64 || (t & 1)) {                   // a group ends here
+                    const int gi = G == 64 ? t : t >> 1;
+                    const float sw = tile_scale<G>(cur, gi);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        if constexpr (DBG) {
+                            int s = acc[m];
+                            s += __shfl_xor(s, 16);
+                            s += __shfl_xor(s, 32);
+                            if (q == 0 && cb_ok && n < a.N && m < a.M)
+                                a.acc_out[((int64_t)m * (a.K / G) + kt * GPT + gi) * a.N + n] = s >> 6;
+                        }
+                        y[m] = fmaf(sw, (float)acc[m], y[m]);
+                        acc[m] = 0;
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (DBG) return;
+
+    // cross-lane: the four k-blocks of a tile live in lanes l, l^16, l^32, l^48
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        y[m] += __shfl_xor(y[m], 16);
+        y[m] += __shfl_xor(y[m], 32);
+    }
+    __syncthreads();                                        // activations no longer needed
+    float* red = reinterpret_cast<float*>(smem);            // [waves][MT][16]
+    if (q == 0) {
+#pragma unroll
+        for (int m = 0; m < MT; ++m) red[(wave * MT + m) * 16 + lane] = y[m];
+    }
+    __syncthreads();
+    const int outs = cfg.cbw * MT * 16;
+    for (int i = threadIdx.x; i < outs; i += blockDim.x) {
+        const int nl = i & 15, m = (i >> 4) % MT, ci = i / (16 * MT);
+        float s = 0.0f;
+        for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * MT + m) * 16 + nl];
+        const int64_t nn = ((int64_t)blockIdx.x * cfg.cbw + ci) * TILE_N + nl;
+        if (m < a.M && nn < a.N)
+            a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * (a.sx[m] * 0.015625f));
+    }
+}
+
+// ---------------------------------------------------------------- SMALLM (MFMA)
+template <int G, bool DBG>
+__global__ void __launch_bounds__(1024)
+a8_smallm_kernel(A8Args a, SmallCfg cfg)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int cbi = wave % cfg.cbw;
+    const int ks = wave / cfg.cbw;
+    const int64_t cb = (int64_t)blockIdx.x * cfg.cbw + cbi;
+    const bool cb_ok = cb < a.n_cb;
+    const int64_t cbc = cb_ok ? cb : a.n_cb - 1;
+    const int q = lane >> 4;
+    const int64_t n = cb * TILE_N + (lane & 15);
+    constexpr int GPT = TILE_K / G;
+    const int tiles_per_chunk = cfg.kc / TILE_K;
+    const int rows = (int)a.M;                              // 1..16
+    const int arow = (lane & 15) < rows ? (lane & 15) : rows - 1;   // padded rows repeat the last
+
+    float y[4] = {0.f, 0.f, 0.f, 0.f};
+    v4i acc = {0, 0, 0, 0};
+
+    int64_t kt = ks;
+    TileRegs t0 = {}, t1 = {};
+    if (kt < a.n_kt) t0 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt, lane);
+    if (kt + cfg.ks < a.n_kt) t1 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt + cfg.ks, lane);
+
+    const int n_chunks = (int)((a.n_kt + tiles_per_chunk - 1) / tiles_per_chunk);
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t kt_begin = (int64_t)c * tiles_per_chunk;
+        const int64_t kt_end = min(kt_begin + tiles_per_chunk, a.n_kt);
+        if (c > 0) __syncthreads();
+        stage_activations(a.xq, a.K, rows, kt_begin * TILE_K, (int)(kt_end - kt_begin) * TILE_K, smem);
+        __syncthreads();
+        const int cur_stride = (int)(kt_end - kt_begin) * TILE_K + XS_PAD;
+        for (; kt < kt_end; kt += cfg.ks) {
+            const TileRegs cur = t0;
+            t0 = t1;
+            if (kt + 2 * cfg.ks < a.n_kt)
+                t1 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt + 2 * cfg.ks, lane);
+            const int8_t* xrow = smem + arow * cur_stride + (int)(kt - kt_begin) * TILE_K + q * 16;
+            const uint32_t wd[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                int u[4];
+                upconvert(wd[t], u);
+                const v4i bop = {u[0], u[1], u[2], u[3]};
+                const v4i aop = *reinterpret_cast<const v4i*>(xrow + t * 64);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, bop, acc, 0, 0, 0);
+                if (G == 64 || (t & 1)) {
+                    const int gi = G == 64 ? t : t >> 1;
+                    const float sw = tile_scale<G>(cur, gi);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if constexpr (DBG) {
+                            const int m = 4 * q + r;
+                            if (cb_ok && n < a.N && m < a.M)
+                                a.acc_out[((int64_t)m * (a.K / G) + kt * GPT + gi) * a.N + n] = acc[r] >> 6;
+                        }
+                        y[r] = fmaf(sw, (float)acc[r], y[r]);
+                    }
+                    acc = (v4i){0, 0, 0, 0};
+                }
+            }
+        }
+    }
+    if constexpr (DBG) return;
+
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem);            // [waves][16 m][16 n]
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[(wave * 16 + 4 * q + r) * 16 + (lane & 15)] = y[r];
+    __syncthreads();
+    const int outs = cfg.cbw * rows * 16;
+    for (int i = threadIdx.x; i < outs; i += blockDim.x) {
+        const int nl = i & 15, m = (i >> 4) % rows, ci = i / (16 * rows);
+        float s = 0.0f;
+        for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * 16 + m) * 16 + nl];
+        const int64_t nn = ((int64_t)blockIdx.x * cfg.cbw + ci) * TILE_N + nl;
+        if (nn < a.N) a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * (a.sx[m] * 0.015625f));
+    }
+}
+
+// ---------------------------------------------------------------- host side
+
+// Picks (column blocks per workgroup, k-splits) so that the grid has a few
+// workgroups per CU and every wave still streams several tiles.
+static SmallCfg pick_cfg(const A8Args& a, int rows, int max_waves)
+{
+    SmallCfg c;
+    int waves = env_int("W2_SMALL_WAVES", 8);
+    if (waves > max_waves) waves = max_waves;
+    int cbw = env_int("W2_SMALL_CBW", 0);
+    if (cbw <= 0) {
+        // aim for >= 512 workgroups (2 per CU) but never fewer than 1 cb per WG
+        cbw = 4;
+        while (cbw > 1 && (a.n_cb + cbw - 1) / cbw < 512) cbw >>= 1;
+    }
+    if (cbw > waves) cbw = waves;
+    c.cbw = cbw;
+    c.ks = waves / cbw;
+    if (c.ks > a.n_kt) c.ks = (int)a.n_kt;
+    if (c.ks < 1) c.ks = 1;
+    // LDS budget for the activation chunk
+    const int64_t budget = 64 * 1024;
+    int64_t kc = a.n_kt * TILE_K;
+    while (kc > TILE_K && (int64_t)rows * (kc + XS_PAD) > budget) kc -= TILE_K;
+    const int force = env_int("W2_SMALL_KC", 0);
+    if (force >= TILE_K && force % TILE_K == 0 && force < kc) kc = force;
+    c.kc = (int)kc;
+    return c;
+}
+
+static size_t small_lds_bytes(const SmallCfg& c, int rows, int red_rows)
+{
+    size_t act = (size_t)rows * (c.kc + XS_PAD);
+    size_t red = (size_t)c.cbw * c.ks * red_rows * 16 * sizeof(float);
+    return act > red ? act : red;
+}
+
+bool a8_dot4_supports(const A8Args& a) { return a.M >= 1 && a.M <= 4; }
+bool a8_smallm_supports(const A8Args& a) { return a.M >= 1 && a.M <= 16; }
+
+template <int MT, int G>
+static int launch_dot4_t(const A8Args& a, hipStream_t stream)
+{
+    const SmallCfg c = pick_cfg(a, MT, 16);
+    const size_t lds = small_lds_bytes(c, MT, MT);
+    const dim3 grid((unsigned)((a.n_cb + c.cbw - 1) / c.cbw)), block(64 * c.cbw * c.ks);
+    if (a.acc_out)
+        hipLaunchKernelGGL((a8_dot4_kernel<MT, G, true>), grid, block, lds, stream, a, c);
+    else
+        hipLaunchKernelGGL((a8_dot4_kernel<MT, G, false>), grid, block, lds, stream, a, c);
+    return check_launch("w2_matmul_a8[dot4]");
+}
+
+int launch_a8_dot4(const A8Args& a, hipStream_t stream)
+{
+    const int mt = a.M <= 1 ? 1 : a.M <= 2 ? 2 : 4;
+    if (a.G == 128) {
+        if (mt == 1) return launch_dot4_t<1, 128>(a, stream);
+        if (mt == 2) return launch_dot4_t<2, 128>(a, stream);
+        return launch_dot4_t<4, 128>(a, stream);
+    }
+    if (mt == 1) return launch_dot4_t<1, 64>(a, stream);
+    if (mt == 2) return launch_dot4_t<2, 64>(a, stream);
+    return launch_dot4_t<4, 64>(a, stream);
+}
+
+template <int G>
+static int launch_smallm_t(const A8Args& a, hipStream_t stream)
+{
+    const int rows = (int)a.M;
+    const SmallCfg c = pick_cfg(a, rows, 16);
+    const size_t lds = small_lds_bytes(c, rows, 16);
+    const dim3 grid((unsigned)((a.n_cb + c.cbw - 1) / c.cbw)), block(64 * c.cbw * c.ks);
+    if (a.acc_out)
+        hipLaunchKernelGGL((a8_smallm_kernel<G, true>), grid, block, lds, stream, a, c);
+    else
+        hipLaunchKernelGGL((a8_smallm_kernel<G, false>), grid, block, lds, stream, a, c);
+    return check_launch("w2_matmul_a8[smallm]");
+}
+
+int launch_a8_smallm(const A8Args& a, hipStream_t stream)
+{
+    return a.G == 128 ? launch_smallm_t<128>(a, stream) : launch_smallm_t<64>(a, stream);
+}
+
+}  // namespace w2

@@ -1,0 +1,60 @@
+// Internal declarations shared by the translation units of libw2mm.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "w2_layout.h"
+
+namespace w2 {
+
+// Records `what` + the HIP error string as this thread's last error if the
+// preceding launches failed; returns a w2_status_t.
+int check_launch(const char* what);
+void set_error(const char* fmt, ...);
+
+int launch_prepack(const uint8_t* codes, const uint16_t* scales, const Layout& L, int codec,
+                   void* packed, int32_t* bad_codes, hipStream_t stream);
+int launch_unpack(const void* packed, const Layout& L, int codec, uint8_t* codes,
+                  uint16_t* scales, hipStream_t stream);
+int launch_quantize(const void* X, int x_is_bf16, int64_t M, int64_t K, int64_t ldx, int G,
+                    int8_t* xq, float* sx, int32_t* gsum, hipStream_t stream);
+int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
+
+// Arguments common to the w2a8 kernels.  acc_out != nullptr selects the debug
+// mode that stores the int32 group accumulators and skips Y.
+struct A8Args {
+    const uint32_t* codes;
+    const uint16_t* scales;
+    const int8_t* xq;
+    const float* sx;
+    uint16_t* Y;
+    int32_t* acc_out;
+    int64_t M, K, N, ldy;
+    int64_t n_cb, n_kt;
+    int G;
+};
+
+bool a8_dot4_supports(const A8Args& a);
+int launch_a8_dot4(const A8Args& a, hipStream_t stream);
+bool a8_smallm_supports(const A8Args& a);
+int launch_a8_smallm(const A8Args& a, hipStream_t stream);
+int launch_a8_tiled(const A8Args& a, hipStream_t stream);
+
+struct A16Args {
+    const uint32_t* codes;
+    const uint16_t* scales;
+    const uint16_t* X;
+    uint16_t* Y;
+    int64_t M, K, N, ldx, ldy;
+    int64_t n_cb, n_kt;
+    int G;
+};
+
+bool a16_smallm_supports(const A16Args& a);
+int launch_a16_smallm(const A16Args& a, hipStream_t stream);
+int launch_a16_tiled(const A16Args& a, hipStream_t stream);
+
+// Environment override for tuning sweeps (read once per call on the host).
+int env_int(const char* name, int dflt);
+
+}  // namespace w2

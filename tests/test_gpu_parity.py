@@ -1,0 +1,238 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Integer work (packed round trip, int8 codes,
+int32 group accumulators) must match bit for bit; bf16 outputs must satisfy
+|Y - Yor| <= 1e-2*|Yor| + 2^-10 * sum|terms| (the second term is the floor for
+outputs that are a cancelling sum; fp32 vs fp64 association alone moves
+those)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2508_06753_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def w2():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_06753_amd import binding
+    return binding
+
+
+def dev(a):
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def bf16_bits(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def bits_to_f64(b):
+    return synth.bf16_bits_to_f32(b).astype(np.float64)
+
+
+def check_y(Y_gpu_bits, Y_or_bits, y64, mag, what):
+    yg = bits_to_f64(Y_gpu_bits)
+    yo = bits_to_f64(Y_or_bits)
+    tol = 1e-2 * np.abs(yo) + 2.0 ** -10 * mag
+    bad = np.abs(yg - yo) > tol
+    assert not bad.any(), (f"{what}: {bad.sum()} of {bad.size} outputs off; worst "
+                           f"{np.abs(yg - yo)[bad].max()} vs tol {tol[bad].min()}")
+    # typical-size outputs: must be within a bf16 ulp or so, without the floor
+    big = np.abs(yo) > 0.05 * np.sqrt(np.mean(yo ** 2) + 1e-300)
+    if big.any():
+        rel = np.abs(yg - yo)[big] / np.abs(yo)[big]
+        assert rel.max() <= 1e-2, f"{what}: max relative error {rel.max()}"
+
+
+# ------------------------------------------------------------------ prepack
+@pytest.mark.parametrize("codec", [0, 1])
+@pytest.mark.parametrize("K,N,G", [(256, 16, 128), (512, 40, 64), (1024, 272, 128), (768, 8, 64)])
+def test_prepack_roundtrip(w2, codec, K, N, G):
+    codes, scales = synth.make_weights(K, N, G, codec, seed=K + N)
+    packed = w2.prepack(dev(codes), dev(scales), G, codec)
+    assert packed.numel() == w2.packed_size(K, N, G)
+    c2, s2 = w2.debug_unpack(packed, K, N, G, codec)
+    assert np.array_equal(c2.cpu().numpy(), codes)
+    assert np.array_equal(s2.cpu().numpy().view(np.uint16), scales)
+
+
+def test_prepack_counts_bad_codes(w2):
+    codes, scales = synth.make_weights(256, 32, 128, 1, seed=3)
+    codes[5, 7] = 3
+    codes[200, 31] = 3
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    w2.prepack(dev(codes), dev(scales), 128, 1, bad_codes=flag)
+    assert int(flag.item()) == 2
+    flag.zero_()
+    w2.prepack(dev(codes), dev(scales), 128, 0, bad_codes=flag)     # 3 is legal under int2
+    assert int(flag.item()) == 0
+    assert oracle.check_codes(codes, 1) == oracle.ERR_BAD_CODE
+
+
+# ------------------------------------------------------------------ quantise
+@pytest.mark.parametrize("M,K", [(1, 256), (3, 1024), (5, 4096), (2, 14336), (70, 512)])
+@pytest.mark.parametrize("G", [64, 128])
+def test_quantize_bit_exact_fp32(w2, M, K, G):
+    X = synth.make_activations(M, K, seed=M * 1000 + K)
+    if M > 2:
+        X[1] = 0.0                                   # all-zero row
+        X[2] *= np.float32(1e-20)                    # tiny values
+    xq, sx, gs = w2.quantize_rows(dev(X), G, want_gsum=True)
+    oq, os_, og = oracle.quantize_rows(X, G)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), os_.view(np.uint32))
+    assert np.array_equal(gs.cpu().numpy(), og)
+
+
+def test_quantize_ties_and_bf16_and_stride(w2):
+    X = np.zeros((2, 256), np.float32)
+    X[0, :8] = [127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5]
+    X[1] = synth.make_activations(1, 256, seed=9)[0]
+    xq, sx, _ = w2.quantize_rows(dev(X))
+    oq, os_, _ = oracle.quantize_rows(X, 128)
+    assert xq.cpu().numpy()[0, :8].tolist() == [127, 0, 2, 2, 0, -2, -2, 126]
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    # bf16 input
+    Xb = synth.f32_to_bf16_bits(synth.make_activations(4, 1024, seed=10))
+    xq, sx, gs = w2.quantize_rows(dev(Xb).view(torch.bfloat16), 64, want_gsum=True)
+    oq, os_, og = oracle.quantize_rows(Xb, 64, x_is_bf16=True)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), os_.view(np.uint32))
+    assert np.array_equal(gs.cpu().numpy(), og)
+    # strided rows
+    Xw = synth.make_activations(3, 1024, seed=11)
+    t = dev(Xw)[:, :512]
+    xq, sx, _ = w2.quantize_rows(t)
+    oq, os_, _ = oracle.quantize_rows(np.ascontiguousarray(Xw[:, :512]), 128)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+
+
+# ------------------------------------------------------------------ w2a8
+def run_a8_case(w2, M, K, N, G, codec, variant, seed):
+    codes, scales, X = synth.make_problem(M, K, N, G, codec, seed)
+    packed = w2.prepack(dev(codes), dev(scales), G, codec)
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    oq, osx, _ = oracle.quantize_rows(X, G)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    acc = w2.debug_group_acc_a8(packed, K, N, G, xq, variant)
+    oacc = oracle.group_acc(codes, G, codec, oq)
+    assert np.array_equal(acc.cpu().numpy(), oacc), "int32 group accumulators differ"
+    Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=variant)
+    Y2 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=variant)
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "not deterministic"
+    Yo, y64 = oracle.matmul_a8(codes, scales, G, codec, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, G, codec, oq, osx)
+    check_y(bf16_bits(Y), Yo, y64, mag, f"a8 M={M} K={K} N={N} G={G} codec={codec} variant={variant}")
+
+
+# shapes span several 16x256 tiles, ragged N (not a multiple of 16 / 64 / 256), one-tile K
+SMALL_SHAPES = [(256, 16), (512, 40), (1024, 272), (2048, 1032), (768, 8)]
+
+
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", SMALL_SHAPES)
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+def test_a8_dot4(w2, M, K, N, G):
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_DOT4, seed=M + K + N + G)
+
+
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", SMALL_SHAPES)
+@pytest.mark.parametrize("M", [1, 4, 7, 16])
+def test_a8_smallm(w2, M, K, N, G):
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SMALLM, seed=M + K + N + G)
+
+
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (512, 1032)])
+@pytest.mark.parametrize("M", [1, 17, 127, 128, 200])
+def test_a8_tiled(w2, M, K, N, G):
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G)
+
+
+@pytest.mark.parametrize("M", [1, 4, 16, 17, 130])
+def test_a8_auto_dispatch(w2, M):
+    run_a8_case(w2, M, 1024, 528, 128, 0, w2.VARIANT_AUTO, seed=M)
+
+
+@pytest.mark.parametrize("codec", [0, 1])
+def test_config0_gemv_2048(w2, codec):
+    """The single-GEMV configuration: M=1, K=N=2048, G=128, seed 0."""
+    run_a8_case(w2, 1, 2048, 2048, 128, codec, w2.VARIANT_AUTO, seed=0)
+
+
+def test_a8_lds_chunking_long_k(w2):
+    # K large enough that 16 rows do not fit one LDS chunk: exercises the chunk loop
+    run_a8_case(w2, 16, 14336, 64, 128, 0, w2.VARIANT_SMALLM, seed=5)
+    run_a8_case(w2, 2, 14336, 64, 128, 1, w2.VARIANT_DOT4, seed=6)
+
+
+def test_a8_rows_independent_across_variants(w2):
+    M, K, N, G = 4, 1024, 272, 128
+    codes, scales, X = synth.make_problem(M, K, N, G, 0, 77)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    accs = [w2.debug_group_acc_a8(packed, K, N, G, xq, v).cpu().numpy()
+            for v in (w2.VARIANT_DOT4, w2.VARIANT_SMALLM, w2.VARIANT_TILED)]
+    assert np.array_equal(accs[0], accs[1]) and np.array_equal(accs[0], accs[2])
+    one = w2.debug_group_acc_a8(packed, K, N, G, xq[2:3].contiguous(), w2.VARIANT_DOT4).cpu().numpy()
+    assert np.array_equal(one[0], accs[0][2])
+
+
+def test_a8_closed_forms(w2):
+    K, N, G = 512, 48, 128
+    # all weights at the zero-point value -> Y == 0
+    codes = np.full((K, N), 2, np.uint8)
+    _, scales, X = synth.make_problem(2, K, N, G, 0, 1)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    for v in (w2.VARIANT_DOT4, w2.VARIANT_SMALLM, w2.VARIANT_TILED):
+        Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=v)
+        assert torch.all(Y.view(torch.int16) == 0)
+    # unit scales, xq = 1, sx = 1 -> column sums of q, exact in bf16 when |sum| < 256
+    codes, _, _ = synth.make_problem(1, K, N, G, 1, 2)         # ternary: values average to 0
+    ones = np.full((K // G, N), 0x3F80, np.uint16)
+    packed = w2.prepack(dev(codes), dev(ones), G, 1)
+    xq1 = torch.ones((1, K), dtype=torch.int8, device="cuda")
+    sx1 = torch.ones(1, dtype=torch.float32, device="cuda")
+    colsum = (codes.astype(np.int64) - 1).sum(0)
+    assert np.abs(colsum).max() < 256
+    for v in (w2.VARIANT_DOT4, w2.VARIANT_SMALLM, w2.VARIANT_TILED):
+        Y = w2.matmul_a8(packed, K, N, G, xq1, sx1, variant=v)
+        assert np.array_equal(bits_to_f64(bf16_bits(Y))[0], colsum.astype(np.float64))
+
+
+# ------------------------------------------------------------------ argument errors
+def test_argument_errors_write_nothing(w2):
+    import ctypes
+    lib = w2.raw()
+    out = ctypes.c_size_t(0)
+    assert lib.w2_packed_size(100, 64, 128, ctypes.byref(out)) == w2.ERR_UNSUPPORTED_SHAPE
+    assert lib.w2_packed_size(256, 64, 32, ctypes.byref(out)) == w2.ERR_UNSUPPORTED_SHAPE
+    assert lib.w2_packed_size(256, 64, 128, None) == w2.ERR_INVALID_ARG
+    assert b"multiple of 256" in lib.w2_last_error() or b"NULL" in lib.w2_last_error()
+    codes, scales, X = synth.make_problem(1, 256, 64, 128, 0, 0)
+    packed = w2.prepack(dev(codes), dev(scales), 128, 0)
+    xq, sx, _ = w2.quantize_rows(dev(X))
+    Y = torch.full((1, 64), 7.0, dtype=torch.bfloat16, device="cuda")
+    s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    # misaligned Y, short ldy, forced variant that does not cover M
+    assert lib.w2_matmul_a8(p(packed), 256, 64, 128, p(xq), p(sx), 1,
+                            ctypes.c_void_p(Y.data_ptr() + 2), 64, None, 0, s) == w2.ERR_MISALIGNED
+    assert lib.w2_matmul_a8(p(packed), 256, 64, 128, p(xq), p(sx), 1, p(Y), 32, None, 0, s) == w2.ERR_MISALIGNED
+    assert lib.w2_matmul_a8(p(packed), 256, 64, 128, None, p(sx), 1, p(Y), 64, None, 0, s) == w2.ERR_INVALID_ARG
+    assert lib.w2_matmul_a8_ex(p(packed), 256, 64, 128, p(xq), p(sx), 1, p(Y), 64, None, 0, 9, s) == w2.ERR_INVALID_ARG
+    # M == 0 is a no-op
+    assert lib.w2_matmul_a8(p(packed), 256, 64, 128, p(xq), p(sx), 0, p(Y), 64, None, 0, s) == 0
+    torch.cuda.synchronize()
+    assert torch.all(Y == 7.0)
+    with pytest.raises(w2.W2Error):
+        w2.matmul_a8(packed, 256, 64, 128, xq.repeat(5, 1), sx.repeat(5), variant=w2.VARIANT_DOT4)
