@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the w2a8 hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: for each of the
+four projections of an 8B-class decoder layer (QKV, O, gate+up, down) at M=1,
+quantise the fp32 activation row to int8 (per token) and run the fused
+2-bit-weight matmul (bf16 out).  Weights are prepacked once (off-line step)
+and resident in HBM; successive steps walk a pool of distinct prepacked layers
+larger than twice the 256 MB last-level cache, so every step streams its
+weights from HBM as a real decode does.  Steps are replayed from HIP graphs so
+that host launch cost does not hide the GPU time.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+INT8_PEAK_TOPS = 5000.0        # dense int8 MFMA peak
+POOL_BYTES = 704 << 20         # > 2 x 256 MB last-level cache
+G = 128
+
+
+def algorithmic_bytes(M, K, N, g=G):
+    """Bytes the method itself must move for one matmul call: 2-bit codes, group
+    scales, int8 activations in, bf16 out."""
+    return K * N // 4 + (K // g) * N * 2 + M * K + 2 * M * N
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+                 "use --gpus 1.  DESIGN.md says how the path would shard.")
+
+    import numpy as np
+    import torch
+    from paper_2508_06753_amd import binding as w2, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    M = 1
+    shapes = synth.SHAPES_8B
+
+    def to_dev(a):
+        if a.dtype == np.uint16:
+            a = a.view(np.int16)
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---- synthetic layer (seed 1), prepacked once; the pool holds copies of the packed blobs
+    # (kernel time does not depend on the values, only on the bytes streamed)
+    host = {}
+    packed0 = {}
+    for i, (name, (K, N)) in enumerate(shapes.items()):
+        codes, scales, X = synth.make_problem(M, K, N, G, synth.CODEC_INT2, seed=1 + i)
+        host[name] = (codes, scales, X)
+        packed0[name] = w2.prepack(to_dev(codes), to_dev(scales), G, w2.CODEC_INT2)
+    layer_bytes = sum(p.numel() for p in packed0.values())
+    n_pool = max(2, -(-POOL_BYTES // layer_bytes))
+    pool = [packed0] + [{k: v.clone() for k, v in packed0.items()} for _ in range(n_pool - 1)]
+    Xd = {name: to_dev(host[name][2]) for name in shapes}
+    Yd = {name: torch.empty((M, shapes[name][1]), dtype=torch.bfloat16, device=dev) for name in shapes}
+    xq = {name: torch.empty((M, shapes[name][0]), dtype=torch.int8, device=dev) for name in shapes}
+    sx = {name: torch.empty((M,), dtype=torch.float32, device=dev) for name in shapes}
+
+    import ctypes
+    lib = w2.raw()
+
+    def vp(t):
+        return ctypes.c_void_p(t.data_ptr())
+
+    def step(layer):
+        s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        for name, (K, N) in shapes.items():
+            rc = lib.w2_quantize_rows(vp(Xd[name]), w2.DT_F32, M, K, K, G, vp(xq[name]), vp(sx[name]),
+                                      None, s)
+            assert rc == 0, lib.w2_last_error()
+            rc = lib.w2_matmul_a8(vp(layer[name]), K, N, G, vp(xq[name]), vp(sx[name]), M,
+                                  vp(Yd[name]), N, None, 0, s)
+            assert rc == 0, lib.w2_last_error()
+
+    def capture(fn):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g
+
+    step(pool[0])
+    torch.cuda.synchronize()
+    use_graph = os.environ.get("W2_BENCH_NO_GRAPH", "0") != "1"
+    graphs = [capture(lambda l=l: step(l)) for l in pool] if use_graph else None
+
+    def run_step(i):
+        if graphs:
+            graphs[i % n_pool].replay()
+        else:
+            step(pool[i % n_pool])
+
+    for i in range(args.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(args.steps):
+        run_step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = wall_ms / args.steps
+    gpu_ms_per_step = e0.elapsed_time(e1) / args.steps
+    step_bytes = sum(algorithmic_bytes(M, K, N) for K, N in shapes.values())
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- roofline of the dominant kernel: the GEMV on the largest projection (gate+up),
+    # launched alone, back to back over the pool, timed with events on the launch stream
+    Kd, Nd = shapes["gate_up"]
+
+    def gemv_only(layer):
+        s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        rc = lib.w2_matmul_a8(vp(layer["gate_up"]), Kd, Nd, G, vp(xq["gate_up"]), vp(sx["gate_up"]), M,
+                              vp(Yd["gate_up"]), Nd, None, 0, s)
+        assert rc == 0, lib.w2_last_error()
+
+    def all_gemv():
+        for l in pool:
+            gemv_only(l)
+
+    gg = capture(all_gemv) if use_graph else None
+    reps = 20
+    for _ in range(3):
+        gg.replay() if gg else all_gemv()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        gg.replay() if gg else all_gemv()
+    e1.record()
+    torch.cuda.synchronize()
+    gemv_us = e0.elapsed_time(e1) * 1e3 / (reps * n_pool)
+    gemv_bytes = algorithmic_bytes(M, Kd, Nd)
+    achieved = gemv_bytes / gemv_us / 1e3           # GB/s
+
+    # attainable read ceiling: a plain 128-bit streaming read of the same number of bytes
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def all_read():
+        s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        for l in pool:
+            lib.w2_debug_stream_read(vp(l["gate_up"]), l["gate_up"].numel(), vp(sink), s)
+
+    gr = capture(all_read) if use_graph else None
+    for _ in range(3):
+        gr.replay() if gr else all_read()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        gr.replay() if gr else all_read()
+    e1.record()
+    torch.cuda.synchronize()
+    read_us = e0.elapsed_time(e1) * 1e3 / (reps * n_pool)
+
+    out = {
+        "metric": "M=1 weight-stream GB/s (% of HBM peak); TOPS at M=2048 (% of int8 MFMA peak)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "gpu_ms_per_step": round(gpu_ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": "8B-class decode layer, M=1, w2a8, G=128: quantise + matmul for "
+                               "QKV 4096x6144, O 4096x4096, gate+up 4096x28672, down 14336x4096",
+                   "bytes_per_step": step_bytes, "pool_layers": n_pool, "hip_graph": bool(graphs),
+                   "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2)},
+        "roofline": {"bound": "hbm", "kernel": "w2a8 GEMV (dot4) on gate+up 4096x28672, M=1",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "us_per_launch": round(gemv_us, 3), "bytes_per_launch": gemv_bytes,
+                     "stream_read_us_same_bytes": round(read_us, 3),
+                     "frac_of_stream_read": round(read_us / gemv_us, 4)},
+    }
+
+    # ---- secondary headline: compute-bound prefill, 70B-class gate+up at M=2048
+    if not args.no_prefill:
+        Kp, Np, Mp = 8192, 57344, 2048
+        nb = w2.packed_size(Kp, Np, G)
+        pk = torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev)   # any bytes are valid weights
+        pk[Kp * Np // 4:].view(torch.int16)[:] = 0x3C00                    # scales region: finite bf16
+        xqp = torch.randint(-127, 128, (Mp, Kp), dtype=torch.int8, device=dev)
+        sxp = torch.rand(Mp, device=dev)
+        Yp = torch.empty((Mp, Np), dtype=torch.bfloat16, device=dev)
+        for _ in range(2):
+            w2.matmul_a8(pk, Kp, Np, G, xqp, sxp, out=Yp)
+        torch.cuda.synchronize()
+        e0.record()
+        nrep = 5
+        for _ in range(nrep):
+            w2.matmul_a8(pk, Kp, Np, G, xqp, sxp, out=Yp)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / nrep
+        tops = 2.0 * Mp * Kp * Np / us / 1e6
+        out["prefill"] = {"workload": "70B-class gate+up 8192x57344, M=2048, w2a8, G=128 (matmul only)",
+                          "us_per_launch": round(us, 1), "value": round(tops, 1), "unit": "TOPS",
+                          "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": INT8_PEAK_TOPS,
+                                       "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
+                                       "traffic": None}}
+        del pk, xqp, Yp
+
+    # ---- the CPU oracle, timed as it stands on the host cores, on the same layer
+    if not args.no_cpu_baseline:
+        import oracle
+        best = None
+        for _ in range(2):
+            t = time.perf_counter()
+            for name in shapes:
+                codes, scales, X = host[name]
+                oq, osx, _ = oracle.quantize_rows(X, G, want_gsum=False)
+                oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+            dt = time.perf_counter() - t
+            best = dt if best is None else min(best, dt)
+        out["cpu_baseline"] = {"value": round(step_bytes / best / 1e9, 3), "unit": "GB/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "the full step (all four projections of the layer, M=1), "
+                                         "best of 2 runs; %.3f s per step" % best}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -38,30 +38,47 @@ int env_int(const char* name, int dflt)
     return atoi(v);
 }
 
-// Streaming-read probe: grid-stride 128-bit loads, xor-reduced.
+// Streaming-read probe.  Each wave reads U consecutive 1 KiB chunks (one
+// 128-bit load per lane per chunk) with all U loads in flight before any is
+// consumed, then strides on; the loaded words are xor-reduced.
+template <int U>
 __global__ void __launch_bounds__(256)
-stream_read_kernel(const uint4* __restrict__ src, size_t n_vec, uint32_t* __restrict__ sink)
+stream_read_kernel(const uint4* __restrict__ src, size_t n_chunks, uint32_t* __restrict__ sink)
 {
     uint32_t x = 0;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) {
-        const uint4 v = src[i];
-        x ^= v.x ^ v.y ^ v.z ^ v.w;
+    const int lane = threadIdx.x & 63;
+    const size_t gwave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const size_t n_waves = ((size_t)gridDim.x * blockDim.x) >> 6;
+    for (size_t base = gwave * U; base < n_chunks; base += n_waves * U) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t c = base + u < n_chunks ? base + u : n_chunks - 1;
+            v[u] = src[c * 64 + lane];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) x ^= __shfl_xor(x, off);
-    if ((threadIdx.x & 63) == 0 && x == 0x9e3779b9u) atomicXor(sink, x);   // practically never taken
+    if (lane == 0 && x == 0x9e3779b9u) atomicXor(sink, x);   // keeps the loads alive; rarely taken
 }
 
 int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream)
 {
-    const size_t n_vec = bytes / 16;
-    if (n_vec == 0) return W2_OK;
-    size_t blocks = (n_vec + 255) / 256;
-    const size_t cap = (size_t)env_int("W2_STREAM_BLOCKS", 256 * 16);
+    const size_t n_chunks = bytes / 1024;
+    if (n_chunks == 0) return W2_OK;
+    const int unroll = env_int("W2_STREAM_UNROLL", 8);
+    const size_t cap = (size_t)env_int("W2_STREAM_BLOCKS", 2048);
+    size_t blocks = (n_chunks + 4 * (size_t)unroll - 1) / (4 * (size_t)unroll);   // 4 waves per block
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       (const uint4*)src, n_vec, sink);
+    const dim3 grid((unsigned)blocks), block(256);
+    if (unroll >= 16)
+        hipLaunchKernelGGL(stream_read_kernel<16>, grid, block, 0, stream, (const uint4*)src, n_chunks, sink);
+    else if (unroll >= 8)
+        hipLaunchKernelGGL(stream_read_kernel<8>, grid, block, 0, stream, (const uint4*)src, n_chunks, sink);
+    else
+        hipLaunchKernelGGL(stream_read_kernel<4>, grid, block, 0, stream, (const uint4*)src, n_chunks, sink);
     return check_launch("w2_debug_stream_read");
 }
 

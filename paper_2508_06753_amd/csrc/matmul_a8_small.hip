@@ -70,14 +70,56 @@ __device__ __forceinline__ float tile_scale(const TileRegs& r, int gi)
     return (gi & 1) ? __uint_as_float(pair & 0xffff0000u) : __uint_as_float(pair << 16);
 }
 
-// Copies rows [0,rows) x k in [k0, k0+len) of xq into LDS rows of stride
-// len + XS_PAD.  len % 16 == 0.
-__device__ __forceinline__ void stage_activations(const int8_t* __restrict__ xq, int64_t K,
-                                                  int rows, int64_t k0, int len, int8_t* xs)
+// Staging of the activation rows [0,rows) x k in [k0, k0+len) into LDS rows of
+// stride len + XS_PAD (len % 16 == 0), split in two so that the global loads
+// can be issued BEFORE the weight-tile loads and the LDS stores after them:
+// vector memory returns in order, so waiting for the activations then does
+// not wait for the weights behind them.  Up to SV 16-byte pieces per thread go
+// through registers; anything beyond that is copied directly.
+constexpr int SV = 4;
+
+struct StageRegs { uint4 v0, v1, v2, v3; };
+
+__device__ __forceinline__ uint4 stage_load1(const int8_t* __restrict__ xq, int64_t K, int64_t k0,
+                                             int vec_per_row, int total, int j)
+{
+    int i = threadIdx.x + j * blockDim.x;                 // branch-free: surplus threads re-read the last piece
+    i = i < total ? i : total - 1;
+    const int r = i / vec_per_row, v = i - r * vec_per_row;
+    return *reinterpret_cast<const uint4*>(xq + (int64_t)r * K + k0 + v * 16);
+}
+
+__device__ __forceinline__ void stage_load(const int8_t* __restrict__ xq, int64_t K, int rows,
+                                           int64_t k0, int len, StageRegs& st)
 {
     const int vec_per_row = len >> 4;
     const int total = rows * vec_per_row;
-    for (int i = threadIdx.x; i < total; i += blockDim.x) {
+    st.v0 = stage_load1(xq, K, k0, vec_per_row, total, 0);
+    st.v1 = stage_load1(xq, K, k0, vec_per_row, total, 1);
+    st.v2 = stage_load1(xq, K, k0, vec_per_row, total, 2);
+    st.v3 = stage_load1(xq, K, k0, vec_per_row, total, 3);
+}
+
+__device__ __forceinline__ void stage_store1(int8_t* xs, int len, int vec_per_row, int total, int j,
+                                             const uint4& val)
+{
+    const int i = threadIdx.x + j * blockDim.x;
+    if (i < total) {
+        const int r = i / vec_per_row, v = i - r * vec_per_row;
+        *reinterpret_cast<uint4*>(xs + r * (len + XS_PAD) + v * 16) = val;
+    }
+}
+
+__device__ __forceinline__ void stage_store(const int8_t* __restrict__ xq, int64_t K, int rows,
+                                            int64_t k0, int len, const StageRegs& st, int8_t* xs)
+{
+    const int vec_per_row = len >> 4;
+    const int total = rows * vec_per_row;
+    stage_store1(xs, len, vec_per_row, total, 0, st.v0);
+    stage_store1(xs, len, vec_per_row, total, 1, st.v1);
+    stage_store1(xs, len, vec_per_row, total, 2, st.v2);
+    stage_store1(xs, len, vec_per_row, total, 3, st.v3);
+    for (int i = threadIdx.x + SV * blockDim.x; i < total; i += blockDim.x) {
         const int r = i / vec_per_row, v = i - r * vec_per_row;
         *reinterpret_cast<uint4*>(xs + r * (len + XS_PAD) + v * 16) =
             *reinterpret_cast<const uint4*>(xq + (int64_t)r * K + k0 + v * 16);
@@ -90,82 +132,112 @@ struct SmallCfg {
     int kc;         // k per LDS chunk (multiple of 256)
 };
 
+// The per-wave schedule shared by both kernel families.  A wave owns column
+// block cb and the k tiles ks, ks+KS, ...  Inside one LDS chunk it first issues
+// the loads of ALL its tiles (up to TMAX, 1 KiB each per wave) and only then
+// consumes them, so a wave has its whole share of the weight stream in flight
+// after one round trip: the kernels live for a few microseconds, about as long
+// as a handful of dependent HBM round trips.
+#define W2_SMALL_PROLOGUE()                                                                   \
+    extern __shared__ __align__(16) int8_t smem[];                                            \
+    const int lane = threadIdx.x & 63;                                                        \
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);                        \
+    const int cbi = wave % cfg.cbw;                                                           \
+    const int ks = wave / cfg.cbw;                                                            \
+    const int64_t cb = (int64_t)blockIdx.x * cfg.cbw + cbi;                                   \
+    const bool cb_ok = cb < a.n_cb;                                                           \
+    const int64_t cbc = cb_ok ? cb : a.n_cb - 1; /* clamp: keeps loads in bounds */           \
+    const int q = lane >> 4;                                                                  \
+    const int64_t n = cb * TILE_N + (lane & 15);                                              \
+    constexpr int GPT = TILE_K / G;                                                           \
+    const int tiles_per_chunk = cfg.kc / TILE_K;                                              \
+    const int n_chunks = (int)((a.n_kt + tiles_per_chunk - 1) / tiles_per_chunk);             \
+    (void)n; (void)q; (void)GPT
+
 // ---------------------------------------------------------------- DOT4
-template <int MT, int G, bool DBG>
+template <int MT, int G, int TMAX, bool DBG>
 __global__ void __launch_bounds__(1024)
 a8_dot4_kernel(A8Args a, SmallCfg cfg)
 {
-    extern __shared__ __align__(16) int8_t smem[];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int cbi = wave % cfg.cbw;
-    const int ks = wave / cfg.cbw;
-    const int64_t cb = (int64_t)blockIdx.x * cfg.cbw + cbi;
-    const bool cb_ok = cb < a.n_cb;
-    const int64_t cbc = cb_ok ? cb : a.n_cb - 1;           // clamp: keeps loads in bounds
-    const int q = lane >> 4;
-    const int64_t n = cb * TILE_N + (lane & 15);
-    constexpr int GPT = TILE_K / G;
-    const int tiles_per_chunk = cfg.kc / TILE_K;
-    const int row_stride = cfg.kc + XS_PAD;
+    W2_SMALL_PROLOGUE();
+    const int rows = MT < (int)a.M ? MT : (int)a.M;
+    // activation scale for the output this thread stores first, fetched before the stream starts
+    const int m_first = (threadIdx.x >> 4) % MT;
+    const float sx_first = (!DBG && m_first < a.M) ? a.sx[m_first] : 0.0f;
 
     float y[MT];
     int acc[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m) { y[m] = 0.0f; acc[m] = 0; }
 
-    int64_t kt = ks;                                        // this wave's tiles: ks, ks+KS, ...
-    TileRegs t0 = {}, t1 = {};
-    if (kt < a.n_kt) t0 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt, lane);
-    if (kt + cfg.ks < a.n_kt) t1 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt + cfg.ks, lane);
-
-    const int n_chunks = (int)((a.n_kt + tiles_per_chunk - 1) / tiles_per_chunk);
     for (int c = 0; c < n_chunks; ++c) {
         const int64_t kt_begin = (int64_t)c * tiles_per_chunk;
         const int64_t kt_end = min(kt_begin + tiles_per_chunk, a.n_kt);
-        if (c > 0) __syncthreads();
-        stage_activations(a.xq, a.K, MT < (int)a.M ? MT : (int)a.M, kt_begin * TILE_K,
-                          (int)(kt_end - kt_begin) * TILE_K, smem);
-        __syncthreads();
+        // first tile of this wave inside the chunk: smallest kt >= kt_begin with kt % KS == ks
+        int64_t kt0 = kt_begin + ((ks - kt_begin % cfg.ks) + cfg.ks) % cfg.ks;
         const int cur_stride = (int)(kt_end - kt_begin) * TILE_K + XS_PAD;
-        (void)row_stride;
-        for (; kt < kt_end; kt += cfg.ks) {
-            const TileRegs cur = t0;
-            t0 = t1;
-            if (kt + 2 * cfg.ks < a.n_kt)
-                t1 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt + 2 * cfg.ks, lane);
-            const int8_t* xrow = smem + (int)(kt - kt_begin) * TILE_K + q * 16;
-            const uint32_t wd[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
+        auto load_batch = [&](int64_t kb, TileRegs (&tr)[TMAX]) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                int u[4];
-                upconvert(wd[t], u);
+            for (int i = 0; i < TMAX; ++i) {             // branch-free: past-the-end slots re-read the last tile
+                const int64_t kt = kb + (int64_t)i * cfg.ks;
+                tr[i] = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + (kt < kt_end ? kt : kt_end - 1), lane);
+            }
+        };
+        auto compute_batch = [&](int64_t kb, const TileRegs (&tr)[TMAX]) {
 #pragma unroll
-                for (int m = 0; m < MT; ++m) {
-                    const int mr = m < (int)a.M ? m : (int)a.M - 1;
-                    const v4i x = *reinterpret_cast<const v4i*>(xrow + mr * cur_stride + t * 64);
-                    acc[m] = __builtin_amdgcn_sdot4(u[0], x[0], acc[m], false);
-                    acc[m] = __builtin_amdgcn_sdot4(u[1], x[1], acc[m], false);
-                    acc[m] = __builtin_amdgcn_sdot4(u[2], x[2], acc[m], false);
-                    acc[m] = __builtin_amdgcn_sdot4(u[3], x[3], acc[m], false);
-                }
-                if (G == 64 || (t & 1)) {                   // a group ends here
-                    const int gi = G == 64 ? t : t >> 1;
-                    const float sw = tile_scale<G>(cur, gi);
+            for (int i = 0; i < TMAX; ++i) {
+                const int64_t kt = kb + (int64_t)i * cfg.ks;
+                if (kt >= kt_end) break;
+                const TileRegs cur = tr[i];
+                const int8_t* xrow = smem + (int)(kt - kt_begin) * TILE_K + q * 16;
+                const uint32_t wd[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    int u[4];
+                    upconvert(wd[t], u);
 #pragma unroll
                     for (int m = 0; m < MT; ++m) {
-                        if constexpr (DBG) {
-                            int s = acc[m];
-                            s += __shfl_xor(s, 16);
-                            s += __shfl_xor(s, 32);
-                            if (q == 0 && cb_ok && n < a.N && m < a.M)
-                                a.acc_out[((int64_t)m * (a.K / G) + kt * GPT + gi) * a.N + n] = s >> 6;
+                        const int mr = m < rows ? m : rows - 1;
+                        const v4i x = *reinterpret_cast<const v4i*>(xrow + mr * cur_stride + t * 64);
+                        acc[m] = __builtin_amdgcn_sdot4(u[0], x[0], acc[m], false);
+                        acc[m] = __builtin_amdgcn_sdot4(u[1], x[1], acc[m], false);
+                        acc[m] = __builtin_amdgcn_sdot4(u[2], x[2], acc[m], false);
+                        acc[m] = __builtin_amdgcn_sdot4(u[3], x[3], acc[m], false);
+                    }
+                    if (G == 64 || (t & 1)) {                   // a group ends here
+                        const int gi = G == 64 ? t : t >> 1;
+                        const float sw = tile_scale<G>(cur, gi);
+#pragma unroll
+                        for (int m = 0; m < MT; ++m) {
+                            if constexpr (DBG) {
+                                int s = acc[m];
+                                s += __shfl_xor(s, 16);
+                                s += __shfl_xor(s, 32);
+                                if (q == 0 && cb_ok && n < a.N && m < a.M)
+                                    a.acc_out[((int64_t)m * (a.K / G) + kt * GPT + gi) * a.N + n] = s >> 6;
+                            }
+                            y[m] = fmaf(sw, (float)acc[m], y[m]);
+                            acc[m] = 0;
                         }
-                        y[m] = fmaf(sw, (float)acc[m], y[m]);
-                        acc[m] = 0;
                     }
                 }
             }
+        };
+        // first batch: activation loads, then weight loads, then the LDS stores
+        {
+            StageRegs st;
+            stage_load(a.xq, a.K, rows, kt_begin * TILE_K, (int)(kt_end - kt_begin) * TILE_K, st);
+            TileRegs tr[TMAX];
+            load_batch(kt0, tr);
+            if (c > 0) __syncthreads();          // everyone is done reading the previous chunk
+            stage_store(a.xq, a.K, rows, kt_begin * TILE_K, (int)(kt_end - kt_begin) * TILE_K, st, smem);
+            __syncthreads();
+            compute_batch(kt0, tr);
+        }
+        for (kt0 += (int64_t)TMAX * cfg.ks; kt0 < kt_end; kt0 += (int64_t)TMAX * cfg.ks) {
+            TileRegs tr[TMAX];
+            load_batch(kt0, tr);
+            compute_batch(kt0, tr);
         }
     }
     if constexpr (DBG) return;
@@ -189,76 +261,85 @@ a8_dot4_kernel(A8Args a, SmallCfg cfg)
         float s = 0.0f;
         for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * MT + m) * 16 + nl];
         const int64_t nn = ((int64_t)blockIdx.x * cfg.cbw + ci) * TILE_N + nl;
-        if (m < a.M && nn < a.N)
-            a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * (a.sx[m] * 0.015625f));
+        if (m < a.M && nn < a.N) {
+            const float sxm = i == (int)threadIdx.x ? sx_first : a.sx[m];
+            a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * (sxm * 0.015625f));
+        }
     }
 }
 
 // ---------------------------------------------------------------- SMALLM (MFMA)
-template <int G, bool DBG>
+template <int G, int TMAX, bool DBG>
 __global__ void __launch_bounds__(1024)
 a8_smallm_kernel(A8Args a, SmallCfg cfg)
 {
-    extern __shared__ __align__(16) int8_t smem[];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int cbi = wave % cfg.cbw;
-    const int ks = wave / cfg.cbw;
-    const int64_t cb = (int64_t)blockIdx.x * cfg.cbw + cbi;
-    const bool cb_ok = cb < a.n_cb;
-    const int64_t cbc = cb_ok ? cb : a.n_cb - 1;
-    const int q = lane >> 4;
-    const int64_t n = cb * TILE_N + (lane & 15);
-    constexpr int GPT = TILE_K / G;
-    const int tiles_per_chunk = cfg.kc / TILE_K;
+    W2_SMALL_PROLOGUE();
     const int rows = (int)a.M;                              // 1..16
     const int arow = (lane & 15) < rows ? (lane & 15) : rows - 1;   // padded rows repeat the last
+    const float sx_first = DBG ? 0.0f : a.sx[(threadIdx.x >> 4) % rows];
 
     float y[4] = {0.f, 0.f, 0.f, 0.f};
     v4i acc = {0, 0, 0, 0};
 
-    int64_t kt = ks;
-    TileRegs t0 = {}, t1 = {};
-    if (kt < a.n_kt) t0 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt, lane);
-    if (kt + cfg.ks < a.n_kt) t1 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt + cfg.ks, lane);
-
-    const int n_chunks = (int)((a.n_kt + tiles_per_chunk - 1) / tiles_per_chunk);
     for (int c = 0; c < n_chunks; ++c) {
         const int64_t kt_begin = (int64_t)c * tiles_per_chunk;
         const int64_t kt_end = min(kt_begin + tiles_per_chunk, a.n_kt);
-        if (c > 0) __syncthreads();
-        stage_activations(a.xq, a.K, rows, kt_begin * TILE_K, (int)(kt_end - kt_begin) * TILE_K, smem);
-        __syncthreads();
+        int64_t kt0 = kt_begin + ((ks - kt_begin % cfg.ks) + cfg.ks) % cfg.ks;
         const int cur_stride = (int)(kt_end - kt_begin) * TILE_K + XS_PAD;
-        for (; kt < kt_end; kt += cfg.ks) {
-            const TileRegs cur = t0;
-            t0 = t1;
-            if (kt + 2 * cfg.ks < a.n_kt)
-                t1 = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt + 2 * cfg.ks, lane);
-            const int8_t* xrow = smem + arow * cur_stride + (int)(kt - kt_begin) * TILE_K + q * 16;
-            const uint32_t wd[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
+        auto load_batch = [&](int64_t kb, TileRegs (&tr)[TMAX]) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                int u[4];
-                upconvert(wd[t], u);
-                const v4i bop = {u[0], u[1], u[2], u[3]};
-                const v4i aop = *reinterpret_cast<const v4i*>(xrow + t * 64);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, bop, acc, 0, 0, 0);
-                if (G == 64 || (t & 1)) {
-                    const int gi = G == 64 ? t : t >> 1;
-                    const float sw = tile_scale<G>(cur, gi);
+            for (int i = 0; i < TMAX; ++i) {             // branch-free: past-the-end slots re-read the last tile
+                const int64_t kt = kb + (int64_t)i * cfg.ks;
+                tr[i] = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + (kt < kt_end ? kt : kt_end - 1), lane);
+            }
+        };
+        auto compute_batch = [&](int64_t kb, const TileRegs (&tr)[TMAX]) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        if constexpr (DBG) {
-                            const int m = 4 * q + r;
-                            if (cb_ok && n < a.N && m < a.M)
-                                a.acc_out[((int64_t)m * (a.K / G) + kt * GPT + gi) * a.N + n] = acc[r] >> 6;
+            for (int i = 0; i < TMAX; ++i) {
+                const int64_t kt = kb + (int64_t)i * cfg.ks;
+                if (kt >= kt_end) break;
+                const TileRegs cur = tr[i];
+                const int8_t* xrow = smem + arow * cur_stride + (int)(kt - kt_begin) * TILE_K + q * 16;
+                const uint32_t wd[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    int u[4];
+                    upconvert(wd[t], u);
+                    const v4i bop = {u[0], u[1], u[2], u[3]};
+                    const v4i aop = *reinterpret_cast<const v4i*>(xrow + t * 64);
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, bop, acc, 0, 0, 0);
+                    if (G == 64 || (t & 1)) {
+                        const int gi = G == 64 ? t : t >> 1;
+                        const float sw = tile_scale<G>(cur, gi);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            if constexpr (DBG) {
+                                const int m = 4 * q + r;
+                                if (cb_ok && n < a.N && m < a.M)
+                                    a.acc_out[((int64_t)m * (a.K / G) + kt * GPT + gi) * a.N + n] = acc[r] >> 6;
+                            }
+                            y[r] = fmaf(sw, (float)acc[r], y[r]);
                         }
-                        y[r] = fmaf(sw, (float)acc[r], y[r]);
+                        acc = (v4i){0, 0, 0, 0};
                     }
-                    acc = (v4i){0, 0, 0, 0};
                 }
             }
+        };
+        // first batch: activation loads, then weight loads, then the LDS stores
+        {
+            StageRegs st;
+            stage_load(a.xq, a.K, rows, kt_begin * TILE_K, (int)(kt_end - kt_begin) * TILE_K, st);
+            TileRegs tr[TMAX];
+            load_batch(kt0, tr);
+            if (c > 0) __syncthreads();          // everyone is done reading the previous chunk
+            stage_store(a.xq, a.K, rows, kt_begin * TILE_K, (int)(kt_end - kt_begin) * TILE_K, st, smem);
+            __syncthreads();
+            compute_batch(kt0, tr);
+        }
+        for (kt0 += (int64_t)TMAX * cfg.ks; kt0 < kt_end; kt0 += (int64_t)TMAX * cfg.ks) {
+            TileRegs tr[TMAX];
+            load_batch(kt0, tr);
+            compute_batch(kt0, tr);
         }
     }
     if constexpr (DBG) return;
@@ -274,23 +355,33 @@ a8_smallm_kernel(A8Args a, SmallCfg cfg)
         float s = 0.0f;
         for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * 16 + m) * 16 + nl];
         const int64_t nn = ((int64_t)blockIdx.x * cfg.cbw + ci) * TILE_N + nl;
-        if (nn < a.N) a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * (a.sx[m] * 0.015625f));
+        if (nn < a.N) {
+            const float sxm = i == (int)threadIdx.x ? sx_first : a.sx[m];
+            a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * (sxm * 0.015625f));
+        }
     }
 }
 
 // ---------------------------------------------------------------- host side
 
-// Picks (column blocks per workgroup, k-splits) so that the grid has a few
-// workgroups per CU and every wave still streams several tiles.
-static SmallCfg pick_cfg(const A8Args& a, int rows, int max_waves)
+constexpr int TMAX = 8;                      // most tiles a wave keeps in flight
+constexpr int64_t LDS_BUDGET = 128 * 1024;   // activation chunk + reduction scratch
+
+// Picks (column blocks per workgroup, k-splits): enough workgroups to fill 256
+// CUs a few times over, and a k-split that leaves each wave at most TMAX tiles
+// when the wave budget allows it.
+static SmallCfg pick_cfg(const A8Args& a, int rows)
 {
     SmallCfg c;
     int waves = env_int("W2_SMALL_WAVES", 8);
-    if (waves > max_waves) waves = max_waves;
+    if (waves > 16) waves = 16;
+    if (waves < 1) waves = 1;
     int cbw = env_int("W2_SMALL_CBW", 0);
     if (cbw <= 0) {
-        // aim for >= 512 workgroups (2 per CU) but never fewer than 1 cb per WG
-        cbw = 4;
+        cbw = waves;
+        // split K until a wave has at most TMAX tiles, while there are waves to split over
+        while (cbw > 1 && a.n_kt * cbw > (int64_t)TMAX * waves) cbw >>= 1;
+        // and keep at least ~2 workgroups per CU
         while (cbw > 1 && (a.n_cb + cbw - 1) / cbw < 512) cbw >>= 1;
     }
     if (cbw > waves) cbw = waves;
@@ -298,10 +389,8 @@ static SmallCfg pick_cfg(const A8Args& a, int rows, int max_waves)
     c.ks = waves / cbw;
     if (c.ks > a.n_kt) c.ks = (int)a.n_kt;
     if (c.ks < 1) c.ks = 1;
-    // LDS budget for the activation chunk
-    const int64_t budget = 64 * 1024;
     int64_t kc = a.n_kt * TILE_K;
-    while (kc > TILE_K && (int64_t)rows * (kc + XS_PAD) > budget) kc -= TILE_K;
+    while (kc > TILE_K && (int64_t)rows * (kc + XS_PAD) > LDS_BUDGET) kc -= TILE_K;
     const int force = env_int("W2_SMALL_KC", 0);
     if (force >= TILE_K && force % TILE_K == 0 && force < kc) kc = force;
     c.kc = (int)kc;
@@ -315,20 +404,45 @@ static size_t small_lds_bytes(const SmallCfg& c, int rows, int red_rows)
     return act > red ? act : red;
 }
 
+// Most tiles any wave owns inside one LDS chunk.
+static int tiles_per_wave(const A8Args& a, const SmallCfg& c)
+{
+    int64_t chunk_tiles = c.kc / TILE_K;
+    if (chunk_tiles > a.n_kt) chunk_tiles = a.n_kt;
+    return (int)((chunk_tiles + c.ks - 1) / c.ks);
+}
+
+template <typename Kern>
+static int launch_small(Kern kern, const char* what, const A8Args& a, const SmallCfg& c, size_t lds,
+                        hipStream_t stream)
+{
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) {
+            set_error("%s: hipFuncSetAttribute(%zu): %s", what, lds, hipGetErrorString(e));
+            return -5;
+        }
+    }
+    const dim3 grid((unsigned)((a.n_cb + c.cbw - 1) / c.cbw)), block(64 * c.cbw * c.ks);
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, c);
+    return check_launch(what);
+}
+
 bool a8_dot4_supports(const A8Args& a) { return a.M >= 1 && a.M <= 4; }
 bool a8_smallm_supports(const A8Args& a) { return a.M >= 1 && a.M <= 16; }
 
 template <int MT, int G>
 static int launch_dot4_t(const A8Args& a, hipStream_t stream)
 {
-    const SmallCfg c = pick_cfg(a, MT, 16);
-    const size_t lds = small_lds_bytes(c, MT, MT);
-    const dim3 grid((unsigned)((a.n_cb + c.cbw - 1) / c.cbw)), block(64 * c.cbw * c.ks);
-    if (a.acc_out)
-        hipLaunchKernelGGL((a8_dot4_kernel<MT, G, true>), grid, block, lds, stream, a, c);
-    else
-        hipLaunchKernelGGL((a8_dot4_kernel<MT, G, false>), grid, block, lds, stream, a, c);
-    return check_launch("w2_matmul_a8[dot4]");
+    const int rows = MT < (int)a.M ? MT : (int)a.M;
+    const SmallCfg c = pick_cfg(a, rows);
+    const size_t lds = small_lds_bytes(c, rows, MT);
+    if (a.acc_out) return launch_small(a8_dot4_kernel<MT, G, TMAX, true>, "w2_matmul_a8[dot4]", a, c, lds, stream);
+    // in-flight depth = tiles per wave, so that no load slot re-reads a tile
+    const int tpw = tiles_per_wave(a, c);
+    if (tpw <= 2) return launch_small(a8_dot4_kernel<MT, G, 2, false>, "w2_matmul_a8[dot4]", a, c, lds, stream);
+    if (tpw <= 4) return launch_small(a8_dot4_kernel<MT, G, 4, false>, "w2_matmul_a8[dot4]", a, c, lds, stream);
+    return launch_small(a8_dot4_kernel<MT, G, TMAX, false>, "w2_matmul_a8[dot4]", a, c, lds, stream);
 }
 
 int launch_a8_dot4(const A8Args& a, hipStream_t stream)
@@ -348,14 +462,13 @@ template <int G>
 static int launch_smallm_t(const A8Args& a, hipStream_t stream)
 {
     const int rows = (int)a.M;
-    const SmallCfg c = pick_cfg(a, rows, 16);
+    const SmallCfg c = pick_cfg(a, rows);
     const size_t lds = small_lds_bytes(c, rows, 16);
-    const dim3 grid((unsigned)((a.n_cb + c.cbw - 1) / c.cbw)), block(64 * c.cbw * c.ks);
-    if (a.acc_out)
-        hipLaunchKernelGGL((a8_smallm_kernel<G, true>), grid, block, lds, stream, a, c);
-    else
-        hipLaunchKernelGGL((a8_smallm_kernel<G, false>), grid, block, lds, stream, a, c);
-    return check_launch("w2_matmul_a8[smallm]");
+    if (a.acc_out) return launch_small(a8_smallm_kernel<G, TMAX, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+    const int tpw = tiles_per_wave(a, c);
+    if (tpw <= 2) return launch_small(a8_smallm_kernel<G, 2, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+    if (tpw <= 4) return launch_small(a8_smallm_kernel<G, 4, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+    return launch_small(a8_smallm_kernel<G, TMAX, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
 }
 
 int launch_a8_smallm(const A8Args& a, hipStream_t stream)
