@@ -13,22 +13,11 @@
 // -> bf16) is fused: per group y += sw * float(acc), at the end y * sx / 64.
 #include <hip/hip_runtime.h>
 
-#include "w2_internal.h"
+#include "w2_small_common.h"
 
 namespace w2 {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-
-constexpr int XS_PAD = 16;   // bytes of padding per LDS activation row (bank spread)
-
-__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
 
 // 16 two-bit fields -> four dwords of int8 lanes holding 64*q.
 __device__ __forceinline__ void upconvert(uint32_t w, int (&u)[4])
@@ -37,37 +26,6 @@ __device__ __forceinline__ void upconvert(uint32_t w, int (&u)[4])
     u[1] = (int)((w << 4) & 0xC0C0C0C0u);
     u[2] = (int)((w << 2) & 0xC0C0C0C0u);
     u[3] = (int)(w & 0xC0C0C0C0u);
-}
-
-// One streamed tile: 16 B of codes and the tile's group scales for this lane.
-struct TileRegs {
-    uint4 w;
-    uint32_t s0, s1;   // bf16 scales: G=128 -> s0 = {g0,g1}; G=64 -> s0 = {g0,g1}, s1 = {g2,g3}
-};
-
-template <int G>
-__device__ __forceinline__ TileRegs load_tile(const uint32_t* __restrict__ codes,
-                                              const uint16_t* __restrict__ scales, int64_t tile,
-                                              int lane)
-{
-    TileRegs r;
-    r.w = *reinterpret_cast<const uint4*>(codes + (tile * 64 + lane) * 4);
-    if constexpr (G == 128) {
-        r.s0 = *reinterpret_cast<const uint32_t*>(scales + (tile * TILE_N + (lane & 15)) * 2);
-        r.s1 = 0;
-    } else {
-        const uint2 s = *reinterpret_cast<const uint2*>(scales + (tile * TILE_N + (lane & 15)) * 4);
-        r.s0 = s.x; r.s1 = s.y;
-    }
-    return r;
-}
-
-template <int G>
-__device__ __forceinline__ float tile_scale(const TileRegs& r, int gi)
-{
-    // gi = group index inside the tile
-    const uint32_t pair = (G == 128 || gi < 2) ? r.s0 : r.s1;
-    return (gi & 1) ? __uint_as_float(pair & 0xffff0000u) : __uint_as_float(pair << 16);
 }
 
 // Staging of the activation rows [0,rows) x k in [k0, k0+len) into LDS rows of
@@ -125,34 +83,6 @@ __device__ __forceinline__ void stage_store(const int8_t* __restrict__ xq, int64
             *reinterpret_cast<const uint4*>(xq + (int64_t)r * K + k0 + v * 16);
     }
 }
-
-struct SmallCfg {
-    int cbw;        // column blocks per workgroup
-    int ks;         // k-splits inside the workgroup (waves = cbw * ks)
-    int kc;         // k per LDS chunk (multiple of 256)
-};
-
-// The per-wave schedule shared by both kernel families.  A wave owns column
-// block cb and the k tiles ks, ks+KS, ...  Inside one LDS chunk it first issues
-// the loads of ALL its tiles (up to TMAX, 1 KiB each per wave) and only then
-// consumes them, so a wave has its whole share of the weight stream in flight
-// after one round trip: the kernels live for a few microseconds, about as long
-// as a handful of dependent HBM round trips.
-#define W2_SMALL_PROLOGUE()                                                                   \
-    extern __shared__ __align__(16) int8_t smem[];                                            \
-    const int lane = threadIdx.x & 63;                                                        \
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);                        \
-    const int cbi = wave % cfg.cbw;                                                           \
-    const int ks = wave / cfg.cbw;                                                            \
-    const int64_t cb = (int64_t)blockIdx.x * cfg.cbw + cbi;                                   \
-    const bool cb_ok = cb < a.n_cb;                                                           \
-    const int64_t cbc = cb_ok ? cb : a.n_cb - 1; /* clamp: keeps loads in bounds */           \
-    const int q = lane >> 4;                                                                  \
-    const int64_t n = cb * TILE_N + (lane & 15);                                              \
-    constexpr int GPT = TILE_K / G;                                                           \
-    const int tiles_per_chunk = cfg.kc / TILE_K;                                              \
-    const int n_chunks = (int)((a.n_kt + tiles_per_chunk - 1) / tiles_per_chunk);             \
-    (void)n; (void)q; (void)GPT
 
 // ---------------------------------------------------------------- DOT4
 template <int MT, int G, int TMAX, bool DBG>
@@ -364,70 +294,6 @@ a8_smallm_kernel(A8Args a, SmallCfg cfg)
 
 // ---------------------------------------------------------------- host side
 
-constexpr int TMAX = 8;                      // most tiles a wave keeps in flight
-constexpr int64_t LDS_BUDGET = 128 * 1024;   // activation chunk + reduction scratch
-
-// Picks (column blocks per workgroup, k-splits): enough workgroups to fill 256
-// CUs a few times over, and a k-split that leaves each wave at most TMAX tiles
-// when the wave budget allows it.
-static SmallCfg pick_cfg(const A8Args& a, int rows)
-{
-    SmallCfg c;
-    int waves = env_int("W2_SMALL_WAVES", 8);
-    if (waves > 16) waves = 16;
-    if (waves < 1) waves = 1;
-    int cbw = env_int("W2_SMALL_CBW", 0);
-    if (cbw <= 0) {
-        cbw = waves;
-        // split K until a wave has at most TMAX tiles, while there are waves to split over
-        while (cbw > 1 && a.n_kt * cbw > (int64_t)TMAX * waves) cbw >>= 1;
-        // and keep at least ~2 workgroups per CU
-        while (cbw > 1 && (a.n_cb + cbw - 1) / cbw < 512) cbw >>= 1;
-    }
-    if (cbw > waves) cbw = waves;
-    c.cbw = cbw;
-    c.ks = waves / cbw;
-    if (c.ks > a.n_kt) c.ks = (int)a.n_kt;
-    if (c.ks < 1) c.ks = 1;
-    int64_t kc = a.n_kt * TILE_K;
-    while (kc > TILE_K && (int64_t)rows * (kc + XS_PAD) > LDS_BUDGET) kc -= TILE_K;
-    const int force = env_int("W2_SMALL_KC", 0);
-    if (force >= TILE_K && force % TILE_K == 0 && force < kc) kc = force;
-    c.kc = (int)kc;
-    return c;
-}
-
-static size_t small_lds_bytes(const SmallCfg& c, int rows, int red_rows)
-{
-    size_t act = (size_t)rows * (c.kc + XS_PAD);
-    size_t red = (size_t)c.cbw * c.ks * red_rows * 16 * sizeof(float);
-    return act > red ? act : red;
-}
-
-// Most tiles any wave owns inside one LDS chunk.
-static int tiles_per_wave(const A8Args& a, const SmallCfg& c)
-{
-    int64_t chunk_tiles = c.kc / TILE_K;
-    if (chunk_tiles > a.n_kt) chunk_tiles = a.n_kt;
-    return (int)((chunk_tiles + c.ks - 1) / c.ks);
-}
-
-template <typename Kern>
-static int launch_small(Kern kern, const char* what, const A8Args& a, const SmallCfg& c, size_t lds,
-                        hipStream_t stream)
-{
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) {
-            set_error("%s: hipFuncSetAttribute(%zu): %s", what, lds, hipGetErrorString(e));
-            return -5;
-        }
-    }
-    const dim3 grid((unsigned)((a.n_cb + c.cbw - 1) / c.cbw)), block(64 * c.cbw * c.ks);
-    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, c);
-    return check_launch(what);
-}
-
 bool a8_dot4_supports(const A8Args& a) { return a.M >= 1 && a.M <= 4; }
 bool a8_smallm_supports(const A8Args& a) { return a.M >= 1 && a.M <= 16; }
 
@@ -435,11 +301,11 @@ template <int MT, int G>
 static int launch_dot4_t(const A8Args& a, hipStream_t stream)
 {
     const int rows = MT < (int)a.M ? MT : (int)a.M;
-    const SmallCfg c = pick_cfg(a, rows);
-    const size_t lds = small_lds_bytes(c, rows, MT);
+    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 1);
+    const size_t lds = small_lds_bytes(c, rows, MT, 1, 0);
     if (a.acc_out) return launch_small(a8_dot4_kernel<MT, G, TMAX, true>, "w2_matmul_a8[dot4]", a, c, lds, stream);
     // in-flight depth = tiles per wave, so that no load slot re-reads a tile
-    const int tpw = tiles_per_wave(a, c);
+    const int tpw = tiles_per_wave(a.n_kt, c);
     if (tpw <= 2) return launch_small(a8_dot4_kernel<MT, G, 2, false>, "w2_matmul_a8[dot4]", a, c, lds, stream);
     if (tpw <= 4) return launch_small(a8_dot4_kernel<MT, G, 4, false>, "w2_matmul_a8[dot4]", a, c, lds, stream);
     return launch_small(a8_dot4_kernel<MT, G, TMAX, false>, "w2_matmul_a8[dot4]", a, c, lds, stream);
@@ -462,10 +328,10 @@ template <int G>
 static int launch_smallm_t(const A8Args& a, hipStream_t stream)
 {
     const int rows = (int)a.M;
-    const SmallCfg c = pick_cfg(a, rows);
-    const size_t lds = small_lds_bytes(c, rows, 16);
+    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 1);
+    const size_t lds = small_lds_bytes(c, rows, 16, 1, 0);
     if (a.acc_out) return launch_small(a8_smallm_kernel<G, TMAX, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
-    const int tpw = tiles_per_wave(a, c);
+    const int tpw = tiles_per_wave(a.n_kt, c);
     if (tpw <= 2) return launch_small(a8_smallm_kernel<G, 2, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
     if (tpw <= 4) return launch_small(a8_smallm_kernel<G, 4, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
     return launch_small(a8_smallm_kernel<G, TMAX, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);

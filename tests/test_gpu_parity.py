@@ -209,6 +209,54 @@ def test_a8_closed_forms(w2):
         assert np.array_equal(bits_to_f64(bf16_bits(Y))[0], colsum.astype(np.float64))
 
 
+# ------------------------------------------------------------------ w2a16
+def run_a16_case(w2, M, K, N, G, codec, variant, seed):
+    codes, scales, X = synth.make_problem(M, K, N, G, codec, seed)
+    Xb = synth.f32_to_bf16_bits(X)
+    packed = w2.prepack(dev(codes), dev(scales), G, codec)
+    Xd = dev(Xb).view(torch.bfloat16)
+    Y = w2.matmul_a16(packed, K, N, G, Xd, variant=variant)
+    Y2 = w2.matmul_a16(packed, K, N, G, Xd, variant=variant)
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "not deterministic"
+    Yo, y64, mag = oracle.matmul_a16(codes, scales, G, codec, Xb)
+    check_y(bf16_bits(Y), Yo, y64, mag, f"a16 M={M} K={K} N={N} G={G} codec={codec} variant={variant}")
+
+
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", SMALL_SHAPES)
+@pytest.mark.parametrize("M", [1, 4, 7, 16])
+def test_a16_smallm(w2, M, K, N, G):
+    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SMALLM, seed=M + K + N + G)
+
+
+def test_a16_lds_chunking_and_outliers(w2):
+    run_a16_case(w2, 16, 14336, 64, 128, 0, w2.VARIANT_SMALLM, seed=5)
+    # activation outliers: the 130*X_g cancellation must stay inside the tolerance
+    M, K, N, G = 4, 2048, 64, 128
+    codes, scales, X = synth.make_problem(M, K, N, G, 0, 21)
+    X[:, ::97] *= np.float32(60.0)
+    X[2] += np.float32(3.0)                                  # a row with a large mean
+    Xb = synth.f32_to_bf16_bits(X)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    Y = w2.matmul_a16(packed, K, N, G, dev(Xb).view(torch.bfloat16))
+    Yo, y64, mag = oracle.matmul_a16(codes, scales, G, 0, Xb)
+    check_y(bf16_bits(Y), Yo, y64, mag, "a16 outliers")
+
+
+def test_a16_exact_small_integers(w2):
+    # unit scales and small-integer activations: every product and sum is exact
+    K, N, G = 512, 48, 128
+    codes, _, _ = synth.make_problem(1, K, N, G, 1, 2)
+    ones = np.full((K // G, N), 0x3F80, np.uint16)
+    packed = w2.prepack(dev(codes), dev(ones), G, 1)
+    rng = np.random.default_rng(0)
+    Xi = rng.integers(-2, 3, size=(3, K)).astype(np.float32)
+    Y = w2.matmul_a16(packed, K, N, G, dev(synth.f32_to_bf16_bits(Xi)).view(torch.bfloat16))
+    ref = Xi.astype(np.int64) @ (codes.astype(np.int64) - 1)
+    assert np.abs(ref).max() < 256
+    assert np.array_equal(bits_to_f64(bf16_bits(Y)), ref.astype(np.float64))
+
+
 # ------------------------------------------------------------------ argument errors
 def test_argument_errors_write_nothing(w2):
     import ctypes
