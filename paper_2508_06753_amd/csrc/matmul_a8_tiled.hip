@@ -1,17 +1,27 @@
 // w2a8 for large M (prefill): the compute-bound regime (Sec. III-C, GEMM
 // results) on the int8 matrix cores.  The workgroup / wave tile hierarchy
 // plays the role of the wg_tile / sg_tile split of Sec. II-D, re-derived for
-// CDNA4: a 128(M) x 256(N) workgroup tile, eight waves of 64 x 64, each wave
-// 4 x 4 tiles of v_mfma_i32_16x16x64_i8.
-//   - activations (int8) are staged through LDS, double-buffered, 256 k per
+// CDNA4: a 128(M) x 256(N) workgroup tile, eight waves of 64 x 64 (two per
+// SIMD), each wave 4 x 4 tiles of v_mfma_i32_16x16x64_i8.
+//   - activations (int8) are staged through LDS, double-buffered, 128 k per
 //     stage, rows padded by 16 B so ds_read_b128 is conflict-free;
 //   - the 2-bit weights never touch LDS: the packed layout IS the MFMA
-//     B-operand layout, so each lane loads its dwords straight from global
-//     memory and up-converts them in registers (Sec. II-C "up-convert and
-//     compute"), reused across the wave's four row tiles;
-//   - the dequant (Sec. II-D: int32 -> float, x scale) is applied per group of
-//     G k's in registers: y += sw * float(acc); the activation scale and the
-//     exact 1/64 of the up-convert are applied once in the epilogue.
+//     B-operand layout, so each lane loads its dwords (64 bits per column
+//     block and stage) straight from global memory and up-converts them in
+//     registers (Sec. II-C "up-convert and compute"), reused across the wave's
+//     four row tiles;
+//   - the dequant (Sec. II-D: int32 -> float, x scale) runs once per group of G
+//     k's on the 64 accumulators of a wave and would cost as many VALU slots as
+//     the matrix instructions leave free.  It is done in ONE fma per
+//     accumulator: every group starts from the constant BIAS = 2^21 (a third
+//     MFMA operand, never written), so the int32 result acc = BIAS + 64*sum is
+//     positive and below 2^23, i.e. its bit pattern read as binary32 is the
+//     denormal acc * 2^-149; y += as_float(acc) * (sw * 2^64) needs no int->float
+//     conversion.  The bias term, BIAS * 2^-149 * sum_g sw_g * 2^64, is
+//     subtracted once in the epilogue; it exceeds the wanted sum by about 2^6
+//     per group (2^10 over a long K), which leaves 14+ of fp32's 24 bits for a
+//     bf16 result.  The int32 group accumulators themselves stay exact
+//     (acc - BIAS is what the debug export stores).
 #include <hip/hip_runtime.h>
 
 #include "w2_internal.h"
@@ -22,11 +32,12 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 namespace tiled {
 
-constexpr int BM = 128, BN = 256, BK = TILE_K;
+constexpr int BM = 128, BN = 256, BK = 128;       // BK: k per pipeline stage (half a packed tile)
 constexpr int THREADS = 512;
 constexpr int A_STRIDE = BK + 16;                 // bytes per LDS row
 constexpr int A_BUF = BM * A_STRIDE;              // bytes per stage
 constexpr int WM = 64, WN = 64;                   // wave tile
+constexpr int BIAS = 1 << 21;                     // > 64 * 127 * 2 * 128 = 2 080 768
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
@@ -45,34 +56,26 @@ __device__ __forceinline__ v4i upconvert(uint32_t w)
     return u;
 }
 
-struct WRegs {
-    uint4 w[4];         // four column blocks of this wave, one k tile
-    uint32_t s[4][2];   // their group scales (bf16 pairs)
+// Weights and scales of one stage (128 k) for the wave's four column blocks.
+struct WStage {
+    uint2 w[4];       // two dwords = two 64-k steps
+    uint32_t s[4];    // G=128: one bf16 scale (low half); G=64: two bf16 scales
 };
 
 template <int G>
-__device__ __forceinline__ void load_w(const A8Args& a, const int64_t (&cb)[4], int64_t kt, int lane,
-                                       WRegs& r)
+__device__ __forceinline__ void load_w(const uint32_t* const (&wp)[4], const uint16_t* const (&sp)[4],
+                                       int64_t it, WStage& r)
 {
+    const int64_t kt = it >> 1;
+    const int h = (int)(it & 1);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int64_t tile = cb[j] * a.n_kt + kt;
-        r.w[j] = *reinterpret_cast<const uint4*>(a.codes + (tile * 64 + lane) * 4);
-        if constexpr (G == 128) {
-            r.s[j][0] = *reinterpret_cast<const uint32_t*>(a.scales + (tile * TILE_N + (lane & 15)) * 2);
-            r.s[j][1] = 0;
-        } else {
-            const uint2 s = *reinterpret_cast<const uint2*>(a.scales + (tile * TILE_N + (lane & 15)) * 4);
-            r.s[j][0] = s.x; r.s[j][1] = s.y;
-        }
+        r.w[j] = *reinterpret_cast<const uint2*>(wp[j] + kt * 256 + h * 2);
+        if constexpr (G == 128)
+            r.s[j] = sp[j][kt * (TILE_N * 2) + h];
+        else
+            r.s[j] = *reinterpret_cast<const uint32_t*>(sp[j] + kt * (TILE_N * 4) + h * 2);
     }
-}
-
-template <int G>
-__device__ __forceinline__ float w_scale(const WRegs& r, int j, int gi)
-{
-    const uint32_t pair = (G == 128 || gi < 2) ? r.s[j][0] : r.s[j][1];
-    return (gi & 1) ? __uint_as_float(pair & 0xffff0000u) : __uint_as_float(pair << 16);
 }
 
 template <int G, bool DBG>
@@ -93,132 +96,139 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     // columns through that XCD's L2.
     const int64_t total = (int64_t)tiles_m * tiles_n;
     int64_t id = blockIdx.x;
-    {
-        const int64_t per_xcd = (total + 7) / 8;
-        const int64_t x = id & 7, i = id >> 3;
-        const int64_t rid = x * per_xcd + i;
-        // chunks are equal-sized only if total % 8 == 0; otherwise keep ids as they are
-        if (total % 8 == 0) id = rid;
-    }
+    if (total % 8 == 0) id = (id & 7) * (total >> 3) + (id >> 3);
     const int64_t band = id / ((int64_t)group_m * tiles_n);
     const int64_t first_m = band * group_m;
     const int gm = (int)min((int64_t)group_m, tiles_m - first_m);
     const int64_t in_band = id - band * group_m * tiles_n;
     const int64_t tile_m = first_m + in_band % gm;
     const int64_t tile_n = in_band / gm;
-
     const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
-    int64_t cb[4];
+
+    // per column block: base pointers of this lane's dwords and scales
+    const uint32_t* wp[4];
+    const uint16_t* sp[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int64_t c = tile_n * (BN / TILE_N) + wn * 4 + j;
-        cb[j] = c < a.n_cb ? c : a.n_cb - 1;                 // clamp: loads stay in bounds
+        int64_t c = tile_n * (BN / TILE_N) + wn * 4 + j;
+        c = c < a.n_cb ? c : a.n_cb - 1;                     // clamp: loads stay in bounds
+        wp[j] = a.codes + (c * a.n_kt * 64 + lane) * 4;
+        sp[j] = a.scales + (c * a.n_kt * TILE_N + l16) * (TILE_K / G);
     }
 
-    // global -> LDS copy assignment: 16 threads per 256-byte row, 32 rows per pass
-    const int cp_v = tid & 15, cp_r = tid >> 4;
-    const int8_t* cp_src[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        int64_t m = m0 + cp_r + 32 * p;
-        if (m >= a.M) m = a.M - 1;                           // padded rows repeat the last row
-        cp_src[p] = a.xq + m * a.K + cp_v * 16;
-    }
-    const int cp_dst = cp_r * A_STRIDE + cp_v * 16;
+    // global -> LDS copy: 4 threads per 128-byte row piece, 32 bytes each
+    const int cp_row = tid >> 2, cp_seg = tid & 3;
+    int64_t cp_m = m0 + cp_row;
+    if (cp_m >= a.M) cp_m = a.M - 1;                         // padded rows repeat the last row
+    const int8_t* cp_src = a.xq + cp_m * a.K + cp_seg * 32;
+    const int cp_dst = cp_row * A_STRIDE + cp_seg * 32;
 
     v4i acc[4][4];
     float y[4][4][4];
+    float ssum[4] = {0.f, 0.f, 0.f, 0.f};                    // sum of the scaled group scales per column block
+    const v4i biasv = {BIAS, BIAS, BIAS, BIAS};
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            acc[i][j] = (v4i){0, 0, 0, 0};
+            acc[i][j] = biasv;
 #pragma unroll
             for (int r = 0; r < 4; ++r) y[i][j][r] = 0.0f;
         }
 
-    // prologue: stage 0
-    uint4 areg[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) areg[p] = *reinterpret_cast<const uint4*>(cp_src[p]);
-    WRegs wcur;
-    load_w<G>(a, cb, 0, lane, wcur);
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-        *reinterpret_cast<uint4*>(smem + cp_dst + 32 * p * A_STRIDE) = areg[p];
+    const int64_t n_it = a.n_kt * 2;
+    uint4 ar0 = *reinterpret_cast<const uint4*>(cp_src);
+    uint4 ar1 = *reinterpret_cast<const uint4*>(cp_src + 16);
+    WStage wc, wn_;
+    load_w<G>(wp, sp, 0, wc);
+    *reinterpret_cast<uint4*>(smem + cp_dst) = ar0;
+    *reinterpret_cast<uint4*>(smem + cp_dst + 16) = ar1;
     __syncthreads();
 
     const int8_t* a_base = smem + (wm * WM + l16) * A_STRIDE + q * 16;
-    constexpr int GPT = TILE_K / G;
 
-    for (int64_t kt = 0; kt < a.n_kt; ++kt) {
-        const int buf = (int)(kt & 1);
-        const bool more = kt + 1 < a.n_kt;
-        if (more) {
+    // y += as_float(acc) * (sw * 2^64) for one column block, then restart the group
+    auto dequant_col = [&](int j, float swS, int64_t g) {
 #pragma unroll
-            for (int p = 0; p < 4; ++p)
-                areg[p] = *reinterpret_cast<const uint4*>(cp_src[p] + (kt + 1) * BK);
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if constexpr (DBG) {
+                    const int64_t m = m0 + wm * WM + i * 16 + 4 * q + r;
+                    const int64_t n = n0 + wn * WN + j * 16 + l16;
+                    if (m < a.M && n < a.N)
+                        a.acc_out[(m * (a.K / G) + g) * a.N + n] = (acc[i][j][r] - BIAS) >> 6;
+                }
+                y[i][j][r] = fmaf(__int_as_float(acc[i][j][r]), swS, y[i][j][r]);
+            }
+        }
+    };
+
+    for (int64_t it = 0; it < n_it; ++it) {
+        const int buf = (int)(it & 1);
+        const bool more = it + 1 < n_it;
+        if (more) {
+            ar0 = *reinterpret_cast<const uint4*>(cp_src + (it + 1) * BK);
+            ar1 = *reinterpret_cast<const uint4*>(cp_src + (it + 1) * BK + 16);
+            load_w<G>(wp, sp, it + 1, wn_);
         }
         const int8_t* ab = a_base + buf * A_BUF;
+        float swS[4][2];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (G == 128) {
+                swS[j][0] = __uint_as_float(wc.s[j] << 16) * 0x1p64f;
+                swS[j][1] = 0.f;
+                ssum[j] += swS[j][0];
+            } else {
+                swS[j][0] = __uint_as_float(wc.s[j] << 16) * 0x1p64f;
+                swS[j][1] = __uint_as_float(wc.s[j] & 0xffff0000u) * 0x1p64f;
+                ssum[j] += swS[j][0];
+                ssum[j] += swS[j][1];
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
             v4i aop[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 aop[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE + t * 64);
+            const bool first = (G == 64) || t == 0;          // first k-step of a group starts from BIAS
+            const bool last = (G == 64) || t == 1;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint32_t wd = t == 0 ? wcur.w[j].x : t == 1 ? wcur.w[j].y
-                                  : t == 2 ? wcur.w[j].z : wcur.w[j].w;
-                const v4i bop = upconvert(wd);
+                const v4i bop = upconvert(t == 0 ? wc.w[j].x : wc.w[j].y);
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[i], bop, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[i], bop, first ? biasv : acc[i][j], 0, 0, 0);
+                // the previous column's results are ready by now: dequantise them under these MFMAs
+                if (last && j > 0) dequant_col(j - 1, swS[j - 1][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
             }
-            if (G == 64 || (t & 1)) {
-                const int gi = G == 64 ? t : t >> 1;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float sw = w_scale<G>(wcur, j, gi);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            if constexpr (DBG) {
-                                const int64_t m = m0 + wm * WM + i * 16 + 4 * q + r;
-                                const int64_t n = n0 + wn * WN + j * 16 + l16;
-                                if (m < a.M && n < a.N)
-                                    a.acc_out[(m * (a.K / G) + kt * GPT + gi) * a.N + n] = acc[i][j][r] >> 6;
-                            }
-                            y[i][j][r] = fmaf(sw, (float)acc[i][j][r], y[i][j][r]);
-                        }
-                        acc[i][j] = (v4i){0, 0, 0, 0};
-                    }
-                }
-            }
+            if (last) dequant_col(3, swS[3][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
         }
         if (more) {
             int8_t* dst = smem + (buf ^ 1) * A_BUF + cp_dst;
-#pragma unroll
-            for (int p = 0; p < 4; ++p)
-                *reinterpret_cast<uint4*>(dst + 32 * p * A_STRIDE) = areg[p];
-            load_w<G>(a, cb, kt + 1, lane, wcur);
+            *reinterpret_cast<uint4*>(dst) = ar0;
+            *reinterpret_cast<uint4*>(dst + 16) = ar1;
+            wc = wn_;
         }
         __syncthreads();
     }
     if constexpr (DBG) return;
 
+    // y_true = (y - BIAS*2^-149 * ssum) * 2^(149-64) * 2^-6 * sx   (2^-128 = BIAS * 2^-149)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int64_t m = m0 + wm * WM + i * 16 + 4 * q + r;
             if (m >= a.M) continue;
-            const float s = a.sx[m] * 0.015625f;
+            const float s = a.sx[m];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int64_t n = n0 + wn * WN + j * 16 + l16;
-                if (n < a.N) a.Y[m * a.ldy + n] = f32_to_bf16_rne(y[i][j][r] * s);
+                const float v = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f;
+                if (n < a.N) a.Y[m * a.ldy + n] = f32_to_bf16_rne(v * s);
             }
         }
     }
@@ -226,7 +236,8 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 
 }  // namespace tiled
 
-int launch_a8_tiled(const A8Args& a, hipStream_t stream)
+template <typename Kern>
+static int launch_tiled(Kern kern, const A8Args& a, hipStream_t stream)
 {
     using namespace tiled;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
@@ -235,29 +246,18 @@ int launch_a8_tiled(const A8Args& a, hipStream_t stream)
     int group_m = env_int("W2_TILED_GROUP_M", 4);
     if (group_m < 1) group_m = 1;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(THREADS);
-    hipError_t e = hipSuccess;
-    if (a.G == 128) {
-        if (a.acc_out) {
-            e = hipFuncSetAttribute((const void*)a8_tiled_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e == hipSuccess) hipLaunchKernelGGL((a8_tiled_kernel<128, true>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
-        } else {
-            e = hipFuncSetAttribute((const void*)a8_tiled_kernel<128, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e == hipSuccess) hipLaunchKernelGGL((a8_tiled_kernel<128, false>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
-        }
-    } else {
-        if (a.acc_out) {
-            e = hipFuncSetAttribute((const void*)a8_tiled_kernel<64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e == hipSuccess) hipLaunchKernelGGL((a8_tiled_kernel<64, true>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
-        } else {
-            e = hipFuncSetAttribute((const void*)a8_tiled_kernel<64, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e == hipSuccess) hipLaunchKernelGGL((a8_tiled_kernel<64, false>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
-        }
-    }
-    if (e != hipSuccess) {
-        set_error("w2_matmul_a8[tiled]: hipFuncSetAttribute: %s", hipGetErrorString(e));
-        return -5;
-    }
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
     return check_launch("w2_matmul_a8[tiled]");
+}
+
+int launch_a8_tiled(const A8Args& a, hipStream_t stream)
+{
+    using namespace tiled;
+    if (a.G == 128)
+        return a.acc_out ? launch_tiled(a8_tiled_kernel<128, true>, a, stream)
+                         : launch_tiled(a8_tiled_kernel<128, false>, a, stream);
+    return a.acc_out ? launch_tiled(a8_tiled_kernel<64, true>, a, stream)
+                     : launch_tiled(a8_tiled_kernel<64, false>, a, stream);
 }
 
 }  // namespace w2
