@@ -223,10 +223,206 @@ int launch_a16_smallm(const A16Args& a, hipStream_t stream)
     return a.G == 128 ? launch_a16_smallm_t<128>(a, stream) : launch_a16_smallm_t<64>(a, stream);
 }
 
-int launch_a16_tiled(const A16Args&, hipStream_t)
+// ---------------------------------------------------------------- TILED (bf16 MFMA, any M)
+// Same workgroup / wave geometry as the w2a8 tiled kernel: 128(M) x 256(N) per
+// workgroup, eight waves of 64 x 64, 4 x 4 tiles of v_mfma_f32_16x16x32_bf16.
+// A stage is 64 k: one packed dword per column block and lane (two matrix
+// instructions per tile: even k, odd k), and 128 rows x 128 B of activations in
+// LDS, stored de-interleaved by the copy threads, which also leave the
+// per-row sums of the stage in a ring of four slots for the zero-point term.
+namespace tiled16 {
+
+constexpr int BM = 128, BN = 256, BK = 64;
+constexpr int THREADS = 512;
+constexpr int A_STRIDE = BK * 2 + 16;             // bytes per LDS row
+constexpr int A_BUF = BM * A_STRIDE;
+constexpr int XS_OFF = 2 * A_BUF;                 // float xpart[4][BM]
+constexpr int LDS_BYTES = XS_OFF + 4 * BM * 4;
+constexpr int WM = 64, WN = 64;
+
+template <int G>
+__global__ void __launch_bounds__(THREADS)
+a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
 {
-    set_error("w2_matmul_a16: the tiled kernel is not built yet (M > 16)");
-    return -2;
+    extern __shared__ __align__(16) int8_t smem[];
+    float* xpart = reinterpret_cast<float*>(smem + XS_OFF);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int q = lane >> 4, l16 = lane & 15;
+
+    const int64_t total = (int64_t)tiles_m * tiles_n;
+    int64_t id = blockIdx.x;
+    if (total % 8 == 0) id = (id & 7) * (total >> 3) + (id >> 3);       // one contiguous chunk per XCD
+    const int64_t band = id / ((int64_t)group_m * tiles_n);
+    const int64_t first_m = band * group_m;
+    const int gm = (int)min((int64_t)group_m, tiles_m - first_m);
+    const int64_t in_band = id - band * group_m * tiles_n;
+    const int64_t tile_m = first_m + in_band % gm;
+    const int64_t tile_n = in_band / gm;
+    const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const uint32_t* wp[4];
+    const uint16_t* sp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int64_t c = tile_n * (BN / TILE_N) + wn * 4 + j;
+        c = c < a.n_cb ? c : a.n_cb - 1;                     // clamp: loads stay in bounds
+        wp[j] = a.codes + (c * a.n_kt * 64 + lane) * 4;
+        sp[j] = a.scales + (c * a.n_kt * TILE_N + l16) * (TILE_K / G);
+    }
+
+    // copy: 4 threads per row, one 16-k block (32 B) each
+    const int cp_row = tid >> 2, cp_seg = tid & 3;
+    int64_t cp_m = m0 + cp_row;
+    if (cp_m >= a.M) cp_m = a.M - 1;                         // padded rows repeat the last row
+    const uint16_t* cp_src = a.X + cp_m * a.ldx + cp_seg * 16;
+    const int cp_dst = cp_row * A_STRIDE + cp_seg * 32;
+
+    v4f acc[4][4];
+    float y[4][4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) y[i][j][r] = 0.0f;
+        }
+
+    // stores one 16-k block de-interleaved and the row's partial sum of this stage
+    auto stage_store = [&](const uint4& lo, const uint4& hi, int buf, int slot) __attribute__((always_inline)) {
+        const uint32_t d[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        float s = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += pair_sum(d[e]);
+        s += __shfl_xor(s, 1);
+        s += __shfl_xor(s, 2);
+        uint4 ev, od;
+        ev.x = __builtin_amdgcn_perm(d[1], d[0], 0x05040100u);
+        ev.y = __builtin_amdgcn_perm(d[3], d[2], 0x05040100u);
+        ev.z = __builtin_amdgcn_perm(d[5], d[4], 0x05040100u);
+        ev.w = __builtin_amdgcn_perm(d[7], d[6], 0x05040100u);
+        od.x = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
+        od.y = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
+        od.z = __builtin_amdgcn_perm(d[5], d[4], 0x07060302u);
+        od.w = __builtin_amdgcn_perm(d[7], d[6], 0x07060302u);
+        uint4* dst = reinterpret_cast<uint4*>(smem + buf * A_BUF + cp_dst);
+        dst[0] = ev;
+        dst[1] = od;
+        if (cp_seg == 0) xpart[slot * BM + cp_row] = s;
+    };
+    auto load_w = [&](int64_t st, uint32_t (&w)[4], uint32_t (&sc)[4]) __attribute__((always_inline)) {
+        const int64_t kt = st >> 2;
+        const int t = (int)(st & 3);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            w[j] = wp[j][kt * 256 + t];
+            if constexpr (G == 128)
+                sc[j] = sp[j][kt * (TILE_N * 2) + (t >> 1)];
+            else
+                sc[j] = sp[j][kt * (TILE_N * 4) + t];
+        }
+    };
+
+    const int64_t n_st = a.n_kt * 4;                         // stages of 64 k
+    uint4 ar0 = *reinterpret_cast<const uint4*>(cp_src);
+    uint4 ar1 = *reinterpret_cast<const uint4*>(cp_src + 8);
+    uint32_t wc[4], sc[4], wnx[4], snx[4];
+    load_w(0, wc, sc);
+    stage_store(ar0, ar1, 0, 0);
+    __syncthreads();
+
+    const int8_t* a_base = smem + (wm * WM + l16) * A_STRIDE + q * 32;
+
+    for (int64_t st = 0; st < n_st; ++st) {
+        const int buf = (int)(st & 1);
+        const bool more = st + 1 < n_st;
+        if (more) {
+            ar0 = *reinterpret_cast<const uint4*>(cp_src + (st + 1) * BK);
+            ar1 = *reinterpret_cast<const uint4*>(cp_src + (st + 1) * BK + 8);
+            load_w(st + 1, wnx, snx);
+        }
+        const int8_t* ab = a_base + buf * A_BUF;
+        v4i a0[4], a1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a0[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE);
+            a1[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE + 16);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            v4i b0, b1;
+            upconvert_bf16(wc[j], b0, b1);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[i][j] = mfma_bf16(a0[i], b0, acc[i][j]);
+                acc[i][j] = mfma_bf16(a1[i], b1, acc[i][j]);
+            }
+        }
+        const bool group_end = (G == 64) || (st & 1);
+        if (group_end) {
+            // X_g[m] for this lane's rows: the stage partials of the group (ring slots)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = wm * WM + i * 16 + 4 * q;
+                v4f xg = *reinterpret_cast<const v4f*>(xpart + (int)(st & 3) * BM + row);
+                if constexpr (G == 128) {
+                    const v4f xp = *reinterpret_cast<const v4f*>(xpart + (int)((st - 1) & 3) * BM + row);
+                    xg += xp;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float sw = __uint_as_float(sc[j] << 16);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        y[i][j][r] = fmaf(sw, fmaf(-ZP, xg[r], acc[i][j][r]), y[i][j][r]);
+                    acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        }
+        if (more) {
+            stage_store(ar0, ar1, buf ^ 1, (int)((st + 1) & 3));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { wc[j] = wnx[j]; sc[j] = snx[j]; }
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t m = m0 + wm * WM + i * 16 + 4 * q + r;
+            if (m >= a.M) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t n = n0 + wn * WN + j * 16 + l16;
+                if (n < a.N) a.Y[m * a.ldy + n] = f32_to_bf16_rne(y[i][j][r]);
+            }
+        }
+    }
+}
+
+}  // namespace tiled16
+
+template <int G>
+static int launch_a16_tiled_t(const A16Args& a, hipStream_t stream)
+{
+    using namespace tiled16;
+    const int tiles_m = (int)((a.M + BM - 1) / BM);
+    const int tiles_n = (int)((a.N + BN - 1) / BN);
+    int group_m = env_int("W2_TILED_GROUP_M", 4);
+    if (group_m < 1) group_m = 1;
+    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(THREADS);
+    hipLaunchKernelGGL(a16_tiled_kernel<G>, grid, block, LDS_BYTES, stream, a, tiles_m, tiles_n, group_m);
+    return check_launch("w2_matmul_a16[tiled]");
+}
+
+int launch_a16_tiled(const A16Args& a, hipStream_t stream)
+{
+    return a.G == 128 ? launch_a16_tiled_t<128>(a, stream) : launch_a16_tiled_t<64>(a, stream);
 }
 
 }  // namespace w2

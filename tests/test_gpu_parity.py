@@ -229,6 +229,18 @@ def test_a16_smallm(w2, M, K, N, G):
     run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SMALLM, seed=M + K + N + G)
 
 
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (512, 1032)])
+@pytest.mark.parametrize("M", [1, 17, 127, 128, 200])
+def test_a16_tiled(w2, M, K, N, G):
+    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G)
+
+
+@pytest.mark.parametrize("M", [1, 16, 17, 130])
+def test_a16_auto_dispatch(w2, M):
+    run_a16_case(w2, M, 1024, 528, 128, 0, w2.VARIANT_AUTO, seed=M)
+
+
 def test_a16_lds_chunking_and_outliers(w2):
     run_a16_case(w2, 16, 14336, 64, 128, 0, w2.VARIANT_SMALLM, seed=5)
     # activation outliers: the 130*X_g cancellation must stay inside the tolerance
