@@ -18,9 +18,9 @@
 //     positive and below 2^23, i.e. its bit pattern read as binary32 is the
 //     denormal acc * 2^-149; y += as_float(acc) * (sw * 2^64) needs no int->float
 //     conversion.  The bias term, BIAS * 2^-149 * sum_g sw_g * 2^64, is
-//     subtracted once in the epilogue; it exceeds the wanted sum by about 2^6
-//     per group (2^10 over a long K), which leaves 14+ of fp32's 24 bits for a
-//     bf16 result.  The int32 group accumulators themselves stay exact
+//     subtracted every 8 stages and in the epilogue; while it rides along it
+//     exceeds the wanted sum by about 2^9, which leaves 15 of fp32's 24 bits
+//     for a bf16 result.  The int32 group accumulators themselves stay exact
 //     (acc - BIAS is what the debug export stores).
 #include <hip/hip_runtime.h>
 
@@ -205,6 +205,20 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
                 if (last && j > 0) dequant_col(j - 1, swS[j - 1][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
             }
             if (last) dequant_col(3, swS[3][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
+        }
+        if ((it & 7) == 7) {
+            // take the accumulated bias term out every 8 stages, so that the running sums
+            // never carry more than 8 stages of it (keeps the rounding error near 2^-15 of
+            // the result, whatever K is)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float corr = ssum[j] * 0x1p-128f;     // BIAS * 2^-149 = 2^-128
+                ssum[j] = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) y[i][j][r] -= corr;
+            }
         }
         if (more) {
             int8_t* dst = smem + (buf ^ 1) * A_BUF + cp_dst;

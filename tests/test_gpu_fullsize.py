@@ -1,0 +1,112 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration the
+benchmark times (AUTO dispatch).  The oracle evaluates every row on a seeded
+sample of output columns plus the first and last 64 columns (tile edges);
+columns are independent, so a column subset of the oracle's inputs gives the
+same values as the full problem."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2508_06753_amd import synth
+from test_gpu_parity import bf16_bits, check_y, dev
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def w2():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_06753_amd import binding
+    return binding
+
+
+def sample_cols(N, n, seed):
+    rng = np.random.default_rng(seed)
+    mid = rng.choice(np.arange(64, N - 64), size=n, replace=False)
+    return np.unique(np.concatenate([np.arange(64), mid, np.arange(N - 64, N)]))
+
+
+_weights = {}
+
+
+def weights(w2, K, N, G, codec, seed):
+    """Weights are the expensive part to draw; cache per shape inside the module."""
+    key = (K, N, G, codec, seed)
+    if key not in _weights:
+        _weights.clear()                      # keep at most one large problem alive
+        codes, scales = synth.make_weights(K, N, G, codec, seed=seed)
+        packed = w2.prepack(dev(codes), dev(scales), G, codec)
+        _weights[key] = (codes, scales, packed)
+    return _weights[key]
+
+
+def check_a8(w2, M, K, N, G, codec, seed, ncols=256, acc_check=True):
+    codes, scales, packed = weights(w2, K, N, G, codec, seed)
+    X = synth.make_activations(M, K, seed=seed + 1000 + M)
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    oq, osx, _ = oracle.quantize_rows(X, G, want_gsum=False)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), osx.view(np.uint32))
+    cols = sample_cols(N, ncols, seed)
+    cs, ss = np.ascontiguousarray(codes[:, cols]), np.ascontiguousarray(scales[:, cols])
+    Y = w2.matmul_a8(packed, K, N, G, xq, sx)
+    Yo, y64 = oracle.matmul_a8(cs, ss, G, codec, oq, osx)
+    mag = oracle.a8_term_magnitude(cs, ss, G, codec, oq, osx)
+    check_y(bf16_bits(Y)[:, cols], Yo, y64, mag, f"a8 full M={M} K={K} N={N} G={G}")
+    if acc_check:
+        # int32 group accumulators, bit-exact, on a slice of rows to bound the output size
+        mr = min(M, 16)
+        acc = w2.debug_group_acc_a8(packed, K, N, G, xq[:mr].contiguous())
+        oacc = oracle.group_acc(cs, G, codec, oq[:mr])
+        assert np.array_equal(acc.cpu().numpy()[:, :, cols], oacc)
+
+
+def check_a16(w2, M, K, N, G, codec, seed, ncols=128):
+    codes, scales, packed = weights(w2, K, N, G, codec, seed)
+    Xb = synth.f32_to_bf16_bits(synth.make_activations(M, K, seed=seed + 2000 + M))
+    cols = sample_cols(N, ncols, seed)
+    cs, ss = np.ascontiguousarray(codes[:, cols]), np.ascontiguousarray(scales[:, cols])
+    Y = w2.matmul_a16(packed, K, N, G, dev(Xb).view(torch.bfloat16))
+    Yo, y64, mag = oracle.matmul_a16(cs, ss, G, codec, Xb)
+    check_y(bf16_bits(Y)[:, cols], Yo, y64, mag, f"a16 full M={M} K={K} N={N} G={G}")
+
+
+@pytest.mark.parametrize("name", list(synth.SHAPES_8B))
+def test_8b_decode_layer(w2, name):
+    """8B-class decode layer, M = 1 and 4, w2a8 and w2a16, G = 128, seed 1."""
+    K, N = synth.SHAPES_8B[name]
+    for M in (1, 4):
+        check_a8(w2, M, K, N, 128, 0, seed=1)
+        check_a16(w2, M, K, N, 128, 0, seed=1)
+
+
+@pytest.mark.parametrize("G", [64, 128])
+def test_small_batch_sweep_gate_up(w2, G):
+    """gate+up 4096 x 28672, M in {1,2,4,8,16}, w2a8, both group sizes, seed 2."""
+    K, N = synth.SHAPES_8B["gate_up"]
+    for M in (1, 2, 4, 8, 16):
+        check_a8(w2, M, K, N, G, 0, seed=2, ncols=128, acc_check=(M in (1, 16)))
+
+
+@pytest.mark.parametrize("name", list(synth.SHAPES_27B))
+def test_27b_decode_ternary(w2, name):
+    """27B-class decode shapes, ternary codes (about one third zeros), M = 1 and 8, seed 3."""
+    K, N = synth.SHAPES_27B[name]
+    for M in (1, 8):
+        check_a8(w2, M, K, N, 128, 1, seed=3, ncols=128)
+
+
+def test_70b_prefill_gate_up(w2):
+    """70B-class gate+up 8192 x 57344, M = 2048 (the benchmark's prefill launch) and M = 512."""
+    K, N = synth.SHAPES_70B["gate_up"]
+    check_a8(w2, 2048, K, N, 128, 0, seed=4, ncols=256)
+    check_a8(w2, 512, K, N, 128, 0, seed=4, ncols=64, acc_check=False)
+
+
+def test_70b_prefill_down(w2):
+    K, N = synth.SHAPES_70B["down"]
+    check_a8(w2, 512, K, N, 128, 0, seed=4, ncols=128)
+    check_a16(w2, 256, K, N, 128, 0, seed=4, ncols=64)
