@@ -190,7 +190,7 @@ def main():
                                "QKV 4096x6144, O 4096x4096, gate+up 4096x28672, down 14336x4096",
                    "bytes_per_step": step_bytes, "pool_layers": n_pool, "hip_graph": bool(graphs),
                    "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2)},
-        "roofline": {"bound": "hbm", "kernel": "w2a8 GEMV (dot4) on gate+up 4096x28672, M=1",
+        "roofline": {"bound": "hbm", "kernel": "w2a8 small-M kernel (a8_smallm_kernel, int8 MFMA) on gate+up 4096x28672, M=1",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "us_per_launch": round(gemv_us, 3), "bytes_per_launch": gemv_bytes,

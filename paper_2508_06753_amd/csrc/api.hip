@@ -178,7 +178,8 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     a.M = M; a.K = K; a.N = N; a.ldy = ldy;
     a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
     if (variant == W2_VARIANT_AUTO) {
-        const int dot4_max = env_int("W2_DOT4_MAX_M", 1);
+        // measured: the MFMA form is at least as fast as dot4 from M = 1 on
+        const int dot4_max = env_int("W2_DOT4_MAX_M", 0);
         variant = M <= dot4_max && a8_dot4_supports(a) ? W2_VARIANT_DOT4
                 : a8_smallm_supports(a)                 ? W2_VARIANT_SMALLM
                                                         : W2_VARIANT_TILED;

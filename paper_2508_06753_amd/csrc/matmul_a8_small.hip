@@ -199,7 +199,9 @@ a8_dot4_kernel(A8Args a, SmallCfg cfg)
 }
 
 // ---------------------------------------------------------------- SMALLM (MFMA)
-template <int G, int TMAX, bool DBG>
+// RL = accumulator registers that hold live rows: the 16x16 result puts row 4*(lane>>4)+r in
+// register r, so for M <= RL <= 4 only registers r < RL need the dequant step.
+template <int G, int TMAX, int RL, bool DBG>
 __global__ void __launch_bounds__(1024)
 a8_smallm_kernel(A8Args a, SmallCfg cfg)
 {
@@ -208,7 +210,9 @@ a8_smallm_kernel(A8Args a, SmallCfg cfg)
     const int arow = (lane & 15) < rows ? (lane & 15) : rows - 1;   // padded rows repeat the last
     const float sx_first = DBG ? 0.0f : a.sx[(threadIdx.x >> 4) % rows];
 
-    float y[4] = {0.f, 0.f, 0.f, 0.f};
+    float y[RL];
+#pragma unroll
+    for (int r = 0; r < RL; ++r) y[r] = 0.f;
     v4i acc = {0, 0, 0, 0};
 
     for (int c = 0; c < n_chunks; ++c) {
@@ -242,7 +246,7 @@ a8_smallm_kernel(A8Args a, SmallCfg cfg)
                         const int gi = G == 64 ? t : t >> 1;
                         const float sw = tile_scale<G>(cur, gi);
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
+                        for (int r = 0; r < RL; ++r) {
                             if constexpr (DBG) {
                                 const int m = 4 * q + r;
                                 if (cb_ok && n < a.N && m < a.M)
@@ -277,7 +281,7 @@ a8_smallm_kernel(A8Args a, SmallCfg cfg)
     __syncthreads();
     float* red = reinterpret_cast<float*>(smem);            // [waves][16 m][16 n]
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[(wave * 16 + 4 * q + r) * 16 + (lane & 15)] = y[r];
+    for (int r = 0; r < RL; ++r) red[(wave * 16 + 4 * q + r) * 16 + (lane & 15)] = y[r];
     __syncthreads();
     const int outs = cfg.cbw * rows * 16;
     for (int i = threadIdx.x; i < outs; i += blockDim.x) {
@@ -324,22 +328,30 @@ int launch_a8_dot4(const A8Args& a, hipStream_t stream)
     return launch_dot4_t<4, 64>(a, stream);
 }
 
-template <int G>
+template <int G, int RL>
 static int launch_smallm_t(const A8Args& a, hipStream_t stream)
 {
     const int rows = (int)a.M;
     const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 1);
     const size_t lds = small_lds_bytes(c, rows, 16, 1, 0);
-    if (a.acc_out) return launch_small(a8_smallm_kernel<G, TMAX, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+    if (a.acc_out) return launch_small(a8_smallm_kernel<G, TMAX, 4, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
     const int tpw = tiles_per_wave(a.n_kt, c);
-    if (tpw <= 2) return launch_small(a8_smallm_kernel<G, 2, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
-    if (tpw <= 4) return launch_small(a8_smallm_kernel<G, 4, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
-    return launch_small(a8_smallm_kernel<G, TMAX, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+    if (tpw <= 2) return launch_small(a8_smallm_kernel<G, 2, RL, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+    if (tpw <= 4) return launch_small(a8_smallm_kernel<G, 4, RL, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+    return launch_small(a8_smallm_kernel<G, TMAX, RL, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
 }
 
 int launch_a8_smallm(const A8Args& a, hipStream_t stream)
 {
-    return a.G == 128 ? launch_smallm_t<128>(a, stream) : launch_smallm_t<64>(a, stream);
+    const int rl = a.M <= 1 ? 1 : a.M <= 2 ? 2 : 4;
+    if (a.G == 128) {
+        if (rl == 1) return launch_smallm_t<128, 1>(a, stream);
+        if (rl == 2) return launch_smallm_t<128, 2>(a, stream);
+        return launch_smallm_t<128, 4>(a, stream);
+    }
+    if (rl == 1) return launch_smallm_t<64, 1>(a, stream);
+    if (rl == 2) return launch_smallm_t<64, 2>(a, stream);
+    return launch_smallm_t<64, 4>(a, stream);
 }
 
 }  // namespace w2

@@ -97,8 +97,8 @@ static SmallCfg pick_cfg(int64_t n_cb, int64_t n_kt, int rows, int bytes_per_k)
         cbw = waves;
         // split K until a wave has at most TMAX tiles, while there are waves to split over
         while (cbw > 1 && n_kt * cbw > (int64_t)TMAX * waves) cbw >>= 1;
-        // and keep at least ~2 workgroups per CU
-        while (cbw > 1 && (n_cb + cbw - 1) / cbw < 512) cbw >>= 1;
+        // and keep at least one workgroup per CU
+        while (cbw > 1 && (n_cb + cbw - 1) / cbw < 256) cbw >>= 1;
     }
     if (cbw > waves) cbw = waves;
     c.cbw = cbw;
