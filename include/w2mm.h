@@ -134,6 +134,18 @@ W2_API int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, cons
                     const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                     size_t workspace_bytes, int variant, void* stream);
 
+/* Fused variant for M <= 4 (Sec. II-D: activation quantisation fused into the
+ * GEMM kernel; the abs-max is reduced per workgroup, redundantly, and kept in
+ * local memory; Sec. III-C: fusing wins for matrix-vector shapes).  Takes the
+ * unquantised activations (fp32 or bf16, row stride ldx) and produces exactly
+ * what w2_quantize_rows followed by w2_matmul_a8 produces, bit for bit, in one
+ * launch.  Returns W2_ERR_UNSUPPORTED_SHAPE (nothing launched) when M > 4 or
+ * the rows do not fit a workgroup's local memory (M*K*elem_size beyond about
+ * 64 KiB); use the two-call path then. */
+W2_API int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const void* X,
+                              w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * w2a16 (Sec. II-D, "Alternative implementation": weights rebuilt as 16-bit
  * values from code and group scale, activations left unquantised, 16-bit

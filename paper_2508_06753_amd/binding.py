@@ -35,6 +35,7 @@ _SIGS = {
     "w2_quantize_rows": [_vp, _int, _i64, _i64, _i64, _int, _vp, _vp, _vp, _vp],
     "w2_matmul_a8": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _sz, _vp],
     "w2_matmul_a8_ex": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _sz, _int, _vp],
+    "w2_matmul_a8_fused": [_vp, _i64, _i64, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp, _sz, _vp],
     "w2_matmul_a16": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _sz, _vp],
     "w2_matmul_a16_ex": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _sz, _int, _vp],
     "w2_workspace_size": [_i64, _i64, _i64, _int, _int, ctypes.POINTER(_sz)],
@@ -147,6 +148,25 @@ def matmul_a8(packed, K, N, G, xq, sx, out=None, variant=VARIANT_AUTO):
     ldy = Y.stride(0) if M > 1 else N
     _check("w2_matmul_a8", _lib.w2_matmul_a8_ex(_ptr(packed), K, N, G, _ptr(xq), _ptr(sx), M,
                                                 _ptr(Y), ldy, None, 0, variant, _stream()))
+    return Y
+
+
+def matmul_a8_fused(packed, K, N, G, X, out=None):
+    """Y bf16 [M,N] from unquantised X (fp32 or bf16) in one launch, M <= 4."""
+    if X.dtype == torch.float32:
+        dt = DT_F32
+    elif X.dtype == torch.bfloat16:
+        dt = DT_BF16
+    else:
+        raise ValueError("X must be float32 or bfloat16")
+    if not X.is_cuda or X.dim() != 2 or X.shape[1] != K or X.stride(1) != 1:
+        raise ValueError("X must be a device tensor [M,K] with unit inner stride")
+    M = X.shape[0]
+    Y = out if out is not None else torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    ldx = X.stride(0) if M > 1 else K
+    ldy = Y.stride(0) if M > 1 else N
+    _check("w2_matmul_a8_fused", _lib.w2_matmul_a8_fused(_ptr(packed), K, N, G, _ptr(X), dt, ldx, M,
+                                                         _ptr(Y), ldy, None, 0, _stream()))
     return Y
 
 

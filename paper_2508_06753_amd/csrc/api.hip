@@ -213,6 +213,28 @@ int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* 
                            W2_VARIANT_AUTO, stream);
 }
 
+int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const void* X,
+                       w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    const char* fn = "w2_matmul_a8_fused";
+    int rc = check_shape(fn, K, N, G);
+    if (rc) return rc;
+    if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
+    if (x_dtype != W2_DT_F32 && x_dtype != W2_DT_BF16)
+        return fail(W2_ERR_INVALID_ARG, "%s: unknown dtype %d", fn, (int)x_dtype);
+    if (M == 0) return W2_OK;
+    if (!packed || !X || !Y) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
+    if (!aligned16(packed) || !aligned16(X) || !aligned16(Y))
+        return fail(W2_ERR_MISALIGNED, "%s: packed, X and Y must be 16-byte aligned", fn);
+    if (ldx < K || ldx % 8 || ldy < N || ldy % 8)
+        return fail(W2_ERR_MISALIGNED, "%s: ldx >= K, ldy >= N, both multiples of 8", fn);
+    const Layout L = make_layout(K, N, G);
+    return launch_a8_fusedq(packed, (const char*)packed + L.codes_bytes, X, x_dtype == W2_DT_BF16, ldx,
+                            M, K, N, G, L.n_cb, L.n_kt, Y, ldy, (hipStream_t)stream);
+}
+
 int w2_debug_group_acc_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
                           int64_t M, int variant, int32_t* acc, void* stream)
 {

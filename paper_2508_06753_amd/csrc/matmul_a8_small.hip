@@ -17,16 +17,6 @@
 
 namespace w2 {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-
-// 16 two-bit fields -> four dwords of int8 lanes holding 64*q.
-__device__ __forceinline__ void upconvert(uint32_t w, int (&u)[4])
-{
-    u[0] = (int)((w << 6) & 0xC0C0C0C0u);
-    u[1] = (int)((w << 4) & 0xC0C0C0C0u);
-    u[2] = (int)((w << 2) & 0xC0C0C0C0u);
-    u[3] = (int)(w & 0xC0C0C0C0u);
-}
 
 // Staging of the activation rows [0,rows) x k in [k0, k0+len) into LDS rows of
 // stride len + XS_PAD (len % 16 == 0), split in two so that the global loads

@@ -40,6 +40,10 @@ bool a8_smallm_supports(const A8Args& a);
 int launch_a8_smallm(const A8Args& a, hipStream_t stream);
 int launch_a8_tiled(const A8Args& a, hipStream_t stream);
 
+int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x_is_bf16, int64_t ldx,
+                     int64_t M, int64_t K, int64_t N, int G, int64_t n_cb, int64_t n_kt, uint16_t* Y,
+                     int64_t ldy, hipStream_t stream);
+
 struct A16Args {
     const uint32_t* codes;
     const uint16_t* scales;

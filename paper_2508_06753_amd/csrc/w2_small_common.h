@@ -7,6 +7,8 @@
 
 namespace w2 {
 
+typedef int v4i __attribute__((ext_vector_type(4)));
+
 constexpr int XS_PAD = 16;   // bytes of padding per LDS activation row (bank spread)
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
@@ -16,6 +18,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     uint32_t u = __float_as_uint(f);
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+// 16 two-bit fields -> four dwords of int8 lanes holding 64*q.
+__device__ __forceinline__ void upconvert(uint32_t w, int (&u)[4])
+{
+    u[0] = (int)((w << 6) & 0xC0C0C0C0u);
+    u[1] = (int)((w << 4) & 0xC0C0C0C0u);
+    u[2] = (int)((w << 2) & 0xC0C0C0C0u);
+    u[3] = (int)(w & 0xC0C0C0C0u);
 }
 
 // One streamed tile: 16 B of codes and the tile's group scales for this lane.

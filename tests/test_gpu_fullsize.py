@@ -83,6 +83,21 @@ def test_8b_decode_layer(w2, name):
         check_a16(w2, M, K, N, 128, 0, seed=1)
 
 
+@pytest.mark.parametrize("name", list(synth.SHAPES_8B))
+def test_8b_decode_layer_fused_quantise(w2, name):
+    """The benchmark's step at M=1: fp32 row in, one fused launch, against the oracle."""
+    K, N = synth.SHAPES_8B[name]
+    codes, scales, packed = weights(w2, K, N, 128, 0, 1)
+    X = synth.make_activations(1, K, seed=77)
+    Y = w2.matmul_a8_fused(packed, K, N, 128, dev(X))
+    oq, osx, _ = oracle.quantize_rows(X, 128, want_gsum=False)
+    cols = sample_cols(N, 512, 5)
+    cs, ss = np.ascontiguousarray(codes[:, cols]), np.ascontiguousarray(scales[:, cols])
+    Yo, y64 = oracle.matmul_a8(cs, ss, 128, 0, oq, osx)
+    mag = oracle.a8_term_magnitude(cs, ss, 128, 0, oq, osx)
+    check_y(bf16_bits(Y)[:, cols], Yo, y64, mag, f"a8 fused full {name}")
+
+
 @pytest.mark.parametrize("G", [64, 128])
 def test_small_batch_sweep_gate_up(w2, G):
     """gate+up 4096 x 28672, M in {1,2,4,8,16}, w2a8, both group sizes, seed 2."""

@@ -209,6 +209,44 @@ def test_a8_closed_forms(w2):
         assert np.array_equal(bits_to_f64(bf16_bits(Y))[0], colsum.astype(np.float64))
 
 
+# ------------------------------------------------------------------ fused quantise + matmul
+@pytest.mark.parametrize("bf16_in", [False, True])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (2048, 1032), (4096, 512), (14336, 64)])
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+def test_a8_fused_equals_two_call_path(w2, M, K, N, G, bf16_in):
+    codes, scales, X = synth.make_problem(M, K, N, G, M % 2, seed=M + K + N)
+    if M > 1:
+        X[1] = 0.0                                            # all-zero row
+    packed = w2.prepack(dev(codes), dev(scales), G, M % 2)
+    if bf16_in:
+        Xb = synth.f32_to_bf16_bits(X)
+        Xd = dev(Xb).view(torch.bfloat16)
+        oq, osx, _ = oracle.quantize_rows(Xb, G, x_is_bf16=True)
+    else:
+        Xd = dev(X)
+        oq, osx, _ = oracle.quantize_rows(X, G)
+    try:
+        Yf = w2.matmul_a8_fused(packed, K, N, G, Xd)
+    except w2.W2Error as e:                                   # shape beyond the fused budget
+        assert e.status == w2.ERR_UNSUPPORTED_SHAPE
+        return
+    xq, sx, _ = w2.quantize_rows(Xd, G)
+    Y2 = w2.matmul_a8(packed, K, N, G, xq, sx)
+    assert torch.equal(Yf.view(torch.int16), Y2.view(torch.int16)), "fused and two-call results differ"
+    Yo, y64 = oracle.matmul_a8(codes, scales, G, M % 2, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, G, M % 2, oq, osx)
+    check_y(bf16_bits(Yf), Yo, y64, mag, f"a8 fused M={M} K={K} N={N} G={G} bf16_in={bf16_in}")
+
+
+def test_a8_fused_rejects_large_m(w2):
+    codes, scales, X = synth.make_problem(5, 256, 16, 128, 0, 1)
+    packed = w2.prepack(dev(codes), dev(scales), 128, 0)
+    with pytest.raises(w2.W2Error) as e:
+        w2.matmul_a8_fused(packed, 256, 16, 128, dev(X))
+    assert e.value.status == w2.ERR_UNSUPPORTED_SHAPE
+
+
 # ------------------------------------------------------------------ w2a16
 def run_a16_case(w2, M, K, N, G, codec, variant, seed):
     codes, scales, X = synth.make_problem(M, K, N, G, codec, seed)
