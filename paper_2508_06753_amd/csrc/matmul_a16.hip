@@ -59,7 +59,7 @@ struct Piece { uint4 lo, hi; };
 __device__ __forceinline__ Piece piece_load(const uint16_t* __restrict__ X, int64_t ldx, int64_t k0,
                                             int ppr, int total, int i)
 {
-    i = i < total ? i : total - 1;               // branch-free: surplus threads re-read the last piece
+    i = i < total ? i : (int)((unsigned)i % (unsigned)total);   // surplus threads re-read pieces spread over the rows
     const int r = i / ppr, v = i - r * ppr;
     const uint4* p = reinterpret_cast<const uint4*>(X + (int64_t)r * ldx + k0 + v * 16);
     Piece pc;

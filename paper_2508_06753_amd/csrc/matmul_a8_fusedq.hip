@@ -64,14 +64,26 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
     int8_t* xs = smem + FQ_HDR;                             // int8 rows
     uint4* stash = reinterpret_cast<uint4*>(xs + ((rows * row_stride + 15) & ~15));
 
+    // piece index -> (row, piece inside the row); a single row needs no division
+    auto split = [&](unsigned i, int& r, int& v) __attribute__((always_inline)) {
+        if constexpr (RL == 1) { r = 0; v = (int)i; }
+        else { r = (int)(i / (unsigned)ppr); v = (int)i - r * ppr; }
+    };
+
     // 1. activation rows: vector loads first
     uint4 pc[FQ_PIECES];
 #pragma unroll
     for (int j = 0; j < FQ_PIECES; ++j) {
-        int i = threadIdx.x + j * blockDim.x;
-        i = i < total ? i : total - 1;                      // branch-free: surplus slots re-read the last piece
-        const int r = i / ppr, v = i - r * ppr;
-        pc[j] = *reinterpret_cast<const uint4*>((const char*)a.X + ((int64_t)r * a.ldx * ES) + (int64_t)v * 16);
+        // slots wholly past the end are skipped (uniform branch); surplus threads of the last slot
+        // re-read pieces spread over the rows, never one common cache line
+        pc[j] = make_uint4(0, 0, 0, 0);
+        if (j * (int)blockDim.x < total) {
+            unsigned i = threadIdx.x + j * blockDim.x;
+            i = i < (unsigned)total ? i : i % (unsigned)total;
+            int r, v;
+            split(i, r, v);
+            pc[j] = *reinterpret_cast<const uint4*>((const char*)a.X + ((int64_t)r * a.ldx * ES) + (int64_t)v * 16);
+        }
     }
     // 2. the wave's whole share of the weight stream
     int64_t kt0 = ks;
@@ -87,13 +99,16 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
     load_batch(kt0, tr0);
 
     // 3. park the rows in LDS and reduce abs-max per row
-    float amax[4] = {0.f, 0.f, 0.f, 0.f};
+    float amax[RL];
+#pragma unroll
+    for (int rr = 0; rr < RL; ++rr) amax[rr] = 0.f;
 #pragma unroll
     for (int j = 0; j < FQ_PIECES; ++j) {
         const int i = threadIdx.x + j * blockDim.x;
         if (i < total) {
             stash[i] = pc[j];
-            const int r = i / ppr;
+            int r, v_unused;
+            split((unsigned)i, r, v_unused);
             const uint32_t d[4] = {pc[j].x, pc[j].y, pc[j].z, pc[j].w};
             float m = 0.f;
 #pragma unroll
@@ -106,23 +121,23 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
                 }
             }
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) amax[rr] = (rr == r) ? fmaxf(amax[rr], m) : amax[rr];
+            for (int rr = 0; rr < RL; ++rr) amax[rr] = (rr == r) ? fmaxf(amax[rr], m) : amax[rr];
         }
     }
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
+    for (int rr = 0; rr < RL; ++rr) {
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) amax[rr] = fmaxf(amax[rr], __shfl_xor(amax[rr], off));
     }
     if (lane == 0) {
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) s_red[wave * 4 + rr] = amax[rr];
+        for (int rr = 0; rr < RL; ++rr) s_red[wave * 4 + rr] = amax[rr];
     }
     __syncthreads();
     const int n_waves = blockDim.x >> 6;
-    float inv[4], sxv[4];
+    float inv[RL], sxv[RL];
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
+    for (int rr = 0; rr < RL; ++rr) {
         float m = 0.f;
         for (int w = 0; w < n_waves; ++w) m = fmaxf(m, s_red[w * 4 + rr]);
         inv[rr] = 0.f; sxv[rr] = 0.f;
@@ -131,13 +146,18 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
             sxv[rr] = __fdiv_rn(m, 127.0f);
         }
     }
-    if (threadIdx.x < 4) s_sx[threadIdx.x] = sxv[threadIdx.x & 3];
+#pragma unroll
+    for (int rr = 0; rr < RL; ++rr)
+        if (threadIdx.x == (unsigned)rr) s_sx[rr] = sxv[rr];
 
     // 4. quantise from the parked rows into the int8 rows
     for (int i = threadIdx.x; i < total; i += blockDim.x) {
         const uint4 p = stash[i];
-        const int r = i / ppr, v = i - r * ppr;
-        const float iv = r == 0 ? inv[0] : r == 1 ? inv[1] : r == 2 ? inv[2] : inv[3];
+        int r, v;
+        split((unsigned)i, r, v);
+        float iv = inv[0];
+#pragma unroll
+        for (int rr = 1; rr < RL; ++rr) iv = (r == rr) ? inv[rr] : iv;
         const uint32_t d[4] = {p.x, p.y, p.z, p.w};
         if constexpr (BF16IN) {
             int qv[8];

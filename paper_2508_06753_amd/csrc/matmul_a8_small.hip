@@ -31,10 +31,17 @@ struct StageRegs { uint4 v0, v1, v2, v3; };
 __device__ __forceinline__ uint4 stage_load1(const int8_t* __restrict__ xq, int64_t K, int64_t k0,
                                              int vec_per_row, int total, int j)
 {
-    int i = threadIdx.x + j * blockDim.x;                 // branch-free: surplus threads re-read the last piece
-    i = i < total ? i : total - 1;
-    const int r = i / vec_per_row, v = i - r * vec_per_row;
-    return *reinterpret_cast<const uint4*>(xq + (int64_t)r * K + k0 + v * 16);
+    // A slot that lies wholly past the end is skipped (uniform branch).  Inside the last,
+    // partly filled slot the surplus threads re-read pieces spread over the rows (i mod total):
+    // if they all re-read one piece, every workgroup of the grid hammers the same cache line.
+    uint4 r = make_uint4(0, 0, 0, 0);
+    if (j * (int)blockDim.x < total) {
+        unsigned i = threadIdx.x + j * blockDim.x;
+        i = i < (unsigned)total ? i : i % (unsigned)total;
+        const int row = i / vec_per_row, v = i - row * vec_per_row;
+        r = *reinterpret_cast<const uint4*>(xq + (int64_t)row * K + k0 + v * 16);
+    }
+    return r;
 }
 
 __device__ __forceinline__ void stage_load(const int8_t* __restrict__ xq, int64_t K, int rows,
