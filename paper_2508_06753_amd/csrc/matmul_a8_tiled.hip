@@ -3,7 +3,7 @@
 // plays the role of the wg_tile / sg_tile split of Sec. II-D, re-derived for
 // CDNA4: a 128(M) x 256(N) workgroup tile, eight waves of 64 x 64 (two per
 // SIMD), each wave 4 x 4 tiles of v_mfma_i32_16x16x64_i8.
-//   - activations (int8) are staged through LDS, double-buffered, 128 k per
+//   - activations (int8) are staged through LDS, three buffers, 128 k per
 //     stage, rows padded by 16 B so ds_read_b128 is conflict-free;
 //   - the 2-bit weights never touch LDS: the packed layout IS the MFMA
 //     B-operand layout, so each lane loads its dwords (64 bits per column
@@ -32,8 +32,8 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 namespace tiled {
 
-constexpr int BM = 128, BN = 256, BK = 128;       // BK: k per pipeline stage (half a packed tile)
-constexpr int THREADS = 512;
+constexpr int BM = 64, BN = 256, BK = 128;        // BK: k per pipeline stage (half a packed tile)
+constexpr int THREADS = 256;
 constexpr int A_STRIDE = BK + 16;                 // bytes per LDS row
 constexpr int A_BUF = BM * A_STRIDE;              // bytes per stage
 constexpr int WM = 64, WN = 64;                   // wave tile
@@ -79,14 +79,14 @@ __device__ __forceinline__ void load_w(const uint32_t* const (&wp)[4], const uin
 }
 
 template <int G, bool DBG>
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS, 2)
 a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 {
     extern __shared__ __align__(16) int8_t smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = 0, wn = wave;
     const int q = lane >> 4, l16 = lane & 15;
 
     // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (round
@@ -136,13 +136,19 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
             for (int r = 0; r < 4; ++r) y[i][j][r] = 0.0f;
         }
 
-    const int64_t n_it = a.n_kt * 2;
+    // Pipeline: the activations of stage it+1 sit in registers during stage it-1 and are written
+    // to LDS at the top of stage it (three LDS buffers), the weights of stage it are loaded during
+    // stage it-1 and moved into place at the top of stage it: every global load has a whole stage
+    // to land before anything waits for it.
+    const int64_t n_it = a.n_kt * 2;                         // >= 2
     uint4 ar0 = *reinterpret_cast<const uint4*>(cp_src);
     uint4 ar1 = *reinterpret_cast<const uint4*>(cp_src + 16);
     WStage wc, wn_;
-    load_w<G>(wp, sp, 0, wc);
+    load_w<G>(wp, sp, 0, wn_);
     *reinterpret_cast<uint4*>(smem + cp_dst) = ar0;
     *reinterpret_cast<uint4*>(smem + cp_dst + 16) = ar1;
+    ar0 = *reinterpret_cast<const uint4*>(cp_src + BK);
+    ar1 = *reinterpret_cast<const uint4*>(cp_src + BK + 16);
     __syncthreads();
 
     const int8_t* a_base = smem + (wm * WM + l16) * A_STRIDE + q * 16;
@@ -165,12 +171,17 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     };
 
     for (int64_t it = 0; it < n_it; ++it) {
-        const int buf = (int)(it & 1);
-        const bool more = it + 1 < n_it;
-        if (more) {
-            ar0 = *reinterpret_cast<const uint4*>(cp_src + (it + 1) * BK);
-            ar1 = *reinterpret_cast<const uint4*>(cp_src + (it + 1) * BK + 16);
+        const int buf = (int)(it % 3);
+        wc = wn_;                                            // loaded during the previous stage
+        if (it + 1 < n_it) {
+            int8_t* dst = smem + (int)((it + 1) % 3) * A_BUF + cp_dst;
+            *reinterpret_cast<uint4*>(dst) = ar0;            // activations of stage it+1
+            *reinterpret_cast<uint4*>(dst + 16) = ar1;
             load_w<G>(wp, sp, it + 1, wn_);
+        }
+        if (it + 2 < n_it) {
+            ar0 = *reinterpret_cast<const uint4*>(cp_src + (it + 2) * BK);
+            ar1 = *reinterpret_cast<const uint4*>(cp_src + (it + 2) * BK + 16);
         }
         const int8_t* ab = a_base + buf * A_BUF;
         float swS[4][2];
@@ -220,12 +231,6 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
                     for (int r = 0; r < 4; ++r) y[i][j][r] -= corr;
             }
         }
-        if (more) {
-            int8_t* dst = smem + (buf ^ 1) * A_BUF + cp_dst;
-            *reinterpret_cast<uint4*>(dst) = ar0;
-            *reinterpret_cast<uint4*>(dst + 16) = ar1;
-            wc = wn_;
-        }
         __syncthreads();
     }
     if constexpr (DBG) return;
@@ -256,8 +261,8 @@ static int launch_tiled(Kern kern, const A8Args& a, hipStream_t stream)
     using namespace tiled;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
-    const size_t lds = 2 * A_BUF;
-    int group_m = env_int("W2_TILED_GROUP_M", 4);
+    const size_t lds = 3 * A_BUF;
+    int group_m = env_int("W2_TILED_GROUP_M", 8);
     if (group_m < 1) group_m = 1;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(THREADS);
     hipLaunchKernelGGL(kern, grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
