@@ -36,6 +36,48 @@ def algorithmic_bytes(M, K, N, g=G):
     return K * N // 4 + (K // g) * N * 2 + M * K + 2 * M * N
 
 
+def read_traffic(kernel_key):
+    """HBM bytes per launch of a kernel as measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`
+    (two runs of `bench.py --pmc`, scaled by the plain copy); the summary under profiles/ carries a
+    line `traffic_bytes_per_launch[<key>] = <bytes>`.  None when no such measurement is on file."""
+    path = os.path.join(ROOT, "profiles", "pmc_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch[%s]" % kernel_key):
+                return int(float(line.rsplit("=", 1)[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
+def pmc_mode(torch, w2, lib, vp, pool, shapes, Xd, Yd, dev):
+    import ctypes
+    M = 1
+    s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    src = torch.randint(0, 255, (256 << 20,), dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    Kd, Nd = shapes["gate_up"]
+    for _ in range(3):
+        dst.copy_(src)                                   # calibration: reads 256 MiB, writes 256 MiB
+    for l in pool:
+        lib.w2_debug_stream_read(vp(l["gate_up"]), l["gate_up"].numel(), vp(sink), s)
+    for l in pool:
+        rc = lib.w2_matmul_a8_fused(vp(l["gate_up"]), Kd, Nd, G, vp(Xd["gate_up"]), w2.DT_F32, Kd, M,
+                                    vp(Yd["gate_up"]), Nd, None, 0, s)
+        assert rc == 0, lib.w2_last_error()
+    Kp, Np, Mp = 8192, 57344, 2048
+    pk = torch.randint(0, 255, (w2.packed_size(Kp, Np, G),), dtype=torch.uint8, device=dev)
+    pk[Kp * Np // 4:].view(torch.int16)[:] = 0x3C00
+    xqp = torch.randint(-127, 128, (Mp, Kp), dtype=torch.int8, device=dev)
+    sxp = torch.rand(Mp, device=dev)
+    Yp = torch.empty((Mp, Np), dtype=torch.bfloat16, device=dev)
+    for _ in range(3):
+        w2.matmul_a8(pk, Kp, Np, G, xqp, sxp, out=Yp)
+    torch.cuda.synchronize()
+    print("bench.py --pmc: launched copy x3 (256 MiB), stream read and fused GEMV x%d, prefill x3" % len(pool))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,6 +85,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--pmc", action="store_true",
+                    help="counter-collection mode for `rocprofv3 --pmc`: launch, eagerly and a few times each, a plain "
+                         "256 MiB device copy (the calibration kernel), the streaming read, the dominant GEMV over "
+                         "the pool and the prefill kernel; print no bench line")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -111,6 +157,8 @@ def main():
     step(pool[0])
     step_two_call(pool[0])
     torch.cuda.synchronize()
+    if args.pmc:
+        return pmc_mode(torch, w2, lib, vp, pool, shapes, Xd, Yd, dev)
     use_graph = os.environ.get("W2_BENCH_NO_GRAPH", "0") != "1"
     graphs = [capture(lambda l=l: step(l)) for l in pool] if use_graph else None
     graphs2 = [capture(lambda l=l: step_two_call(l)) for l in pool] if use_graph else None
@@ -216,7 +264,7 @@ def main():
                    "two_call_gpu_ms_per_step": round(two_call_ms, 5)},
         "roofline": {"bound": "hbm", "kernel": "a8_fusedq_kernel (quantise + int8 MFMA GEMV + dequant) on gate+up 4096x28672, M=1",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic("a8_fusedq gate_up M=1"),
                      "us_per_launch": round(gemv_us, 3), "bytes_per_launch": gemv_bytes,
                      "stream_read_us_same_bytes": round(read_us, 3),
                      "frac_of_stream_read": round(read_us / gemv_us, 4)},
@@ -246,7 +294,7 @@ def main():
                           "us_per_launch": round(us, 1), "value": round(tops, 1), "unit": "TOPS",
                           "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": INT8_PEAK_TOPS,
                                        "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
-                                       "traffic": None}}
+                                       "traffic": read_traffic("a8_tiled gate_up 70B M=2048")}}
         del pk, xqp, Yp
 
     # ---- the CPU oracle, timed as it stands on the host cores, on the same layer

@@ -1,8 +1,13 @@
 // w2a8 for large M (prefill): the compute-bound regime (Sec. III-C, GEMM
 // results) on the int8 matrix cores.  The workgroup / wave tile hierarchy
 // plays the role of the wg_tile / sg_tile split of Sec. II-D, re-derived for
-// CDNA4: a 128(M) x 256(N) workgroup tile, eight waves of 64 x 64 (two per
-// SIMD), each wave 4 x 4 tiles of v_mfma_i32_16x16x64_i8.
+// CDNA4: a 64(M) x 256(N) workgroup tile, four waves of 64 x 64 (one per SIMD,
+// two workgroups per CU so that their barriers fall at different times), each
+// wave 4 x 4 tiles of v_mfma_i32_16x16x64_i8.  The SIMD issues one vector
+// instruction (matrix ones included) every four clocks or so while a matrix
+// instruction keeps its pipe busy for sixteen, so the loop is written to keep
+// the vector instructions per MFMA low: scalar base + 32-bit lane offset
+// addressing, two alternating register sets for the weights (no copies).
 //   - activations (int8) are staged through LDS, three buffers, 128 k per
 //     stage, rows padded by 16 B so ds_read_b128 is conflict-free;
 //   - the 2-bit weights never touch LDS: the packed layout IS the MFMA
@@ -62,19 +67,24 @@ struct WStage {
     uint32_t s[4];    // G=128: one bf16 scale (low half); G=64: two bf16 scales
 };
 
+// wb[j] / sb[j]: wave-uniform byte pointers to column block j's codes / scales (scalar registers);
+// w_lane / s_lane: this lane's byte offset inside a packed tile.  The stage offset is uniform, so
+// every load is "scalar base + 32-bit lane offset" and costs no vector address arithmetic.
 template <int G>
-__device__ __forceinline__ void load_w(const uint32_t* const (&wp)[4], const uint16_t* const (&sp)[4],
-                                       int64_t it, WStage& r)
+__device__ __forceinline__ void load_w(const char* const (&wb)[4], const char* const (&sb)[4],
+                                       uint32_t w_lane, uint32_t s_lane, int64_t it, WStage& r)
 {
     const int64_t kt = it >> 1;
     const int h = (int)(it & 1);
+    const int64_t w_off = (kt * 256 + h * 2) * 4;
+    const int64_t s_off = G == 128 ? (kt * (TILE_N * 2) + h) * 2 : (kt * (TILE_N * 4) + h * 2) * 2;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        r.w[j] = *reinterpret_cast<const uint2*>(wp[j] + kt * 256 + h * 2);
+        r.w[j] = *reinterpret_cast<const uint2*>(wb[j] + w_off + w_lane);
         if constexpr (G == 128)
-            r.s[j] = sp[j][kt * (TILE_N * 2) + h];
+            r.s[j] = *reinterpret_cast<const uint16_t*>(sb[j] + s_off + s_lane);
         else
-            r.s[j] = *reinterpret_cast<const uint32_t*>(sp[j] + kt * (TILE_N * 4) + h * 2);
+            r.s[j] = *reinterpret_cast<const uint32_t*>(sb[j] + s_off + s_lane);
     }
 }
 
@@ -105,22 +115,26 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     const int64_t tile_n = in_band / gm;
     const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
 
-    // per column block: base pointers of this lane's dwords and scales
-    const uint32_t* wp[4];
-    const uint16_t* sp[4];
+    // per column block: wave-uniform base pointers of its codes and scales
+    const char* wb[4];
+    const char* sb[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         int64_t c = tile_n * (BN / TILE_N) + wn * 4 + j;
         c = c < a.n_cb ? c : a.n_cb - 1;                     // clamp: loads stay in bounds
-        wp[j] = a.codes + (c * a.n_kt * 64 + lane) * 4;
-        sp[j] = a.scales + (c * a.n_kt * TILE_N + l16) * (TILE_K / G);
+        wb[j] = reinterpret_cast<const char*>(a.codes + c * a.n_kt * 256);
+        sb[j] = reinterpret_cast<const char*>(a.scales + c * a.n_kt * TILE_N * (TILE_K / G));
     }
+    uint32_t w_lane = (uint32_t)lane * 16u;
+    uint32_t s_lane = (uint32_t)l16 * (uint32_t)(TILE_K / G) * 2u;
 
-    // global -> LDS copy: 4 threads per 128-byte row piece, 32 bytes each
+    // global -> LDS copy: 4 threads per 128-byte row piece, 32 bytes each.  Rows past M repeat
+    // the last row; the lane offset (< 64 K) fits 32 bits.
     const int cp_row = tid >> 2, cp_seg = tid & 3;
     int64_t cp_m = m0 + cp_row;
-    if (cp_m >= a.M) cp_m = a.M - 1;                         // padded rows repeat the last row
-    const int8_t* cp_src = a.xq + cp_m * a.K + cp_seg * 32;
+    if (cp_m >= a.M) cp_m = a.M - 1;
+    const char* cp_base = reinterpret_cast<const char*>(a.xq) + m0 * a.K;          // uniform
+    uint32_t cp_lane = (uint32_t)((cp_m - m0) * a.K) + (uint32_t)cp_seg * 32u;
     const int cp_dst = cp_row * A_STRIDE + cp_seg * 32;
 
     v4i acc[4][4];
@@ -137,18 +151,25 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         }
 
     // Pipeline: the activations of stage it+1 sit in registers during stage it-1 and are written
-    // to LDS at the top of stage it (three LDS buffers), the weights of stage it are loaded during
-    // stage it-1 and moved into place at the top of stage it: every global load has a whole stage
-    // to land before anything waits for it.
-    const int64_t n_it = a.n_kt * 2;                         // >= 2
-    uint4 ar0 = *reinterpret_cast<const uint4*>(cp_src);
-    uint4 ar1 = *reinterpret_cast<const uint4*>(cp_src + 16);
-    WStage wc, wn_;
-    load_w<G>(wp, sp, 0, wn_);
+    // to LDS at the top of stage it (three LDS buffers); the weights of stage it+1 are loaded at
+    // the top of stage it into the other of two register sets.  Every global load has a whole
+    // stage to land before anything waits for it.
+    const int64_t n_it = a.n_kt * 2;                         // even, >= 2
+    // The empty asm statements keep the zero-extension of a lane offset next to its load, which is
+    // what lets the compiler pick the "scalar base + 32-bit vector offset" addressing mode.
+    auto load_a = [&](int64_t it, uint4& r0, uint4& r1) {
+        const char* p = cp_base + it * BK;                   // uniform
+        asm volatile("" : "+v"(cp_lane));
+        r0 = *reinterpret_cast<const uint4*>(p + cp_lane);
+        r1 = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
+    };
+    uint4 ar0, ar1;
+    WStage w0, w1;
+    load_a(0, ar0, ar1);
+    load_w<G>(wb, sb, w_lane, s_lane, 0, w0);
     *reinterpret_cast<uint4*>(smem + cp_dst) = ar0;
     *reinterpret_cast<uint4*>(smem + cp_dst + 16) = ar1;
-    ar0 = *reinterpret_cast<const uint4*>(cp_src + BK);
-    ar1 = *reinterpret_cast<const uint4*>(cp_src + BK + 16);
+    load_a(1, ar0, ar1);
     __syncthreads();
 
     const int8_t* a_base = smem + (wm * WM + l16) * A_STRIDE + q * 16;
@@ -170,19 +191,16 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         }
     };
 
-    for (int64_t it = 0; it < n_it; ++it) {
-        const int buf = (int)(it % 3);
-        wc = wn_;                                            // loaded during the previous stage
+    // One stage: wc holds this stage's weights, wnx receives the next stage's.
+    auto stage = [&](int64_t it, int buf, int buf_next, const WStage& wc, WStage& wnx) {
         if (it + 1 < n_it) {
-            int8_t* dst = smem + (int)((it + 1) % 3) * A_BUF + cp_dst;
+            int8_t* dst = smem + buf_next * A_BUF + cp_dst;
             *reinterpret_cast<uint4*>(dst) = ar0;            // activations of stage it+1
             *reinterpret_cast<uint4*>(dst + 16) = ar1;
-            load_w<G>(wp, sp, it + 1, wn_);
+            asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+            load_w<G>(wb, sb, w_lane, s_lane, it + 1, wnx);
         }
-        if (it + 2 < n_it) {
-            ar0 = *reinterpret_cast<const uint4*>(cp_src + (it + 2) * BK);
-            ar1 = *reinterpret_cast<const uint4*>(cp_src + (it + 2) * BK + 16);
-        }
+        if (it + 2 < n_it) load_a(it + 2, ar0, ar1);
         const int8_t* ab = a_base + buf * A_BUF;
         float swS[4][2];
 #pragma unroll
@@ -217,7 +235,17 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
             }
             if (last) dequant_col(3, swS[3][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
         }
-        if ((it & 7) == 7) {
+    };
+
+    int buf = 0;
+    for (int64_t it = 0; it < n_it; it += 2) {
+        const int b1 = buf == 2 ? 0 : buf + 1;
+        const int b2 = b1 == 2 ? 0 : b1 + 1;
+        stage(it, buf, b1, w0, w1);
+        __syncthreads();
+        stage(it + 1, b1, b2, w1, w0);
+        buf = b2;
+        if ((it & 7) == 6) {
             // take the accumulated bias term out every 8 stages, so that the running sums
             // never carry more than 8 stages of it (keeps the rounding error near 2^-15 of
             // the result, whatever K is)
