@@ -193,14 +193,20 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 
     // One stage: wc holds this stage's weights, wnx receives the next stage's.
     auto stage = [&](int64_t it, int buf, int buf_next, const WStage& wc, WStage& wnx) {
-        if (it + 1 < n_it) {
+        // No branch around the loads: past the end they re-read the last stage (and the last
+        // LDS write lands in a buffer nobody reads any more).  With loads under a condition the
+        // compiler cannot count how many are in flight and its waits for the previous stage's
+        // registers also wait for the loads just issued, i.e. a full memory round trip per stage.
+        {
             int8_t* dst = smem + buf_next * A_BUF + cp_dst;
             *reinterpret_cast<uint4*>(dst) = ar0;            // activations of stage it+1
             *reinterpret_cast<uint4*>(dst + 16) = ar1;
             asm volatile("" : "+v"(w_lane), "+v"(s_lane));
-            load_w<G>(wb, sb, w_lane, s_lane, it + 1, wnx);
+            load_w<G>(wb, sb, w_lane, s_lane, min(it + 1, n_it - 1), wnx);
         }
-        if (it + 2 < n_it) load_a(it + 2, ar0, ar1);
+        load_a(min(it + 2, n_it - 1), ar0, ar1);
+        // keep the loads up here: the scheduler otherwise sinks them to their first use, one stage on
+        __builtin_amdgcn_sched_barrier(0);
         const int8_t* ab = a_base + buf * A_BUF;
         float swS[4][2];
 #pragma unroll
