@@ -160,7 +160,7 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     int rc = check_shape(fn, K, N, G);
     if (rc) return rc;
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
-    if (variant < W2_VARIANT_AUTO || variant > W2_VARIANT_TILED)
+    if (variant < W2_VARIANT_AUTO || variant > W2_VARIANT_MIDM)
         return fail(W2_ERR_INVALID_ARG, "%s: unknown variant %d", fn, variant);
     if (M == 0) return W2_OK;
     if (!packed || !xq) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
@@ -182,6 +182,7 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         const int dot4_max = env_int("W2_DOT4_MAX_M", 0);
         variant = M <= dot4_max && a8_dot4_supports(a) ? W2_VARIANT_DOT4
                 : a8_smallm_supports(a)                 ? W2_VARIANT_SMALLM
+                : M <= env_int("W2_MIDM_MAX_M", 64) && a8_midm_supports(a) ? W2_VARIANT_MIDM
                                                         : W2_VARIANT_TILED;
     }
     hipStream_t s = (hipStream_t)stream;
@@ -192,6 +193,9 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     case W2_VARIANT_SMALLM:
         if (!a8_smallm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: SMALLM needs M <= 16", fn);
         return launch_a8_smallm(a, s);
+    case W2_VARIANT_MIDM:
+        if (!a8_midm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: MIDM needs M <= 64", fn);
+        return launch_a8_midm(a, s);
     default:
         return launch_a8_tiled(a, s);
     }

@@ -1,0 +1,272 @@
+// w2a8 for medium M (17..64): between the memory-bound GEMV regime and the
+// compute-bound GEMM regime of Sec. III-C.  The weight stream is still read
+// exactly once ("up-convert and compute", Sec. II-C): a wave owns one 16-column
+// block and every KS-th 256-k tile of it, up-converts each dword once and feeds
+// it to RT row tiles of v_mfma_i32_16x16x64_i8 (M <= 16*RT), so the shift/mask
+// cost per matrix instruction falls with M.  K is split across the waves of a
+// workgroup (Sec. II-D, K-splitting for small shapes) and reduced through LDS in
+// a fixed order; the dequant epilogue is fused (Sec. II-D).
+//
+// Schedule.  Eight waves: CBW = 2*TPC column blocks x KS = 4/TPC k-splits.  The
+// activations go through LDS in chunks of 1024 k (four tiles; every wave works
+// on TPC of them), one buffer: the next chunk is fetched into registers while
+// the current one is being multiplied, and stored between two barriers.  The
+// weight tiles run through a rolling window of eight per wave (8 KiB in
+// flight): the load of tile s+8 is issued as soon as tile s has been consumed,
+// whatever the chunk boundaries do.
+#include <hip/hip_runtime.h>
+
+#include "w2_small_common.h"
+
+namespace w2 {
+
+namespace midm {
+
+constexpr int THREADS = 512;
+constexpr int CHUNK_TILES = 4;                               // k tiles per LDS chunk
+constexpr int ROW_STRIDE = CHUNK_TILES * TILE_K + XS_PAD;    // bytes per LDS activation row
+constexpr int D = 8;                                         // weight tiles in flight per wave
+
+template <int G, int RT, int TPC, bool DBG>
+__global__ void __launch_bounds__(THREADS)
+a8_midm_kernel(A8Args a)
+{
+    constexpr int KS = CHUNK_TILES / TPC;                    // k-splits
+    constexpr int CBW = 8 / KS;                              // column blocks per workgroup
+    constexpr int NS = 2 * RT;                               // 16-byte activation pieces per thread and chunk
+    constexpr int GPT = TILE_K / G;
+    extern __shared__ __align__(16) int8_t smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int cbi = wave % CBW, ks = wave / CBW;
+    const int q = lane >> 4, l16 = lane & 15;
+    const int64_t cb = (int64_t)blockIdx.x * CBW + cbi;
+    const bool cb_ok = cb < a.n_cb;
+    const int64_t cbc = cb_ok ? cb : a.n_cb - 1;             // clamp: keeps loads in bounds
+    const int64_t n = cb * TILE_N + l16;
+    const int rows = (int)a.M;                               // 1..16*RT
+    const int n_chunks = (int)((a.n_kt + CHUNK_TILES - 1) / CHUNK_TILES);
+    (void)n;
+
+    int arow[RT];                                            // padded rows repeat the last
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) arow[rt] = (rt * 16 + l16 < rows ? rt * 16 + l16 : rows - 1) * ROW_STRIDE;
+
+    // Dequant as in the tiled kernel: every group starts from BIAS = 2^21 (third MFMA operand), so
+    // acc = BIAS + 64*sum is positive and below 2^23 and its bit pattern read as binary32 is the
+    // denormal acc * 2^-149: y += as_float(acc) * (sw * 2^64) is ONE fma per accumulator, no
+    // int->float conversion.  The bias term 2^-128 * (sum of the scaled scales) is taken out every
+    // few tiles and at the end.  Two accumulator sets alternate between groups, and a finished
+    // group is dequantised right after the next group's first matrix instructions have been
+    // issued, so that the vector work runs under them.
+    constexpr int BIAS = 1 << 21;                            // > 64 * 127 * 2 * 128
+    const v4i biasv = {BIAS, BIAS, BIAS, BIAS};
+    float y[RT][4];
+    v4i acc[2][RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        acc[0][rt] = biasv;
+        acc[1][rt] = biasv;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) y[rt][r] = 0.f;
+    }
+    float ssum = 0.f;                                        // sum of sw * 2^64 over the groups folded into y
+    float pend_sw = 0.f;                                     // the finished group waiting in acc[1]: none yet
+    int64_t pend_g = 0;
+
+    // activation chunk c -> registers.  Every slot always loads (no branch around a load: with
+    // loads under a condition the compiler cannot count how many are in flight, and its waits
+    // for older registers then also wait for loads just issued): slots past the end of the chunk,
+    // and every slot once there is no further chunk (real == false), re-read pieces of row 0,
+    // which another slot of the same workgroup fetches anyway.
+    // Piece i of a chunk is 16 bytes: row i / 64, bytes 16 * (i % 64) of the row's 1024 (shifts, no
+    // division); in a last, shorter chunk the pieces past its end re-read its last valid piece and
+    // land in LDS bytes nobody reads.
+    uint4 xs[NS];
+    constexpr int VPR = CHUNK_TILES * TILE_K / 16;           // pieces per full row: 64
+    auto load_x = [&](int c, bool real) {
+        const int cc = real ? c : 0;
+        const int len_tiles = (int)min((int64_t)CHUNK_TILES, a.n_kt - (int64_t)cc * CHUNK_TILES);
+        const int v_last = len_tiles * (TILE_K / 16) - 1;
+        const unsigned total = real ? rows * VPR : 0;
+        const int8_t* src = a.xq + (int64_t)cc * CHUNK_TILES * TILE_K;
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            xs[j] = make_uint4(0, 0, 0, 0);                  // (a dead store that keeps xs in registers)
+            const unsigned i = threadIdx.x + j * THREADS;
+            const int row = i < total ? (int)(i / VPR) : 0;
+            const int v = min((int)(i % VPR), v_last);
+            xs[j] = *reinterpret_cast<const uint4*>(src + (int64_t)row * a.K + v * 16);
+        }
+        __builtin_amdgcn_sched_barrier(0);                   // the loads stay here, ahead of the arithmetic
+    };
+    auto store_x = [&]() {
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const int i = threadIdx.x + j * THREADS;
+            if (i < rows * VPR) *reinterpret_cast<uint4*>(smem + (i / VPR) * ROW_STRIDE + (i % VPR) * 16) = xs[j];
+        }
+    };
+    // tile s of this wave is k tile ks + s*KS
+    auto load_w = [&](int64_t s) {
+        int64_t kt = ks + s * KS;
+        kt = kt < a.n_kt ? kt : a.n_kt - 1;
+        return load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt, lane);
+    };
+    // y += as_float(acc[b]) * sw for the group waiting in accumulator set b
+    auto dequant = [&](int b) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if constexpr (DBG) {
+                    const int m = rt * 16 + 4 * q + r;
+                    if (pend_sw != 0.f && cb_ok && n < a.N && m < a.M)
+                        a.acc_out[((int64_t)m * (a.K / G) + pend_g) * a.N + n] = (acc[b][rt][r] - BIAS) >> 6;
+                }
+                y[rt][r] = fmaf(__int_as_float(acc[b][rt][r]), pend_sw, y[rt][r]);
+            }
+        ssum += pend_sw;
+    };
+    auto compute = [&](const TileRegs& cur, int64_t kt, int kt_in_chunk) {
+        const int8_t* xk = smem + kt_in_chunk * TILE_K + q * 16;
+        const uint32_t wd[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
+        v4i aop[2][RT];                                      // A operands of this 64-k step and the next
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) aop[0][rt] = *reinterpret_cast<const v4i*>(xk + arow[rt]);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (t < 3) {
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    aop[(t + 1) & 1][rt] = *reinterpret_cast<const v4i*>(xk + arow[rt] + (t + 1) * 64);
+            }
+            int u[4];
+            upconvert(wd[t], u);
+            const v4i bop = {u[0], u[1], u[2], u[3]};
+            const int gi = G == 64 ? t : t >> 1;             // group inside the tile
+            const int b = gi & 1;                            // its accumulator set
+            const bool first = G == 64 || !(t & 1);
+            const bool last = G == 64 || (t & 1);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+                acc[b][rt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[t & 1][rt], bop, first ? biasv : acc[b][rt], 0, 0, 0);
+            if (first) dequant(b ^ 1);                       // the group before this one, under these MFMAs
+            if (last) {
+                pend_sw = DBG ? 1.0f : tile_scale<G>(cur, gi) * 0x1p64f;
+                pend_g = kt * GPT + gi;
+            }
+        }
+    };
+    // take the accumulated bias term out of y (keeps the rounding error near 2^-15 of the result)
+    auto settle = [&]() {
+        const float corr = ssum * 0x1p-128f;                 // BIAS * 2^-149 = 2^-128
+        ssum = 0.f;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) y[rt][r] -= corr;
+    };
+
+    // activation loads first, then the weight window: vector memory returns in order, so the
+    // wait for the activations does not wait for the weights behind them
+    load_x(0, true);
+    TileRegs tr[D];
+#pragma unroll
+    for (int i = 0; i < D; ++i) tr[i] = load_w(i);
+    __builtin_amdgcn_sched_barrier(0);
+
+    const int64_t s_total = (int64_t)n_chunks * TPC;         // the same for every wave: barriers match
+    for (int64_t s0 = 0; s0 < s_total; s0 += D) {
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            const int64_t s = s0 + i;
+            const int c = (int)(s / TPC);
+            if (i % TPC == 0) {
+                if (c >= n_chunks) break;
+                if (c > 0) __syncthreads();                  // everyone is done reading chunk c-1
+                store_x();
+                __syncthreads();
+                load_x(c + 1, c + 1 < n_chunks);
+            }
+            const int64_t kt = ks + s * KS;
+            if (kt < a.n_kt) compute(tr[i], kt, (int)(kt - (int64_t)c * CHUNK_TILES));
+            if ((i & 3) == 3) settle();                      // every 8 (G=128) or 16 (G=64) groups
+            tr[i] = load_w(s + D);                           // past the end: re-reads the last tile
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    dequant(1);                                             // the last group (GPT is even: it sits in set 1)
+    if constexpr (DBG) return;
+    settle();
+
+    __syncthreads();                                        // activations no longer needed
+    float* red = reinterpret_cast<float*>(smem);            // [waves][16*RT m][16 n]
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[((wave * RT + rt) * 16 + 4 * q + r) * 16 + l16] = y[rt][r] * 0x1p79f;   // 2^(149-64-6)
+    __syncthreads();
+    const int outs = CBW * rows * 16;
+    for (int i = threadIdx.x; i < outs; i += THREADS) {
+        const int nl = i & 15, m = (i >> 4) % rows, ci = i / (16 * rows);
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < KS; ++k) s += red[((k * CBW + ci) * (RT * 16) + m) * 16 + nl];
+        const int64_t nn = ((int64_t)blockIdx.x * CBW + ci) * TILE_N + nl;
+        if (nn < a.N) a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * a.sx[m]);
+    }
+}
+
+template <int G, int RT, int TPC>
+static int launch_t(const A8Args& a, hipStream_t stream)
+{
+    constexpr int CBW = 2 * TPC;
+    const size_t act = (size_t)a.M * ROW_STRIDE;
+    const size_t red = (size_t)8 * RT * 16 * 16 * sizeof(float);
+    const size_t lds = act > red ? act : red;
+    const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW)), block(THREADS);
+    auto go = [&](auto kern) {
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) {
+                set_error("w2_matmul_a8[midm]: hipFuncSetAttribute(%zu): %s", lds, hipGetErrorString(e));
+                return -5;
+            }
+        }
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
+        return check_launch("w2_matmul_a8[midm]");
+    };
+    if (a.acc_out) return go(a8_midm_kernel<G, RT, TPC, true>);
+    return go(a8_midm_kernel<G, RT, TPC, false>);
+}
+
+template <int G, int RT>
+static int launch_rt(const A8Args& a, hipStream_t stream)
+{
+    // column blocks per workgroup: as many as still leave at least 128 workgroups, since every
+    // workgroup reads all M rows of the activations (fewer, wider workgroups move less through L2)
+    int cbw = env_int("W2_MIDM_CBW", 0);
+    if (cbw != 2 && cbw != 4 && cbw != 8) cbw = a.n_cb >= 8 * 128 ? 8 : a.n_cb >= 4 * 128 ? 4 : 2;
+    if (cbw == 8) return launch_t<G, RT, 4>(a, stream);
+    if (cbw == 4) return launch_t<G, RT, 2>(a, stream);
+    return launch_t<G, RT, 1>(a, stream);
+}
+
+template <int G>
+static int launch_g(const A8Args& a, hipStream_t stream)
+{
+    if (a.M <= 32) return launch_rt<G, 2>(a, stream);
+    return launch_rt<G, 4>(a, stream);                       // eight row tiles would not fit the registers
+}
+
+}  // namespace midm
+
+bool a8_midm_supports(const A8Args& a) { return a.M >= 1 && a.M <= 64; }
+
+int launch_a8_midm(const A8Args& a, hipStream_t stream)
+{
+    return a.G == 128 ? midm::launch_g<128>(a, stream) : midm::launch_g<64>(a, stream);
+}
+
+}  // namespace w2

@@ -38,6 +38,8 @@ bool a8_dot4_supports(const A8Args& a);
 int launch_a8_dot4(const A8Args& a, hipStream_t stream);
 bool a8_smallm_supports(const A8Args& a);
 int launch_a8_smallm(const A8Args& a, hipStream_t stream);
+bool a8_midm_supports(const A8Args& a);
+int launch_a8_midm(const A8Args& a, hipStream_t stream);
 int launch_a8_tiled(const A8Args& a, hipStream_t stream);
 
 int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x_is_bf16, int64_t ldx,
