@@ -74,44 +74,68 @@ a8_midm_kernel(A8Args a)
     float pend_sw = 0.f;                                     // the finished group waiting in acc[1]: none yet
     int64_t pend_g = 0;
 
-    // activation chunk c -> registers.  Every slot always loads (no branch around a load: with
-    // loads under a condition the compiler cannot count how many are in flight, and its waits
-    // for older registers then also wait for loads just issued): slots past the end of the chunk,
-    // and every slot once there is no further chunk (real == false), re-read pieces of row 0,
-    // which another slot of the same workgroup fetches anyway.
-    // Piece i of a chunk is 16 bytes: row i / 64, bytes 16 * (i % 64) of the row's 1024 (shifts, no
-    // division); in a last, shorter chunk the pieces past its end re-read its last valid piece and
-    // land in LDS bytes nobody reads.
+    // Activation chunks -> registers -> LDS.  Chunk c starts at k tile min(4c, n_kt - 4), so every
+    // chunk is 1024 k wide (the last one overlaps its predecessor when K is not a multiple of 1024;
+    // a K below 1024 is one narrower chunk) and a thread's pieces sit at the same offsets in every
+    // chunk: piece i = 16 bytes, row i / 64, bytes 16 * (i % 64) of the row; both offsets are
+    // computed once.  Every slot always loads (no branch around a load: with loads under a
+    // condition the compiler cannot count how many are in flight, and its waits for older
+    // registers then also wait for loads just issued): slots past the last row, and every slot
+    // once there is no further chunk (real == false), re-read pieces of row 0.
     uint4 xs[NS];
     constexpr int VPR = CHUNK_TILES * TILE_K / 16;           // pieces per full row: 64
+    const int64_t last_base = a.n_kt > CHUNK_TILES ? a.n_kt - CHUNK_TILES : 0;
+    uint32_t goff[NS], loff[NS];
+    {
+        const int v_last = (int)min((int64_t)CHUNK_TILES, a.n_kt) * (TILE_K / 16) - 1;
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const unsigned i = threadIdx.x + j * THREADS;
+            const unsigned row = i < (unsigned)(rows * VPR) ? i / VPR : 0;
+            const unsigned v = min(i % VPR, (unsigned)v_last);
+            goff[j] = row * (uint32_t)a.K + v * 16;          // < 64 K: fits 32 bits (K <= 2^24)
+            loff[j] = (i / VPR) * ROW_STRIDE + (i % VPR) * 16;
+        }
+    }
+    auto chunk_base = [&](int c) { return min((int64_t)c * CHUNK_TILES, last_base); };
     auto load_x = [&](int c, bool real) {
-        const int cc = real ? c : 0;
-        const int len_tiles = (int)min((int64_t)CHUNK_TILES, a.n_kt - (int64_t)cc * CHUNK_TILES);
-        const int v_last = len_tiles * (TILE_K / 16) - 1;
-        const unsigned total = real ? rows * VPR : 0;
-        const int8_t* src = a.xq + (int64_t)cc * CHUNK_TILES * TILE_K;
+        const int8_t* src = a.xq + (real ? chunk_base(c) : 0) * TILE_K;    // uniform
+        // no further chunk: stay inside the first min(K, 1024) bytes of row 0 (x & m <= m)
+        const uint32_t mask = real ? 0xffffffffu : (uint32_t)min((int64_t)CHUNK_TILES * TILE_K, a.K) - 16u;
 #pragma unroll
         for (int j = 0; j < NS; ++j) {
             xs[j] = make_uint4(0, 0, 0, 0);                  // (a dead store that keeps xs in registers)
-            const unsigned i = threadIdx.x + j * THREADS;
-            const int row = i < total ? (int)(i / VPR) : 0;
-            const int v = min((int)(i % VPR), v_last);
-            xs[j] = *reinterpret_cast<const uint4*>(src + (int64_t)row * a.K + v * 16);
+            uint32_t off = goff[j] & mask;
+            asm volatile("" : "+v"(off));                    // keeps "scalar base + 32-bit offset" addressing
+            xs[j] = *reinterpret_cast<const uint4*>(src + off);
         }
         __builtin_amdgcn_sched_barrier(0);                   // the loads stay here, ahead of the arithmetic
     };
     auto store_x = [&]() {
 #pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            const int i = threadIdx.x + j * THREADS;
-            if (i < rows * VPR) *reinterpret_cast<uint4*>(smem + (i / VPR) * ROW_STRIDE + (i % VPR) * 16) = xs[j];
-        }
+        for (int j = 0; j < NS; ++j)
+            if (threadIdx.x + j * THREADS < (unsigned)(rows * VPR)) *reinterpret_cast<uint4*>(smem + loff[j]) = xs[j];
     };
-    // tile s of this wave is k tile ks + s*KS
+    // tile s of this wave is k tile ks + s*KS; its address is a wave-uniform base plus a 32-bit
+    // lane offset, so the loads need no vector address arithmetic
+    uint32_t w_lane = (uint32_t)lane * 16u, s_lane = (uint32_t)l16 * (GPT * 2u);
     auto load_w = [&](int64_t s) {
         int64_t kt = ks + s * KS;
         kt = kt < a.n_kt ? kt : a.n_kt - 1;
-        return load_tile<G>(a.codes, a.scales, cbc * a.n_kt + kt, lane);
+        const int64_t tile = cbc * a.n_kt + kt;
+        const char* wbase = reinterpret_cast<const char*>(a.codes) + tile * (TILE_N * TILE_K / 4);
+        const char* sbase = reinterpret_cast<const char*>(a.scales) + tile * (TILE_N * GPT * 2);
+        asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+        TileRegs r;
+        r.w = *reinterpret_cast<const uint4*>(wbase + w_lane);
+        if constexpr (G == 128) {
+            r.s0 = *reinterpret_cast<const uint32_t*>(sbase + s_lane);
+            r.s1 = 0;
+        } else {
+            const uint2 sc = *reinterpret_cast<const uint2*>(sbase + s_lane);
+            r.s0 = sc.x; r.s1 = sc.y;
+        }
+        return r;
     };
     // y += as_float(acc[b]) * sw for the group waiting in accumulator set b
     auto dequant = [&](int b) {
@@ -190,7 +214,7 @@ a8_midm_kernel(A8Args a)
                 load_x(c + 1, c + 1 < n_chunks);
             }
             const int64_t kt = ks + s * KS;
-            if (kt < a.n_kt) compute(tr[i], kt, (int)(kt - (int64_t)c * CHUNK_TILES));
+            if (kt < a.n_kt) compute(tr[i], kt, (int)(kt - chunk_base(c)));
             if ((i & 3) == 3) settle();                      // every 8 (G=128) or 16 (G=64) groups
             tr[i] = load_w(s + D);                           // past the end: re-reads the last tile
             __builtin_amdgcn_sched_barrier(0);
