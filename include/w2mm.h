@@ -65,12 +65,12 @@ typedef enum {
 } w2_status_t;
 
 /* Kernel families, for w2_matmul_a8_ex / w2_matmul_a16_ex and the debug export.
- * AUTO picks by M (SMALLM for M <= 16, w2a8 only: MIDM for 17 <= M <= 64,
- * else TILED).  DOT4: per-lane v_dot4_i32_i8 with split-K across the waves of
- * a workgroup (M <= 4; kept as the dot-product form of the microkernel,
+ * AUTO picks by M (w2a8: SMALLM for M <= 8, MIDM for 9 <= M <= 64, else TILED;
+ * w2a16: SMALLM for M <= 16, else TILED).  DOT4: per-lane v_dot4_i32_i8
+ * with split-K across the waves of a workgroup (M <= 4; kept as the dot-product form of the microkernel,
  * selectable here).  SMALLM: one 16-row int8 (bf16 for a16) MFMA tile per
  * wave, split-K across waves (M <= 16).  MIDM (w2a8 only): the weight stream
- * is still read once; every streamed tile is multiplied into up to four
+ * is still read once; every streamed tile is multiplied into one to four
  * 16-row MFMA tiles (M <= 64).  TILED: LDS-staged MFMA tiles (any M). */
 typedef enum { W2_VARIANT_AUTO = 0, W2_VARIANT_DOT4 = 1, W2_VARIANT_SMALLM = 2,
                W2_VARIANT_TILED = 3, W2_VARIANT_MIDM = 4 } w2_variant_t;

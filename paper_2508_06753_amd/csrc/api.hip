@@ -178,12 +178,15 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     a.M = M; a.K = K; a.N = N; a.ldy = ldy;
     a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
     if (variant == W2_VARIANT_AUTO) {
-        // measured: the MFMA form is at least as fast as dot4 from M = 1 on
+        // measured: the MFMA form is at least as fast as dot4 from M = 1 on; from M = 9 the
+        // mid-M kernel (one fma per accumulator in the dequant, rolling weight window) is faster
+        // than the small-M one, and up to M = 64 faster than the tiled one
         const int dot4_max = env_int("W2_DOT4_MAX_M", 0);
-        variant = M <= dot4_max && a8_dot4_supports(a) ? W2_VARIANT_DOT4
-                : a8_smallm_supports(a)                 ? W2_VARIANT_SMALLM
-                : M <= env_int("W2_MIDM_MAX_M", 64) && a8_midm_supports(a) ? W2_VARIANT_MIDM
-                                                        : W2_VARIANT_TILED;
+        const int midm_min = env_int("W2_MIDM_MIN_M", 9), midm_max = env_int("W2_MIDM_MAX_M", 64);
+        variant = M <= dot4_max && a8_dot4_supports(a)                       ? W2_VARIANT_DOT4
+                : M >= midm_min && M <= midm_max && a8_midm_supports(a)     ? W2_VARIANT_MIDM
+                : a8_smallm_supports(a)                                      ? W2_VARIANT_SMALLM
+                                                                             : W2_VARIANT_TILED;
     }
     hipStream_t s = (hipStream_t)stream;
     switch (variant) {

@@ -1,4 +1,4 @@
-// w2a8 for medium M (17..64): between the memory-bound GEMV regime and the
+// w2a8 for medium M (9..64): between the memory-bound GEMV regime and the
 // compute-bound GEMM regime of Sec. III-C.  The weight stream is still read
 // exactly once ("up-convert and compute", Sec. II-C): a wave owns one 16-column
 // block and every KS-th 256-k tile of it, up-converts each dword once and feeds
@@ -280,6 +280,7 @@ static int launch_rt(const A8Args& a, hipStream_t stream)
 template <int G>
 static int launch_g(const A8Args& a, hipStream_t stream)
 {
+    if (a.M <= 16) return launch_rt<G, 1>(a, stream);
     if (a.M <= 32) return launch_rt<G, 2>(a, stream);
     return launch_rt<G, 4>(a, stream);                       // eight row tiles would not fit the registers
 }

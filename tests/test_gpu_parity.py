@@ -153,9 +153,9 @@ def test_a8_smallm(w2, M, K, N, G):
 @pytest.mark.parametrize("cbw", [0, 2, 4, 8])
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (2304, 1032), (768, 8)])
-@pytest.mark.parametrize("M", [17, 31, 32, 33, 50, 64])
+@pytest.mark.parametrize("M", [9, 16, 17, 31, 32, 33, 50, 64])
 def test_a8_midm(w2, M, K, N, G, cbw, monkeypatch):
-    # two / four 16-row tiles per streamed weight tile; every split of the eight waves
+    # one / two / four 16-row tiles per streamed weight tile; every split of the eight waves
     # into column blocks x k-splits; K of one chunk, of a ragged last chunk (2304 = 2 x 1024 + 256)
     monkeypatch.setenv("W2_MIDM_CBW", str(cbw))
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_MIDM, seed=M + K + N + G)
@@ -179,7 +179,7 @@ def test_a8_tiled(w2, M, K, N, G):
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G)
 
 
-@pytest.mark.parametrize("M", [1, 4, 16, 17, 64, 65, 130])
+@pytest.mark.parametrize("M", [1, 4, 8, 9, 16, 17, 64, 65, 130])
 def test_a8_auto_dispatch(w2, M):
     run_a8_case(w2, M, 1024, 528, 128, 0, w2.VARIANT_AUTO, seed=M)
 
