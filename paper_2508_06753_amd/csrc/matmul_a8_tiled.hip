@@ -270,20 +270,33 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     if constexpr (DBG) return;
 
     // y_true = (y - BIAS*2^-149 * ssum) * 2^(149-64) * 2^-6 * sx   (2^-128 = BIAS * 2^-149)
+    // Each lane holds single columns of four rows per tile, which would make 2-byte stores in
+    // 32-byte runs; the wave's 64 x 64 result goes through LDS instead (its own 64 x 144 B
+    // region; the barrier at the end of the last stage freed the activation buffers) and leaves
+    // as 16-byte stores, eight lanes per 128-byte row piece.
+    uint16_t* eb = reinterpret_cast<uint16_t*>(smem + wn * A_BUF);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int64_t m = m0 + wm * WM + i * 16 + 4 * q + r;
-            if (m >= a.M) continue;
-            const float s = a.sx[m];
+            const int row = i * 16 + 4 * q + r;
+            const int64_t m = m0 + row;
+            const float s = a.sx[m < a.M ? m : a.M - 1];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int64_t n = n0 + wn * WN + j * 16 + l16;
                 const float v = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f;
-                if (n < a.N) a.Y[m * a.ldy + n] = f32_to_bf16_rne(v * s);
+                eb[row * (A_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(v * s);
             }
         }
+    }
+    // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
+    const int64_t ncol = n0 + wn * WN + (lane & 7) * 8;      // first of this lane's 8 columns
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const int row = p * 8 + (lane >> 3);
+        const int64_t m = m0 + row;
+        const uint4 v = *reinterpret_cast<const uint4*>(smem + wn * A_BUF + row * A_STRIDE + (lane & 7) * 16);
+        if (m < a.M && ncol < a.N) *reinterpret_cast<uint4*>(a.Y + m * a.ldy + ncol) = v;   // N % 8 == 0: all 8 or none
     }
 }
 
@@ -295,7 +308,7 @@ static int launch_tiled(Kern kern, const A8Args& a, hipStream_t stream)
     using namespace tiled;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
-    const size_t lds = 3 * A_BUF;
+    const size_t lds = 4 * A_BUF;                            // three activation stages; four epilogue regions
     int group_m = env_int("W2_TILED_GROUP_M", 8);
     if (group_m < 1) group_m = 1;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(THREADS);
