@@ -25,6 +25,8 @@
 // block), so both MFMA operands are single ds_read_b128.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "w2_small_common.h"
 
 namespace w2 {
@@ -223,21 +225,39 @@ int launch_a16_smallm(const A16Args& a, hipStream_t stream)
 }
 
 // ---------------------------------------------------------------- TILED (bf16 MFMA, any M)
-// Same workgroup / wave geometry as the w2a8 tiled kernel: 128(M) x 256(N) per
-// workgroup, eight waves of 64 x 64, 4 x 4 tiles of v_mfma_f32_16x16x32_bf16.
-// A stage is 64 k: one packed dword per column block and lane (two matrix
-// instructions per tile: even k, odd k), and 128 rows x 128 B of activations in
-// LDS, stored de-interleaved by the copy threads, which also leave the
-// per-row sums of the stage in a ring of four slots for the zero-point term.
+// 64(M) x 256(N) per workgroup, eight waves of 64 x 32: 4 x 2 tiles of
+// v_mfma_f32_16x16x32_bf16 each (32 accumulators + 32 running sums per lane,
+// which leaves the registers for deep prefetch).  A stage is 64 k: one packed dword per column block
+// and lane (two matrix instructions per tile: even k, odd k), and 64 rows x
+// 128 B of activations in LDS, stored de-interleaved by the copy threads, which
+// also leave the per-row sums of the stage in a ring of four slots.
+//
+// The zero-point term costs no instruction per accumulator: a group's
+// accumulators START from -130 * X_g[m] (the third MFMA operand, one value per
+// row, shared by the wave's four column tiles), so that at the group's end
+// acc = sum x*q and the dequant is one fma, y += sw * acc.  For that the row
+// sums of a stage must be in LDS before the group begins: activations are
+// written to LDS two stages ahead (four buffers) and loaded from global memory
+// four stages ahead (two register sets, by the first four waves); weights are
+// loaded three stages ahead (four register sets; the loop is unrolled by four,
+// sets and buffers are indexed by the stage number mod 4).  All loads are issued
+// unconditionally (clamped past the end) and pinned at the top of the stage, so
+// the compiler's wait counts never wait for a load just issued.
 namespace tiled16 {
 
-constexpr int BM = 128, BN = 256, BK = 64;
+constexpr int BM = 64, BN = 256, BK = 64;
+constexpr int CJ = 2;                             // column blocks per wave
 constexpr int THREADS = 512;
+constexpr int COPY_THREADS = 256;                 // 4 per row, one 16-k block (32 B) each
 constexpr int A_STRIDE = BK * 2 + 16;             // bytes per LDS row
 constexpr int A_BUF = BM * A_STRIDE;
-constexpr int XS_OFF = 2 * A_BUF;                 // float xpart[4][BM]
+constexpr int NBUF = 4;
+constexpr int XS_OFF = NBUF * A_BUF;              // float xpart[4][BM]
 constexpr int LDS_BYTES = XS_OFF + 4 * BM * 4;
-constexpr int WM = 64, WN = 64;
+constexpr int WN = 16 * CJ;
+
+struct WSet { uint32_t w[CJ], sc[CJ]; };
+struct ASet { uint4 lo, hi; };
 
 template <int G>
 __global__ void __launch_bounds__(THREADS)
@@ -247,9 +267,9 @@ a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
     float* xpart = reinterpret_cast<float*>(smem + XS_OFF);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wn = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane >> 4, l16 = lane & 15;
+    constexpr int GPT = TILE_K / G;
 
     const int64_t total = (int64_t)tiles_m * tiles_n;
     int64_t id = blockIdx.x;
@@ -262,37 +282,63 @@ a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
     const int64_t tile_n = in_band / gm;
     const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const uint32_t* wp[4];
-    const uint16_t* sp[4];
+    // wave-uniform base pointers of the four column blocks + 32-bit lane offsets
+    const char* wb[CJ];
+    const char* sb[CJ];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        int64_t c = tile_n * (BN / TILE_N) + wn * 4 + j;
+    for (int j = 0; j < CJ; ++j) {
+        int64_t c = tile_n * (BN / TILE_N) + wn * CJ + j;
         c = c < a.n_cb ? c : a.n_cb - 1;                     // clamp: loads stay in bounds
-        wp[j] = a.codes + (c * a.n_kt * 64 + lane) * 4;
-        sp[j] = a.scales + (c * a.n_kt * TILE_N + l16) * (TILE_K / G);
+        wb[j] = reinterpret_cast<const char*>(a.codes + c * a.n_kt * 256);
+        sb[j] = reinterpret_cast<const char*>(a.scales + c * a.n_kt * TILE_N * GPT);
     }
+    uint32_t w_lane = (uint32_t)lane * 16u;
+    uint32_t s_lane = (uint32_t)l16 * (GPT * 2u);
 
-    // copy: 4 threads per row, one 16-k block (32 B) each
-    const int cp_row = tid >> 2, cp_seg = tid & 3;
+    // copy: 4 threads per row, one 16-k block (32 B) each; rows past M repeat the last row
+    const bool copier = tid < COPY_THREADS;                  // waves 0..3 (wave-uniform)
+    const int cp_row = (tid & (COPY_THREADS - 1)) >> 2, cp_seg = tid & 3;
     int64_t cp_m = m0 + cp_row;
-    if (cp_m >= a.M) cp_m = a.M - 1;                         // padded rows repeat the last row
-    const uint16_t* cp_src = a.X + cp_m * a.ldx + cp_seg * 16;
+    if (cp_m >= a.M) cp_m = a.M - 1;
+    const char* cp_base = reinterpret_cast<const char*>(a.X + m0 * a.ldx);               // uniform
+    uint32_t cp_lane = (uint32_t)((cp_m - m0) * a.ldx * 2) + (uint32_t)cp_seg * 32u;     // < 128 ldx: fits 32 bits
     const int cp_dst = cp_row * A_STRIDE + cp_seg * 32;
 
-    v4f acc[4][4];
-    float y[4][4][4];
+    v4f acc[4][CJ];
+    float y[4][CJ][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < CJ; ++j) {
             acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int r = 0; r < 4; ++r) y[i][j][r] = 0.0f;
         }
 
-    // stores one 16-k block de-interleaved and the row's partial sum of this stage
-    auto stage_store = [&](const uint4& lo, const uint4& hi, int buf, int slot) __attribute__((always_inline)) {
-        const uint32_t d[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    const int64_t n_st = a.n_kt * 4;                         // stages of 64 k; a multiple of 4
+    auto load_a = [&](int64_t st, ASet& r) {
+        st = min(st, n_st - 1);
+        const char* p = cp_base + st * (BK * 2);             // uniform
+        asm volatile("" : "+v"(cp_lane));                    // keeps "scalar base + 32-bit offset" addressing
+        r.lo = *reinterpret_cast<const uint4*>(p + cp_lane);
+        r.hi = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
+    };
+    auto load_w = [&](int64_t st, WSet& r) {
+        st = min(st, n_st - 1);
+        const int64_t kt = st >> 2;
+        const int t = (int)(st & 3);
+        const int64_t w_off = kt * 1024 + t * 4;
+        const int64_t s_off = kt * (TILE_N * GPT * 2) + (G == 128 ? (t >> 1) : t) * 2;
+        asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) {
+            r.w[j] = *reinterpret_cast<const uint32_t*>(wb[j] + w_off + w_lane);
+            r.sc[j] = *reinterpret_cast<const uint16_t*>(sb[j] + s_off + s_lane);
+        }
+    };
+    // stores one 16-k block de-interleaved into buffer `buf` and the row's partial sum into ring slot `buf`
+    auto stage_store = [&](const ASet& r, int buf) {
+        const uint32_t d[8] = {r.lo.x, r.lo.y, r.lo.z, r.lo.w, r.hi.x, r.hi.y, r.hi.z, r.hi.w};
         float s = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) s += pair_sum(d[e]);
@@ -307,96 +353,99 @@ a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
         od.y = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
         od.z = __builtin_amdgcn_perm(d[5], d[4], 0x07060302u);
         od.w = __builtin_amdgcn_perm(d[7], d[6], 0x07060302u);
-        uint4* dst = reinterpret_cast<uint4*>(smem + buf * A_BUF + cp_dst);
-        dst[0] = ev;
-        dst[1] = od;
-        if (cp_seg == 0) xpart[slot * BM + cp_row] = s;
-    };
-    auto load_w = [&](int64_t st, uint32_t (&w)[4], uint32_t (&sc)[4]) __attribute__((always_inline)) {
-        const int64_t kt = st >> 2;
-        const int t = (int)(st & 3);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            w[j] = wp[j][kt * 256 + t];
-            if constexpr (G == 128)
-                sc[j] = sp[j][kt * (TILE_N * 2) + (t >> 1)];
-            else
-                sc[j] = sp[j][kt * (TILE_N * 4) + t];
+        if (copier) {
+            uint4* dst = reinterpret_cast<uint4*>(smem + buf * A_BUF + cp_dst);
+            dst[0] = ev;
+            dst[1] = od;
+            if (cp_seg == 0) xpart[buf * BM + cp_row] = s;
         }
     };
 
-    const int64_t n_st = a.n_kt * 4;                         // stages of 64 k
-    uint4 ar0 = *reinterpret_cast<const uint4*>(cp_src);
-    uint4 ar1 = *reinterpret_cast<const uint4*>(cp_src + 8);
-    uint32_t wc[4], sc[4], wnx[4], snx[4];
-    load_w(0, wc, sc);
-    stage_store(ar0, ar1, 0, 0);
+    ASet as0, as1;
+    WSet ws0, ws1, ws2, ws3;
+    load_a(0, as0);
+    load_a(1, as1);
+    load_w(0, ws0);
+    load_w(1, ws1);
+    load_w(2, ws2);
+    stage_store(as0, 0);
+    stage_store(as1, 1);
+    load_a(2, as0);
+    load_a(3, as1);
     __syncthreads();
 
-    const int8_t* a_base = smem + (wm * WM + l16) * A_STRIDE + q * 32;
+    const int8_t* a_base = smem + l16 * A_STRIDE + q * 32;
+    v4f cinit[4];                                            // -130 * X_g for the rows of each row tile
 
-    for (int64_t st = 0; st < n_st; ++st) {
-        const int buf = (int)(st & 1);
-        const bool more = st + 1 < n_st;
-        if (more) {
-            ar0 = *reinterpret_cast<const uint4*>(cp_src + (st + 1) * BK);
-            ar1 = *reinterpret_cast<const uint4*>(cp_src + (st + 1) * BK + 8);
-            load_w(st + 1, wnx, snx);
-        }
-        const int8_t* ab = a_base + buf * A_BUF;
+    // One stage.  T = stage index mod 4 (LDS buffer, ring slot, weight set); `as` holds the
+    // activations of stage st+2 and then receives those of st+4; wfar receives the weights of st+3.
+    auto stage = [&](int64_t st, auto Tc, ASet& as, const WSet& wc, WSet& wfar) {
+        constexpr int T = decltype(Tc)::value;
+        stage_store(as, (T + 2) & 3);                        // activations of stage st+2
+        load_a(st + 4, as);
+        load_w(st + 3, wfar);
+        __builtin_amdgcn_sched_barrier(0);                   // the loads stay up here
+        const int8_t* ab = a_base + T * A_BUF;
         v4i a0[4], a1[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             a0[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE);
             a1[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE + 16);
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            v4i b0, b1;
-            upconvert_bf16(wc[j], b0, b1);
+        constexpr bool group_begin = (G == 64) || !(T & 1);
+        constexpr bool group_end = (G == 64) || (T & 1);
+        if constexpr (group_begin) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                acc[i][j] = mfma_bf16(a0[i], b0, acc[i][j]);
+                v4f xg = *reinterpret_cast<const v4f*>(xpart + T * BM + i * 16 + 4 * q);
+                if constexpr (G == 128) xg += *reinterpret_cast<const v4f*>(xpart + ((T + 1) & 3) * BM + i * 16 + 4 * q);
+                cinit[i] = xg * -ZP;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) {
+            v4i b0, b1;
+            upconvert_bf16(wc.w[j], b0, b1);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[i][j] = mfma_bf16(a0[i], b0, group_begin ? cinit[i] : acc[i][j]);
                 acc[i][j] = mfma_bf16(a1[i], b1, acc[i][j]);
             }
-        }
-        const bool group_end = (G == 64) || (st & 1);
-        if (group_end) {
-            // X_g[m] for this lane's rows: the stage partials of the group (ring slots)
+            if constexpr (group_end) {
+                if (j > 0) {                                 // the previous column's results, under these MFMAs
+                    const float sw = __uint_as_float(wc.sc[j - 1] << 16);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = wm * WM + i * 16 + 4 * q;
-                v4f xg = *reinterpret_cast<const v4f*>(xpart + (int)(st & 3) * BM + row);
-                if constexpr (G == 128) {
-                    const v4f xp = *reinterpret_cast<const v4f*>(xpart + (int)((st - 1) & 3) * BM + row);
-                    xg += xp;
-                }
+                    for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float sw = __uint_as_float(sc[j] << 16);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        y[i][j][r] = fmaf(sw, fmaf(-ZP, xg[r], acc[i][j][r]), y[i][j][r]);
-                    acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+                        for (int r = 0; r < 4; ++r) y[i][j - 1][r] = fmaf(sw, acc[i][j - 1][r], y[i][j - 1][r]);
                 }
             }
         }
-        if (more) {
-            stage_store(ar0, ar1, buf ^ 1, (int)((st + 1) & 3));
+        if constexpr (group_end) {
+            const float sw = __uint_as_float(wc.sc[CJ - 1] << 16);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { wc[j] = wnx[j]; sc[j] = snx[j]; }
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) y[i][CJ - 1][r] = fmaf(sw, acc[i][CJ - 1][r], y[i][CJ - 1][r]);
         }
         __syncthreads();
+    };
+
+    for (int64_t st = 0; st < n_st; st += 4) {
+        stage(st, std::integral_constant<int, 0>{}, as0, ws0, ws3);
+        stage(st + 1, std::integral_constant<int, 1>{}, as1, ws1, ws0);
+        stage(st + 2, std::integral_constant<int, 2>{}, as0, ws2, ws1);
+        stage(st + 3, std::integral_constant<int, 3>{}, as1, ws3, ws2);
     }
 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int64_t m = m0 + wm * WM + i * 16 + 4 * q + r;
+            const int64_t m = m0 + i * 16 + 4 * q + r;
             if (m >= a.M) continue;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < CJ; ++j) {
                 const int64_t n = n0 + wn * WN + j * 16 + l16;
                 if (n < a.N) a.Y[m * a.ldy + n] = f32_to_bf16_rne(y[i][j][r]);
             }
@@ -412,7 +461,7 @@ static int launch_a16_tiled_t(const A16Args& a, hipStream_t stream)
     using namespace tiled16;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
-    int group_m = env_int("W2_TILED_GROUP_M", 4);
+    int group_m = env_int("W2_TILED_GROUP_M", 8);
     if (group_m < 1) group_m = 1;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(THREADS);
     hipLaunchKernelGGL(a16_tiled_kernel<G>, grid, block, LDS_BYTES, stream, a, tiles_m, tiles_n, group_m);

@@ -189,7 +189,13 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
                 y[i][j][r] = fmaf(__int_as_float(acc[i][j][r]), swS, y[i][j][r]);
             }
         }
+        ssum[j] += swS;
     };
+    // The last column block of a group is dequantised under the first matrix instructions of the
+    // NEXT group (its accumulators are not written again before that group reaches the last
+    // column), so no stage ends with vector work that has nothing to hide under.
+    float pend_sw = 0.f;                                     // nothing pending yet: adds BIAS * 0
+    int64_t pend_g = 0;
 
     // One stage: wc holds this stage's weights, wnx receives the next stage's.
     auto stage = [&](int64_t it, int buf, int buf_next, const WStage& wc, WStage& wnx) {
@@ -214,12 +220,9 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
             if constexpr (G == 128) {
                 swS[j][0] = __uint_as_float(wc.s[j] << 16) * 0x1p64f;
                 swS[j][1] = 0.f;
-                ssum[j] += swS[j][0];
             } else {
                 swS[j][0] = __uint_as_float(wc.s[j] << 16) * 0x1p64f;
                 swS[j][1] = __uint_as_float(wc.s[j] & 0xffff0000u) * 0x1p64f;
-                ssum[j] += swS[j][0];
-                ssum[j] += swS[j][1];
             }
         }
 #pragma unroll
@@ -238,8 +241,15 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[i], bop, first ? biasv : acc[i][j], 0, 0, 0);
                 // the previous column's results are ready by now: dequantise them under these MFMAs
                 if (last && j > 0) dequant_col(j - 1, swS[j - 1][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
+                if (first && j == 0) {
+                    if constexpr (DBG) { if (pend_sw != 0.f) dequant_col(3, pend_sw, pend_g); }
+                    else dequant_col(3, pend_sw, pend_g);
+                }
             }
-            if (last) dequant_col(3, swS[3][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
+            if (last) {
+                pend_sw = DBG ? 1.0f : swS[3][G == 64 ? t : 0];
+                pend_g = it * (128 / G) + (G == 64 ? t : 0);
+            }
         }
     };
 
@@ -267,6 +277,7 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         }
         __syncthreads();
     }
+    dequant_col(3, pend_sw, pend_g);                    // the very last group's last column
     if constexpr (DBG) return;
 
     // y_true = (y - BIAS*2^-149 * ssum) * 2^(149-64) * 2^-6 * sx   (2^-128 = BIAS * 2^-149)
