@@ -1,32 +1,37 @@
 // w2a8 for large M (prefill): the compute-bound regime (Sec. III-C, GEMM
 // results) on the int8 matrix cores.  The workgroup / wave tile hierarchy
 // plays the role of the wg_tile / sg_tile split of Sec. II-D, re-derived for
-// CDNA4: a 64(M) x 256(N) workgroup tile, four waves of 64 x 64 (one per SIMD,
-// two workgroups per CU so that their barriers fall at different times), each
-// wave 4 x 4 tiles of v_mfma_i32_16x16x64_i8.  The SIMD issues one vector
-// instruction (matrix ones included) every four clocks or so while a matrix
-// instruction keeps its pipe busy for sixteen, so the loop is written to keep
-// the vector instructions per MFMA low: scalar base + 32-bit lane offset
-// addressing, two alternating register sets for the weights (no copies).
+// CDNA4: a 64(M) x 256(N) workgroup tile, eight waves of 64 x 32 (RI = 4 row
+// tiles x CJ = 2 column blocks of v_mfma_i32_16x16x64_i8; two workgroups per
+// CU, four waves per SIMD).  Measured on MI355X: the chip is power-limited in
+// this kernel (its speed depends on how many operand bits toggle), so what
+// counts is work per result: vector instructions per matrix instruction (the
+// SIMD issues one vector instruction, matrix ones included, every four clocks
+// or so) and bytes moved.
 //   - activations (int8) are staged through LDS, three buffers, 128 k per
-//     stage, rows padded by 16 B so ds_read_b128 is conflict-free;
+//     stage, rows padded by 16 B;
 //   - the 2-bit weights never touch LDS: the packed layout IS the MFMA
 //     B-operand layout, so each lane loads its dwords (64 bits per column
 //     block and stage) straight from global memory and up-converts them in
 //     registers (Sec. II-C "up-convert and compute"), reused across the wave's
-//     four row tiles;
+//     four row tiles; addresses are scalar base + 32-bit lane offset;
+//   - all loads are issued unconditionally (clamped past the end) at the top of
+//     a stage and pinned there: with loads under a condition the compiler
+//     cannot count how many are in flight, and its waits for the previous
+//     stage's registers then also wait for the loads just issued;
 //   - the dequant (Sec. II-D: int32 -> float, x scale) runs once per group of G
-//     k's on the 64 accumulators of a wave and would cost as many VALU slots as
-//     the matrix instructions leave free.  It is done in ONE fma per
-//     accumulator: every group starts from the constant BIAS = 2^21 (a third
-//     MFMA operand, never written), so the int32 result acc = BIAS + 64*sum is
-//     positive and below 2^23, i.e. its bit pattern read as binary32 is the
-//     denormal acc * 2^-149; y += as_float(acc) * (sw * 2^64) needs no int->float
+//     k's on the accumulators of a wave, in ONE fma per accumulator: every
+//     group starts from the constant BIAS = 2^21 (a third MFMA operand, never
+//     written), so the int32 result acc = BIAS + 64*sum is positive and below
+//     2^23, i.e. its bit pattern read as binary32 is the denormal
+//     acc * 2^-149; y += as_float(acc) * (sw * 2^64) needs no int->float
 //     conversion.  The bias term, BIAS * 2^-149 * sum_g sw_g * 2^64, is
 //     subtracted every 8 stages and in the epilogue; while it rides along it
 //     exceeds the wanted sum by about 2^9, which leaves 15 of fp32's 24 bits
 //     for a bf16 result.  The int32 group accumulators themselves stay exact
-//     (acc - BIAS is what the debug export stores).
+//     (acc - BIAS is what the debug export stores).  A column block is
+//     dequantised under the matrix instructions of the next one;
+//   - results leave through LDS as 16-byte stores.
 #include <hip/hip_runtime.h>
 
 #include "w2_internal.h"
@@ -37,11 +42,16 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 namespace tiled {
 
-constexpr int BM = 64, BN = 256, BK = 128;        // BK: k per pipeline stage (half a packed tile)
-constexpr int THREADS = 256;
+constexpr int RI = 4;                             // 16-row tiles per wave
+constexpr int CJ = 2;                             // 16-column blocks per wave
+constexpr int BM = 16 * RI, BN = 256, BK = 128;       // BK: k per pipeline stage (half a packed tile)
+constexpr int WAVES = BN / (16 * CJ);
+constexpr int THREADS = 64 * WAVES;
 constexpr int A_STRIDE = BK + 16;                 // bytes per LDS row
 constexpr int A_BUF = BM * A_STRIDE;              // bytes per stage
-constexpr int WM = 64, WN = 64;                   // wave tile
+constexpr int WM = BM, WN = 16 * CJ;                // wave tile
+constexpr int E_STRIDE = WN * 2 + 16;             // epilogue: bytes per LDS row of a wave's result
+constexpr int WGS_PER_CU = (RI * CJ <= 16 && THREADS <= 256) || (RI * CJ <= 8) ? 2 : 1;
 constexpr int BIAS = 1 << 21;                     // > 64 * 127 * 2 * 128 = 2 080 768
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
@@ -61,17 +71,17 @@ __device__ __forceinline__ v4i upconvert(uint32_t w)
     return u;
 }
 
-// Weights and scales of one stage (128 k) for the wave's four column blocks.
+// Weights and scales of one stage (128 k) for the wave's column blocks.
 struct WStage {
-    uint2 w[4];       // two dwords = two 64-k steps
-    uint32_t s[4];    // G=128: one bf16 scale (low half); G=64: two bf16 scales
+    uint2 w[CJ];      // two dwords = two 64-k steps
+    uint32_t s[CJ];   // G=128: one bf16 scale (low half); G=64: two bf16 scales
 };
 
 // wb[j] / sb[j]: wave-uniform byte pointers to column block j's codes / scales (scalar registers);
 // w_lane / s_lane: this lane's byte offset inside a packed tile.  The stage offset is uniform, so
 // every load is "scalar base + 32-bit lane offset" and costs no vector address arithmetic.
 template <int G>
-__device__ __forceinline__ void load_w(const char* const (&wb)[4], const char* const (&sb)[4],
+__device__ __forceinline__ void load_w(const char* const (&wb)[CJ], const char* const (&sb)[CJ],
                                        uint32_t w_lane, uint32_t s_lane, int64_t it, WStage& r)
 {
     const int64_t kt = it >> 1;
@@ -79,7 +89,7 @@ __device__ __forceinline__ void load_w(const char* const (&wb)[4], const char* c
     const int64_t w_off = (kt * 256 + h * 2) * 4;
     const int64_t s_off = G == 128 ? (kt * (TILE_N * 2) + h) * 2 : (kt * (TILE_N * 4) + h * 2) * 2;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < CJ; ++j) {
         r.w[j] = *reinterpret_cast<const uint2*>(wb[j] + w_off + w_lane);
         if constexpr (G == 128)
             r.s[j] = *reinterpret_cast<const uint16_t*>(sb[j] + s_off + s_lane);
@@ -89,7 +99,7 @@ __device__ __forceinline__ void load_w(const char* const (&wb)[4], const char* c
 }
 
 template <int G, bool DBG>
-__global__ void __launch_bounds__(THREADS, 2)
+__global__ void __launch_bounds__(THREADS, WGS_PER_CU)
 a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 {
     extern __shared__ __align__(16) int8_t smem[];
@@ -116,11 +126,11 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
 
     // per column block: wave-uniform base pointers of its codes and scales
-    const char* wb[4];
-    const char* sb[4];
+    const char* wb[CJ];
+    const char* sb[CJ];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        int64_t c = tile_n * (BN / TILE_N) + wn * 4 + j;
+    for (int j = 0; j < CJ; ++j) {
+        int64_t c = tile_n * (BN / TILE_N) + wn * CJ + j;
         c = c < a.n_cb ? c : a.n_cb - 1;                     // clamp: loads stay in bounds
         wb[j] = reinterpret_cast<const char*>(a.codes + c * a.n_kt * 256);
         sb[j] = reinterpret_cast<const char*>(a.scales + c * a.n_kt * TILE_N * (TILE_K / G));
@@ -130,21 +140,23 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 
     // global -> LDS copy: 4 threads per 128-byte row piece, 32 bytes each.  Rows past M repeat
     // the last row; the lane offset (< 64 K) fits 32 bits.
-    const int cp_row = tid >> 2, cp_seg = tid & 3;
+    constexpr int CPT = THREADS / BM, CPB = BK / CPT;        // threads per row, bytes each: 4 x 32 or 8 x 16
+    static_assert(CPB == 32 || CPB == 16, "copy geometry");
+    const int cp_row = tid / CPT, cp_seg = tid % CPT;
     int64_t cp_m = m0 + cp_row;
     if (cp_m >= a.M) cp_m = a.M - 1;
     const char* cp_base = reinterpret_cast<const char*>(a.xq) + m0 * a.K;          // uniform
-    uint32_t cp_lane = (uint32_t)((cp_m - m0) * a.K) + (uint32_t)cp_seg * 32u;
-    const int cp_dst = cp_row * A_STRIDE + cp_seg * 32;
+    uint32_t cp_lane = (uint32_t)((cp_m - m0) * a.K) + (uint32_t)cp_seg * CPB;
+    const int cp_dst = cp_row * A_STRIDE + cp_seg * CPB;
 
-    v4i acc[4][4];
-    float y[4][4][4];
-    float ssum[4] = {0.f, 0.f, 0.f, 0.f};                    // sum of the scaled group scales per column block
+    v4i acc[RI][CJ];
+    float y[RI][CJ][4];
+    float ssum[CJ] = {};                   // sum of the scaled group scales per column block
     const v4i biasv = {BIAS, BIAS, BIAS, BIAS};
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < CJ; ++j) {
             acc[i][j] = biasv;
 #pragma unroll
             for (int r = 0; r < 4; ++r) y[i][j][r] = 0.0f;
@@ -161,14 +173,14 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         const char* p = cp_base + it * BK;                   // uniform
         asm volatile("" : "+v"(cp_lane));
         r0 = *reinterpret_cast<const uint4*>(p + cp_lane);
-        r1 = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
+        if constexpr (CPB == 32) r1 = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
     };
-    uint4 ar0, ar1;
+    uint4 ar0, ar1 = make_uint4(0, 0, 0, 0);
     WStage w0, w1;
     load_a(0, ar0, ar1);
     load_w<G>(wb, sb, w_lane, s_lane, 0, w0);
     *reinterpret_cast<uint4*>(smem + cp_dst) = ar0;
-    *reinterpret_cast<uint4*>(smem + cp_dst + 16) = ar1;
+    if constexpr (CPB == 32) *reinterpret_cast<uint4*>(smem + cp_dst + 16) = ar1;
     load_a(1, ar0, ar1);
     __syncthreads();
 
@@ -177,7 +189,7 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     // y += as_float(acc) * (sw * 2^64) for one column block, then restart the group
     auto dequant_col = [&](int j, float swS, int64_t g) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < RI; ++i) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 if constexpr (DBG) {
@@ -206,7 +218,7 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         {
             int8_t* dst = smem + buf_next * A_BUF + cp_dst;
             *reinterpret_cast<uint4*>(dst) = ar0;            // activations of stage it+1
-            *reinterpret_cast<uint4*>(dst + 16) = ar1;
+            if constexpr (CPB == 32) *reinterpret_cast<uint4*>(dst + 16) = ar1;
             asm volatile("" : "+v"(w_lane), "+v"(s_lane));
             load_w<G>(wb, sb, w_lane, s_lane, min(it + 1, n_it - 1), wnx);
         }
@@ -214,9 +226,9 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         // keep the loads up here: the scheduler otherwise sinks them to their first use, one stage on
         __builtin_amdgcn_sched_barrier(0);
         const int8_t* ab = a_base + buf * A_BUF;
-        float swS[4][2];
+        float swS[CJ][2];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < CJ; ++j) {
             if constexpr (G == 128) {
                 swS[j][0] = __uint_as_float(wc.s[j] << 16) * 0x1p64f;
                 swS[j][1] = 0.f;
@@ -227,27 +239,27 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            v4i aop[4];
+            v4i aop[RI];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < RI; ++i)
                 aop[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE + t * 64);
             const bool first = (G == 64) || t == 0;          // first k-step of a group starts from BIAS
             const bool last = (G == 64) || t == 1;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < CJ; ++j) {
                 const v4i bop = upconvert(t == 0 ? wc.w[j].x : wc.w[j].y);
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < RI; ++i)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[i], bop, first ? biasv : acc[i][j], 0, 0, 0);
                 // the previous column's results are ready by now: dequantise them under these MFMAs
                 if (last && j > 0) dequant_col(j - 1, swS[j - 1][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
                 if (first && j == 0) {
-                    if constexpr (DBG) { if (pend_sw != 0.f) dequant_col(3, pend_sw, pend_g); }
-                    else dequant_col(3, pend_sw, pend_g);
+                    if constexpr (DBG) { if (pend_sw != 0.f) dequant_col(CJ - 1, pend_sw, pend_g); }
+                    else dequant_col(CJ - 1, pend_sw, pend_g);
                 }
             }
             if (last) {
-                pend_sw = DBG ? 1.0f : swS[3][G == 64 ? t : 0];
+                pend_sw = DBG ? 1.0f : swS[CJ - 1][G == 64 ? t : 0];
                 pend_g = it * (128 / G) + (G == 64 ? t : 0);
             }
         }
@@ -266,47 +278,50 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
             // never carry more than 8 stages of it (keeps the rounding error near 2^-15 of
             // the result, whatever K is)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < CJ; ++j) {
                 const float corr = ssum[j] * 0x1p-128f;     // BIAS * 2^-149 = 2^-128
                 ssum[j] = 0.f;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < RI; ++i)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) y[i][j][r] -= corr;
             }
         }
         __syncthreads();
     }
-    dequant_col(3, pend_sw, pend_g);                    // the very last group's last column
+    dequant_col(CJ - 1, pend_sw, pend_g);                    // the very last group's last column
     if constexpr (DBG) return;
 
     // y_true = (y - BIAS*2^-149 * ssum) * 2^(149-64) * 2^-6 * sx   (2^-128 = BIAS * 2^-149)
     // Each lane holds single columns of four rows per tile, which would make 2-byte stores in
-    // 32-byte runs; the wave's 64 x 64 result goes through LDS instead (its own 64 x 144 B
+    // 32-byte runs; the wave's 64 x 64 result goes through LDS instead (its own
     // region; the barrier at the end of the last stage freed the activation buffers) and leaves
     // as 16-byte stores, eight lanes per 128-byte row piece.
-    uint16_t* eb = reinterpret_cast<uint16_t*>(smem + wn * A_BUF);
+    int8_t* ebase = smem + wn * (BM * E_STRIDE);
+    uint16_t* eb = reinterpret_cast<uint16_t*>(ebase);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < RI; ++i) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = i * 16 + 4 * q + r;
             const int64_t m = m0 + row;
             const float s = a.sx[m < a.M ? m : a.M - 1];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < CJ; ++j) {
                 const float v = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f;
-                eb[row * (A_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(v * s);
+                eb[row * (E_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(v * s);
             }
         }
     }
     // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
-    const int64_t ncol = n0 + wn * WN + (lane & 7) * 8;      // first of this lane's 8 columns
+    constexpr int LPR = WN * 2 / 16;                         // lanes per row piece (16 bytes each)
+    constexpr int RPP = 64 / LPR;                            // rows per pass
+    const int64_t ncol = n0 + wn * WN + (lane % LPR) * 8;    // first of this lane's 8 columns
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-        const int row = p * 8 + (lane >> 3);
+    for (int p = 0; p < BM / RPP; ++p) {
+        const int row = p * RPP + lane / LPR;
         const int64_t m = m0 + row;
-        const uint4 v = *reinterpret_cast<const uint4*>(smem + wn * A_BUF + row * A_STRIDE + (lane & 7) * 16);
+        const uint4 v = *reinterpret_cast<const uint4*>(ebase + row * E_STRIDE + (lane % LPR) * 16);
         if (m < a.M && ncol < a.N) *reinterpret_cast<uint4*>(a.Y + m * a.ldy + ncol) = v;   // N % 8 == 0: all 8 or none
     }
 }
@@ -319,7 +334,8 @@ static int launch_tiled(Kern kern, const A8Args& a, hipStream_t stream)
     using namespace tiled;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
-    const size_t lds = 4 * A_BUF;                            // three activation stages; four epilogue regions
+    const size_t act = 3 * A_BUF, epi = (size_t)WAVES * BM * E_STRIDE;   // three activation stages; the epilogue regions reuse them
+    const size_t lds = act > epi ? act : epi;
     int group_m = env_int("W2_TILED_GROUP_M", 8);
     if (group_m < 1) group_m = 1;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(THREADS);
