@@ -78,6 +78,100 @@ def pmc_mode(torch, w2, lib, vp, pool, shapes, Xd, Yd, dev):
     print("bench.py --pmc: launched copy x3 (256 MiB), stream read and fused GEMV x%d, prefill x3" % len(pool))
 
 
+def sweep_mode(torch, w2, synth, dev):
+    """One line per (configuration, projection, M, call): microseconds per launch, the method's own
+    bytes / time (GB/s, % of 8 TB/s) for M <= 64, ops / time (TOP/s, % of the MFMA peak) above."""
+    def pool_for(K, N, g):
+        nb = w2.packed_size(K, N, g)
+        n = max(2, -(-POOL_BYTES // nb))
+        base = torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev)      # any bytes are valid codes
+        base[K * N // 4:].view(torch.int16)[:] = 0x3C00                         # scales region: finite bf16
+        return [base] + [base.clone() for _ in range(n - 1)]
+
+    def timed(fn, pool, reps=6):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for l in pool:
+                fn(l)
+        t_end = time.perf_counter() + 0.1
+        while time.perf_counter() < t_end:
+            g.replay()
+            torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * len(pool))
+
+    def line(cfg, name, K, N, g, M, call, us):
+        if M <= 64:
+            act = {"a8": M * K, "a8 fused(f32 in)": 4 * M * K, "a16": 2 * M * K, "stream read": 0}[call]
+            by = K * N // 4 + (K // g) * N * 2 + act + (0 if call == "stream read" else 2 * M * N)
+            rate = "%8.1f GB/s %5.1f%% of 8 TB/s" % (by / us / 1e3, by / us / 1e3 / HBM_PEAK_GBS * 100)
+        else:
+            tops = 2.0 * M * K * N / us / 1e6
+            peak = 2500.0 if call == "a16" else INT8_PEAK_TOPS
+            rate = "%8.1f TOP/s %5.1f%% of %.1f POP/s" % (tops, tops / peak * 100, peak / 1e3)
+        print("%-6s %-8s K=%5d N=%5d G=%3d M=%4d %-17s %9.2f us  %s" % (cfg, name, K, N, g, M, call, us, rate), flush=True)
+
+    def decode_case(cfg, name, K, N, g, Ms, calls):
+        pool = pool_for(K, N, g)
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        if "stream read" in calls:
+            line(cfg, name, K, N, g, 1, "stream read", timed(lambda l: w2.debug_stream_read(l, sink), pool))
+        for M in Ms:
+            X = torch.randn(M, K, device=dev)
+            xq, sx, _ = w2.quantize_rows(X, g)
+            Xb = X.to(torch.bfloat16)
+            Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            if "a8" in calls:
+                line(cfg, name, K, N, g, M, "a8", timed(lambda l: w2.matmul_a8(l, K, N, g, xq, sx, out=Y), pool))
+            if "fused" in calls:
+                nws = w2.workspace_size(M, K, N, g)
+                ws = torch.empty(nws, dtype=torch.uint8, device=dev) if nws else None
+                line(cfg, name, K, N, g, M, "a8 fused(f32 in)",
+                     timed(lambda l: w2.matmul_a8_fused(l, K, N, g, X, out=Y, workspace=ws), pool))
+            if "a16" in calls:
+                line(cfg, name, K, N, g, M, "a16", timed(lambda l: w2.matmul_a16(l, K, N, g, Xb, out=Y), pool))
+        del pool
+
+    print("# every launch reads a different prepacked copy (pool > 2 x 256 MB last-level cache); times are per launch "
+          "inside a replayed HIP graph, gaps between launches included")
+    decode_case("cfg0", "single", 2048, 2048, 128, (1,), ("a8", "fused", "stream read"))
+    for name, (K, N) in synth.SHAPES_8B.items():
+        decode_case("cfg1", name, K, N, 128, (1, 4), ("a8", "fused", "a16", "stream read"))
+    for g in (128, 64):
+        decode_case("cfg2", "gate_up", 4096, 28672, g, (1, 2, 4, 8, 16, 32, 64), ("a8",))
+    for name, (K, N) in synth.SHAPES_27B.items():
+        decode_case("cfg3", name, K, N, 128, (1, 8), ("a8", "fused", "stream read"))
+    print("# prefill: 40 launches to warm the clock up, 20 timed")
+    for name, (K, N) in synth.SHAPES_70B.items():
+        nb = w2.packed_size(K, N, G)
+        pk = torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev)
+        pk[K * N // 4:].view(torch.int16)[:] = 0x3C00
+        for M in (512, 2048):
+            X = torch.randn(M, K, device=dev)
+            xq, sx, _ = w2.quantize_rows(X, G)
+            Xb = X.to(torch.bfloat16)
+            del X
+            Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            for call, fn in (("a8", lambda: w2.matmul_a8(pk, K, N, G, xq, sx, out=Y)),
+                             ("a16", lambda: w2.matmul_a16(pk, K, N, G, Xb, out=Y))):
+                for _ in range(40 if call == "a8" else 15):
+                    fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                n = 20 if call == "a8" else 8
+                e0.record()
+                for _ in range(n):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                line("cfg4", name, K, N, G, M, call, e0.elapsed_time(e1) * 1e3 / n)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +183,10 @@ def main():
                     help="counter-collection mode for `rocprofv3 --pmc`: launch, eagerly and a few times each, a plain "
                          "256 MiB device copy (the calibration kernel), the streaming read, the dominant GEMV over "
                          "the pool and the prefill kernel; print no bench line")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time every configuration BASELINE.json lists (decode shapes from HIP graphs over a pool "
+                         "of distinct weight copies, prefill shapes under sustained launches) and print a table "
+                         "instead of the bench line")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -101,6 +199,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.sweep:
+        return sweep_mode(torch, w2, synth, dev)
     M = 1
     shapes = synth.SHAPES_8B
 

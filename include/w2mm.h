@@ -65,7 +65,8 @@ typedef enum {
 } w2_status_t;
 
 /* Kernel families, for w2_matmul_a8_ex / w2_matmul_a16_ex and the debug export.
- * AUTO picks by M (w2a8: SMALLM for M <= 8, MIDM for 9 <= M <= 64, else TILED;
+ * AUTO picks by M (w2a8: SMALLM for M <= 8 (M <= 3 when N >= 6144 or K > 16384), MIDM up to
+ * M = 64, else TILED;
  * w2a16: SMALLM for M <= 16, else TILED).  DOT4: per-lane v_dot4_i32_i8
  * with split-K across the waves of a workgroup (M <= 4; kept as the dot-product form of the microkernel,
  * selectable here).  SMALLM: one 16-row int8 (bf16 for a16) MFMA tile per
@@ -124,8 +125,8 @@ W2_API int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_
  * packed  dev, from w2_prepack with the same K, N, G
  * xq, sx  dev, as produced by w2_quantize_rows ([M][K] dense, [M])
  * Y       dev, bf16 bit patterns [M][N], row stride ldy
- * workspace  unused by the current kernels (split-K is reduced inside a
- *            workgroup); pass NULL / 0.  w2_workspace_size reports 0. */
+ * workspace  unused by this call (split-K is reduced inside a workgroup);
+ *            pass NULL / 0. */
 W2_API int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
                  const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                  size_t workspace_bytes, void* stream);
@@ -136,14 +137,21 @@ W2_API int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, cons
                     const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                     size_t workspace_bytes, int variant, void* stream);
 
-/* Fused variant for M <= 4 (Sec. II-D: activation quantisation fused into the
- * GEMM kernel; the abs-max is reduced per workgroup, redundantly, and kept in
- * local memory; Sec. III-C: fusing wins for matrix-vector shapes).  Takes the
- * unquantised activations (fp32 or bf16, row stride ldx) and produces exactly
- * what w2_quantize_rows followed by w2_matmul_a8 produces, bit for bit, in one
- * launch.  Returns W2_ERR_UNSUPPORTED_SHAPE (nothing launched) when M > 4 or
- * the rows do not fit a workgroup's local memory (M*K*elem_size beyond about
- * 64 KiB); use the two-call path then. */
+/* The int2 x {fp32, bf16} -> bf16 call (Sec. II-D: activation quantisation
+ * fused into the GEMM; Sec. III-C: fusing wins for matrix-vector shapes, a
+ * separate abs-max pass for multi-row activations).  Takes the unquantised
+ * activations (fp32 or bf16, row stride ldx) and produces exactly what
+ * w2_quantize_rows followed by w2_matmul_a8 produces, bit for bit.
+ *   M <= 2: one launch; the abs-max is reduced per workgroup, redundantly, and
+ *           kept in local memory.
+ *   M >= 3: with a workspace of w2_workspace_size(M, K, N, G, 0) bytes (dev,
+ *           16-byte aligned; holds the int8 rows and their scales, contents
+ *           undefined afterwards) two launches: quantise, then the kernel family
+ *           w2_matmul_a8 picks for M.  Without one, M <= 4 still runs as one
+ *           launch (slower than two from M = 3 on) as long as the rows fit a
+ *           workgroup's local memory (M*K*elem_size up to about 64 KiB);
+ *           otherwise W2_ERR_UNSUPPORTED_SHAPE, nothing launched.  A workspace
+ *           that is too small for M > 4 gives W2_ERR_BUFFER_TOO_SMALL. */
 W2_API int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const void* X,
                               w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
                               void* workspace, size_t workspace_bytes, void* stream);
@@ -162,8 +170,10 @@ W2_API int w2_matmul_a16_ex(const void* packed, int64_t K, int64_t N, int G, con
                      int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                      size_t workspace_bytes, int variant, void* stream);
 
-/* Bytes of workspace the matmul calls need for this problem (host out-pointer).
- * a16: 0 = w2a8, 1 = w2a16. */
+/* Bytes of workspace (host out-pointer) with which w2_matmul_a8_fused takes its
+ * fastest route for this problem (a16 = 0): 0 where one launch covers it (one
+ * or two rows of up to 64 KiB as fp32), else room for the int8 rows and their
+ * scales.  The other matmul calls need none (a16 = 1: 0). */
 W2_API int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* bytes);
 
 /* ------------------------------------------------------------------------

@@ -151,8 +151,9 @@ def matmul_a8(packed, K, N, G, xq, sx, out=None, variant=VARIANT_AUTO):
     return Y
 
 
-def matmul_a8_fused(packed, K, N, G, X, out=None):
-    """Y bf16 [M,N] from unquantised X (fp32 or bf16) in one launch, M <= 4."""
+def matmul_a8_fused(packed, K, N, G, X, out=None, workspace=None):
+    """Y bf16 [M,N] from unquantised X (fp32 or bf16); `workspace`: a uint8 device tensor of
+    workspace_size(M, K, N, G) bytes, needed for M > 4 and faster from M = 3 on."""
     if X.dtype == torch.float32:
         dt = DT_F32
     elif X.dtype == torch.bfloat16:
@@ -165,8 +166,9 @@ def matmul_a8_fused(packed, K, N, G, X, out=None):
     Y = out if out is not None else torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
     ldx = X.stride(0) if M > 1 else K
     ldy = Y.stride(0) if M > 1 else N
+    ws, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), workspace.numel() * workspace.element_size())
     _check("w2_matmul_a8_fused", _lib.w2_matmul_a8_fused(_ptr(packed), K, N, G, _ptr(X), dt, ldx, M,
-                                                         _ptr(Y), ldy, None, 0, _stream()))
+                                                         _ptr(Y), ldy, ws, ws_bytes, _stream()))
     return Y
 
 

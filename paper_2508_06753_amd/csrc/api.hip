@@ -178,11 +178,13 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     a.M = M; a.K = K; a.N = N; a.ldy = ldy;
     a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
     if (variant == W2_VARIANT_AUTO) {
-        // measured: the MFMA form is at least as fast as dot4 from M = 1 on; from M = 9 the
-        // mid-M kernel (one fma per accumulator in the dequant, rolling weight window) is faster
-        // than the small-M one, and up to M = 64 faster than the tiled one
+        // measured: the MFMA form is at least as fast as dot4 from M = 1 on; the mid-M kernel (one
+        // fma per accumulator in the dequant, rolling weight window; its time hardly grows with M)
+        // overtakes the small-M one at M = 4 on wide or very deep projections and at M = 9 on narrow ones (few
+        // column blocks: it then splits K four ways with a barrier pair per tile), and is faster
+        // than the tiled one up to M = 64
         const int dot4_max = env_int("W2_DOT4_MAX_M", 0);
-        const int midm_min = env_int("W2_MIDM_MIN_M", 9), midm_max = env_int("W2_MIDM_MAX_M", 64);
+        const int midm_min = env_int("W2_MIDM_MIN_M", (a.n_cb >= 384 || a.n_kt > 64) ? 4 : 9), midm_max = env_int("W2_MIDM_MAX_M", 64);
         variant = M <= dot4_max && a8_dot4_supports(a)                       ? W2_VARIANT_DOT4
                 : M >= midm_min && M <= midm_max && a8_midm_supports(a)     ? W2_VARIANT_MIDM
                 : a8_smallm_supports(a)                                      ? W2_VARIANT_SMALLM
@@ -220,11 +222,16 @@ int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* 
                            W2_VARIANT_AUTO, stream);
 }
 
+// Workspace that lets w2_matmul_a8_fused take the two-kernel route: int8 rows + one scale per row.
+static size_t fused_workspace_bytes(int64_t M, int64_t K)
+{
+    return (size_t)((M * K + 15) & ~(int64_t)15) + (size_t)M * sizeof(float);
+}
+
 int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const void* X,
                        w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
                        void* workspace, size_t workspace_bytes, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
     const char* fn = "w2_matmul_a8_fused";
     int rc = check_shape(fn, K, N, G);
     if (rc) return rc;
@@ -237,9 +244,26 @@ int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const vo
         return fail(W2_ERR_MISALIGNED, "%s: packed, X and Y must be 16-byte aligned", fn);
     if (ldx < K || ldx % 8 || ldy < N || ldy % 8)
         return fail(W2_ERR_MISALIGNED, "%s: ldx >= K, ldy >= N, both multiples of 8", fn);
+    if (workspace && !aligned16(workspace))
+        return fail(W2_ERR_MISALIGNED, "%s: workspace must be 16-byte aligned", fn);
     const Layout L = make_layout(K, N, G);
-    return launch_a8_fusedq(packed, (const char*)packed + L.codes_bytes, X, x_dtype == W2_DT_BF16, ldx,
-                            M, K, N, G, L.n_cb, L.n_kt, Y, ldy, (hipStream_t)stream);
+    // Measured: one launch with the abs-max reduced per workgroup wins for one or two rows; from
+    // three rows on every workgroup re-reading and re-quantising all rows costs more than a
+    // separate quantise launch (the paper's finding for multi-row activations, Sec. III-C).
+    const bool ws_ok = workspace && workspace_bytes >= fused_workspace_bytes(M, K);
+    if (M <= 2 || !ws_ok) {
+        if (M > 4 && workspace)
+            return fail(W2_ERR_BUFFER_TOO_SMALL, "%s: M = %lld needs a workspace of %zu bytes (w2_workspace_size)",
+                        fn, (long long)M, fused_workspace_bytes(M, K));
+        rc = launch_a8_fusedq(packed, (const char*)packed + L.codes_bytes, X, x_dtype == W2_DT_BF16, ldx,
+                              M, K, N, G, L.n_cb, L.n_kt, Y, ldy, (hipStream_t)stream);
+        if (rc != W2_ERR_UNSUPPORTED_SHAPE || !ws_ok) return rc;
+    }
+    int8_t* xq = (int8_t*)workspace;
+    float* sx = (float*)((char*)workspace + ((M * K + 15) & ~(int64_t)15));
+    rc = launch_quantize(X, x_dtype == W2_DT_BF16, M, K, ldx, G, xq, sx, nullptr, (hipStream_t)stream);
+    if (rc) return rc;
+    return a8_common(fn, packed, K, N, G, xq, sx, M, Y, ldy, nullptr, W2_VARIANT_AUTO, stream);
 }
 
 int w2_debug_group_acc_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
@@ -299,11 +323,13 @@ int w2_matmul_a16(const void* packed, int64_t K, int64_t N, int G, const uint16_
 
 int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* bytes)
 {
-    (void)M; (void)a16;
     if (!bytes) return fail(W2_ERR_INVALID_ARG, "w2_workspace_size: bytes is NULL");
     int rc = check_shape("w2_workspace_size", K, N, G);
     if (rc) return rc;
-    *bytes = 0;
+    if (M < 0) return fail(W2_ERR_INVALID_ARG, "w2_workspace_size: M < 0");
+    // one or two rows of up to 64 KiB (as fp32) run as a single launch and need none
+    const bool single = M <= 2 && M * K * 4 <= 64 * 1024;
+    *bytes = (a16 || M == 0 || single) ? 0 : fused_workspace_bytes(M, K);
     return W2_OK;
 }
 

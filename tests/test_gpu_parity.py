@@ -265,8 +265,38 @@ def test_a8_fused_rejects_large_m(w2):
     codes, scales, X = synth.make_problem(5, 256, 16, 128, 0, 1)
     packed = w2.prepack(dev(codes), dev(scales), 128, 0)
     with pytest.raises(w2.W2Error) as e:
-        w2.matmul_a8_fused(packed, 256, 16, 128, dev(X))
+        w2.matmul_a8_fused(packed, 256, 16, 128, dev(X))                       # M > 4 without a workspace
     assert e.value.status == w2.ERR_UNSUPPORTED_SHAPE
+    small = torch.empty(64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(w2.W2Error) as e:
+        w2.matmul_a8_fused(packed, 256, 16, 128, dev(X), workspace=small)      # workspace too small
+    assert e.value.status == w2.ERR_BUFFER_TOO_SMALL
+
+
+@pytest.mark.parametrize("bf16_in", [False, True])
+@pytest.mark.parametrize("M,K,N,G", [(3, 1024, 272, 128), (4, 4096, 512, 64), (7, 512, 40, 128), (40, 1024, 272, 128),
+                                     (130, 512, 1032, 64), (2, 28672, 64, 128)])
+def test_a8_fused_with_workspace_equals_two_call_path(w2, M, K, N, G, bf16_in):
+    # with a workspace the call covers every M (quantise + the kernel family picked for M); the
+    # result is the two-call result bit for bit; (2, 28672) is two rows too long for one launch
+    codes, scales, X = synth.make_problem(M, K, N, G, 0, seed=M + K + N)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    Xd = dev(synth.f32_to_bf16_bits(X)).view(torch.bfloat16) if bf16_in else dev(X)
+    nbytes = w2.workspace_size(M, K, N, G)
+    assert nbytes >= M * K + 4 * M
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    Y = w2.matmul_a8_fused(packed, K, N, G, Xd, workspace=ws)
+    xq, sx, _ = w2.quantize_rows(Xd, G)
+    Y2 = w2.matmul_a8(packed, K, N, G, xq, sx)
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16))
+
+
+def test_workspace_size_rule(w2):
+    assert w2.workspace_size(1, 4096, 4096, 128) == 0            # one launch covers it
+    assert w2.workspace_size(2, 4096, 4096, 128) == 0
+    assert w2.workspace_size(2, 28672, 4096, 128) > 0            # two rows of 112 KiB as fp32
+    assert w2.workspace_size(3, 4096, 4096, 128) >= 3 * 4096 + 12
+    assert w2.workspace_size(2048, 8192, 4096, 128, a16=True) == 0
 
 
 # ------------------------------------------------------------------ w2a16
