@@ -51,7 +51,7 @@ constexpr int A_STRIDE = BK + 16;                 // bytes per LDS row
 constexpr int A_BUF = BM * A_STRIDE;              // bytes per stage
 constexpr int WM = BM, WN = 16 * CJ;                // wave tile
 constexpr int E_STRIDE = WN * 2 + 16;             // epilogue: bytes per LDS row of a wave's result
-constexpr int WGS_PER_CU = (RI * CJ <= 16 && THREADS <= 256) || (RI * CJ <= 8) ? 2 : 1;
+constexpr int WGS_PER_CU = THREADS > 512 ? 1 : ((RI * CJ <= 16 && THREADS <= 256) || (RI * CJ <= 8) ? 2 : 1);
 constexpr int BIAS = 1 << 21;                     // > 64 * 127 * 2 * 128 = 2 080 768
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
@@ -253,14 +253,18 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[i], bop, first ? biasv : acc[i][j], 0, 0, 0);
                 // the previous column's results are ready by now: dequantise them under these MFMAs
                 if (last && j > 0) dequant_col(j - 1, swS[j - 1][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
-                if (first && j == 0) {
+                if (CJ > 1 && first && j == 0) {
                     if constexpr (DBG) { if (pend_sw != 0.f) dequant_col(CJ - 1, pend_sw, pend_g); }
                     else dequant_col(CJ - 1, pend_sw, pend_g);
                 }
             }
             if (last) {
-                pend_sw = DBG ? 1.0f : swS[CJ - 1][G == 64 ? t : 0];
-                pend_g = it * (128 / G) + (G == 64 ? t : 0);
+                if constexpr (CJ > 1) {
+                    pend_sw = DBG ? 1.0f : swS[CJ - 1][G == 64 ? t : 0];
+                    pend_g = it * (128 / G) + (G == 64 ? t : 0);
+                } else {                                     // a single column block has nothing to hide under
+                    dequant_col(0, swS[0][G == 64 ? t : 0], it * (128 / G) + (G == 64 ? t : 0));
+                }
             }
         }
     };
@@ -289,7 +293,7 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         }
         __syncthreads();
     }
-    dequant_col(CJ - 1, pend_sw, pend_g);                    // the very last group's last column
+    if constexpr (CJ > 1) dequant_col(CJ - 1, pend_sw, pend_g);   // the very last group's last column
     if constexpr (DBG) return;
 
     // y_true = (y - BIAS*2^-149 * ssum) * 2^(149-64) * 2^-6 * sx   (2^-128 = BIAS * 2^-149)
