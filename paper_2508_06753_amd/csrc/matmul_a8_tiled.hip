@@ -44,14 +44,15 @@ namespace tiled {
 
 constexpr int RI = 4;                             // 16-row tiles per wave
 constexpr int CJ = 2;                             // 16-column blocks per wave
-constexpr int BM = 16 * RI, BN = 256, BK = 128;       // BK: k per pipeline stage (half a packed tile)
-constexpr int WAVES = BN / (16 * CJ);
-constexpr int THREADS = 64 * WAVES;
+constexpr int BM = 16 * RI, BK = 128;                 // BK: k per pipeline stage (half a packed tile)
+// BN (columns per workgroup, template parameter): 256 = eight waves, or 128 = four waves when the
+// problem would otherwise yield too few workgroups to fill the chip
+constexpr int waves_of(int bn) { return bn / (16 * CJ); }
 constexpr int A_STRIDE = BK + 16;                 // bytes per LDS row
 constexpr int A_BUF = BM * A_STRIDE;              // bytes per stage
 constexpr int WM = BM, WN = 16 * CJ;                // wave tile
 constexpr int E_STRIDE = WN * 2 + 16;             // epilogue: bytes per LDS row of a wave's result
-constexpr int WGS_PER_CU = THREADS > 512 ? 1 : ((RI * CJ <= 16 && THREADS <= 256) || (RI * CJ <= 8) ? 2 : 1);
+constexpr int wgs_per_cu(int threads) { return threads > 512 ? 1 : threads <= 256 && RI * CJ <= 8 ? 4 : ((RI * CJ <= 16 && threads <= 256) || (RI * CJ <= 8) ? 2 : 1); }
 constexpr int BIAS = 1 << 21;                     // > 64 * 127 * 2 * 128 = 2 080 768
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
@@ -98,10 +99,12 @@ __device__ __forceinline__ void load_w(const char* const (&wb)[CJ], const char* 
     }
 }
 
-template <int G, bool DBG>
-__global__ void __launch_bounds__(THREADS, WGS_PER_CU)
+template <int G, bool DBG, int BN>
+__global__ void __launch_bounds__(64 * waves_of(BN), wgs_per_cu(64 * waves_of(BN)))
 a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 {
+    constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
+    (void)WAVES;
     extern __shared__ __align__(16) int8_t smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -332,10 +335,11 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 
 }  // namespace tiled
 
-template <typename Kern>
-static int launch_tiled(Kern kern, const A8Args& a, hipStream_t stream)
+template <int G, bool DBG, int BN>
+static int launch_tiled(const A8Args& a, hipStream_t stream)
 {
     using namespace tiled;
+    constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
     const size_t act = 3 * A_BUF, epi = (size_t)WAVES * BM * E_STRIDE;   // three activation stages; the epilogue regions reuse them
@@ -343,18 +347,25 @@ static int launch_tiled(Kern kern, const A8Args& a, hipStream_t stream)
     int group_m = env_int("W2_TILED_GROUP_M", 8);
     if (group_m < 1) group_m = 1;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(THREADS);
-    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
+    hipLaunchKernelGGL((a8_tiled_kernel<G, DBG, BN>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
     return check_launch("w2_matmul_a8[tiled]");
+}
+
+template <int G, bool DBG>
+static int launch_tiled_bn(const A8Args& a, hipStream_t stream)
+{
+    // 256 columns per workgroup unless that leaves the chip's 512 workgroup slots clearly underfilled
+    const int64_t wgs256 = ((a.M + tiled::BM - 1) / tiled::BM) * ((a.N + 255) / 256);
+    int bn = env_int("W2_TILED_BN", 0);
+    if (bn != 128 && bn != 256) bn = wgs256 < 400 ? 128 : 256;
+    return bn == 128 ? launch_tiled<G, DBG, 128>(a, stream) : launch_tiled<G, DBG, 256>(a, stream);
 }
 
 int launch_a8_tiled(const A8Args& a, hipStream_t stream)
 {
-    using namespace tiled;
     if (a.G == 128)
-        return a.acc_out ? launch_tiled(a8_tiled_kernel<128, true>, a, stream)
-                         : launch_tiled(a8_tiled_kernel<128, false>, a, stream);
-    return a.acc_out ? launch_tiled(a8_tiled_kernel<64, true>, a, stream)
-                     : launch_tiled(a8_tiled_kernel<64, false>, a, stream);
+        return a.acc_out ? launch_tiled_bn<128, true>(a, stream) : launch_tiled_bn<128, false>(a, stream);
+    return a.acc_out ? launch_tiled_bn<64, true>(a, stream) : launch_tiled_bn<64, false>(a, stream);
 }
 
 }  // namespace w2

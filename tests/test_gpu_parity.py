@@ -172,10 +172,13 @@ def test_a8_midm_long_k_and_limits(w2):
         w2.matmul_a8(packed, 256, 16, 128, xq, sx, variant=w2.VARIANT_MIDM)
 
 
+@pytest.mark.parametrize("bn", [128, 256])
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (512, 1032)])
 @pytest.mark.parametrize("M", [1, 17, 127, 128, 200])
-def test_a8_tiled(w2, M, K, N, G):
+def test_a8_tiled(w2, M, K, N, G, bn, monkeypatch):
+    # both workgroup widths (four and eight waves); ragged M, N; one to four stages of K
+    monkeypatch.setenv("W2_TILED_BN", str(bn))
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G)
 
 
