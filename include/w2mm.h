@@ -72,9 +72,13 @@ typedef enum {
  * selectable here).  SMALLM: one 16-row int8 (bf16 for a16) MFMA tile per
  * wave, split-K across waves (M <= 16).  MIDM (w2a8 only): the weight stream
  * is still read once; every streamed tile is multiplied into one to four
- * 16-row MFMA tiles (M <= 64).  TILED: LDS-staged MFMA tiles (any M). */
+ * 16-row MFMA tiles (M <= 64).  TILED: LDS-staged MFMA tiles (any M).
+ * SCALED16 (w2a16 only, M <= 16; never picked by AUTO): the SMALLM kernel with
+ * the weights built as sw*q from code and group scale (Sec. II-D, the
+ * alternative 16-bit construction), no zero-point term and no dequant step;
+ * needs bf16 scales with an exponent field below 254. */
 typedef enum { W2_VARIANT_AUTO = 0, W2_VARIANT_DOT4 = 1, W2_VARIANT_SMALLM = 2,
-               W2_VARIANT_TILED = 3, W2_VARIANT_MIDM = 4 } w2_variant_t;
+               W2_VARIANT_TILED = 3, W2_VARIANT_MIDM = 4, W2_VARIANT_SCALED16 = 5 } w2_variant_t;
 
 /* ------------------------------------------------------------------------
  * Offline weight pre-formatting (Sec. II-B "packed ... off-line"; Sec. II-D

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libw2mm.so")
 
 CODEC_INT2, CODEC_TERNARY = 0, 1
 DT_F32, DT_BF16 = 0, 1
-VARIANT_AUTO, VARIANT_DOT4, VARIANT_SMALLM, VARIANT_TILED, VARIANT_MIDM = 0, 1, 2, 3, 4
+VARIANT_AUTO, VARIANT_DOT4, VARIANT_SMALLM, VARIANT_TILED, VARIANT_MIDM, VARIANT_SCALED16 = 0, 1, 2, 3, 4, 5
 
 OK = 0
 ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED = -1, -2, -3

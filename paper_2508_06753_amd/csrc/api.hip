@@ -281,7 +281,8 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     int rc = check_shape(fn, K, N, G);
     if (rc) return rc;
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
-    if (variant != W2_VARIANT_AUTO && variant != W2_VARIANT_SMALLM && variant != W2_VARIANT_TILED)
+    if (variant != W2_VARIANT_AUTO && variant != W2_VARIANT_SMALLM && variant != W2_VARIANT_TILED &&
+        variant != W2_VARIANT_SCALED16)
         return fail(W2_ERR_INVALID_ARG, "%s: variant %d not available for w2a16", fn, variant);
     if (M == 0) return W2_OK;
     if (!packed || !X || !Y) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
@@ -296,6 +297,8 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     a.scales = (const uint16_t*)((const char*)packed + L.codes_bytes);
     a.X = X; a.Y = Y; a.M = M; a.K = K; a.N = N; a.ldx = ldx; a.ldy = ldy;
     a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
+    a.fold = variant == W2_VARIANT_SCALED16;
+    if (variant == W2_VARIANT_SCALED16) variant = W2_VARIANT_SMALLM;     // same kernel, other weight construction
     if (variant == W2_VARIANT_AUTO)
         variant = a16_smallm_supports(a) ? W2_VARIANT_SMALLM : W2_VARIANT_TILED;
     if (variant == W2_VARIANT_SMALLM) {

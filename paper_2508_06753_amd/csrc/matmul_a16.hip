@@ -36,17 +36,62 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 constexpr float ZP = 130.0f;     // 128 (the bf16 constant) + 2 (s = q + 2)
 
-__device__ __forceinline__ void upconvert_bf16(uint32_t w, v4i& b0, v4i& b1)
+// mask (0x00030003) and base (0x43004300) arrive in vector registers: (x & mask) | base is then
+// ONE instruction (v_and_or_b32 can take neither two literals nor two scalar registers), so a pair
+// of weights costs a shift and an and-or.
+struct Bf16Consts { uint32_t mask, base; };
+
+__device__ __forceinline__ Bf16Consts bf16_consts()
+{
+    Bf16Consts c = {0x00030003u, 0x43004300u};
+    asm volatile("" : "+v"(c.mask), "+v"(c.base));           // opaque: stays in VGPRs
+    return c;
+}
+
+__device__ __forceinline__ void upconvert_bf16(uint32_t w, const Bf16Consts& c, v4i& b0, v4i& b1)
 {
     const uint32_t x = w ^ 0xAAAAAAAAu;
-    b0[0] = (int)((x & 0x00030003u) | 0x43004300u);
-    b0[1] = (int)(((x >> 2) & 0x00030003u) | 0x43004300u);
-    b0[2] = (int)(((x >> 4) & 0x00030003u) | 0x43004300u);
-    b0[3] = (int)(((x >> 6) & 0x00030003u) | 0x43004300u);
-    b1[0] = (int)(((x >> 8) & 0x00030003u) | 0x43004300u);
-    b1[1] = (int)(((x >> 10) & 0x00030003u) | 0x43004300u);
-    b1[2] = (int)(((x >> 12) & 0x00030003u) | 0x43004300u);
-    b1[3] = (int)(((x >> 14) & 0x00030003u) | 0x43004300u);
+    b0[0] = (int)((x & c.mask) | c.base);
+    b0[1] = (int)(((x >> 2) & c.mask) | c.base);
+    b0[2] = (int)(((x >> 4) & c.mask) | c.base);
+    b0[3] = (int)(((x >> 6) & c.mask) | c.base);
+    b1[0] = (int)(((x >> 8) & c.mask) | c.base);
+    b1[1] = (int)(((x >> 10) & c.mask) | c.base);
+    b1[2] = (int)(((x >> 12) & c.mask) | c.base);
+    b1[3] = (int)(((x >> 14) & c.mask) | c.base);
+}
+
+// The other construction of Sec. II-D ("Alternative implementation", the listing that mixes the
+// 2-bit code with the 16-bit group scale): the weight handed to the matrix instruction IS
+// sw * q, so nothing is dequantised afterwards and one accumulator runs over the whole K.  Here
+// the mixing is a byte permute: per group and column a lane keeps the four possible weights as a
+// table of four bf16 values (code 00 -> 0, 01 -> +sw, 10 -> -2 sw: sign flipped and exponent + 1,
+// 11 -> -sw: sign flipped), eight bytes in two registers, and v_perm_b32 picks the two bytes of
+// each weight: for a pair of codes f = c_a | c_b << 16 the selector is f * 0x0202 + 0x01000100
+// (bytes 2c, 2c+1 per weight).  Four instructions per two weights instead of two, no zero-point
+// term, no group sums, both codecs.
+struct FoldLut { uint32_t lo, hi; };
+
+__device__ __forceinline__ FoldLut fold_lut(uint32_t s)      // s: bf16 bit pattern of the group scale
+{
+    FoldLut l;
+    const uint32_t neg = s ^ 0x8000u;
+    // -2 sw: exponent + 1; a zero (or denormal) scale keeps its exponent field: -0 stays -0
+    const uint32_t neg2 = (s & 0x7f80u) ? ((s + 0x0080u) ^ 0x8000u) : neg;
+    l.lo = s << 16;                                          // [0, +sw]
+    l.hi = neg2 | (neg << 16);                               // [-2 sw, -sw]
+    return l;
+}
+
+__device__ __forceinline__ void upconvert_fold(uint32_t w, const FoldLut& l, v4i& b0, v4i& b1)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t f0 = (w >> (2 * j)) & 0x00030003u;        // bytes 0 and 2: even k
+        const uint32_t f1 = (w >> (8 + 2 * j)) & 0x00030003u;    // bytes 1 and 3: odd k
+        b0[j] = (int)__builtin_amdgcn_perm(l.hi, l.lo, f0 * 0x0202u + 0x01000100u);
+        b1[j] = (int)__builtin_amdgcn_perm(l.hi, l.lo, f1 * 0x0202u + 0x01000100u);
+    }
 }
 
 __device__ __forceinline__ v4f mfma_bf16(const v4i& a, const v4i& b, const v4f& c)
@@ -109,7 +154,7 @@ __device__ __forceinline__ void piece_store(const Piece& pc, int ppr, int total,
 constexpr int SVP = 2;    // pieces per thread that go through registers
 
 // ---------------------------------------------------------------- SMALLM (bf16 MFMA)
-template <int G, int TMAX>
+template <int G, int TMAX, bool FOLD>
 __global__ void __launch_bounds__(1024)
 a16_smallm_kernel(A16Args a, SmallCfg cfg)
 {
@@ -118,6 +163,8 @@ a16_smallm_kernel(A16Args a, SmallCfg cfg)
     (void)DBG; (void)cb_ok;
     const int rows = (int)a.M;                              // 1..16
     const int arow = (lane & 15) < rows ? (lane & 15) : rows - 1;
+    const Bf16Consts kc = bf16_consts();
+    (void)kc;
 
     float y[4] = {0.f, 0.f, 0.f, 0.f};
     v4f acc = {0.f, 0.f, 0.f, 0.f};
@@ -149,12 +196,20 @@ a16_smallm_kernel(A16Args a, SmallCfg cfg)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     v4i b0, b1;
-                    upconvert_bf16(wd[t], b0, b1);
+                    if constexpr (FOLD) {
+                        // the scale is folded into the weights: y is not used, acc runs over all of K
+                        const int gi = G == 64 ? t : t >> 1;
+                        const uint32_t pair = (G == 128 || gi < 2) ? cur.s0 : cur.s1;
+                        const FoldLut lut = fold_lut((gi & 1) ? pair >> 16 : pair & 0xffffu);
+                        upconvert_fold(wd[t], lut, b0, b1);
+                    } else {
+                        upconvert_bf16(wd[t], kc, b0, b1);
+                    }
                     const v4i a0 = *reinterpret_cast<const v4i*>(xrow + t * 128);
                     const v4i a1 = *reinterpret_cast<const v4i*>(xrow + t * 128 + 16);
                     acc = mfma_bf16(a0, b0, acc);
                     acc = mfma_bf16(a1, b1, acc);
-                    if (G == 64 || (t & 1)) {
+                    if (!FOLD && (G == 64 || (t & 1))) {
                         const int gi = G == 64 ? t : t >> 1;
                         const float sw = tile_scale<G>(cur, gi);
                         const int gl = (int)(kt - kt_begin) * GPT + gi;      // group inside the chunk
@@ -192,7 +247,7 @@ a16_smallm_kernel(A16Args a, SmallCfg cfg)
     __syncthreads();
     float* red = reinterpret_cast<float*>(smem);            // [waves][16 m][16 n]
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[(wave * 16 + 4 * q + r) * 16 + (lane & 15)] = y[r];
+    for (int r = 0; r < 4; ++r) red[(wave * 16 + 4 * q + r) * 16 + (lane & 15)] = FOLD ? acc[r] : y[r];
     __syncthreads();
     const int outs = cfg.cbw * rows * 16;
     for (int i = threadIdx.x; i < outs; i += blockDim.x) {
@@ -206,7 +261,7 @@ a16_smallm_kernel(A16Args a, SmallCfg cfg)
 
 bool a16_smallm_supports(const A16Args& a) { return a.M >= 1 && a.M <= 16; }
 
-template <int G>
+template <int G, bool FOLD>
 static int launch_a16_smallm_t(const A16Args& a, hipStream_t stream)
 {
     const int rows = (int)a.M;
@@ -214,14 +269,15 @@ static int launch_a16_smallm_t(const A16Args& a, hipStream_t stream)
     const size_t extra = (size_t)(c.kc / G) * 16 * sizeof(float);
     const size_t lds = small_lds_bytes(c, rows, 16, 2, extra);
     const int tpw = tiles_per_wave(a.n_kt, c);
-    if (tpw <= 2) return launch_small(a16_smallm_kernel<G, 2>, "w2_matmul_a16[smallm]", a, c, lds, stream);
-    if (tpw <= 4) return launch_small(a16_smallm_kernel<G, 4>, "w2_matmul_a16[smallm]", a, c, lds, stream);
-    return launch_small(a16_smallm_kernel<G, TMAX>, "w2_matmul_a16[smallm]", a, c, lds, stream);
+    if (tpw <= 2) return launch_small(a16_smallm_kernel<G, 2, FOLD>, "w2_matmul_a16[smallm]", a, c, lds, stream);
+    if (tpw <= 4) return launch_small(a16_smallm_kernel<G, 4, FOLD>, "w2_matmul_a16[smallm]", a, c, lds, stream);
+    return launch_small(a16_smallm_kernel<G, TMAX, FOLD>, "w2_matmul_a16[smallm]", a, c, lds, stream);
 }
 
 int launch_a16_smallm(const A16Args& a, hipStream_t stream)
 {
-    return a.G == 128 ? launch_a16_smallm_t<128>(a, stream) : launch_a16_smallm_t<64>(a, stream);
+    if (a.fold) return a.G == 128 ? launch_a16_smallm_t<128, true>(a, stream) : launch_a16_smallm_t<64, true>(a, stream);
+    return a.G == 128 ? launch_a16_smallm_t<128, false>(a, stream) : launch_a16_smallm_t<64, false>(a, stream);
 }
 
 // ---------------------------------------------------------------- TILED (bf16 MFMA, any M)
@@ -375,6 +431,7 @@ a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
     __syncthreads();
 
     const int8_t* a_base = smem + l16 * A_STRIDE + q * 32;
+    const Bf16Consts kc = bf16_consts();
     v4f cinit[4];                                            // -130 * X_g for the rows of each row tile
 
     // One stage.  T = stage index mod 4 (LDS buffer, ring slot, weight set); `as` holds the
@@ -405,7 +462,7 @@ a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
 #pragma unroll
         for (int j = 0; j < CJ; ++j) {
             v4i b0, b1;
-            upconvert_bf16(wc.w[j], b0, b1);
+            upconvert_bf16(wc.w[j], kc, b0, b1);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 acc[i][j] = mfma_bf16(a0[i], b0, group_begin ? cinit[i] : acc[i][j]);

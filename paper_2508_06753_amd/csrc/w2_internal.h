@@ -54,6 +54,7 @@ struct A16Args {
     int64_t M, K, N, ldx, ldy;
     int64_t n_cb, n_kt;
     int G;
+    int fold;       // small-M kernel only: build the weights as sw*q (scale folded in), no dequant step
 };
 
 bool a16_smallm_supports(const A16Args& a);

@@ -97,11 +97,11 @@ constexpr int64_t LDS_BUDGET = 128 * 1024;   // activation chunk + reduction scr
 // Picks (column blocks per workgroup, k-splits): enough workgroups to fill 256
 // CUs a few times over, and a k-split that leaves each wave at most TMAX tiles
 // when the wave budget allows it.
-static SmallCfg pick_cfg(int64_t n_cb, int64_t n_kt, int rows, int bytes_per_k)
+static SmallCfg pick_cfg(int64_t n_cb, int64_t n_kt, int rows, int bytes_per_k, int max_waves = 16)
 {
     SmallCfg c;
     int waves = env_int("W2_SMALL_WAVES", 8);
-    if (waves > 16) waves = 16;
+    if (waves > max_waves) waves = max_waves;
     if (waves < 1) waves = 1;
     int cbw = env_int("W2_SMALL_CBW", 0);
     if (cbw <= 0) {

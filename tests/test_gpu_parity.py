@@ -334,6 +334,36 @@ def test_a16_auto_dispatch(w2, M):
     run_a16_case(w2, M, 1024, 528, 128, 0, w2.VARIANT_AUTO, seed=M)
 
 
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", SMALL_SHAPES)
+@pytest.mark.parametrize("M", [1, 4, 7, 16])
+def test_a16_scale_folded_weights(w2, M, K, N, G):
+    # the alternative construction: weights built as sw*q by a byte permute, no dequant step
+    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SCALED16, seed=M + K + N + G)
+
+
+def test_a16_scale_folded_zero_scales_and_exact_integers(w2):
+    # a group with scale 0 contributes exactly nothing (-2 * 0 must not become a denormal), and with
+    # unit scales and small-integer activations every product and sum is exact
+    K, N, G = 512, 48, 128
+    codes, scales, _ = synth.make_problem(1, K, N, G, 0, 3)
+    sc = np.full((K // G, N), 0x3F80, np.uint16)
+    sc[1, :] = 0                                             # one all-zero group row
+    sc[2, ::3] = 0x8000                                      # negative zero as well
+    packed = w2.prepack(dev(codes), dev(sc), G, 0)
+    rng = np.random.default_rng(1)
+    Xi = rng.integers(-2, 3, size=(5, K)).astype(np.float32)
+    Y = w2.matmul_a16(packed, K, N, G, dev(synth.f32_to_bf16_bits(Xi)).view(torch.bfloat16), variant=w2.VARIANT_SCALED16)
+    sw = synth.bf16_bits_to_f32(sc).astype(np.float64)
+    W = (codes.astype(np.int64) - 2) * np.repeat(sw, G, axis=0)
+    ref = Xi.astype(np.float64) @ W
+    assert np.abs(ref).max() < 256
+    assert np.array_equal(bits_to_f64(bf16_bits(Y)), ref)
+    with pytest.raises(w2.W2Error):                          # M <= 16 only
+        w2.matmul_a16(packed, K, N, G, dev(synth.f32_to_bf16_bits(np.zeros((17, K), np.float32))).view(torch.bfloat16),
+                      variant=w2.VARIANT_SCALED16)
+
+
 def test_a16_lds_chunking_and_outliers(w2):
     run_a16_case(w2, 16, 14336, 64, 128, 0, w2.VARIANT_SMALLM, seed=5)
     # activation outliers: the 130*X_g cancellation must stay inside the tolerance
