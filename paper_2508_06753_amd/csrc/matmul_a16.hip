@@ -294,7 +294,7 @@ int launch_a16_smallm(const A16Args& a, hipStream_t stream)
 // acc = sum x*q and the dequant is one fma, y += sw * acc.  For that the row
 // sums of a stage must be in LDS before the group begins: activations are
 // written to LDS two stages ahead (four buffers) and loaded from global memory
-// four stages ahead (two register sets, by the first four waves); weights are
+// four stages ahead (two register sets); weights are
 // loaded three stages ahead (four register sets; the loop is unrolled by four,
 // sets and buffers are indexed by the stage number mod 4).  All loads are issued
 // unconditionally (clamped past the end) and pinned at the top of the stage, so
@@ -304,7 +304,7 @@ namespace tiled16 {
 constexpr int BM = 64, BN = 256, BK = 64;
 constexpr int CJ = 2;                             // column blocks per wave
 constexpr int THREADS = 512;
-constexpr int COPY_THREADS = 256;                 // 4 per row, one 16-k block (32 B) each
+constexpr int CPT = THREADS / BM;                  // copy threads per row: 8, eight k (16 B) each
 constexpr int A_STRIDE = BK * 2 + 16;             // bytes per LDS row
 constexpr int A_BUF = BM * A_STRIDE;
 constexpr int NBUF = 4;
@@ -313,7 +313,7 @@ constexpr int LDS_BYTES = XS_OFF + 4 * BM * 4;
 constexpr int WN = 16 * CJ;
 
 struct WSet { uint32_t w[CJ], sc[CJ]; };
-struct ASet { uint4 lo, hi; };
+struct ASet { uint4 v; };
 
 template <int G>
 __global__ void __launch_bounds__(THREADS)
@@ -351,14 +351,15 @@ a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
     uint32_t w_lane = (uint32_t)lane * 16u;
     uint32_t s_lane = (uint32_t)l16 * (GPT * 2u);
 
-    // copy: 4 threads per row, one 16-k block (32 B) each; rows past M repeat the last row
-    const bool copier = tid < COPY_THREADS;                  // waves 0..3 (wave-uniform)
-    const int cp_row = (tid & (COPY_THREADS - 1)) >> 2, cp_seg = tid & 3;
+    // copy: 8 threads per row, eight k (16 B) each: the even k of a half block go to one 8-byte
+    // slot of the block's [8 even | 8 odd] LDS image, the odd k to another; rows past M repeat the
+    // last row
+    const int cp_row = tid / CPT, cp_seg = tid % CPT;
     int64_t cp_m = m0 + cp_row;
     if (cp_m >= a.M) cp_m = a.M - 1;
     const char* cp_base = reinterpret_cast<const char*>(a.X + m0 * a.ldx);               // uniform
-    uint32_t cp_lane = (uint32_t)((cp_m - m0) * a.ldx * 2) + (uint32_t)cp_seg * 32u;     // < 128 ldx: fits 32 bits
-    const int cp_dst = cp_row * A_STRIDE + cp_seg * 32;
+    uint32_t cp_lane = (uint32_t)((cp_m - m0) * a.ldx * 2) + (uint32_t)cp_seg * 16u;     // < 128 ldx: fits 32 bits
+    const int cp_dst = cp_row * A_STRIDE + (cp_seg >> 1) * 32 + (cp_seg & 1) * 8;
 
     v4f acc[4][CJ];
     float y[4][CJ][4];
@@ -376,8 +377,7 @@ a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
         st = min(st, n_st - 1);
         const char* p = cp_base + st * (BK * 2);             // uniform
         asm volatile("" : "+v"(cp_lane));                    // keeps "scalar base + 32-bit offset" addressing
-        r.lo = *reinterpret_cast<const uint4*>(p + cp_lane);
-        r.hi = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
+        r.v = *reinterpret_cast<const uint4*>(p + cp_lane);
     };
     auto load_w = [&](int64_t st, WSet& r) {
         st = min(st, n_st - 1);
@@ -392,29 +392,22 @@ a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
             r.sc[j] = *reinterpret_cast<const uint16_t*>(sb[j] + s_off + s_lane);
         }
     };
-    // stores one 16-k block de-interleaved into buffer `buf` and the row's partial sum into ring slot `buf`
+    // stores eight k de-interleaved into buffer `buf` and the row's partial sum into ring slot `buf`
     auto stage_store = [&](const ASet& r, int buf) {
-        const uint32_t d[8] = {r.lo.x, r.lo.y, r.lo.z, r.lo.w, r.hi.x, r.hi.y, r.hi.z, r.hi.w};
-        float s = 0.0f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s += pair_sum(d[e]);
+        const uint32_t d[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
+        float s = (pair_sum(d[0]) + pair_sum(d[1])) + (pair_sum(d[2]) + pair_sum(d[3]));
         s += __shfl_xor(s, 1);
         s += __shfl_xor(s, 2);
-        uint4 ev, od;
+        s += __shfl_xor(s, 4);
+        uint2 ev, od;
         ev.x = __builtin_amdgcn_perm(d[1], d[0], 0x05040100u);
         ev.y = __builtin_amdgcn_perm(d[3], d[2], 0x05040100u);
-        ev.z = __builtin_amdgcn_perm(d[5], d[4], 0x05040100u);
-        ev.w = __builtin_amdgcn_perm(d[7], d[6], 0x05040100u);
         od.x = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
         od.y = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
-        od.z = __builtin_amdgcn_perm(d[5], d[4], 0x07060302u);
-        od.w = __builtin_amdgcn_perm(d[7], d[6], 0x07060302u);
-        if (copier) {
-            uint4* dst = reinterpret_cast<uint4*>(smem + buf * A_BUF + cp_dst);
-            dst[0] = ev;
-            dst[1] = od;
-            if (cp_seg == 0) xpart[buf * BM + cp_row] = s;
-        }
+        int8_t* dst = smem + buf * A_BUF + cp_dst;
+        *reinterpret_cast<uint2*>(dst) = ev;
+        *reinterpret_cast<uint2*>(dst + 16) = od;
+        if (cp_seg == 0) xpart[buf * BM + cp_row] = s;
     };
 
     ASet as0, as1;
