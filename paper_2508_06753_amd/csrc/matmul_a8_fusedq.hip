@@ -9,8 +9,8 @@
 // result are bit-identical to the two-call path.
 //
 // Built on the small-M MFMA kernel: each workgroup loads the M activation
-// rows (vector loads issued before the weight loads), parks them in LDS,
-// reduces abs-max across its waves, quantises from LDS into the int8 rows the
+// rows (vector loads issued before the weight loads) into registers,
+// reduces abs-max across its waves, quantises them into the int8 rows (LDS) the
 // matrix instructions read.  No vector memory is touched between the weight
 // loads and their first use, so nothing waits behind the weight stream.
 #include <hip/hip_runtime.h>
@@ -62,7 +62,6 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
     float* s_red = reinterpret_cast<float*>(smem);          // [16][4]
     float* s_sx = s_red + 64;                               // [4]
     int8_t* xs = smem + FQ_HDR;                             // int8 rows
-    uint4* stash = reinterpret_cast<uint4*>(xs + ((rows * row_stride + 15) & ~15));
 
     // piece index -> (row, piece inside the row); a single row needs no division
     auto split = [&](unsigned i, int& r, int& v) __attribute__((always_inline)) {
@@ -79,7 +78,7 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
         pc[j] = make_uint4(0, 0, 0, 0);
         if (j * (int)blockDim.x < total) {
             unsigned i = threadIdx.x + j * blockDim.x;
-            i = i < (unsigned)total ? i : i % (unsigned)total;
+            if (i >= (unsigned)total) i %= (unsigned)total;     // only the lanes past the end pay for the division
             int r, v;
             split(i, r, v);
             pc[j] = *reinterpret_cast<const uint4*>((const char*)a.X + ((int64_t)r * a.ldx * ES) + (int64_t)v * 16);
@@ -98,7 +97,7 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
     TileRegs tr0[TMAX];
     load_batch(kt0, tr0);
 
-    // 3. park the rows in LDS and reduce abs-max per row
+    // 3. reduce abs-max per row; the pieces stay in registers (every piece has a slot: a launch condition)
     float amax[RL];
 #pragma unroll
     for (int rr = 0; rr < RL; ++rr) amax[rr] = 0.f;
@@ -106,7 +105,6 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
     for (int j = 0; j < FQ_PIECES; ++j) {
         const int i = threadIdx.x + j * blockDim.x;
         if (i < total) {
-            stash[i] = pc[j];
             int r, v_unused;
             split((unsigned)i, r, v_unused);
             const uint32_t d[4] = {pc[j].x, pc[j].y, pc[j].z, pc[j].w};
@@ -150,28 +148,32 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
     for (int rr = 0; rr < RL; ++rr)
         if (threadIdx.x == (unsigned)rr) s_sx[rr] = sxv[rr];
 
-    // 4. quantise from the parked rows into the int8 rows
-    for (int i = threadIdx.x; i < total; i += blockDim.x) {
-        const uint4 p = stash[i];
-        int r, v;
-        split((unsigned)i, r, v);
-        float iv = inv[0];
+    // 4. quantise the pieces into the int8 rows
 #pragma unroll
-        for (int rr = 1; rr < RL; ++rr) iv = (r == rr) ? inv[rr] : iv;
-        const uint32_t d[4] = {p.x, p.y, p.z, p.w};
-        if constexpr (BF16IN) {
-            int qv[8];
+    for (int j = 0; j < FQ_PIECES; ++j) {
+        const int i = threadIdx.x + j * blockDim.x;
+        if (i < total) {
+            const uint4 p = pc[j];
+            int r, v;
+            split((unsigned)i, r, v);
+            float iv = inv[0];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                qv[2 * e] = fq_quant1(__uint_as_float(d[e] << 16), iv);
-                qv[2 * e + 1] = fq_quant1(__uint_as_float(d[e] & 0xffff0000u), iv);
+            for (int rr = 1; rr < RL; ++rr) iv = (r == rr) ? inv[rr] : iv;
+            const uint32_t d[4] = {p.x, p.y, p.z, p.w};
+            if constexpr (BF16IN) {
+                int qv[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    qv[2 * e] = fq_quant1(__uint_as_float(d[e] << 16), iv);
+                    qv[2 * e + 1] = fq_quant1(__uint_as_float(d[e] & 0xffff0000u), iv);
+                }
+                *reinterpret_cast<uint2*>(xs + r * row_stride + v * 8) =
+                    make_uint2(fq_pack4(qv[0], qv[1], qv[2], qv[3]), fq_pack4(qv[4], qv[5], qv[6], qv[7]));
+            } else {
+                *reinterpret_cast<uint32_t*>(xs + r * row_stride + v * 4) =
+                    fq_pack4(fq_quant1(__uint_as_float(d[0]), iv), fq_quant1(__uint_as_float(d[1]), iv),
+                             fq_quant1(__uint_as_float(d[2]), iv), fq_quant1(__uint_as_float(d[3]), iv));
             }
-            *reinterpret_cast<uint2*>(xs + r * row_stride + v * 8) =
-                make_uint2(fq_pack4(qv[0], qv[1], qv[2], qv[3]), fq_pack4(qv[4], qv[5], qv[6], qv[7]));
-        } else {
-            *reinterpret_cast<uint32_t*>(xs + r * row_stride + v * 4) =
-                fq_pack4(fq_quant1(__uint_as_float(d[0]), iv), fq_quant1(__uint_as_float(d[1]), iv),
-                         fq_quant1(__uint_as_float(d[2]), iv), fq_quant1(__uint_as_float(d[3]), iv));
         }
     }
     __syncthreads();
@@ -253,7 +255,7 @@ int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x
     const int64_t pieces = M * K * es / 16;
     const int threads = 64 * c.cbw * c.ks;
     const size_t xs_bytes = ((size_t)rows * (K + XS_PAD) + 15) & ~(size_t)15;
-    size_t lds = FQ_HDR + xs_bytes + (size_t)M * K * es;
+    size_t lds = FQ_HDR + xs_bytes;
     const size_t red = FQ_HDR + (size_t)c.cbw * c.ks * 16 * 16 * sizeof(float);
     if (red > lds) lds = red;
     if (c.kc != n_kt * TILE_K || pieces > (int64_t)FQ_PIECES * threads || lds > 144 * 1024) {
