@@ -291,6 +291,8 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     if (ldx < K || ldx % 8 || ldy < N || ldy % 8)
         return fail(W2_ERR_MISALIGNED, "%s: ldx >= K, ldy >= N, both multiples of 8", fn);
     if (M > ((int64_t)1 << 24)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: M is limited to 2^24", fn);
+    // the tiled kernel addresses a workgroup's 64 rows with 32-bit byte offsets
+    if (ldx > ((int64_t)1 << 24)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: ldx is limited to 2^24", fn);
     const Layout L = make_layout(K, N, G);
     A16Args a;
     a.codes = (const uint32_t*)packed;
