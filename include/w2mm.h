@@ -81,8 +81,9 @@ typedef enum { W2_VARIANT_AUTO = 0, W2_VARIANT_DOT4 = 1, W2_VARIANT_SMALLM = 2,
                W2_VARIANT_TILED = 3, W2_VARIANT_MIDM = 4, W2_VARIANT_SCALED16 = 5 } w2_variant_t;
 
 /* ------------------------------------------------------------------------
- * Offline weight pre-formatting (Sec. II-B "packed ... off-line"; Sec. II-D
- * "pre-format ... without any overhead during runtime").  The device layout
+ * Offline weight pre-formatting (Sec. II-B and II-D: the 2-bit weights are
+ * packed into the instruction's layout once, before inference, at no run-time
+ * cost).  The device layout
  * is this library's own (the paper's VNNI4-interleaved and VNNI16 layouts are
  * for x86 and Xe2); the principle kept from Sec. II-B is that one shift and
  * one mask land four consecutive-K codes directly in the byte lanes the int8
