@@ -13,7 +13,8 @@ larger than twice the 256 MB last-level cache, so every step streams its
 weights from HBM as a real decode does.  Steps are replayed from HIP graphs so
 that host launch cost does not hide the GPU time.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line: metric / value / unit (whole-step GB/s of the method's own bytes), the
+`roofline` of the dominant kernel, `prefill` (compute-bound TOP/s), `cpu_baseline` (the oracle).
 """
 import argparse
 import json
@@ -190,7 +191,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
-                 "use --gpus 1.  DESIGN.md says how the path would shard.")
+                 "use --gpus 1.")
 
     import numpy as np
     import torch
