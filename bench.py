@@ -75,8 +75,12 @@ def pmc_mode(torch, w2, lib, vp, pool, shapes, Xd, Yd, dev):
     Yp = torch.empty((Mp, Np), dtype=torch.bfloat16, device=dev)
     for _ in range(3):
         w2.matmul_a8(pk, Kp, Np, G, xqp, sxp, out=Yp)
+    xbp = torch.randn((Mp, Kp), dtype=torch.bfloat16, device=dev)
+    for _ in range(3):
+        w2.matmul_a16(pk, Kp, Np, G, xbp, out=Yp)
     torch.cuda.synchronize()
-    print("bench.py --pmc: launched copy x3 (256 MiB), stream read and fused GEMV x%d, prefill x3" % len(pool))
+    print("bench.py --pmc: launched copy x3 (256 MiB), stream read and fused GEMV x%d, prefill x3 (w2a8), "
+          "x3 (w2a16)" % len(pool))
 
 
 def sweep_mode(torch, w2, synth, dev):

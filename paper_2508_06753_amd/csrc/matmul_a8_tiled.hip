@@ -9,7 +9,7 @@
 // SIMD issues one vector instruction, matrix ones included, every four clocks
 // or so) and bytes moved.
 //   - activations (int8) are staged through LDS, three buffers, 128 k per
-//     stage, rows padded by 16 B;
+//     stage, rows padded by 32 B;
 //   - the 2-bit weights never touch LDS: the packed layout IS the MFMA
 //     B-operand layout, so each lane loads its dwords (64 bits per column
 //     block and stage) straight from global memory and up-converts them in
@@ -48,7 +48,9 @@ constexpr int BM = 16 * RI, BK = 128;                 // BK: k per pipeline stag
 // BN (columns per workgroup, template parameter): 256 = eight waves, or 128 = four waves when the
 // problem would otherwise yield too few workgroups to fill the chip
 constexpr int waves_of(int bn) { return bn / (16 * CJ); }
-constexpr int A_STRIDE = BK + 16;                 // bytes per LDS row
+// bytes per LDS row: with a stride of 32 mod 64 bytes the A-operand reads (row = lane & 15, 16-byte
+// piece = lane >> 4) run at full LDS rate; measured, a 16-byte pad costs 1.75x on those reads
+constexpr int A_STRIDE = BK + 32;
 constexpr int A_BUF = BM * A_STRIDE;              // bytes per stage
 constexpr int WM = BM, WN = 16 * CJ;                // wave tile
 constexpr int E_STRIDE = WN * 2 + 16;             // epilogue: bytes per LDS row of a wave's result

@@ -9,7 +9,7 @@ namespace w2 {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int XS_PAD = 16;   // bytes of padding per LDS activation row (bank spread)
+constexpr int XS_PAD = 32;   // bytes of padding per LDS activation row: a row stride of 32 mod 64 bytes spreads the MFMA A-operand reads over all banks
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
