@@ -1,0 +1,325 @@
+// w2a16 for large M with the scale folded into the weights (Sec. II-D,
+// "Alternative implementation": the 2-bit code and the 16-bit group scale are
+// mixed into one 16-bit weight, which goes to a 16-bit matrix instruction with
+// fp32 accumulation; nothing is dequantised afterwards).  With bf16 the four
+// possible weights of a group and column, 0, +sw, -2 sw and -sw, are exact
+// (sign flip, exponent + 1), so the matrix instruction sums exact products
+// and ONE accumulator per output runs over the whole K: no zero-point term, no
+// group sums of the activations, no per-group fma on the accumulators.
+//
+// Per lane and (group, column) the four weights sit in two registers, low
+// bytes in one and high bytes in the other.  A dword of the packed tile holds
+// 16 codes, four per byte; (w >> 2j) & 0x03030303 is four codes as four byte
+// selectors, two v_perm_b32 look the low and the high bytes up, two more
+// interleave them into [k even pair] and [k odd pair] registers: 23 vector
+// instructions per 16 weights.  They are amortised over a 128-row wave tile
+// (RI = 8 row tiles x CJ = 2 column blocks of v_mfma_f32_16x16x32_bf16: 32
+// matrix instructions per 64-k stage and wave), which is what makes this
+// construction the faster one for prefill: per matrix instruction it issues
+// about 2.5 vector instructions where the zero-point kernel issues about 6.
+//
+// Workgroup: 128 rows x (32 columns per wave) x 64 k per stage; activations go
+// through LDS (three buffers, rows de-interleaved [even k | odd k] per 16-k
+// block to match the order the codes come out of a dword, row stride 160 B:
+// conflict-free operand reads); weights go from global memory to registers, one
+// 16-byte load per lane, column block and 256-k tile, a whole tile ahead.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "w2_small_common.h"
+
+namespace w2 {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+namespace fold16 {
+
+constexpr int RI = 8;                              // 16-row tiles per wave
+constexpr int CJ = 2;                              // 16-column blocks per wave
+constexpr int BM = 16 * RI, BK = 64;
+constexpr int WN = 16 * CJ;
+constexpr int A_STRIDE = BK * 2 + 32;              // 32 mod 64 bytes: conflict-free A-operand reads
+constexpr int A_BUF = BM * A_STRIDE;
+constexpr int NBUF = 3;
+constexpr int E_STRIDE = WN * 2 + 16;              // epilogue: bytes per LDS row of a wave's result
+constexpr int waves_of(int bn) { return bn / WN; }
+constexpr int lds_bytes(int bn)
+{
+    return NBUF * A_BUF > waves_of(bn) * BM * E_STRIDE ? NBUF * A_BUF : waves_of(bn) * BM * E_STRIDE;
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// The four weights of one (group, column): low bytes and high bytes, indexed by the raw code
+// (00 -> 0, 01 -> +sw, 10 -> -2 sw, 11 -> -sw).
+struct Lut { uint32_t lo4, hi4; };
+
+__device__ __forceinline__ Lut make_lut(uint32_t s)          // s: bf16 bit pattern of the group scale
+{
+    const uint32_t neg = s ^ 0x8000u;
+    // -2 sw: exponent + 1; a zero (or denormal) scale keeps its exponent field: -0 stays -0
+    const uint32_t neg2 = (s & 0x7f80u) ? ((s + 0x0080u) ^ 0x8000u) : neg;
+    const uint32_t a = s << 16;                              // [0, +sw]
+    const uint32_t b = neg2 | (neg << 16);                   // [-2 sw, -sw]
+    Lut l;
+    l.lo4 = __builtin_amdgcn_perm(b, a, 0x06040200u);
+    l.hi4 = __builtin_amdgcn_perm(b, a, 0x07050301u);
+    return l;
+}
+
+// 16 codes of one dword -> b0 (even k of the lane's 16-k block), b1 (odd k)
+__device__ __forceinline__ void upconvert(uint32_t w, const Lut& l, v4i& b0, v4i& b1)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t t = (w >> (2 * j)) & 0x03030303u;     // the codes of k = 4j .. 4j+3 as byte selectors
+        const uint32_t lo = __builtin_amdgcn_perm(0u, l.lo4, t);
+        const uint32_t hi = __builtin_amdgcn_perm(0u, l.hi4, t);
+        b0[j] = (int)__builtin_amdgcn_perm(hi, lo, 0x06020400u);   // k = 4j, 4j+2
+        b1[j] = (int)__builtin_amdgcn_perm(hi, lo, 0x07030501u);   // k = 4j+1, 4j+3
+    }
+}
+
+__device__ __forceinline__ v4f mfma_bf16(const v4i& a, const v4i& b, const v4f& c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a),
+                                                   __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+}
+
+template <int G>
+struct WTile {
+    uint4 w[CJ];                                   // 16 bytes of codes per column block: dword t = k 64t .. 64t+63
+    uint32_t s[CJ][G == 128 ? 1 : 2];              // the lane's column: 2 (G=128) or 4 (G=64) bf16 group scales
+};
+
+template <int G, int BN>
+__global__ void __launch_bounds__(64 * waves_of(BN), waves_of(BN) > 4 ? 1 : 2)
+a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
+{
+    constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
+    constexpr int GPT = TILE_K / G;
+    constexpr int NP = BM * 8 / THREADS;           // 16-byte activation pieces per thread and stage: 2 or 4
+    extern __shared__ __align__(16) int8_t smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wn = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane >> 4, l16 = lane & 15;
+
+    // workgroup -> tile: one contiguous chunk of ids per XCD, bands of group_m row tiles inside
+    const int64_t total = (int64_t)tiles_m * tiles_n;
+    int64_t id = blockIdx.x;
+    if (total % 8 == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int64_t band = id / ((int64_t)group_m * tiles_n);
+    const int64_t first_m = band * group_m;
+    const int gm = (int)min((int64_t)group_m, tiles_m - first_m);
+    const int64_t in_band = id - band * group_m * tiles_n;
+    const int64_t tile_m = first_m + in_band % gm;
+    const int64_t tile_n = in_band / gm;
+    const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const char* wb[CJ];
+    const char* sb[CJ];
+#pragma unroll
+    for (int j = 0; j < CJ; ++j) {
+        int64_t c = tile_n * (BN / TILE_N) + wn * CJ + j;
+        c = c < a.n_cb ? c : a.n_cb - 1;                     // clamp: loads stay in bounds
+        wb[j] = reinterpret_cast<const char*>(a.codes + c * a.n_kt * 256);
+        sb[j] = reinterpret_cast<const char*>(a.scales + c * a.n_kt * TILE_N * GPT);
+    }
+    uint32_t w_lane = (uint32_t)lane * 16u;
+    uint32_t s_lane = (uint32_t)l16 * (GPT * 2u);
+
+    // copy: eight threads per row, 16 B (eight k) each, NP rows per thread; rows past M repeat the
+    // last row.  Lane offsets stay below 128 * 2 * ldx <= 2^32 (ldx <= 2^24).
+    const int cp_seg = tid & 7;
+    const char* cp_base = reinterpret_cast<const char*>(a.X + m0 * a.ldx);               // uniform
+    uint32_t cp_lane[NP];
+    int cp_dst[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int row = (tid >> 3) + p * (THREADS / 8);
+        int64_t m = m0 + row;
+        if (m >= a.M) m = a.M - 1;
+        cp_lane[p] = (uint32_t)((m - m0) * a.ldx * 2) + (uint32_t)cp_seg * 16u;
+        cp_dst[p] = row * A_STRIDE + (cp_seg >> 1) * 16 + (cp_seg & 1) * 8;
+    }
+
+    v4f acc[RI][CJ];
+#pragma unroll
+    for (int i = 0; i < RI; ++i)
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    const int64_t n_st = a.n_kt * 4;                         // stages of 64 k
+    uint4 ar[NP];
+    auto load_a = [&](int64_t st) {
+        st = min(st, n_st - 1);
+        const char* p = cp_base + st * (BK * 2);             // uniform
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            asm volatile("" : "+v"(cp_lane[i]));             // keeps "scalar base + 32-bit offset" addressing
+            ar[i] = *reinterpret_cast<const uint4*>(p + cp_lane[i]);
+        }
+    };
+    // eight k of a row: the even ones to the [even] half of the 16-k block's image, the odd ones 64 B on
+    auto store_a = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const uint32_t d[4] = {ar[i].x, ar[i].y, ar[i].z, ar[i].w};
+            uint2 ev, od;
+            ev.x = __builtin_amdgcn_perm(d[1], d[0], 0x05040100u);
+            ev.y = __builtin_amdgcn_perm(d[3], d[2], 0x05040100u);
+            od.x = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
+            od.y = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
+            int8_t* dst = smem + buf * A_BUF + cp_dst[i];
+            *reinterpret_cast<uint2*>(dst) = ev;
+            *reinterpret_cast<uint2*>(dst + 64) = od;
+        }
+    };
+    auto load_w = [&](int64_t kt, WTile<G>& r) {
+        kt = min(kt, a.n_kt - 1);
+        const int64_t w_off = kt * 1024;
+        const int64_t s_off = kt * (TILE_N * GPT * 2);
+        asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) {
+            r.w[j] = *reinterpret_cast<const uint4*>(wb[j] + w_off + w_lane);
+            if constexpr (G == 128) {
+                r.s[j][0] = *reinterpret_cast<const uint32_t*>(sb[j] + s_off + s_lane);
+            } else {
+                const uint2 v = *reinterpret_cast<const uint2*>(sb[j] + s_off + s_lane);
+                r.s[j][0] = v.x;
+                r.s[j][1] = v.y;
+            }
+        }
+    };
+
+    WTile<G> w0, w1;
+    load_a(0);
+    load_w(0, w0);
+    store_a(0);
+    load_a(1);
+    __syncthreads();
+
+    const int8_t* a_base = smem + l16 * A_STRIDE + q * 16;
+    Lut lut[CJ];
+    int buf = 0;
+
+    // One 64-k stage: t = its place in the 256-k tile.  The activations of stage it+1 go to LDS, those
+    // of stage it+2 are requested; with t == 0 the next tile's weights are requested too.  All loads
+    // are unconditional (clamped past the end) and stay at the top of the stage.
+    auto stage = [&](int64_t it, auto tc, const WTile<G>& wc, WTile<G>& wnx) {
+        constexpr int t = decltype(tc)::value;
+        const int buf_next = buf == NBUF - 1 ? 0 : buf + 1;
+        store_a(buf_next);
+        if constexpr (t == 0) load_w((it >> 2) + 1, wnx);
+        load_a(it + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (G == 64 || (t & 1) == 0) {             // a group begins: its four weights per column
+#pragma unroll
+            for (int j = 0; j < CJ; ++j) {
+                const uint32_t pair = wc.s[j][G == 128 ? 0 : t >> 1];
+                const int g_in_pair = G == 128 ? t >> 1 : t & 1;
+                lut[j] = make_lut(g_in_pair ? pair >> 16 : pair & 0xffffu);
+            }
+        }
+        const int8_t* ab = a_base + buf * A_BUF;
+        v4i b0[CJ], b1[CJ];
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) {
+            const uint32_t wd = t == 0 ? wc.w[j].x : t == 1 ? wc.w[j].y : t == 2 ? wc.w[j].z : wc.w[j].w;
+            upconvert(wd, lut[j], b0[j], b1[j]);
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            v4i aop[RI];
+#pragma unroll
+            for (int i = 0; i < RI; ++i)
+                aop[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE + e * 64);
+#pragma unroll
+            for (int j = 0; j < CJ; ++j)
+#pragma unroll
+                for (int i = 0; i < RI; ++i)
+                    acc[i][j] = mfma_bf16(aop[i], e == 0 ? b0[j] : b1[j], acc[i][j]);
+        }
+        buf = buf_next;
+        __syncthreads();
+    };
+    auto tile = [&](int64_t kt, const WTile<G>& wc, WTile<G>& wnx) {
+        stage(kt * 4, std::integral_constant<int, 0>{}, wc, wnx);
+        stage(kt * 4 + 1, std::integral_constant<int, 1>{}, wc, wnx);
+        stage(kt * 4 + 2, std::integral_constant<int, 2>{}, wc, wnx);
+        stage(kt * 4 + 3, std::integral_constant<int, 3>{}, wc, wnx);
+    };
+    for (int64_t kt = 0; kt < a.n_kt; kt += 2) {
+        tile(kt, w0, w1);
+        if (kt + 1 < a.n_kt) tile(kt + 1, w1, w0);           // uniform
+    }
+
+    // The wave's 128 x 32 result goes through LDS (its own region; the barrier at the end of the last
+    // stage freed the activation buffers) and leaves as 16-byte stores, four lanes per 64-byte row piece.
+    int8_t* ebase = smem + wn * (BM * E_STRIDE);
+    uint16_t* eb = reinterpret_cast<uint16_t*>(ebase);
+#pragma unroll
+    for (int i = 0; i < RI; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = i * 16 + 4 * q + r;
+#pragma unroll
+            for (int j = 0; j < CJ; ++j) eb[row * (E_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(acc[i][j][r]);
+        }
+    // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
+    constexpr int LPR = WN * 2 / 16;                         // lanes per row piece (16 bytes each)
+    constexpr int RPP = 64 / LPR;                            // rows per pass
+    const int64_t ncol = n0 + wn * WN + (lane % LPR) * 8;    // first of this lane's 8 columns
+#pragma unroll
+    for (int p = 0; p < BM / RPP; ++p) {
+        const int row = p * RPP + lane / LPR;
+        const int64_t m = m0 + row;
+        const uint4 v = *reinterpret_cast<const uint4*>(ebase + row * E_STRIDE + (lane % LPR) * 16);
+        if (m < a.M && ncol < a.N) *reinterpret_cast<uint4*>(a.Y + m * a.ldy + ncol) = v;   // N % 8 == 0: all 8 or none
+    }
+}
+
+}  // namespace fold16
+
+template <int G, int BN>
+static int launch_fold_bn(const A16Args& a, hipStream_t stream)
+{
+    using namespace fold16;
+    const int tiles_m = (int)((a.M + BM - 1) / BM);
+    const int tiles_n = (int)((a.N + BN - 1) / BN);
+    int group_m = env_int("W2_TILED_GROUP_M", 8);
+    if (group_m < 1) group_m = 1;
+    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(64 * waves_of(BN));
+    constexpr int lds = lds_bytes(BN);
+    if (lds > 64 * 1024) {                                   // more than 64 KiB of dynamic LDS needs the opt-in
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(a16_fold_tiled_kernel<G, BN>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) {
+            set_error("w2_matmul_a16[scaled16 tiled]: hipFuncSetAttribute(%d): %s", lds, hipGetErrorString(e));
+            return -5;
+        }
+    }
+    hipLaunchKernelGGL((a16_fold_tiled_kernel<G, BN>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
+    return check_launch("w2_matmul_a16[scaled16 tiled]");
+}
+
+int launch_a16_fold_tiled(const A16Args& a, hipStream_t stream)
+{
+    // 256 columns per workgroup (eight waves, one workgroup per CU) unless that leaves half the
+    // chip without a workgroup; then 128 columns (four waves)
+    const int64_t wgs256 = ((a.M + fold16::BM - 1) / fold16::BM) * ((a.N + 255) / 256);
+    const int bn = env_int("W2_FOLD_BN", wgs256 <= 128 ? 128 : 256);
+    if (bn == 256) return a.G == 128 ? launch_fold_bn<128, 256>(a, stream) : launch_fold_bn<64, 256>(a, stream);
+    return a.G == 128 ? launch_fold_bn<128, 128>(a, stream) : launch_fold_bn<64, 128>(a, stream);
+}
+
+}  // namespace w2

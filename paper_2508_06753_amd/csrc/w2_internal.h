@@ -54,12 +54,13 @@ struct A16Args {
     int64_t M, K, N, ldx, ldy;
     int64_t n_cb, n_kt;
     int G;
-    int fold;       // small-M kernel only: build the weights as sw*q (scale folded in), no dequant step
+    int fold;       // build the weights as sw*q (scale folded in): no zero-point term, no dequant step
 };
 
 bool a16_smallm_supports(const A16Args& a);
 int launch_a16_smallm(const A16Args& a, hipStream_t stream);
 int launch_a16_tiled(const A16Args& a, hipStream_t stream);
+int launch_a16_fold_tiled(const A16Args& a, hipStream_t stream);
 
 // Environment override for tuning sweeps (read once per call on the host).
 int env_int(const char* name, int dflt);

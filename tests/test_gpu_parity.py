@@ -342,6 +342,16 @@ def test_a16_scale_folded_weights(w2, M, K, N, G):
     run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SCALED16, seed=M + K + N + G)
 
 
+@pytest.mark.parametrize("bn", [128, 256])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (768, 1032)])
+@pytest.mark.parametrize("M", [17, 127, 128, 129, 300])
+def test_a16_scale_folded_weights_large_m(w2, M, K, N, G, bn, monkeypatch):
+    # the same construction in the 128-row tiled kernel; both workgroup widths; K = 768 is an odd number of tiles
+    monkeypatch.setenv("W2_FOLD_BN", str(bn))
+    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SCALED16, seed=M + K + N + G)
+
+
 def test_a16_scale_folded_zero_scales_and_exact_integers(w2):
     # a group with scale 0 contributes exactly nothing (-2 * 0 must not become a denormal), and with
     # unit scales and small-integer activations every product and sum is exact
@@ -359,9 +369,12 @@ def test_a16_scale_folded_zero_scales_and_exact_integers(w2):
     ref = Xi.astype(np.float64) @ W
     assert np.abs(ref).max() < 256
     assert np.array_equal(bits_to_f64(bf16_bits(Y)), ref)
-    with pytest.raises(w2.W2Error):                          # M <= 16 only
-        w2.matmul_a16(packed, K, N, G, dev(synth.f32_to_bf16_bits(np.zeros((17, K), np.float32))).view(torch.bfloat16),
-                      variant=w2.VARIANT_SCALED16)
+    # the same through the large-M kernel of this construction (M > 16)
+    Xi = rng.integers(-2, 3, size=(150, K)).astype(np.float32)
+    Y = w2.matmul_a16(packed, K, N, G, dev(synth.f32_to_bf16_bits(Xi)).view(torch.bfloat16), variant=w2.VARIANT_SCALED16)
+    ref = Xi.astype(np.float64) @ W
+    assert np.abs(ref).max() < 256
+    assert np.array_equal(bits_to_f64(bf16_bits(Y)), ref)
 
 
 def test_a16_lds_chunking_and_outliers(w2):
