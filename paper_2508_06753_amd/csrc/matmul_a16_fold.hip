@@ -15,14 +15,17 @@
 // instructions per 16 weights.  They are amortised over a 128-row wave tile
 // (RI = 8 row tiles x CJ = 2 column blocks of v_mfma_f32_16x16x32_bf16: 32
 // matrix instructions per 64-k stage and wave), which is what makes this
-// construction the faster one for prefill: per matrix instruction it issues
-// about 2.5 vector instructions where the zero-point kernel issues about 6.
+// construction the faster one for prefill: measured, it issues 2.3 vector
+// instructions per matrix instruction where the zero-point kernel issues 5.9.
 //
 // Workgroup: 128 rows x (32 columns per wave) x 64 k per stage; activations go
-// through LDS (three buffers, rows de-interleaved [even k | odd k] per 16-k
-// block to match the order the codes come out of a dword, row stride 160 B:
-// conflict-free operand reads); weights go from global memory to registers, one
-// 16-byte load per lane, column block and 256-k tile, a whole tile ahead.
+// through LDS (three or five buffers, rows de-interleaved [even k | odd k] per
+// 16-k block to match the order the codes come out of a dword, row stride
+// 160 B: conflict-free operand reads); weights go from global memory to
+// registers, one 16-byte load per lane, column block and 256-k tile, a whole
+// tile ahead.  Each wave is software-pipelined on its own (next stage's weights
+// are up-converted and its first operands read under this stage's matrix
+// instructions).  Tried and slower: 256-row wave tiles at one wave per SIMD.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -36,18 +39,19 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 namespace fold16 {
 
-constexpr int RI = 8;                              // 16-row tiles per wave
 constexpr int CJ = 2;                              // 16-column blocks per wave
-constexpr int BM = 16 * RI, BK = 64;
+constexpr int BK = 64;
 constexpr int WN = 16 * CJ;
 constexpr int A_STRIDE = BK * 2 + 32;              // 32 mod 64 bytes: conflict-free A-operand reads
-constexpr int A_BUF = BM * A_STRIDE;
-constexpr int NBUF = 3;
+// LDS buffers: 3 with a barrier after every stage; 5 with a barrier after every other stage (eight-wave
+// workgroups, one per CU, where the LDS is there for it)
+constexpr int nbuf_of(int bn) { return bn >= 256 ? 5 : 3; }
 constexpr int E_STRIDE = WN * 2 + 16;              // epilogue: bytes per LDS row of a wave's result
 constexpr int waves_of(int bn) { return bn / WN; }
-constexpr int lds_bytes(int bn)
+constexpr int lds_bytes(int bn, int bm)
 {
-    return NBUF * A_BUF > waves_of(bn) * BM * E_STRIDE ? NBUF * A_BUF : waves_of(bn) * BM * E_STRIDE;
+    return nbuf_of(bn) * bm * A_STRIDE > waves_of(bn) * bm * E_STRIDE ? nbuf_of(bn) * bm * A_STRIDE
+                                                                      : waves_of(bn) * bm * E_STRIDE;
 }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
@@ -99,12 +103,15 @@ struct WTile {
     uint32_t s[CJ][G == 128 ? 1 : 2];              // the lane's column: 2 (G=128) or 4 (G=64) bf16 group scales
 };
 
-template <int G, int BN>
-__global__ void __launch_bounds__(64 * waves_of(BN), waves_of(BN) > 4 ? 1 : 2)
+// RI: 16-row tiles per wave (the workgroup's rows: BM = 16 RI)
+template <int G, int BN, int RI>
+__global__ void __launch_bounds__(64 * waves_of(BN), (waves_of(BN) > 4 || RI > 8) ? 1 : 2)
 a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
 {
+    constexpr int BM = 16 * RI, A_BUF = BM * A_STRIDE;
     constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
     constexpr int GPT = TILE_K / G;
+    constexpr int NBUF = nbuf_of(BN);
     constexpr int NP = BM * 8 / THREADS;           // 16-byte activation pieces per thread and stage: 2 or 4
     extern __shared__ __align__(16) int8_t smem[];
     const int tid = threadIdx.x;
@@ -158,8 +165,9 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
         for (int j = 0; j < CJ; ++j) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
     const int64_t n_st = a.n_kt * 4;                         // stages of 64 k
-    uint4 ar[NP];
-    auto load_a = [&](int64_t st) {
+    // two register sets: a load has two stages to land before its data goes to LDS
+    uint4 ar0[NP], ar1[NP];
+    auto load_a = [&](int64_t st, uint4 (&ar)[NP]) {
         st = min(st, n_st - 1);
         const char* p = cp_base + st * (BK * 2);             // uniform
 #pragma unroll
@@ -169,7 +177,7 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
         }
     };
     // eight k of a row: the even ones to the [even] half of the 16-k block's image, the odd ones 64 B on
-    auto store_a = [&](int buf) {
+    auto store_a = [&](int buf, const uint4 (&ar)[NP]) {
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             const uint32_t d[4] = {ar[i].x, ar[i].y, ar[i].z, ar[i].w};
@@ -202,61 +210,102 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
     };
 
     WTile<G> w0, w1;
-    load_a(0);
     load_w(0, w0);
-    store_a(0);
-    load_a(1);
+    // stages 0 .. WR-1 go to LDS up front; the registers then hold stages WR and WR+1
+    constexpr int WR = NBUF == 3 ? 2 : 3;          // stage it writes the activations of stage it+WR
+#pragma unroll
+    for (int p = 0; p < WR; ++p) {
+        load_a(p, ar0);
+        store_a(p, ar0);
+    }
+    load_a(WR, ar0);
+    load_a(WR + 1, ar1);
     __syncthreads();
 
     const int8_t* a_base = smem + l16 * A_STRIDE + q * 16;
     Lut lut[CJ];
+    struct BSet { v4i b0[CJ], b1[CJ]; };
+
+    // the weights of stage t of tile w, column block j (a group's look-up table is rebuilt where it begins)
+    auto prep_b = [&](auto tc, const WTile<G>& w, int j, BSet& out) {
+        constexpr int t = decltype(tc)::value;
+        if constexpr (G == 64 || (t & 1) == 0) {
+            const uint32_t pair = w.s[j][G == 128 ? 0 : t >> 1];
+            const int g_in_pair = G == 128 ? t >> 1 : t & 1;
+            lut[j] = make_lut(g_in_pair ? pair >> 16 : pair & 0xffffu);
+        }
+        const uint32_t wd = t == 0 ? w.w[j].x : t == 1 ? w.w[j].y : t == 2 ? w.w[j].z : w.w[j].w;
+        upconvert(wd, lut[j], out.b0[j], out.b1[j]);
+    };
+
+    // Software pipeline.  A wave enters stage `it` with the stage's weights up-converted (bc) and its
+    // even-k activation operands (a0) in registers.  Under the stage's 32 matrix instructions it
+    // reads the odd-k operands, up-converts the weights of stage it+1 (bn) and reads that stage's
+    // even-k operands, so every wave keeps the matrix pipe and the vector pipe busy at the same
+    // time whatever the other waves of the workgroup, which the barriers keep in step, are doing.
+    // LDS, three buffers: stage it reads buffers it and it+1 and writes the activations of stage it+2
+    // (loaded from global memory two stages earlier) into the third; the barrier at the end of a stage
+    // orders both.  Five buffers: a barrier after every other stage only; the pair of stages (2S, 2S+1)
+    // reads stages 2S .. 2S+2 and writes stages 2S+3 and 2S+4, five different buffers, so waves of a
+    // workgroup may be a stage apart inside a pair.
+    v4i a0[RI];
+#pragma unroll
+    for (int i = 0; i < RI; ++i) a0[i] = *reinterpret_cast<const v4i*>(a_base + i * 16 * A_STRIDE);
+    BSet bA, bB;
+    prep_b(std::integral_constant<int, 0>{}, w0, 0, bA);
+    prep_b(std::integral_constant<int, 0>{}, w0, 1, bA);
     int buf = 0;
 
-    // One 64-k stage: t = its place in the 256-k tile.  The activations of stage it+1 go to LDS, those
-    // of stage it+2 are requested; with t == 0 the next tile's weights are requested too.  All loads
-    // are unconditional (clamped past the end) and stay at the top of the stage.
-    auto stage = [&](int64_t it, auto tc, const WTile<G>& wc, WTile<G>& wnx) {
+    auto stage = [&](int64_t it, auto tc, const WTile<G>& wc, WTile<G>& wnx, const BSet& bc, BSet& bn) {
         constexpr int t = decltype(tc)::value;
-        const int buf_next = buf == NBUF - 1 ? 0 : buf + 1;
-        store_a(buf_next);
+        constexpr std::integral_constant<int, (t + 1) & 3> tn{};
+        const WTile<G>& wn_tile = t == 3 ? wnx : wc;         // where stage it+1 finds its weights
+        const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;
+        const int bufw = buf + WR >= NBUF ? buf + WR - NBUF : buf + WR;
+        store_a(bufw, (t & 1) ? ar1 : ar0);                  // activations of stage it+WR
         if constexpr (t == 0) load_w((it >> 2) + 1, wnx);
-        load_a(it + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (G == 64 || (t & 1) == 0) {             // a group begins: its four weights per column
+        load_a(it + WR + 2, (t & 1) ? ar1 : ar0);
+        __builtin_amdgcn_sched_barrier(0);                   // all loads are issued up here, unconditionally
+        const int8_t* ab = a_base + buf * A_BUF;
+        const int8_t* abn = a_base + buf1 * A_BUF;
+        v4i a1[RI];
 #pragma unroll
-            for (int j = 0; j < CJ; ++j) {
-                const uint32_t pair = wc.s[j][G == 128 ? 0 : t >> 1];
-                const int g_in_pair = G == 128 ? t >> 1 : t & 1;
-                lut[j] = make_lut(g_in_pair ? pair >> 16 : pair & 0xffffu);
+        for (int i = 0; i < RI; ++i) a1[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE + 64);
+        prep_b(tn, wn_tile, 0, bn);
+#pragma unroll
+        for (int j = 0; j < CJ; ++j)
+#pragma unroll
+            for (int i = 0; i < RI; ++i) acc[i][j] = mfma_bf16(a0[i], bc.b0[j], acc[i][j]);
+        prep_b(tn, wn_tile, 1, bn);
+#pragma unroll
+        for (int i = 0; i < RI; ++i) a0[i] = *reinterpret_cast<const v4i*>(abn + i * 16 * A_STRIDE);
+#pragma unroll
+        for (int j = 0; j < CJ; ++j)
+#pragma unroll
+            for (int i = 0; i < RI; ++i) acc[i][j] = mfma_bf16(a1[i], bc.b1[j], acc[i][j]);
+        // issue order: one matrix instruction, then the LDS read and the two vector instructions it hides
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int k = 0; k < RI; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
+#pragma unroll
+            for (int k = RI; k < RI * CJ; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
             }
         }
-        const int8_t* ab = a_base + buf * A_BUF;
-        v4i b0[CJ], b1[CJ];
-#pragma unroll
-        for (int j = 0; j < CJ; ++j) {
-            const uint32_t wd = t == 0 ? wc.w[j].x : t == 1 ? wc.w[j].y : t == 2 ? wc.w[j].z : wc.w[j].w;
-            upconvert(wd, lut[j], b0[j], b1[j]);
-        }
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            v4i aop[RI];
-#pragma unroll
-            for (int i = 0; i < RI; ++i)
-                aop[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE + e * 64);
-#pragma unroll
-            for (int j = 0; j < CJ; ++j)
-#pragma unroll
-                for (int i = 0; i < RI; ++i)
-                    acc[i][j] = mfma_bf16(aop[i], e == 0 ? b0[j] : b1[j], acc[i][j]);
-        }
-        buf = buf_next;
-        __syncthreads();
+        buf = buf1;
+        if constexpr (NBUF == 3 || (t & 1)) __syncthreads();
     };
     auto tile = [&](int64_t kt, const WTile<G>& wc, WTile<G>& wnx) {
-        stage(kt * 4, std::integral_constant<int, 0>{}, wc, wnx);
-        stage(kt * 4 + 1, std::integral_constant<int, 1>{}, wc, wnx);
-        stage(kt * 4 + 2, std::integral_constant<int, 2>{}, wc, wnx);
-        stage(kt * 4 + 3, std::integral_constant<int, 3>{}, wc, wnx);
+        stage(kt * 4, std::integral_constant<int, 0>{}, wc, wnx, bA, bB);
+        stage(kt * 4 + 1, std::integral_constant<int, 1>{}, wc, wnx, bB, bA);
+        stage(kt * 4 + 2, std::integral_constant<int, 2>{}, wc, wnx, bA, bB);
+        stage(kt * 4 + 3, std::integral_constant<int, 3>{}, wc, wnx, bB, bA);
     };
     for (int64_t kt = 0; kt < a.n_kt; kt += 2) {
         tile(kt, w0, w1);
@@ -290,25 +339,26 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
 
 }  // namespace fold16
 
-template <int G, int BN>
+template <int G, int BN, int RI>
 static int launch_fold_bn(const A16Args& a, hipStream_t stream)
 {
     using namespace fold16;
+    constexpr int BM = 16 * RI;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
     int group_m = env_int("W2_TILED_GROUP_M", 8);
     if (group_m < 1) group_m = 1;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(64 * waves_of(BN));
-    constexpr int lds = lds_bytes(BN);
+    constexpr int lds = lds_bytes(BN, BM);
     if (lds > 64 * 1024) {                                   // more than 64 KiB of dynamic LDS needs the opt-in
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(a16_fold_tiled_kernel<G, BN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(a16_fold_tiled_kernel<G, BN, RI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) {
             set_error("w2_matmul_a16[scaled16 tiled]: hipFuncSetAttribute(%d): %s", lds, hipGetErrorString(e));
             return -5;
         }
     }
-    hipLaunchKernelGGL((a16_fold_tiled_kernel<G, BN>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
+    hipLaunchKernelGGL((a16_fold_tiled_kernel<G, BN, RI>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
     return check_launch("w2_matmul_a16[scaled16 tiled]");
 }
 
@@ -316,10 +366,10 @@ int launch_a16_fold_tiled(const A16Args& a, hipStream_t stream)
 {
     // 256 columns per workgroup (eight waves, one workgroup per CU) unless that leaves half the
     // chip without a workgroup; then 128 columns (four waves)
-    const int64_t wgs256 = ((a.M + fold16::BM - 1) / fold16::BM) * ((a.N + 255) / 256);
+    const int64_t wgs256 = ((a.M + 127) / 128) * ((a.N + 255) / 256);
     const int bn = env_int("W2_FOLD_BN", wgs256 <= 128 ? 128 : 256);
-    if (bn == 256) return a.G == 128 ? launch_fold_bn<128, 256>(a, stream) : launch_fold_bn<64, 256>(a, stream);
-    return a.G == 128 ? launch_fold_bn<128, 128>(a, stream) : launch_fold_bn<64, 128>(a, stream);
+    if (bn == 256) return a.G == 128 ? launch_fold_bn<128, 256, 8>(a, stream) : launch_fold_bn<64, 256, 8>(a, stream);
+    return a.G == 128 ? launch_fold_bn<128, 128, 8>(a, stream) : launch_fold_bn<64, 128, 8>(a, stream);
 }
 
 }  // namespace w2

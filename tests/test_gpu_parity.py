@@ -347,7 +347,7 @@ def test_a16_scale_folded_weights(w2, M, K, N, G):
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (768, 1032)])
 @pytest.mark.parametrize("M", [17, 127, 128, 129, 300])
 def test_a16_scale_folded_weights_large_m(w2, M, K, N, G, bn, monkeypatch):
-    # the same construction in the 128-row tiled kernel; both workgroup widths; K = 768 is an odd number of tiles
+    # the same construction in the tiled kernel; both workgroup widths; K = 768 is an odd number of tiles
     monkeypatch.setenv("W2_FOLD_BN", str(bn))
     run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SCALED16, seed=M + K + N + G)
 
