@@ -357,6 +357,31 @@ def main():
     torch.cuda.synchronize()
     read_us = e0.elapsed_time(e1) * 1e3 / (reps * n_pool)
 
+    # the paper's own comparator: an int8-weight GEMV of the same shape (four times the bytes, no
+    # up-convert), over a pool of distinct copies as well
+    n8 = max(2, -(-POOL_BYTES // (Kd * Nd)))
+    W8 = torch.randint(-128, 128, (Nd, Kd), dtype=torch.int8, device=dev)
+    pool8 = [W8] + [W8.clone() for _ in range(n8 - 1)]
+    xq8 = torch.randint(-127, 128, (Kd,), dtype=torch.int8, device=dev)
+    out8 = torch.empty(Nd, dtype=torch.int32, device=dev)
+
+    def all_int8():
+        for w in pool8:
+            w2.debug_int8_gemv(w, xq8, out=out8)
+
+    g8 = capture(all_int8) if use_graph else None
+    for _ in range(3):
+        g8.replay() if g8 else all_int8()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        g8.replay() if g8 else all_int8()
+    e1.record()
+    torch.cuda.synchronize()
+    int8_us = e0.elapsed_time(e1) * 1e3 / (reps * n8)
+    int8_gbs = (Kd * Nd + Kd + 4 * Nd) / int8_us / 1e3
+    del pool8, W8
+
     out = {
         "metric": "M=1 weight-stream GB/s (% of HBM peak); TOPS at M=2048 (% of int8 MFMA peak)",
         "value": round(value, 1),
@@ -381,7 +406,9 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic("a8_fusedq gate_up M=1"),
                      "us_per_launch": round(gemv_us, 3), "bytes_per_launch": gemv_bytes,
                      "stream_read_us_same_bytes": round(read_us, 3),
-                     "frac_of_stream_read": round(read_us / gemv_us, 4)},
+                     "frac_of_stream_read": round(read_us / gemv_us, 4),
+                     "int8_weight_gemv_same_shape": {"us_per_launch": round(int8_us, 3), "GBps": round(int8_gbs, 1),
+                                                     "speedup_of_2bit": round(int8_us / gemv_us, 3)}},
     }
 
     # ---- secondary headline: compute-bound prefill, 70B-class gate+up at M=2048
@@ -411,9 +438,30 @@ def main():
                           "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": INT8_PEAK_TOPS,
                                        "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
                                        "traffic": read_traffic("a8_tiled gate_up 70B M=2048")}}
+        # comparator, as in the paper's GEMM figure: the vendor library's plain int8 x int8 -> int32
+        # GEMM (no up-convert, no scales, no bf16 output) on the same shape, weights drawn from the
+        # values the 2-bit codes up-convert to, K-contiguous (its faster layout)
+        try:
+            B8 = (torch.randint(-2, 2, (Np, Kp), dtype=torch.int8, device=dev) * 64).t()
+            for _ in range(40):
+                torch._int_mm(xqp, B8)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(nrep):
+                torch._int_mm(xqp, B8)
+            e1.record()
+            torch.cuda.synchronize()
+            lib_us = e0.elapsed_time(e1) * 1e3 / nrep
+            out["prefill"]["library_int8_gemm"] = {"what": "torch._int_mm (hipBLASLt), int8 x int8 -> int32, same shape",
+                                                   "us_per_launch": round(lib_us, 1),
+                                                   "TOPS": round(2.0 * Mp * Kp * Np / lib_us / 1e6, 1),
+                                                   "w2a8_over_library": round(lib_us / us, 3)}
+            del B8
+        except Exception as e:                               # the comparator is optional
+            out["prefill"]["library_int8_gemm"] = {"error": str(e)[:120]}
         # the unquantised-activation variant (w2a16) on the same shape, bf16 MFMA
         Xb = torch.randn(Mp, Kp, device=dev).to(torch.bfloat16)
-        for _ in range(15):
+        for _ in range(25):
             w2.matmul_a16(pk, Kp, Np, G, Xb, out=Yp)
         torch.cuda.synchronize()
         e0.record()
@@ -427,6 +475,24 @@ def main():
                               "value": round(tf16, 1), "unit": "TFLOP/s",
                               "roofline": {"bound": "mfma", "achieved": round(tf16, 1), "peak": 2500.0, "unit": "TFLOP/s",
                                            "frac": round(tf16 / 2500.0, 4), "traffic": None}}
+        try:
+            B16 = torch.randn(Np, Kp, device=dev, dtype=torch.bfloat16).t()
+            for _ in range(15):
+                torch.matmul(Xb, B16, out=Yp)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(8):
+                torch.matmul(Xb, B16, out=Yp)
+            e1.record()
+            torch.cuda.synchronize()
+            lib16_us = e0.elapsed_time(e1) * 1e3 / 8
+            out["prefill_a16"]["library_bf16_gemm"] = {"what": "torch.matmul (hipBLASLt), bf16 x bf16 -> bf16, same shape, 16-bit weights",
+                                                       "us_per_launch": round(lib16_us, 1),
+                                                       "TFLOPS": round(2.0 * Mp * Kp * Np / lib16_us / 1e6, 1),
+                                                       "w2a16_over_library": round(lib16_us / us16, 3)}
+            del B16
+        except Exception as e:
+            out["prefill_a16"]["library_bf16_gemm"] = {"error": str(e)[:120]}
         del pk, xqp, Yp, Xb
 
     # ---- between the two regimes: the weight stream read once for M = 32 rows (mid-M kernel),

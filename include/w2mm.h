@@ -202,6 +202,15 @@ W2_API int w2_debug_unpack(const void* packed, int64_t K, int64_t N, int G, w2_c
  * int8-weight GEMV plays in Sec. III-B/III-C). */
 W2_API int w2_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
 
+/* Comparator for the benchmark, not part of the method: an int8-weight GEMV
+ * (Sec. III-B, III-C read the 2-bit GEMV against the int8 one, which moves
+ * four times the bytes and has no up-convert).  W8: dev int8 [N][K] row-major
+ * (16-byte aligned, K % 16 == 0, K <= 49152); xq: dev int8 [K] (16-byte
+ * aligned); out: dev int32 [N], out[n] = sum_k W8[n][k] * xq[k], exact.
+ * Launches on `stream`; writes nothing on error. */
+W2_API int w2_debug_int8_gemv(const int8_t* W8, int64_t K, int64_t N, const int8_t* xq, int32_t* out,
+                              void* stream);
+
 W2_API const char* w2_status_string(int status);
 /* Thread-local detail of the last error on this host thread (e.g. the HIP error
  * string or the violated rule); empty string if none. */

@@ -42,6 +42,7 @@ _SIGS = {
     "w2_debug_group_acc_a8": [_vp, _i64, _i64, _int, _vp, _i64, _int, _vp, _vp],
     "w2_debug_unpack": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp],
     "w2_debug_stream_read": [_vp, _sz, _vp, _vp],
+    "w2_debug_int8_gemv": [_vp, _i64, _i64, _vp, _vp, _vp],
 }
 for _name, _args in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -201,6 +202,19 @@ def debug_unpack(packed, K, N, G, codec=CODEC_INT2):
     _check("w2_debug_unpack", _lib.w2_debug_unpack(_ptr(packed), K, N, G, codec, _ptr(codes),
                                                    _ptr(scales), _stream()))
     return codes, scales
+
+
+def debug_int8_gemv(W8, xq, out=None):
+    """Comparator: out int32 [N] = W8 int8 [N,K] @ xq int8 [K], exact."""
+    _dev(W8, torch.int8, "W8")
+    _dev(xq, torch.int8, "xq")
+    N, K = W8.shape
+    if not W8.is_contiguous() or xq.numel() != K:
+        raise ValueError("W8 must be contiguous [N,K] and xq [K]")
+    if out is None:
+        out = torch.empty(N, dtype=torch.int32, device=W8.device)
+    _check("w2_debug_int8_gemv", _lib.w2_debug_int8_gemv(_ptr(W8), K, N, _ptr(xq), _ptr(out), _stream()))
+    return out
 
 
 def debug_stream_read(buf, sink=None):

@@ -364,6 +364,16 @@ int w2_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* st
     return launch_stream_read(src, bytes, sink, (hipStream_t)stream);
 }
 
+int w2_debug_int8_gemv(const int8_t* W8, int64_t K, int64_t N, const int8_t* xq, int32_t* out, void* stream)
+{
+    if (K <= 0 || N <= 0) return fail(W2_ERR_INVALID_ARG, "w2_debug_int8_gemv: K and N must be positive");
+    if (K % 16 || K > 49152) return fail(W2_ERR_UNSUPPORTED_SHAPE, "w2_debug_int8_gemv: K must be a multiple of 16, at most 49152");
+    if (N > (int64_t)1 << 24) return fail(W2_ERR_UNSUPPORTED_SHAPE, "w2_debug_int8_gemv: N is limited to 2^24");
+    if (!W8 || !xq || !out) return fail(W2_ERR_INVALID_ARG, "w2_debug_int8_gemv: NULL pointer");
+    if (!aligned16(W8) || !aligned16(xq)) return fail(W2_ERR_MISALIGNED, "w2_debug_int8_gemv: W8 and xq must be 16-byte aligned");
+    return launch_int8_gemv(W8, xq, out, K, N, (hipStream_t)stream);
+}
+
 const char* w2_status_string(int status)
 {
     switch (status) {

@@ -62,6 +62,8 @@ int launch_a16_smallm(const A16Args& a, hipStream_t stream);
 int launch_a16_tiled(const A16Args& a, hipStream_t stream);
 int launch_a16_fold_tiled(const A16Args& a, hipStream_t stream);
 
+int launch_int8_gemv(const int8_t* W8, const int8_t* xq, int32_t* out, int64_t K, int64_t N, hipStream_t stream);
+
 // Environment override for tuning sweeps (read once per call on the host).
 int env_int(const char* name, int dflt);
 

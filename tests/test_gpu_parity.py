@@ -405,6 +405,19 @@ def test_a16_exact_small_integers(w2):
     assert np.array_equal(bits_to_f64(bf16_bits(Y)), ref.astype(np.float64))
 
 
+@pytest.mark.parametrize("K,N", [(256, 16), (4096, 50), (14336, 129), (1040, 7)])
+def test_int8_gemv_comparator_is_exact(w2, K, N):
+    # the benchmark's int8-weight GEMV: integer dot products, compared bit for bit
+    rng = np.random.default_rng(K + N)
+    W8 = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+    xq = rng.integers(-127, 128, size=K, dtype=np.int8)
+    out = w2.debug_int8_gemv(dev(W8), dev(xq))
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), (W8.astype(np.int64) @ xq.astype(np.int64)).astype(np.int32))
+    with pytest.raises(w2.W2Error):
+        w2.debug_int8_gemv(dev(W8[:, :K - 8].copy()), dev(xq[:K - 8].copy()))    # K % 16 != 0
+
+
 # ------------------------------------------------------------------ argument errors
 def test_argument_errors_write_nothing(w2):
     import ctypes
