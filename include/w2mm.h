@@ -67,20 +67,22 @@ typedef enum {
 /* Kernel families, for w2_matmul_a8_ex / w2_matmul_a16_ex and the debug export.
  * AUTO picks by M (w2a8: SMALLM for M <= 8 (M <= 3 when N >= 6144 or K > 16384), MIDM up to
  * M = 64, else TILED;
- * w2a16: SMALLM for M <= 16, else SCALED16).  DOT4: per-lane v_dot4_i32_i8
+ * w2a16: SMALLM for M <= 8, MIDM up to M = 64, else the SCALED16 tiled kernel).
+ * DOT4: per-lane v_dot4_i32_i8
  * with split-K across the waves of a workgroup (M <= 4; kept as the dot-product form of the microkernel,
  * selectable here).  SMALLM: one 16-row int8 (bf16 for a16) MFMA tile per
- * wave, split-K across waves (M <= 16).  MIDM (w2a8 only): the weight stream
+ * wave, split-K across waves (M <= 16).  MIDM: the weight stream
  * is still read once; every streamed tile is multiplied into one to four
- * 16-row MFMA tiles (M <= 64).  TILED: LDS-staged MFMA tiles (any M).
+ * 16-row MFMA tiles (M <= 64; for w2a16 with the SCALED16 weight construction).
+ * TILED: LDS-staged MFMA tiles (any M; for w2a16 the zero-point construction).
  * SCALED16 (w2a16 only): the weights are built as sw*q from code and group
  * scale (Sec. II-D, the alternative 16-bit construction) and go to the bf16
  * matrix instruction as they are: no zero-point term, no dequant step, one
  * fp32 accumulator per output over the whole K.  M <= 16: the SMALLM kernel
  * with this construction (never picked by AUTO: the zero-point form is faster
- * there).  M > 16: a 128-row tiled kernel of its own, AUTO's choice for
- * prefill.  Needs bf16 scales with an exponent field below 254 (-2 sw is made
- * by raising the exponent by one). */
+ * there); M <= 64: the MIDM kernel; above: a 128-row tiled kernel of its own,
+ * AUTO's choice for prefill.  Needs bf16 scales with an exponent field below
+ * 254 (-2 sw is made by raising the exponent by one). */
 typedef enum { W2_VARIANT_AUTO = 0, W2_VARIANT_DOT4 = 1, W2_VARIANT_SMALLM = 2,
                W2_VARIANT_TILED = 3, W2_VARIANT_MIDM = 4, W2_VARIANT_SCALED16 = 5 } w2_variant_t;
 

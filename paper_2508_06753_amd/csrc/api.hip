@@ -282,7 +282,7 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     if (rc) return rc;
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
     if (variant != W2_VARIANT_AUTO && variant != W2_VARIANT_SMALLM && variant != W2_VARIANT_TILED &&
-        variant != W2_VARIANT_SCALED16)
+        variant != W2_VARIANT_SCALED16 && variant != W2_VARIANT_MIDM)
         return fail(W2_ERR_INVALID_ARG, "%s: variant %d not available for w2a16", fn, variant);
     if (M == 0) return W2_OK;
     if (!packed || !X || !Y) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
@@ -301,14 +301,25 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
     a.fold = variant == W2_VARIANT_SCALED16;
     if (variant == W2_VARIANT_SCALED16) {
-        if (!a16_smallm_supports(a)) return launch_a16_fold_tiled(a, (hipStream_t)stream);
-        variant = W2_VARIANT_SMALLM;                                     // same kernel, other weight construction
+        // the scale-folded construction: the small-M kernel with it, or the kernels built on it
+        if (!a16_smallm_supports(a))
+            return a16_midm_supports(a) ? launch_a16_midm(a, (hipStream_t)stream)
+                                        : launch_a16_fold_tiled(a, (hipStream_t)stream);
+        variant = W2_VARIANT_SMALLM;
     }
     if (variant == W2_VARIANT_AUTO) {
-        // large M: the scale-folded construction issues the fewest vector instructions per matrix
-        // instruction (measured 1.7x the zero-point kernel on the prefill shapes)
+        // M <= 8: zero-point construction in the small-M kernel; up to 64 rows the mid-M kernel (the
+        // weight stream is still read once; measured faster from M = 9 on every projection shape);
+        // above, 128-row tiles.  Both of the latter fold the scale into the weights: fewest vector
+        // instructions per matrix instruction.
+        const int midm_min = env_int("W2_A16_MIDM_MIN_M", 9);
+        if (M >= midm_min && a16_midm_supports(a)) return launch_a16_midm(a, (hipStream_t)stream);
         if (!a16_smallm_supports(a)) return launch_a16_fold_tiled(a, (hipStream_t)stream);
         variant = W2_VARIANT_SMALLM;
+    }
+    if (variant == W2_VARIANT_MIDM) {
+        if (!a16_midm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: MIDM needs M <= 64", fn);
+        return launch_a16_midm(a, (hipStream_t)stream);
     }
     if (variant == W2_VARIANT_SMALLM) {
         if (!a16_smallm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: SMALLM needs M <= 16", fn);

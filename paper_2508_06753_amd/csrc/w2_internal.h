@@ -61,6 +61,8 @@ bool a16_smallm_supports(const A16Args& a);
 int launch_a16_smallm(const A16Args& a, hipStream_t stream);
 int launch_a16_tiled(const A16Args& a, hipStream_t stream);
 int launch_a16_fold_tiled(const A16Args& a, hipStream_t stream);
+bool a16_midm_supports(const A16Args& a);
+int launch_a16_midm(const A16Args& a, hipStream_t stream);
 
 int launch_int8_gemv(const int8_t* W8, const int8_t* xq, int32_t* out, int64_t K, int64_t N, hipStream_t stream);
 

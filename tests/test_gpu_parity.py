@@ -329,7 +329,26 @@ def test_a16_tiled(w2, M, K, N, G):
     run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G)
 
 
-@pytest.mark.parametrize("M", [1, 16, 17, 130])
+@pytest.mark.parametrize("cbw", [0, 2, 4, 8])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (768, 1032), (2304, 48)])
+@pytest.mark.parametrize("M", [1, 9, 16, 17, 31, 32, 33, 50, 64])
+def test_a16_midm(w2, M, K, N, G, cbw, monkeypatch):
+    # weight stream read once, scale-folded weights; every workgroup shape; K = 768, 2304: chunks that overlap
+    monkeypatch.setenv("W2_MIDM_CBW", str(cbw))
+    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_MIDM, seed=M + K + N + G)
+
+
+def test_a16_midm_long_k_and_limits(w2):
+    run_a16_case(w2, 40, 14336, 64, 128, 0, w2.VARIANT_MIDM, seed=3)
+    K, N, G = 256, 16, 128
+    codes, scales, X = synth.make_problem(65, K, N, G, 0, 0)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    with pytest.raises(w2.W2Error):
+        w2.matmul_a16(packed, K, N, G, dev(synth.f32_to_bf16_bits(X)).view(torch.bfloat16), variant=w2.VARIANT_MIDM)
+
+
+@pytest.mark.parametrize("M", [1, 16, 17, 64, 65, 130])
 def test_a16_auto_dispatch(w2, M):
     run_a16_case(w2, M, 1024, 528, 128, 0, w2.VARIANT_AUTO, seed=M)
 
