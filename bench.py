@@ -131,15 +131,18 @@ def sweep_mode(torch, w2, synth, dev):
             xq, sx, _ = w2.quantize_rows(X, g)
             Xb = X.to(torch.bfloat16)
             Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            nws = w2.workspace_size(M, K, N, g)
+            ws = torch.empty(nws, dtype=torch.uint8, device=dev) if nws else None
+            nws16 = w2.workspace_size(M, K, N, g, a16=True)
+            ws16 = torch.empty(nws16, dtype=torch.uint8, device=dev) if nws16 else None
             if "a8" in calls:
-                line(cfg, name, K, N, g, M, "a8", timed(lambda l: w2.matmul_a8(l, K, N, g, xq, sx, out=Y), pool))
+                line(cfg, name, K, N, g, M, "a8", timed(lambda l: w2.matmul_a8(l, K, N, g, xq, sx, out=Y, workspace=ws), pool))
             if "fused" in calls:
-                nws = w2.workspace_size(M, K, N, g)
-                ws = torch.empty(nws, dtype=torch.uint8, device=dev) if nws else None
                 line(cfg, name, K, N, g, M, "a8 fused(f32 in)",
                      timed(lambda l: w2.matmul_a8_fused(l, K, N, g, X, out=Y, workspace=ws), pool))
             if "a16" in calls:
-                line(cfg, name, K, N, g, M, "a16", timed(lambda l: w2.matmul_a16(l, K, N, g, Xb, out=Y), pool))
+                line(cfg, name, K, N, g, M, "a16",
+                     timed(lambda l: w2.matmul_a16(l, K, N, g, Xb, out=Y, workspace=ws16), pool))
         del pool
 
     print("# every launch reads a different prepacked copy (pool > 2 x 256 MB last-level cache); times are per launch "
@@ -151,6 +154,10 @@ def sweep_mode(torch, w2, synth, dev):
         decode_case("cfg2", "gate_up", 4096, 28672, g, (1, 2, 4, 8, 16, 32, 64), ("a8",))
     for name, (K, N) in synth.SHAPES_27B.items():
         decode_case("cfg3", name, K, N, 128, (1, 8), ("a8", "fused", "stream read"))
+    print("# between decode and prefill (8B-class projections; workspaces of w2_workspace_size bytes, so the tiled "
+          "kernels may split K)")
+    for name, (K, N) in synth.SHAPES_8B.items():
+        decode_case("mid", name, K, N, 128, (16, 32, 64, 128, 256), ("a8", "a16"))
     print("# prefill: 40 launches to warm the clock up, 20 timed")
     for name, (K, N) in synth.SHAPES_70B.items():
         nb = w2.packed_size(K, N, G)

@@ -136,8 +136,14 @@ W2_API int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_
  * packed  dev, from w2_prepack with the same K, N, G
  * xq, sx  dev, as produced by w2_quantize_rows ([M][K] dense, [M])
  * Y       dev, bf16 bit patterns [M][N], row stride ldy
- * workspace  unused by this call (split-K is reduced inside a workgroup);
- *            pass NULL / 0. */
+ * workspace  optional (NULL / 0: none), dev, 16-byte aligned, contents
+ *            undefined before and after: for M > 64 on shapes with few
+ *            output tiles and a deep K the tiled kernel splits K across
+ *            workgroups (Sec. II-D, K-splitting for the smaller GEMM
+ *            shapes) if it is given room for the fp32 partial results
+ *            (w2_workspace_size; less room = fewer parts or none, same
+ *            result contract).  A second launch on `stream` sums the parts
+ *            in a fixed order.  Not touched otherwise. */
 W2_API int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
                  const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                  size_t workspace_bytes, void* stream);
@@ -152,7 +158,10 @@ W2_API int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, cons
  * fused into the GEMM; Sec. III-C: fusing wins for matrix-vector shapes, a
  * separate abs-max pass for multi-row activations).  Takes the unquantised
  * activations (fp32 or bf16, row stride ldx) and produces exactly what
- * w2_quantize_rows followed by w2_matmul_a8 produces, bit for bit.
+ * w2_quantize_rows followed by w2_matmul_a8 produces, bit for bit (where the
+ * tiled kernel splits K, i.e. M > 64 with room in the workspace beyond the
+ * int8 rows, the fp32 sums are taken in another order and the two agree to the
+ * tolerance of the result contract instead).
  *   M <= 2: one launch; the abs-max is reduced per workgroup, redundantly, and
  *           kept in local memory.
  *   M >= 3: with a workspace of w2_workspace_size(M, K, N, G, 0) bytes (dev,
@@ -172,7 +181,8 @@ W2_API int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, c
  * values from code and group scale, activations left unquantised, 16-bit
  * matrix instructions with fp32 accumulation, no quantise/dequantise):
  *   Y[m,n] = bf16( sum_k x[m,k] * (sw[k/G,n] * q[k,n]) )
- * X  dev, bf16 bit patterns [M][K], row stride ldx. */
+ * X  dev, bf16 bit patterns [M][K], row stride ldx.
+ * workspace  optional, as for w2_matmul_a8 (w2_workspace_size with a16 = 1). */
 W2_API int w2_matmul_a16(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
                   int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                   size_t workspace_bytes, void* stream);
@@ -181,10 +191,13 @@ W2_API int w2_matmul_a16_ex(const void* packed, int64_t K, int64_t N, int G, con
                      int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                      size_t workspace_bytes, int variant, void* stream);
 
-/* Bytes of workspace (host out-pointer) with which w2_matmul_a8_fused takes its
- * fastest route for this problem (a16 = 0): 0 where one launch covers it (one
- * or two rows of up to 64 KiB as fp32), else room for the int8 rows and their
- * scales.  The other matmul calls need none (a16 = 1: 0). */
+/* Bytes of workspace (host out-pointer) with which the calls take their fastest
+ * route for this problem.  a16 = 0 (w2_matmul_a8_fused; w2_matmul_a8 uses the
+ * split-K part only and accepts the same buffer): room for the int8 rows and
+ * their scales, rounded up to 256 bytes (0 where one launch covers the
+ * quantisation: one or two rows of up to 64 KiB as fp32), plus, where the tiled
+ * kernel would split K, 2..16 fp32 copies of the M x N output.  a16 = 1
+ * (w2_matmul_a16): the split-K part alone.  0 means no workspace is used. */
 W2_API int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* bytes);
 
 /* ------------------------------------------------------------------------

@@ -138,8 +138,16 @@ def quantize_rows(X, G=128, want_gsum=False):
     return xq, sx, gsum
 
 
-def matmul_a8(packed, K, N, G, xq, sx, out=None, variant=VARIANT_AUTO):
-    """Y bf16 [M,N] = dequant-fused int8 matmul.  xq int8 [M,K], sx fp32 [M]."""
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    _dev(workspace, torch.uint8, "workspace")
+    return _ptr(workspace), workspace.numel()
+
+
+def matmul_a8(packed, K, N, G, xq, sx, out=None, variant=VARIANT_AUTO, workspace=None):
+    """Y bf16 [M,N] = dequant-fused int8 matmul.  xq int8 [M,K], sx fp32 [M].  `workspace`: optional uint8
+    device tensor; with workspace_size(M, K, N, G) bytes the tiled kernel may split K across workgroups."""
     _dev(xq, torch.int8, "xq")
     _dev(sx, torch.float32, "sx")
     M = xq.shape[0]
@@ -147,8 +155,9 @@ def matmul_a8(packed, K, N, G, xq, sx, out=None, variant=VARIANT_AUTO):
         raise ValueError("xq must be contiguous [M,K], sx [M]")
     Y = out if out is not None else torch.empty((M, N), dtype=torch.bfloat16, device=xq.device)
     ldy = Y.stride(0) if M > 1 else N
+    wp, wb = _ws(workspace)
     _check("w2_matmul_a8", _lib.w2_matmul_a8_ex(_ptr(packed), K, N, G, _ptr(xq), _ptr(sx), M,
-                                                _ptr(Y), ldy, None, 0, variant, _stream()))
+                                                _ptr(Y), ldy, wp, wb, variant, _stream()))
     return Y
 
 
@@ -173,8 +182,9 @@ def matmul_a8_fused(packed, K, N, G, X, out=None, workspace=None):
     return Y
 
 
-def matmul_a16(packed, K, N, G, X, out=None, variant=VARIANT_AUTO):
-    """Y bf16 [M,N] from bf16 activations X [M,K] (unquantised)."""
+def matmul_a16(packed, K, N, G, X, out=None, variant=VARIANT_AUTO, workspace=None):
+    """Y bf16 [M,N] from bf16 activations X [M,K] (unquantised).  `workspace`: as for matmul_a8
+    (workspace_size(..., a16=True) bytes)."""
     _dev(X, torch.bfloat16, "X")
     M = X.shape[0]
     if X.dim() != 2 or X.shape[1] != K or X.stride(1) != 1:
@@ -182,8 +192,9 @@ def matmul_a16(packed, K, N, G, X, out=None, variant=VARIANT_AUTO):
     Y = out if out is not None else torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
     ldx = X.stride(0) if M > 1 else K
     ldy = Y.stride(0) if M > 1 else N
+    wp, wb = _ws(workspace)
     _check("w2_matmul_a16", _lib.w2_matmul_a16_ex(_ptr(packed), K, N, G, _ptr(X), ldx, M, _ptr(Y),
-                                                  ldy, None, 0, variant, _stream()))
+                                                  ldy, wp, wb, variant, _stream()))
     return Y
 
 

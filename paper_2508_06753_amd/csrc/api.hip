@@ -155,7 +155,7 @@ int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_t K, in
 
 static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, int G,
                      const int8_t* xq, const float* sx, int64_t M, uint16_t* Y, int64_t ldy,
-                     int32_t* acc_out, int variant, void* stream)
+                     int32_t* acc_out, void* workspace, size_t workspace_bytes, int variant, void* stream)
 {
     int rc = check_shape(fn, K, N, G);
     if (rc) return rc;
@@ -177,6 +177,10 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     a.xq = xq; a.sx = sx; a.Y = Y; a.acc_out = acc_out;
     a.M = M; a.K = K; a.N = N; a.ldy = ldy;
     a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
+    if (workspace && !aligned16(workspace))
+        return fail(W2_ERR_MISALIGNED, "%s: workspace must be 16-byte aligned", fn);
+    a.part = (float*)workspace;                              // split-K partial results, if the tiled kernel wants them
+    a.part_bytes = workspace ? workspace_bytes : 0;
     if (variant == W2_VARIANT_AUTO) {
         // measured: the MFMA form is at least as fast as dot4 from M = 1 on; the mid-M kernel (one
         // fma per accumulator in the dequant, rolling weight window; its time hardly grows with M)
@@ -210,8 +214,8 @@ int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, const int8_
                     const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                     size_t workspace_bytes, int variant, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
-    return a8_common("w2_matmul_a8", packed, K, N, G, xq, sx, M, Y, ldy, nullptr, variant, stream);
+    return a8_common("w2_matmul_a8", packed, K, N, G, xq, sx, M, Y, ldy, nullptr, workspace, workspace_bytes, variant,
+                     stream);
 }
 
 int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
@@ -222,10 +226,11 @@ int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* 
                            W2_VARIANT_AUTO, stream);
 }
 
-// Workspace that lets w2_matmul_a8_fused take the two-kernel route: int8 rows + one scale per row.
+// Workspace that lets w2_matmul_a8_fused take the two-kernel route: int8 rows + one scale per row
+// (rounded up to 256 bytes: split-K partial results may follow).
 static size_t fused_workspace_bytes(int64_t M, int64_t K)
 {
-    return (size_t)((M * K + 15) & ~(int64_t)15) + (size_t)M * sizeof(float);
+    return ((size_t)((M * K + 15) & ~(int64_t)15) + (size_t)M * sizeof(float) + 255) & ~(size_t)255;
 }
 
 int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const void* X,
@@ -263,20 +268,22 @@ int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const vo
     float* sx = (float*)((char*)workspace + ((M * K + 15) & ~(int64_t)15));
     rc = launch_quantize(X, x_dtype == W2_DT_BF16, M, K, ldx, G, xq, sx, nullptr, (hipStream_t)stream);
     if (rc) return rc;
-    return a8_common(fn, packed, K, N, G, xq, sx, M, Y, ldy, nullptr, W2_VARIANT_AUTO, stream);
+    const size_t used = fused_workspace_bytes(M, K);
+    return a8_common(fn, packed, K, N, G, xq, sx, M, Y, ldy, nullptr, (char*)workspace + used, workspace_bytes - used,
+                     W2_VARIANT_AUTO, stream);
 }
 
 int w2_debug_group_acc_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
                           int64_t M, int variant, int32_t* acc, void* stream)
 {
     if (!acc && M > 0) return fail(W2_ERR_INVALID_ARG, "w2_debug_group_acc_a8: acc is NULL");
-    return a8_common("w2_debug_group_acc_a8", packed, K, N, G, xq, nullptr, M, nullptr, 0, acc,
+    return a8_common("w2_debug_group_acc_a8", packed, K, N, G, xq, nullptr, M, nullptr, 0, acc, nullptr, 0,
                      variant, stream);
 }
 
 static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, int G,
                       const uint16_t* X, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
-                      int variant, void* stream)
+                      void* workspace, size_t workspace_bytes, int variant, void* stream)
 {
     int rc = check_shape(fn, K, N, G);
     if (rc) return rc;
@@ -299,6 +306,10 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     a.scales = (const uint16_t*)((const char*)packed + L.codes_bytes);
     a.X = X; a.Y = Y; a.M = M; a.K = K; a.N = N; a.ldx = ldx; a.ldy = ldy;
     a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
+    if (workspace && !aligned16(workspace))
+        return fail(W2_ERR_MISALIGNED, "%s: workspace must be 16-byte aligned", fn);
+    a.part = (float*)workspace;                              // split-K partial results, if the kernel wants them
+    a.part_bytes = workspace ? workspace_bytes : 0;
     a.fold = variant == W2_VARIANT_SCALED16;
     if (variant == W2_VARIANT_SCALED16) {
         // the scale-folded construction: the small-M kernel with it, or the kernels built on it
@@ -332,8 +343,8 @@ int w2_matmul_a16_ex(const void* packed, int64_t K, int64_t N, int G, const uint
                      int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                      size_t workspace_bytes, int variant, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
-    return a16_common("w2_matmul_a16", packed, K, N, G, X, ldx, M, Y, ldy, variant, stream);
+    return a16_common("w2_matmul_a16", packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes, variant,
+                      stream);
 }
 
 int w2_matmul_a16(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
@@ -352,7 +363,10 @@ int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* b
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "w2_workspace_size: M < 0");
     // one or two rows of up to 64 KiB (as fp32) run as a single launch and need none
     const bool single = M <= 2 && M * K * 4 <= 64 * 1024;
-    *bytes = (a16 || M == 0 || single) ? 0 : fused_workspace_bytes(M, K);
+    const Layout L = make_layout(K, N, G);
+    if (M == 0) *bytes = 0;
+    else if (a16) *bytes = M > 64 ? a16_fold_splitk_bytes(M, N, L.n_kt) : 0;
+    else *bytes = (single ? 0 : fused_workspace_bytes(M, K)) + (M > 64 ? a8_tiled_splitk_bytes(M, N, L.n_kt) : 0);
     return W2_OK;
 }
 

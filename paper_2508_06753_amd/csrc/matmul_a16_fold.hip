@@ -106,7 +106,7 @@ struct WTile {
 // RI: 16-row tiles per wave (the workgroup's rows: BM = 16 RI)
 template <int G, int BN, int RI>
 __global__ void __launch_bounds__(64 * waves_of(BN), (waves_of(BN) > 4 || RI > 8) ? 1 : 2)
-a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
+a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m, int splits)
 {
     constexpr int BM = 16 * RI, A_BUF = BM * A_STRIDE;
     constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
@@ -164,7 +164,9 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
 #pragma unroll
         for (int j = 0; j < CJ; ++j) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    const int64_t n_st = a.n_kt * 4;                         // stages of 64 k
+    // this workgroup's K range (split-K: blockIdx.y of `splits` near-equal ranges of whole tiles)
+    const int64_t kt_b = a.n_kt * blockIdx.y / splits, kt_e = a.n_kt * (blockIdx.y + 1) / splits;
+    const int64_t st_b = kt_b * 4, n_st = kt_e * 4;          // stages of 64 k: [st_b, n_st)
     // two register sets: a load has two stages to land before its data goes to LDS
     uint4 ar0[NP], ar1[NP];
     auto load_a = [&](int64_t st, uint4 (&ar)[NP]) {
@@ -192,7 +194,7 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
         }
     };
     auto load_w = [&](int64_t kt, WTile<G>& r) {
-        kt = min(kt, a.n_kt - 1);
+        kt = min(kt, kt_e - 1);
         const int64_t w_off = kt * 1024;
         const int64_t s_off = kt * (TILE_N * GPT * 2);
         asm volatile("" : "+v"(w_lane), "+v"(s_lane));
@@ -210,16 +212,16 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
     };
 
     WTile<G> w0, w1;
-    load_w(0, w0);
+    load_w(kt_b, w0);
     // stages 0 .. WR-1 go to LDS up front; the registers then hold stages WR and WR+1
     constexpr int WR = NBUF == 3 ? 2 : 3;          // stage it writes the activations of stage it+WR
 #pragma unroll
     for (int p = 0; p < WR; ++p) {
-        load_a(p, ar0);
+        load_a(st_b + p, ar0);
         store_a(p, ar0);
     }
-    load_a(WR, ar0);
-    load_a(WR + 1, ar1);
+    load_a(st_b + WR, ar0);
+    load_a(st_b + WR + 1, ar1);
     __syncthreads();
 
     const int8_t* a_base = smem + l16 * A_STRIDE + q * 16;
@@ -307,9 +309,26 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
         stage(kt * 4 + 2, std::integral_constant<int, 2>{}, wc, wnx, bA, bB);
         stage(kt * 4 + 3, std::integral_constant<int, 3>{}, wc, wnx, bB, bA);
     };
-    for (int64_t kt = 0; kt < a.n_kt; kt += 2) {
+    for (int64_t kt = kt_b; kt < kt_e; kt += 2) {
         tile(kt, w0, w1);
-        if (kt + 1 < a.n_kt) tile(kt + 1, w1, w0);           // uniform
+        if (kt + 1 < kt_e) tile(kt + 1, w1, w0);             // uniform
+    }
+
+    if (a.part) {
+        // split-K: this range's fp32 partial results go to the workspace as they sit in the registers
+        float* dst = a.part + (int64_t)blockIdx.y * a.M * a.N;
+#pragma unroll
+        for (int i = 0; i < RI; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t m = m0 + i * 16 + 4 * q + r;
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) {
+                    const int64_t n = n0 + wn * WN + j * 16 + l16;
+                    if (m < a.M && n < a.N) dst[m * a.N + n] = acc[i][j][r];
+                }
+            }
+        return;
     }
 
     // The wave's 128 x 32 result goes through LDS (its own region; the barrier at the end of the last
@@ -340,15 +359,17 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
 }  // namespace fold16
 
 template <int G, int BN, int RI>
-static int launch_fold_bn(const A16Args& a, hipStream_t stream)
+static int launch_fold_bn(const A16Args& a_in, int splits, hipStream_t stream)
 {
     using namespace fold16;
     constexpr int BM = 16 * RI;
+    A16Args a = a_in;
+    if (splits < 2) a.part = nullptr;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
     int group_m = env_int("W2_TILED_GROUP_M", 8);
     if (group_m < 1) group_m = 1;
-    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(64 * waves_of(BN));
+    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)(splits < 2 ? 1 : splits)), block(64 * waves_of(BN));
     constexpr int lds = lds_bytes(BN, BM);
     if (lds > 64 * 1024) {                                   // more than 64 KiB of dynamic LDS needs the opt-in
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(a16_fold_tiled_kernel<G, BN, RI>),
@@ -358,18 +379,45 @@ static int launch_fold_bn(const A16Args& a, hipStream_t stream)
             return -5;
         }
     }
-    hipLaunchKernelGGL((a16_fold_tiled_kernel<G, BN, RI>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
-    return check_launch("w2_matmul_a16[scaled16 tiled]");
+    hipLaunchKernelGGL((a16_fold_tiled_kernel<G, BN, RI>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m,
+                       (int)grid.y);
+    int rc = check_launch("w2_matmul_a16[scaled16 tiled]");
+    if (rc || !a.part) return rc;
+    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, stream);
+}
+
+// 256 columns per workgroup (eight waves, one workgroup per CU) unless that leaves half the chip
+// without a workgroup; then 128 columns (four waves)
+static int fold_bn(int64_t M, int64_t N)
+{
+    const int64_t wgs256 = ((M + 127) / 128) * ((N + 255) / 256);
+    return env_int("W2_FOLD_BN", wgs256 <= 128 ? 128 : 256);
+}
+
+static int fold_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap)
+{
+    const int bn = fold_bn(M, N);
+    const int forced = env_int("W2_SPLITK", 0);              // tuning and tests: 1 = never, n = n parts if they fit
+    if (forced > 0) return (int)min((int64_t)forced, min(cap, n_kt));
+    // two 128-column workgroups fit a CU, one 256-column one: count in CUs' worth
+    const int64_t wgs = ((M + 127) / 128) * ((N + bn - 1) / bn);
+    return splitk_plan(bn == 128 ? (wgs + 1) / 2 : wgs, n_kt, env_int("W2_SPLITK_MIN_TILES", 4), M, N, cap);
+}
+
+size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt)
+{
+    const int s = fold_splits(M, N, n_kt, 16);
+    return s < 2 ? 0 : (size_t)s * M * N * sizeof(float);
 }
 
 int launch_a16_fold_tiled(const A16Args& a, hipStream_t stream)
 {
-    // 256 columns per workgroup (eight waves, one workgroup per CU) unless that leaves half the
-    // chip without a workgroup; then 128 columns (four waves)
-    const int64_t wgs256 = ((a.M + 127) / 128) * ((a.N + 255) / 256);
-    const int bn = env_int("W2_FOLD_BN", wgs256 <= 128 ? 128 : 256);
-    if (bn == 256) return a.G == 128 ? launch_fold_bn<128, 256, 8>(a, stream) : launch_fold_bn<64, 256, 8>(a, stream);
-    return a.G == 128 ? launch_fold_bn<128, 128, 8>(a, stream) : launch_fold_bn<64, 128, 8>(a, stream);
+    const int bn = fold_bn(a.M, a.N);
+    const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
+    const int splits = fold_splits(a.M, a.N, a.n_kt, cap);
+    if (bn == 256)
+        return a.G == 128 ? launch_fold_bn<128, 256, 8>(a, splits, stream) : launch_fold_bn<64, 256, 8>(a, splits, stream);
+    return a.G == 128 ? launch_fold_bn<128, 128, 8>(a, splits, stream) : launch_fold_bn<64, 128, 8>(a, splits, stream);
 }
 
 }  // namespace w2

@@ -103,7 +103,7 @@ __device__ __forceinline__ void load_w(const char* const (&wb)[CJ], const char* 
 
 template <int G, bool DBG, int BN>
 __global__ void __launch_bounds__(64 * waves_of(BN), wgs_per_cu(64 * waves_of(BN)))
-a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
+a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
 {
     constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
     (void)WAVES;
@@ -171,7 +171,9 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     // to LDS at the top of stage it (three LDS buffers); the weights of stage it+1 are loaded at
     // the top of stage it into the other of two register sets.  Every global load has a whole
     // stage to land before anything waits for it.
-    const int64_t n_it = a.n_kt * 2;                         // even, >= 2
+    // this workgroup's K range (split-K: blockIdx.y of `splits` near-equal ranges of whole 256-k tiles)
+    const int64_t it_b = a.n_kt * blockIdx.y / splits * 2;
+    const int64_t n_it = a.n_kt * (blockIdx.y + 1) / splits * 2;   // stages [it_b, n_it): an even number, >= 2
     // The empty asm statements keep the zero-extension of a lane offset next to its load, which is
     // what lets the compiler pick the "scalar base + 32-bit vector offset" addressing mode.
     auto load_a = [&](int64_t it, uint4& r0, uint4& r1) {
@@ -182,11 +184,11 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     };
     uint4 ar0, ar1 = make_uint4(0, 0, 0, 0);
     WStage w0, w1;
-    load_a(0, ar0, ar1);
-    load_w<G>(wb, sb, w_lane, s_lane, 0, w0);
+    load_a(it_b, ar0, ar1);
+    load_w<G>(wb, sb, w_lane, s_lane, it_b, w0);
     *reinterpret_cast<uint4*>(smem + cp_dst) = ar0;
     if constexpr (CPB == 32) *reinterpret_cast<uint4*>(smem + cp_dst + 16) = ar1;
-    load_a(1, ar0, ar1);
+    load_a(it_b + 1, ar0, ar1);
     __syncthreads();
 
     const int8_t* a_base = smem + (wm * WM + l16) * A_STRIDE + q * 16;
@@ -275,7 +277,7 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     };
 
     int buf = 0;
-    for (int64_t it = 0; it < n_it; it += 2) {
+    for (int64_t it = it_b; it < n_it; it += 2) {
         const int b1 = buf == 2 ? 0 : buf + 1;
         const int b2 = b1 == 2 ? 0 : b1 + 1;
         stage(it, buf, b1, w0, w1);
@@ -306,6 +308,24 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     // 32-byte runs; the wave's 64 x 64 result goes through LDS instead (its own
     // region; the barrier at the end of the last stage freed the activation buffers) and leaves
     // as 16-byte stores, eight lanes per 128-byte row piece.
+    if (a.part) {
+        // split-K: this range's results, dequantised, go to the workspace as fp32
+        float* dst = a.part + (int64_t)blockIdx.y * a.M * a.N;
+#pragma unroll
+        for (int i = 0; i < RI; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t m = m0 + i * 16 + 4 * q + r;
+                const float s = a.sx[m < a.M ? m : a.M - 1];
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) {
+                    const int64_t n = n0 + wn * WN + j * 16 + l16;
+                    const float v = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f;
+                    if (m < a.M && n < a.N) dst[m * a.N + n] = v * s;
+                }
+            }
+        return;
+    }
     int8_t* ebase = smem + wn * (BM * E_STRIDE);
     uint16_t* eb = reinterpret_cast<uint16_t*>(ebase);
 #pragma unroll
@@ -338,29 +358,57 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 }  // namespace tiled
 
 template <int G, bool DBG, int BN>
-static int launch_tiled(const A8Args& a, hipStream_t stream)
+static int launch_tiled(const A8Args& a_in, int splits, hipStream_t stream)
 {
     using namespace tiled;
     constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
+    A8Args a = a_in;
+    if (splits < 2 || DBG) { a.part = nullptr; splits = 1; }
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
     const size_t act = 3 * A_BUF, epi = (size_t)WAVES * BM * E_STRIDE;   // three activation stages; the epilogue regions reuse them
     const size_t lds = act > epi ? act : epi;
     int group_m = env_int("W2_TILED_GROUP_M", 8);
     if (group_m < 1) group_m = 1;
-    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(THREADS);
-    hipLaunchKernelGGL((a8_tiled_kernel<G, DBG, BN>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
-    return check_launch("w2_matmul_a8[tiled]");
+    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)splits), block(THREADS);
+    hipLaunchKernelGGL((a8_tiled_kernel<G, DBG, BN>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m, splits);
+    int rc = check_launch("w2_matmul_a8[tiled]");
+    if (rc || !a.part) return rc;
+    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, stream);
+}
+
+// 256 columns per workgroup unless that leaves the chip's 512 workgroup slots clearly underfilled
+static int tiled_bn(int64_t M, int64_t N)
+{
+    const int64_t wgs256 = ((M + tiled::BM - 1) / tiled::BM) * ((N + 255) / 256);
+    int bn = env_int("W2_TILED_BN", 0);
+    if (bn != 128 && bn != 256) bn = wgs256 < 400 ? 128 : 256;
+    return bn;
+}
+
+static int tiled_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap)
+{
+    const int bn = tiled_bn(M, N);
+    const int forced = env_int("W2_SPLITK", 0);              // tuning and tests: 1 = never, n = n parts if they fit
+    if (forced > 0) return (int)min((int64_t)forced, min(cap, n_kt));
+    // four 128-column workgroups fit a CU, two 256-column ones: count in units of half a CU's worth
+    const int64_t wgs = ((M + tiled::BM - 1) / tiled::BM) * ((N + bn - 1) / bn);
+    return splitk_plan(bn == 128 ? (wgs + 1) / 2 : wgs, n_kt, env_int("W2_SPLITK_MIN_TILES", 12), M, N, cap);
+}
+
+size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt)
+{
+    const int s = tiled_splits(M, N, n_kt, 16);
+    return s < 2 ? 0 : (size_t)s * M * N * sizeof(float);
 }
 
 template <int G, bool DBG>
 static int launch_tiled_bn(const A8Args& a, hipStream_t stream)
 {
-    // 256 columns per workgroup unless that leaves the chip's 512 workgroup slots clearly underfilled
-    const int64_t wgs256 = ((a.M + tiled::BM - 1) / tiled::BM) * ((a.N + 255) / 256);
-    int bn = env_int("W2_TILED_BN", 0);
-    if (bn != 128 && bn != 256) bn = wgs256 < 400 ? 128 : 256;
-    return bn == 128 ? launch_tiled<G, DBG, 128>(a, stream) : launch_tiled<G, DBG, 256>(a, stream);
+    const int bn = tiled_bn(a.M, a.N);
+    const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
+    const int splits = DBG ? 1 : tiled_splits(a.M, a.N, a.n_kt, cap);
+    return bn == 128 ? launch_tiled<G, DBG, 128>(a, splits, stream) : launch_tiled<G, DBG, 256>(a, splits, stream);
 }
 
 int launch_a8_tiled(const A8Args& a, hipStream_t stream)

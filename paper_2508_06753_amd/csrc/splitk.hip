@@ -1,0 +1,62 @@
+// Split-K across workgroups (Sec. II-D: K-splitting extracts parallelism along
+// K for the smaller GEMM shapes): when a problem has too few output tiles to
+// fill the chip, each tile's K range is cut into `splits` parts computed by
+// different workgroups, which leave fp32 partial results in a workspace; this
+// file holds the plan and the second launch that sums the parts in a fixed
+// order and rounds to bf16 once.
+#include <hip/hip_runtime.h>
+
+#include "w2_internal.h"
+
+namespace w2 {
+
+int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t N, int64_t cap)
+{
+    // enough parts for about 1.5 workgroups per CU; a part spans at least min_tiles 256-k tiles (below
+    // that the partial results and the second launch cost more than the idle CUs); at most 16 parts
+    // and at most 16 MiB of partial results (the second launch reads them all)
+    if (wgs >= 192 || cap < 2) return 1;
+    int64_t s = (384 + wgs - 1) / wgs;
+    s = min(s, n_kt / min_tiles);
+    s = min(s, (int64_t)16);
+    s = min(s, ((int64_t)16 << 20) / (M * N * (int64_t)sizeof(float)));
+    s = min(s, cap);
+    return s < 2 ? 1 : (int)s;
+}
+
+__global__ void __launch_bounds__(256)
+splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t M, int64_t N, uint16_t* __restrict__ Y,
+                     int64_t ldy)
+{
+    const int64_t n8 = N / 8;                                // N % 8 == 0
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * n8) return;
+    const int64_t m = i / n8, n = (i - m * n8) * 8;
+    float acc[8] = {};
+    for (int s = 0; s < splits; ++s) {
+        const float4* p = reinterpret_cast<const float4*>(part + ((int64_t)s * M + m) * N + n);
+        const float4 a = p[0], b = p[1];
+        acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
+        acc[4] += b.x; acc[5] += b.y; acc[6] += b.z; acc[7] += b.w;
+    }
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        uint32_t lo = __float_as_uint(acc[2 * e]), hi = __float_as_uint(acc[2 * e + 1]);
+        lo += 0x7fffu + ((lo >> 16) & 1u);                   // round to nearest even
+        hi += 0x7fffu + ((hi >> 16) & 1u);
+        o[e] = (lo >> 16) | (hi & 0xffff0000u);
+    }
+    *reinterpret_cast<uint4*>(Y + m * ldy + n) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+int launch_splitk_reduce(const float* part, int splits, int64_t M, int64_t N, uint16_t* Y, int64_t ldy,
+                         hipStream_t stream)
+{
+    const int64_t items = M * (N / 8);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, part,
+                       splits, M, N, Y, ldy);
+    return check_launch("split-K reduce");
+}
+
+}  // namespace w2

@@ -32,6 +32,10 @@ struct A8Args {
     int64_t M, K, N, ldy;
     int64_t n_cb, n_kt;
     int G;
+    // split-K across workgroups (tiled kernel only): fp32 partial results [splits][M][N] in a caller's
+    // workspace, summed and rounded by a second launch; nullptr / 0 = not available
+    float* part = nullptr;
+    size_t part_bytes = 0;
 };
 
 bool a8_dot4_supports(const A8Args& a);
@@ -55,6 +59,8 @@ struct A16Args {
     int64_t n_cb, n_kt;
     int G;
     int fold;       // build the weights as sw*q (scale folded in): no zero-point term, no dequant step
+    float* part = nullptr;      // split-K workspace, as in A8Args (scale-folded tiled kernel only)
+    size_t part_bytes = 0;
 };
 
 bool a16_smallm_supports(const A16Args& a);
@@ -63,6 +69,18 @@ int launch_a16_tiled(const A16Args& a, hipStream_t stream);
 int launch_a16_fold_tiled(const A16Args& a, hipStream_t stream);
 bool a16_midm_supports(const A16Args& a);
 int launch_a16_midm(const A16Args& a, hipStream_t stream);
+
+// Split-K across workgroups for shapes whose output tiles are too few to fill the chip (Sec. II-D,
+// K-splitting for smaller GEMM shapes).  splitk_plan: number of K ranges for `wgs` output tiles of a
+// kernel whose K loop has `n_kt` 256-k tiles (a part spans at least `min_tiles` of them), given room
+// for `cap` fp32 copies of the M x N output.
+int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t N, int64_t cap);
+// Bytes of workspace with which the tiled kernels would split K for this problem (0: they would not).
+size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt);
+size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt);
+// Y[m][n] = bf16(sum_s part[s][m][n]), a fixed order of summation
+int launch_splitk_reduce(const float* part, int splits, int64_t M, int64_t N, uint16_t* Y, int64_t ldy,
+                         hipStream_t stream);
 
 int launch_int8_gemv(const int8_t* W8, const int8_t* xq, int32_t* out, int64_t K, int64_t N, hipStream_t stream);
 

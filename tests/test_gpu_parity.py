@@ -299,7 +299,42 @@ def test_workspace_size_rule(w2):
     assert w2.workspace_size(2, 4096, 4096, 128) == 0
     assert w2.workspace_size(2, 28672, 4096, 128) > 0            # two rows of 112 KiB as fp32
     assert w2.workspace_size(3, 4096, 4096, 128) >= 3 * 4096 + 12
-    assert w2.workspace_size(2048, 8192, 4096, 128, a16=True) == 0
+    assert w2.workspace_size(2048, 8192, 57344, 128, a16=True) == 0   # enough output tiles: no split-K
+    quant = lambda M, K: (M * K + 4 * M + 255) // 256 * 256      # int8 rows + one scale per row
+    assert w2.workspace_size(2048, 8192, 57344, 128) == quant(2048, 8192)
+    # few output tiles and a deep K: room for the split-K partial results, whole fp32 copies of the output
+    for a16 in (False, True):
+        extra = w2.workspace_size(128, 14336, 4096, 128, a16=a16) - (0 if a16 else quant(128, 14336))
+        assert extra > 0 and extra % (128 * 4096 * 4) == 0 and 2 <= extra // (128 * 4096 * 4) <= 16
+
+
+@pytest.mark.parametrize("splitk", [0, 2, 3, 5])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("M,K,N", [(65, 1024, 272), (130, 2304, 48), (200, 512, 1032)])
+def test_tiled_split_k(w2, M, K, N, G, splitk, monkeypatch):
+    # K cut into ranges computed by different workgroups, fp32 partial results summed by a second launch:
+    # forced numbers of parts (uneven ranges included) and the planner's own choice (0), both kernels
+    monkeypatch.setenv("W2_SPLITK", str(splitk))
+    codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + N + G)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    ws = torch.empty(16 * M * N * 4, dtype=torch.uint8, device="cuda")
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED, workspace=ws)
+    oq, osx, _ = oracle.quantize_rows(X, G)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    Yo, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+    check_y(bf16_bits(Y), Yo, y64, mag, f"a8 split-K {splitk} M={M} K={K} N={N} G={G}")
+    Xb = synth.f32_to_bf16_bits(X)
+    Y16 = w2.matmul_a16(packed, K, N, G, dev(Xb).view(torch.bfloat16), workspace=ws)
+    Yo, y64, mag = oracle.matmul_a16(codes, scales, G, 0, Xb)
+    check_y(bf16_bits(Y16), Yo, y64, mag, f"a16 split-K {splitk} M={M} K={K} N={N} G={G}")
+    if splitk >= 2:
+        # a workspace too small for two parts: no split, same contract
+        small = torch.empty(M * N * 4, dtype=torch.uint8, device="cuda")
+        Y1 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED, workspace=small)
+        Y0 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED)
+        assert torch.equal(Y1.view(torch.int16), Y0.view(torch.int16))
 
 
 # ------------------------------------------------------------------ w2a16
