@@ -176,6 +176,36 @@ W2_API int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, c
                               w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* Fused epilogues (Sec. II-D: further operations such as a bias addition or a
+ * post-GEMM activation function are applied while the outputs are still in
+ * registers, before the store).  With z[m,n] the fp32 result of the call
+ * before rounding, plus bias[n] when bias is not NULL (dev, bf16 bit patterns
+ * [N]):
+ *   W2_ACT_NONE      Y[m,n] = bf16(z[m,n])
+ *   W2_ACT_SILU      Y[m,n] = bf16(z * sigmoid(z))
+ *   W2_ACT_SILU_MUL  the gated MLP form: the matrix holds gate and up
+ *                    projections interleaved in blocks of 16 columns (block 2b =
+ *                    gate columns 16b..16b+15, block 2b+1 = the up columns of the
+ *                    same indices; the caller orders the columns so before
+ *                    w2_prepack), N % 32 == 0, and Y has N/2 columns:
+ *                    Y[m,16b+l] = bf16( silu(z[m,32b+l]) * z[m,32b+16+l] ),
+ *                    ldy >= N/2.
+ * epi == NULL is W2_ACT_NONE without bias.  Everything else as w2_matmul_a8_ex
+ * and w2_matmul_a8_fused. */
+typedef enum { W2_ACT_NONE = 0, W2_ACT_SILU = 1, W2_ACT_SILU_MUL = 2 } w2_act_t;
+typedef struct {
+    const uint16_t* bias;
+    int act;                /* w2_act_t */
+} w2_epilogue_t;
+W2_API int w2_matmul_a8_epi(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
+                            const float* sx, int64_t M, uint16_t* Y, int64_t ldy,
+                            const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes,
+                            int variant, void* stream);
+W2_API int w2_matmul_a8_fused_epi(const void* packed, int64_t K, int64_t N, int G, const void* X,
+                                  w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                                  const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+
 /* ------------------------------------------------------------------------
  * w2a16 (Sec. II-D, "Alternative implementation": weights rebuilt as 16-bit
  * values from code and group scale, activations left unquantised, 16-bit

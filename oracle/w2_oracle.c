@@ -294,6 +294,45 @@ int w2o_bruteforce_a8(const uint8_t* codes, const uint16_t* scales, int64_t K, i
     return W2O_OK;
 }
 
+/* ---- fused epilogue (Sec. II-D: bias addition and post-GEMM activation
+ * functions applied to the result before it is stored) --------------------- */
+
+/* z[m][n] = y64[m][n] + bias[n] (bias: bf16 bit patterns [N], may be NULL).
+ * act 0: out = z.  act 1: out = z * sigmoid(z) (SiLU), sigmoid(z) = 1/(1+e^-z).
+ * act 2, the gated form: the columns come in blocks of 16 that alternate gate,
+ * up, gate, up, ...; out has N/2 columns,
+ *   out[m][16 b + l] = silu(z[m][32 b + l]) * z[m][32 b + 16 + l].
+ * Reading (the paper names the operations, not their layout): bias is added in
+ * the wide precision before the activation; one rounding to bf16 at the end.
+ * Y: bf16 bits, out64: unrounded, both [M][N_out] dense, N_out = N or N/2. */
+int w2o_epilogue(const double* y64, int64_t M, int64_t N, const uint16_t* bias, int act,
+                 uint16_t* Y, double* out64)
+{
+    if (M < 0 || N <= 0 || act < 0 || act > 2) return W2O_ERR_ARG;
+    if (act == 2 && N % 32) return W2O_ERR_ARG;
+    const int64_t n_out = act == 2 ? N / 2 : N;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t no = 0; no < n_out; ++no) {
+            double r;
+            if (act == 2) {
+                const int64_t ng = (no / 16) * 32 + no % 16, nu = ng + 16;
+                double g = y64[m * N + ng], u = y64[m * N + nu];
+                if (bias) {
+                    g += (double)w2o_bf16_to_f32(bias[ng]);
+                    u += (double)w2o_bf16_to_f32(bias[nu]);
+                }
+                r = g * (1.0 / (1.0 + exp(-g))) * u;
+            } else {
+                double z = y64[m * N + no];
+                if (bias) z += (double)w2o_bf16_to_f32(bias[no]);
+                r = act == 1 ? z * (1.0 / (1.0 + exp(-z))) : z;
+            }
+            if (out64) out64[m * n_out + no] = r;
+            if (Y) Y[m * n_out + no] = w2o_f64_to_bf16(r);
+        }
+    return W2O_OK;
+}
+
 /* Number of OpenMP threads the timed baseline will use. */
 int w2o_num_threads(void)
 {

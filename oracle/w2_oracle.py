@@ -162,6 +162,18 @@ def matmul_a16(codes, scales, G, codec, X_bf16):
     return Y, y64, mag
 
 
+def epilogue(y64, bias=None, act=0):
+    """Fused epilogue on the unrounded result.  Returns (Y bf16 bits, out64), [M, N or N/2]."""
+    y64 = _c(y64, np.float64)
+    M, N = y64.shape
+    bias = None if bias is None else _c(bias, np.uint16)
+    n_out = N // 2 if act == 2 else N
+    Y = np.empty((M, n_out), np.uint16)
+    out64 = np.empty((M, n_out), np.float64)
+    _chk("w2o_epilogue", lib().w2o_epilogue(_p(y64), _i64(M), _i64(N), _p(bias), int(act), _p(Y), _p(out64)))
+    return Y, out64
+
+
 def bruteforce_a8(codes, scales, G, codec, xq, sx):
     codes = _c(codes, np.uint8)
     scales = _c(scales, np.uint16)

@@ -43,6 +43,8 @@ _SIGS = {
     "w2_debug_unpack": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp],
     "w2_debug_stream_read": [_vp, _sz, _vp, _vp],
     "w2_debug_int8_gemv": [_vp, _i64, _i64, _vp, _vp, _vp],
+    "w2_matmul_a8_epi": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _int, _vp],
+    "w2_matmul_a8_fused_epi": [_vp, _i64, _i64, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp, _vp, _sz, _vp],
 }
 for _name, _args in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -158,6 +160,59 @@ def matmul_a8(packed, K, N, G, xq, sx, out=None, variant=VARIANT_AUTO, workspace
     wp, wb = _ws(workspace)
     _check("w2_matmul_a8", _lib.w2_matmul_a8_ex(_ptr(packed), K, N, G, _ptr(xq), _ptr(sx), M,
                                                 _ptr(Y), ldy, wp, wb, variant, _stream()))
+    return Y
+
+
+ACT_NONE, ACT_SILU, ACT_SILU_MUL = 0, 1, 2
+
+
+class _Epilogue(ctypes.Structure):
+    _fields_ = [("bias", ctypes.c_void_p), ("act", ctypes.c_int)]
+
+
+def _epi(bias, act, N):
+    if bias is not None:
+        if bias.dtype not in (torch.int16, torch.bfloat16) or bias.numel() != N or not bias.is_cuda:
+            raise ValueError("bias must be a device tensor of N bf16 values")
+    return _Epilogue(bias.data_ptr() if bias is not None else None, int(act))
+
+
+def matmul_a8_epi(packed, K, N, G, xq, sx, bias=None, act=ACT_NONE, out=None, variant=VARIANT_AUTO, workspace=None):
+    """matmul_a8 with the fused epilogue: bias (bf16 [N]) and activation; ACT_SILU_MUL gives N/2 columns."""
+    _dev(xq, torch.int8, "xq")
+    _dev(sx, torch.float32, "sx")
+    M = xq.shape[0]
+    if tuple(xq.shape) != (M, K) or not xq.is_contiguous() or tuple(sx.shape) != (M,):
+        raise ValueError("xq must be contiguous [M,K], sx [M]")
+    n_out = N // 2 if act == ACT_SILU_MUL else N
+    Y = out if out is not None else torch.empty((M, n_out), dtype=torch.bfloat16, device=xq.device)
+    ldy = Y.stride(0) if M > 1 else n_out
+    e = _epi(bias, act, N)
+    wp, wb = _ws(workspace)
+    _check("w2_matmul_a8_epi", _lib.w2_matmul_a8_epi(_ptr(packed), K, N, G, _ptr(xq), _ptr(sx), M, _ptr(Y), ldy,
+                                                     ctypes.byref(e), wp, wb, variant, _stream()))
+    return Y
+
+
+def matmul_a8_fused_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, workspace=None):
+    """matmul_a8_fused with the fused epilogue."""
+    if X.dtype == torch.float32:
+        dt = DT_F32
+    elif X.dtype == torch.bfloat16:
+        dt = DT_BF16
+    else:
+        raise ValueError("X must be float32 or bfloat16")
+    if not X.is_cuda or X.dim() != 2 or X.shape[1] != K or X.stride(1) != 1:
+        raise ValueError("X must be a device tensor [M,K] with unit inner stride")
+    M = X.shape[0]
+    n_out = N // 2 if act == ACT_SILU_MUL else N
+    Y = out if out is not None else torch.empty((M, n_out), dtype=torch.bfloat16, device=X.device)
+    ldx = X.stride(0) if M > 1 else K
+    ldy = Y.stride(0) if M > 1 else n_out
+    e = _epi(bias, act, N)
+    wp, wb = _ws(workspace)
+    _check("w2_matmul_a8_fused_epi", _lib.w2_matmul_a8_fused_epi(_ptr(packed), K, N, G, _ptr(X), dt, ldx, M,
+                                                                 _ptr(Y), ldy, ctypes.byref(e), wp, wb, _stream()))
     return Y
 
 

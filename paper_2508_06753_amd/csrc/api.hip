@@ -93,6 +93,14 @@ static int fail(int code, const char* fmt, ...)
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+static int check_epilogue(const char* fn, const Epilogue& e, int64_t N)
+{
+    if (e.act < ACT_NONE || e.act > ACT_SILU_MUL) return fail(W2_ERR_INVALID_ARG, "%s: unknown activation %d", fn, e.act);
+    if (e.act == ACT_SILU_MUL && N % 32)
+        return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: the gated epilogue pairs 16-column blocks: N must be a multiple of 32", fn);
+    return W2_OK;
+}
+
 static int check_shape(const char* fn, int64_t K, int64_t N, int G)
 {
     if (K <= 0 || N <= 0) return fail(W2_ERR_INVALID_ARG, "%s: K and N must be positive", fn);
@@ -155,11 +163,15 @@ int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_t K, in
 
 static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, int G,
                      const int8_t* xq, const float* sx, int64_t M, uint16_t* Y, int64_t ldy,
-                     int32_t* acc_out, void* workspace, size_t workspace_bytes, int variant, void* stream)
+                     int32_t* acc_out, void* workspace, size_t workspace_bytes, int variant, void* stream,
+                     const Epilogue& epi = Epilogue())
 {
     int rc = check_shape(fn, K, N, G);
     if (rc) return rc;
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
+    rc = check_epilogue(fn, epi, N);
+    if (rc) return rc;
+    const int64_t n_out = epi.act == ACT_SILU_MUL ? N / 2 : N;
     if (variant < W2_VARIANT_AUTO || variant > W2_VARIANT_MIDM)
         return fail(W2_ERR_INVALID_ARG, "%s: unknown variant %d", fn, variant);
     if (M == 0) return W2_OK;
@@ -167,8 +179,8 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     if (!acc_out && (!sx || !Y)) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
     if (!aligned16(packed) || !aligned16(xq) || (Y && !aligned16(Y)))
         return fail(W2_ERR_MISALIGNED, "%s: packed, xq and Y must be 16-byte aligned", fn);
-    if (!acc_out && (ldy < N || ldy % 8))
-        return fail(W2_ERR_MISALIGNED, "%s: ldy must be >= N and a multiple of 8", fn);
+    if (!acc_out && (ldy < n_out || ldy % 8))
+        return fail(W2_ERR_MISALIGNED, "%s: ldy must be >= the number of output columns and a multiple of 8", fn);
     if (M > ((int64_t)1 << 24)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: M is limited to 2^24", fn);
     const Layout L = make_layout(K, N, G);
     A8Args a;
@@ -181,6 +193,7 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         return fail(W2_ERR_MISALIGNED, "%s: workspace must be 16-byte aligned", fn);
     a.part = (float*)workspace;                              // split-K partial results, if the tiled kernel wants them
     a.part_bytes = workspace ? workspace_bytes : 0;
+    a.epi = epi;
     if (variant == W2_VARIANT_AUTO) {
         // measured: the MFMA form is at least as fast as dot4 from M = 1 on; the mid-M kernel (one
         // fma per accumulator in the dequant, rolling weight window; its time hardly grows with M)
@@ -233,13 +246,15 @@ static size_t fused_workspace_bytes(int64_t M, int64_t K)
     return ((size_t)((M * K + 15) & ~(int64_t)15) + (size_t)M * sizeof(float) + 255) & ~(size_t)255;
 }
 
-int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const void* X,
-                       w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
-                       void* workspace, size_t workspace_bytes, void* stream)
+static int a8_fused_common(const char* fn, const void* packed, int64_t K, int64_t N, int G, const void* X,
+                           w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                           void* workspace, size_t workspace_bytes, void* stream, const Epilogue& epi)
 {
-    const char* fn = "w2_matmul_a8_fused";
     int rc = check_shape(fn, K, N, G);
     if (rc) return rc;
+    rc = check_epilogue(fn, epi, N);
+    if (rc) return rc;
+    const int64_t n_out = epi.act == ACT_SILU_MUL ? N / 2 : N;
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
     if (x_dtype != W2_DT_F32 && x_dtype != W2_DT_BF16)
         return fail(W2_ERR_INVALID_ARG, "%s: unknown dtype %d", fn, (int)x_dtype);
@@ -247,8 +262,8 @@ int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const vo
     if (!packed || !X || !Y) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
     if (!aligned16(packed) || !aligned16(X) || !aligned16(Y))
         return fail(W2_ERR_MISALIGNED, "%s: packed, X and Y must be 16-byte aligned", fn);
-    if (ldx < K || ldx % 8 || ldy < N || ldy % 8)
-        return fail(W2_ERR_MISALIGNED, "%s: ldx >= K, ldy >= N, both multiples of 8", fn);
+    if (ldx < K || ldx % 8 || ldy < n_out || ldy % 8)
+        return fail(W2_ERR_MISALIGNED, "%s: ldx >= K, ldy >= the number of output columns, both multiples of 8", fn);
     if (workspace && !aligned16(workspace))
         return fail(W2_ERR_MISALIGNED, "%s: workspace must be 16-byte aligned", fn);
     const Layout L = make_layout(K, N, G);
@@ -261,7 +276,7 @@ int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const vo
             return fail(W2_ERR_BUFFER_TOO_SMALL, "%s: M = %lld needs a workspace of %zu bytes (w2_workspace_size)",
                         fn, (long long)M, fused_workspace_bytes(M, K));
         rc = launch_a8_fusedq(packed, (const char*)packed + L.codes_bytes, X, x_dtype == W2_DT_BF16, ldx,
-                              M, K, N, G, L.n_cb, L.n_kt, Y, ldy, (hipStream_t)stream);
+                              M, K, N, G, L.n_cb, L.n_kt, Y, ldy, epi, (hipStream_t)stream);
         if (rc != W2_ERR_UNSUPPORTED_SHAPE || !ws_ok) return rc;
     }
     int8_t* xq = (int8_t*)workspace;
@@ -270,7 +285,38 @@ int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const vo
     if (rc) return rc;
     const size_t used = fused_workspace_bytes(M, K);
     return a8_common(fn, packed, K, N, G, xq, sx, M, Y, ldy, nullptr, (char*)workspace + used, workspace_bytes - used,
-                     W2_VARIANT_AUTO, stream);
+                     W2_VARIANT_AUTO, stream, epi);
+}
+
+static Epilogue to_epilogue(const w2_epilogue_t* e)
+{
+    Epilogue r;
+    if (e) { r.bias = e->bias; r.act = e->act; }
+    return r;
+}
+
+int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const void* X,
+                       w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    return a8_fused_common("w2_matmul_a8_fused", packed, K, N, G, X, x_dtype, ldx, M, Y, ldy, workspace,
+                           workspace_bytes, stream, Epilogue());
+}
+
+int w2_matmul_a8_fused_epi(const void* packed, int64_t K, int64_t N, int G, const void* X,
+                           w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                           const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return a8_fused_common("w2_matmul_a8_fused_epi", packed, K, N, G, X, x_dtype, ldx, M, Y, ldy, workspace,
+                           workspace_bytes, stream, to_epilogue(epi));
+}
+
+int w2_matmul_a8_epi(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq, const float* sx,
+                     int64_t M, uint16_t* Y, int64_t ldy, const w2_epilogue_t* epi, void* workspace,
+                     size_t workspace_bytes, int variant, void* stream)
+{
+    return a8_common("w2_matmul_a8_epi", packed, K, N, G, xq, sx, M, Y, ldy, nullptr, workspace, workspace_bytes,
+                     variant, stream, to_epilogue(epi));
 }
 
 int w2_debug_group_acc_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,

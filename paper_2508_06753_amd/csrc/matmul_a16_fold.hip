@@ -383,7 +383,7 @@ static int launch_fold_bn(const A16Args& a_in, int splits, hipStream_t stream)
                        (int)grid.y);
     int rc = check_launch("w2_matmul_a16[scaled16 tiled]");
     if (rc || !a.part) return rc;
-    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, stream);
+    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, Epilogue(), stream);
 }
 
 // 256 columns per workgroup (eight waves, one workgroup per CU) unless that leaves half the chip

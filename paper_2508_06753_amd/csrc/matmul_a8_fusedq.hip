@@ -43,6 +43,7 @@ struct FusedArgs {
     int64_t M, K, N, ldx, ldy;
     int64_t n_cb, n_kt;
     int G;
+    Epilogue epi;
 };
 
 template <int G, int TMAX, int RL, bool BF16IN>
@@ -219,14 +220,12 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
 #pragma unroll
     for (int r = 0; r < RL; ++r) red[(wave * 16 + 4 * q + r) * 16 + (lane & 15)] = y[r];
     __syncthreads();
-    const int outs = cfg.cbw * rows * 16;
-    for (int i = threadIdx.x; i < outs; i += blockDim.x) {
-        const int nl = i & 15, m = (i >> 4) % rows, ci = i / (16 * rows);
-        float s = 0.0f;
-        for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * 16 + m) * 16 + nl];
-        const int64_t nn = ((int64_t)blockIdx.x * cfg.cbw + ci) * TILE_N + nl;
-        if (nn < a.N) a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * (s_sx[m] * 0.015625f));
-    }
+    store_outputs(a.epi, a.Y, a.ldy, a.N, (int64_t)blockIdx.x * cfg.cbw, cfg.cbw, rows,
+                  [&](int ci, int m, int nl, int) {
+                      float s = 0.0f;
+                      for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * 16 + m) * 16 + nl];
+                      return s * (s_sx[m] * 0.015625f);
+                  });
 }
 
 template <int G, int RL, bool BF16IN>
@@ -243,14 +242,14 @@ static int launch_fusedq_t(const FusedArgs& a, const SmallCfg& c, size_t lds, hi
 // per-workgroup budget; the caller then uses w2_quantize_rows + w2_matmul_a8.
 int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x_is_bf16, int64_t ldx,
                      int64_t M, int64_t K, int64_t N, int G, int64_t n_cb, int64_t n_kt, uint16_t* Y,
-                     int64_t ldy, hipStream_t stream)
+                     int64_t ldy, const Epilogue& epi, hipStream_t stream)
 {
     if (M < 1 || M > 4) {
         set_error("w2_matmul_a8_fused: M must be 1..4 (use w2_quantize_rows + w2_matmul_a8)");
         return -2;
     }
     const int rows = (int)M;
-    SmallCfg c = pick_cfg(n_cb, n_kt, rows, 1);
+    SmallCfg c = pick_cfg(n_cb, n_kt, rows, 1, 16, epi.act == ACT_SILU_MUL);
     const int es = x_is_bf16 ? 2 : 4;
     const int64_t pieces = M * K * es / 16;
     const int threads = 64 * c.cbw * c.ks;
@@ -265,6 +264,7 @@ int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x
     FusedArgs a;
     a.codes = (const uint32_t*)codes; a.scales = (const uint16_t*)scales; a.X = X; a.Y = Y;
     a.M = M; a.K = K; a.N = N; a.ldx = ldx; a.ldy = ldy; a.n_cb = n_cb; a.n_kt = n_kt; a.G = G;
+    a.epi = epi;
     const int rl = M <= 1 ? 1 : M <= 2 ? 2 : 4;
 #define W2_FQ(GG, RLL)                                                                         \
     return x_is_bf16 ? launch_fusedq_t<GG, RLL, true>(a, c, lds, stream)                       \

@@ -89,7 +89,7 @@ a8_dot4_kernel(A8Args a, SmallCfg cfg)
     W2_SMALL_PROLOGUE();
     const int rows = MT < (int)a.M ? MT : (int)a.M;
     // activation scale for the output this thread stores first, fetched before the stream starts
-    const int m_first = (threadIdx.x >> 4) % MT;
+    const int m_first = (threadIdx.x >> 4) % rows;           // the row of this thread's first output
     const float sx_first = (!DBG && m_first < a.M) ? a.sx[m_first] : 0.0f;
 
     float y[MT];
@@ -182,17 +182,13 @@ a8_dot4_kernel(A8Args a, SmallCfg cfg)
         for (int m = 0; m < MT; ++m) red[(wave * MT + m) * 16 + lane] = y[m];
     }
     __syncthreads();
-    const int outs = cfg.cbw * MT * 16;
-    for (int i = threadIdx.x; i < outs; i += blockDim.x) {
-        const int nl = i & 15, m = (i >> 4) % MT, ci = i / (16 * MT);
-        float s = 0.0f;
-        for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * MT + m) * 16 + nl];
-        const int64_t nn = ((int64_t)blockIdx.x * cfg.cbw + ci) * TILE_N + nl;
-        if (m < a.M && nn < a.N) {
-            const float sxm = i == (int)threadIdx.x ? sx_first : a.sx[m];
-            a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * (sxm * 0.015625f));
-        }
-    }
+    store_outputs(a.epi, a.Y, a.ldy, a.N, (int64_t)blockIdx.x * cfg.cbw, cfg.cbw, rows,
+                  [&](int ci, int m, int nl, int i) {
+                      float s = 0.0f;
+                      for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * MT + m) * 16 + nl];
+                      const float sxm = i == (int)threadIdx.x ? sx_first : a.sx[m];
+                      return s * (sxm * 0.015625f);
+                  });
 }
 
 // ---------------------------------------------------------------- SMALLM (MFMA)
@@ -280,17 +276,13 @@ a8_smallm_kernel(A8Args a, SmallCfg cfg)
 #pragma unroll
     for (int r = 0; r < RL; ++r) red[(wave * 16 + 4 * q + r) * 16 + (lane & 15)] = y[r];
     __syncthreads();
-    const int outs = cfg.cbw * rows * 16;
-    for (int i = threadIdx.x; i < outs; i += blockDim.x) {
-        const int nl = i & 15, m = (i >> 4) % rows, ci = i / (16 * rows);
-        float s = 0.0f;
-        for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * 16 + m) * 16 + nl];
-        const int64_t nn = ((int64_t)blockIdx.x * cfg.cbw + ci) * TILE_N + nl;
-        if (nn < a.N) {
-            const float sxm = i == (int)threadIdx.x ? sx_first : a.sx[m];
-            a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s * (sxm * 0.015625f));
-        }
-    }
+    store_outputs(a.epi, a.Y, a.ldy, a.N, (int64_t)blockIdx.x * cfg.cbw, cfg.cbw, rows,
+                  [&](int ci, int m, int nl, int i) {
+                      float s = 0.0f;
+                      for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * 16 + m) * 16 + nl];
+                      const float sxm = i == (int)threadIdx.x ? sx_first : a.sx[m];
+                      return s * (sxm * 0.015625f);
+                  });
 }
 
 // ---------------------------------------------------------------- host side
@@ -302,7 +294,7 @@ template <int MT, int G>
 static int launch_dot4_t(const A8Args& a, hipStream_t stream)
 {
     const int rows = MT < (int)a.M ? MT : (int)a.M;
-    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 1);
+    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 1, 16, a.epi.act == ACT_SILU_MUL);
     const size_t lds = small_lds_bytes(c, rows, MT, 1, 0);
     if (a.acc_out) return launch_small(a8_dot4_kernel<MT, G, TMAX, true>, "w2_matmul_a8[dot4]", a, c, lds, stream);
     // in-flight depth = tiles per wave, so that no load slot re-reads a tile
@@ -329,7 +321,7 @@ template <int G, int RL>
 static int launch_smallm_t(const A8Args& a, hipStream_t stream)
 {
     const int rows = (int)a.M;
-    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 1);
+    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 1, 16, a.epi.act == ACT_SILU_MUL);
     const size_t lds = small_lds_bytes(c, rows, 16, 1, 0);
     if (a.acc_out) return launch_small(a8_smallm_kernel<G, TMAX, 4, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
     const int tpw = tiles_per_wave(a.n_kt, c);

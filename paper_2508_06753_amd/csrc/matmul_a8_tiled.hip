@@ -328,6 +328,16 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
     }
     int8_t* ebase = smem + wn * (BM * E_STRIDE);
     uint16_t* eb = reinterpret_cast<uint16_t*>(ebase);
+    // fused epilogue (Sec. II-D: bias and activation applied while the outputs are in registers).
+    // The gated form combines the wave's two column blocks, an even (gate) and an odd (up) one,
+    // into one block of outputs.
+    const bool gated = a.epi.act == ACT_SILU_MUL;
+    float bias[CJ];
+#pragma unroll
+    for (int j = 0; j < CJ; ++j) {
+        const int64_t n = n0 + wn * WN + j * 16 + l16;
+        bias[j] = (a.epi.bias && n < a.N) ? __uint_as_float((uint32_t)a.epi.bias[n] << 16) : 0.f;
+    }
 #pragma unroll
     for (int i = 0; i < RI; ++i) {
 #pragma unroll
@@ -335,23 +345,31 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
             const int row = i * 16 + 4 * q + r;
             const int64_t m = m0 + row;
             const float s = a.sx[m < a.M ? m : a.M - 1];
+            float z[CJ];
 #pragma unroll
-            for (int j = 0; j < CJ; ++j) {
-                const float v = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f;
-                eb[row * (E_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(v * s);
+            for (int j = 0; j < CJ; ++j) z[j] = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f * s + bias[j];
+            if (CJ == 2 && gated) {
+                eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(z[0] / (1.0f + __expf(-z[0])) * z[1]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) {
+                    const float v = a.epi.act == ACT_SILU ? z[j] / (1.0f + __expf(-z[j])) : z[j];
+                    eb[row * (E_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(v);
+                }
             }
         }
     }
     // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
-    constexpr int LPR = WN * 2 / 16;                         // lanes per row piece (16 bytes each)
-    constexpr int RPP = 64 / LPR;                            // rows per pass
-    const int64_t ncol = n0 + wn * WN + (lane % LPR) * 8;    // first of this lane's 8 columns
-#pragma unroll
-    for (int p = 0; p < BM / RPP; ++p) {
-        const int row = p * RPP + lane / LPR;
+    const int wcols = gated ? WN / 2 : WN;                   // output columns of this wave
+    const int lpr = wcols * 2 / 16;                          // lanes per row piece (16 bytes each): 4 or 2
+    const int rpp = 64 / lpr;                                // rows per pass
+    const int64_t ncol = (gated ? (n0 + wn * WN) / 2 : n0 + wn * WN) + (lane % lpr) * 8;   // first of this lane's 8 columns
+    const int64_t n_out = gated ? a.N / 2 : a.N;
+    for (int p = 0; p < BM / rpp; ++p) {
+        const int row = p * rpp + lane / lpr;
         const int64_t m = m0 + row;
-        const uint4 v = *reinterpret_cast<const uint4*>(ebase + row * E_STRIDE + (lane % LPR) * 16);
-        if (m < a.M && ncol < a.N) *reinterpret_cast<uint4*>(a.Y + m * a.ldy + ncol) = v;   // N % 8 == 0: all 8 or none
+        const uint4 v = *reinterpret_cast<const uint4*>(ebase + row * E_STRIDE + (lane % lpr) * 16);
+        if (m < a.M && ncol < n_out) *reinterpret_cast<uint4*>(a.Y + m * a.ldy + ncol) = v;   // N % 8 == 0: all 8 or none
     }
 }
 
@@ -374,7 +392,7 @@ static int launch_tiled(const A8Args& a_in, int splits, hipStream_t stream)
     hipLaunchKernelGGL((a8_tiled_kernel<G, DBG, BN>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m, splits);
     int rc = check_launch("w2_matmul_a8[tiled]");
     if (rc || !a.part) return rc;
-    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, stream);
+    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, a.epi, stream);
 }
 
 // 256 columns per workgroup unless that leaves the chip's 512 workgroup slots clearly underfilled

@@ -24,20 +24,52 @@ int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t
     return s < 2 ? 1 : (int)s;
 }
 
-__global__ void __launch_bounds__(256)
-splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t M, int64_t N, uint16_t* __restrict__ Y,
-                     int64_t ldy)
+__device__ __forceinline__ void sum8(const float* __restrict__ part, int splits, int64_t M, int64_t N, int64_t m,
+                                     int64_t n, float (&acc)[8])
 {
-    const int64_t n8 = N / 8;                                // N % 8 == 0
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= M * n8) return;
-    const int64_t m = i / n8, n = (i - m * n8) * 8;
-    float acc[8] = {};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     for (int s = 0; s < splits; ++s) {
         const float4* p = reinterpret_cast<const float4*>(part + ((int64_t)s * M + m) * N + n);
         const float4 a = p[0], b = p[1];
         acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
         acc[4] += b.x; acc[5] += b.y; acc[6] += b.z; acc[7] += b.w;
+    }
+}
+
+// One thread per eight adjacent output columns.  The fused epilogue is applied here, after the sum:
+// bias, SiLU, or (gated) silu(gate block) * (up block) for the pairs of adjacent 16-column blocks.
+__global__ void __launch_bounds__(256)
+splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t M, int64_t N, uint16_t* __restrict__ Y,
+                     int64_t ldy, Epilogue epi)
+{
+    const bool gated = epi.act == ACT_SILU_MUL;
+    const int64_t n_out = gated ? N / 2 : N;
+    const int64_t n8 = n_out / 8;                            // N % 8 == 0 (gated: N % 32 == 0)
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * n8) return;
+    const int64_t m = i / n8, no = (i - m * n8) * 8;
+    float acc[8];
+    if (!gated) {
+        sum8(part, splits, M, N, m, no, acc);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (epi.bias) acc[e] += __uint_as_float((uint32_t)epi.bias[no + e] << 16);
+            if (epi.act == ACT_SILU) acc[e] = acc[e] / (1.0f + __expf(-acc[e]));
+        }
+    } else {
+        const int64_t ng = (no / 16) * 32 + (no % 16);       // the gate columns of these outputs; up: 16 further
+        float up[8];
+        sum8(part, splits, M, N, m, ng, acc);
+        sum8(part, splits, M, N, m, ng + 16, up);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (epi.bias) {
+                acc[e] += __uint_as_float((uint32_t)epi.bias[ng + e] << 16);
+                up[e] += __uint_as_float((uint32_t)epi.bias[ng + 16 + e] << 16);
+            }
+            acc[e] = acc[e] / (1.0f + __expf(-acc[e])) * up[e];
+        }
     }
     uint32_t o[4];
 #pragma unroll
@@ -47,15 +79,15 @@ splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t M, int6
         hi += 0x7fffu + ((hi >> 16) & 1u);
         o[e] = (lo >> 16) | (hi & 0xffff0000u);
     }
-    *reinterpret_cast<uint4*>(Y + m * ldy + n) = make_uint4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<uint4*>(Y + m * ldy + no) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
 int launch_splitk_reduce(const float* part, int splits, int64_t M, int64_t N, uint16_t* Y, int64_t ldy,
-                         hipStream_t stream)
+                         const Epilogue& epi, hipStream_t stream)
 {
-    const int64_t items = M * (N / 8);
+    const int64_t items = M * ((epi.act == ACT_SILU_MUL ? N / 2 : N) / 8);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, part,
-                       splits, M, N, Y, ldy);
+                       splits, M, N, Y, ldy, epi);
     return check_launch("split-K reduce");
 }
 

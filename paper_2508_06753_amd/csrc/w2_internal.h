@@ -20,6 +20,17 @@ int launch_quantize(const void* X, int x_is_bf16, int64_t M, int64_t K, int64_t 
                     int8_t* xq, float* sx, int32_t* gsum, hipStream_t stream);
 int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
 
+// Work fused into the store of the result (Sec. II-D: bias addition and post-GEMM activation
+// functions are applied while the outputs are still in registers).  z = fp32 result + bias[n];
+// act 0: Y = bf16(z); 1: Y = bf16(silu(z)); 2: the 16-column blocks of the matrix alternate
+// gate, up, gate, up ... and Y[m][16 b + l] = bf16(silu(z[m][32 b + l]) * z[m][32 b + 16 + l])
+// (N / 2 output columns).
+struct Epilogue {
+    const uint16_t* bias = nullptr;     // bf16 [N], or nullptr
+    int act = 0;
+};
+constexpr int ACT_NONE = 0, ACT_SILU = 1, ACT_SILU_MUL = 2;
+
 // Arguments common to the w2a8 kernels.  acc_out != nullptr selects the debug
 // mode that stores the int32 group accumulators and skips Y.
 struct A8Args {
@@ -36,6 +47,7 @@ struct A8Args {
     // workspace, summed and rounded by a second launch; nullptr / 0 = not available
     float* part = nullptr;
     size_t part_bytes = 0;
+    Epilogue epi;
 };
 
 bool a8_dot4_supports(const A8Args& a);
@@ -48,7 +60,7 @@ int launch_a8_tiled(const A8Args& a, hipStream_t stream);
 
 int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x_is_bf16, int64_t ldx,
                      int64_t M, int64_t K, int64_t N, int G, int64_t n_cb, int64_t n_kt, uint16_t* Y,
-                     int64_t ldy, hipStream_t stream);
+                     int64_t ldy, const Epilogue& epi, hipStream_t stream);
 
 struct A16Args {
     const uint32_t* codes;
@@ -80,7 +92,7 @@ size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt);
 size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt);
 // Y[m][n] = bf16(sum_s part[s][m][n]), a fixed order of summation
 int launch_splitk_reduce(const float* part, int splits, int64_t M, int64_t N, uint16_t* Y, int64_t ldy,
-                         hipStream_t stream);
+                         const Epilogue& epi, hipStream_t stream);
 
 int launch_int8_gemv(const int8_t* W8, const int8_t* xq, int32_t* out, int64_t K, int64_t N, hipStream_t stream);
 

@@ -20,6 +20,45 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
+// x * sigmoid(x); v_exp_f32 and v_rcp_f32 are good to about 1e-6 relative, far inside a bf16 result
+__device__ __forceinline__ float silu_f32(float z) { return z * __frcp_rn(1.0f + __expf(-z)); }
+
+// The store loop shared by the kernels that reduce their k-splits through LDS: a workgroup holds
+// `cbw` adjacent column blocks starting at block first_cb, `rows` rows; z(ci, m, nl) returns the
+// finished fp32 result of column block ci, row m, column nl of the block.  Applies the fused
+// epilogue; for the gated form cbw and first_cb are even and a thread combines a gate and an up
+// column.
+template <typename ZFn>
+__device__ __forceinline__ void store_outputs(const Epilogue& e, uint16_t* __restrict__ Y, int64_t ldy, int64_t N,
+                                              int64_t first_cb, int cbw, int rows, ZFn z)
+{
+    if (e.act != ACT_SILU_MUL) {
+        const int outs = cbw * rows * 16;
+        for (int i = threadIdx.x; i < outs; i += blockDim.x) {
+            const int nl = i & 15, m = (i >> 4) % rows, ci = i / (16 * rows);
+            const int64_t nn = (first_cb + ci) * TILE_N + nl;
+            if (nn >= N) continue;
+            float v = z(ci, m, nl, i);
+            if (e.bias) v += bf16_to_f32(e.bias[nn]);
+            if (e.act == ACT_SILU) v = silu_f32(v);
+            Y[(int64_t)m * ldy + nn] = f32_to_bf16_rne(v);
+        }
+    } else {
+        const int outs = (cbw >> 1) * rows * 16;
+        for (int i = threadIdx.x; i < outs; i += blockDim.x) {
+            const int nl = i & 15, m = (i >> 4) % rows, p = i / (16 * rows);
+            const int64_t ng = (first_cb + 2 * p) * TILE_N + nl, nu = ng + TILE_N;
+            if (nu >= N) continue;                           // N % 32 == 0: both or neither
+            float g = z(2 * p, m, nl, i), u = z(2 * p + 1, m, nl, i);
+            if (e.bias) {
+                g += bf16_to_f32(e.bias[ng]);
+                u += bf16_to_f32(e.bias[nu]);
+            }
+            Y[(int64_t)m * ldy + ((first_cb >> 1) + p) * TILE_N + nl] = f32_to_bf16_rne(silu_f32(g) * u);
+        }
+    }
+}
+
 // 16 two-bit fields -> four dwords of int8 lanes holding 64*q.
 __device__ __forceinline__ void upconvert(uint32_t w, int (&u)[4])
 {
@@ -97,7 +136,8 @@ constexpr int64_t LDS_BUDGET = 128 * 1024;   // activation chunk + reduction scr
 // Picks (column blocks per workgroup, k-splits): enough workgroups to fill 256
 // CUs a few times over, and a k-split that leaves each wave at most TMAX tiles
 // when the wave budget allows it.
-static SmallCfg pick_cfg(int64_t n_cb, int64_t n_kt, int rows, int bytes_per_k, int max_waves = 16)
+static SmallCfg pick_cfg(int64_t n_cb, int64_t n_kt, int rows, int bytes_per_k, int max_waves = 16,
+                         bool even_cbw = false)
 {
     SmallCfg c;
     int waves = env_int("W2_SMALL_WAVES", 8);
@@ -112,6 +152,7 @@ static SmallCfg pick_cfg(int64_t n_cb, int64_t n_kt, int rows, int bytes_per_k, 
         while (cbw > 1 && (n_cb + cbw - 1) / cbw < 256) cbw >>= 1;
     }
     if (cbw > waves) cbw = waves;
+    if (even_cbw && (cbw & 1)) cbw = cbw == 1 ? 2 : cbw - 1;     // the gated epilogue pairs adjacent column blocks
     c.cbw = cbw;
     c.ks = waves / cbw;
     if (c.ks > n_kt) c.ks = (int)n_kt;

@@ -337,6 +337,89 @@ def test_tiled_split_k(w2, M, K, N, G, splitk, monkeypatch):
         assert torch.equal(Y1.view(torch.int16), Y0.view(torch.int16))
 
 
+# ------------------------------------------------------------------ fused epilogues
+def check_epilogue(Yg_bits, y64, mag, bias, act, what):
+    """Tolerance: the matmul's own (1e-2 relative + 2^-10 of the summed term magnitudes) carried through
+    the epilogue: silu has slope <= 1.1, the gated product is bilinear in (silu(gate), up)."""
+    Yo, out = oracle.epilogue(y64, bias=bias, act=act)
+    yg = bits_to_f64(Yg_bits)
+    b = 0.0 if bias is None else synth.bf16_bits_to_f32(bias).astype(np.float64)[None, :]
+    z = y64 + b
+    dz = 1e-2 * np.abs(y64) + 2.0 ** -10 * mag                      # what the matmul itself may be off by
+    if act == 2:
+        M, N = z.shape
+        zb = z.reshape(M, N // 32, 2, 16)
+        db = dz.reshape(M, N // 32, 2, 16)
+        g, u = zb[:, :, 0, :].reshape(M, -1), zb[:, :, 1, :].reshape(M, -1)
+        dg, du = db[:, :, 0, :].reshape(M, -1), db[:, :, 1, :].reshape(M, -1)
+        sg = g / (1.0 + np.exp(-g))
+        tol = 1.1 * dg * (np.abs(u) + du) + np.abs(sg) * du + 2.0 ** -8 * np.abs(out)
+    else:
+        tol = (1.1 if act == 1 else 1.0) * dz + 2.0 ** -8 * np.abs(out)
+    bad = np.abs(yg - out) > tol
+    assert yg.shape == out.shape and not bad.any(), f"{what}: {bad.sum()} of {bad.size} outputs off"
+    # and on the whole it is bf16-accurate: the median error is a fraction of an ulp of the result
+    nz = np.abs(out) > 1e-3 * np.abs(out).max()
+    assert np.median(np.abs(yg - out)[nz] / np.abs(out)[nz]) < 2.0 ** -8, what
+
+
+EPI_VARIANTS = [("SMALLM", 2, [1, 3, 16]), ("DOT4", 1, [2]), ("MIDM", 4, [5, 33, 64]), ("TILED", 3, [7, 130])]
+
+
+@pytest.mark.parametrize("with_bias,act", [(True, 0), (False, 1), (True, 1), (False, 2), (True, 2)])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(256, 32), (1024, 288), (512, 1056)])
+def test_a8_fused_epilogues(w2, K, N, G, with_bias, act):
+    # bias and activation applied in the kernels' stores, every kernel family; N = 288, 1056: ragged last workgroup
+    rng = np.random.default_rng(K + N + G + act)
+    bias = synth.f32_to_bf16_bits(rng.standard_normal(N).astype(np.float32)) if with_bias else None
+    bias_d = dev(bias) if with_bias else None
+    for name, variant, Ms in EPI_VARIANTS:
+        for M in Ms:
+            codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + N)
+            packed = w2.prepack(dev(codes), dev(scales), G, 0)
+            xq, sx, _ = w2.quantize_rows(dev(X), G)
+            oq, osx, _ = oracle.quantize_rows(X, G)
+            _, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+            mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+            Y = w2.matmul_a8_epi(packed, K, N, G, xq, sx, bias=bias_d, act=act, variant=variant)
+            check_epilogue(bf16_bits(Y), y64, mag, bias, act, f"epilogue {name} M={M} K={K} N={N} G={G} act={act}")
+
+
+@pytest.mark.parametrize("act", [1, 2])
+@pytest.mark.parametrize("M", [1, 2, 4, 40, 130])
+def test_a8_fused_entry_with_epilogue_and_split_k(w2, M, act, monkeypatch):
+    # the one-call entry point (quantisation fused or through the workspace) with bias + activation; for the large M
+    # the tiled kernel splits K and the epilogue runs in the reduce launch
+    K, N, G = 1024, 320, 128
+    if M > 64:
+        monkeypatch.setenv("W2_SPLITK", "3")
+    codes, scales, X = synth.make_problem(M, K, N, G, 0, M + act)
+    bias = synth.f32_to_bf16_bits(np.random.default_rng(M).standard_normal(N).astype(np.float32))
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    ws = torch.empty(w2.workspace_size(M, K, N, G) + 4 * M * N * 4, dtype=torch.uint8, device="cuda")
+    Y = w2.matmul_a8_fused_epi(packed, K, N, G, dev(X), bias=dev(bias), act=act, workspace=ws)
+    oq, osx, _ = oracle.quantize_rows(X, G)
+    _, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+    check_epilogue(bf16_bits(Y), y64, mag, bias, act, f"fused entry + epilogue M={M} act={act}")
+
+
+def test_epilogue_argument_errors(w2):
+    K, N, G = 256, 48, 128                                   # N % 32 != 0
+    codes, scales, X = synth.make_problem(1, K, N, G, 0, 0)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    with pytest.raises(w2.W2Error):
+        w2.matmul_a8_epi(packed, K, N, G, xq, sx, act=w2.ACT_SILU_MUL)
+    with pytest.raises(w2.W2Error):
+        w2.matmul_a8_epi(packed, K, N, G, xq, sx, act=7)
+    # no epilogue through the new entry point = the plain call, bit for bit
+    Y0 = w2.matmul_a8(packed, K, N, G, xq, sx)
+    Y1 = w2.matmul_a8_epi(packed, K, N, G, xq, sx)
+    assert torch.equal(Y0.view(torch.int16), Y1.view(torch.int16))
+
+
 # ------------------------------------------------------------------ w2a16
 def run_a16_case(w2, M, K, N, G, codec, variant, seed):
     codes, scales, X = synth.make_problem(M, K, N, G, codec, seed)

@@ -3,6 +3,8 @@ are not itself -- a hand-worked example, numpy int64/fp64 matmuls of the
 dequantised operands, closed forms, invariants and exact special cases --
 chosen so that a dropped term, a wrong sign/index/zero-point or a transposed
 operand fails at least one test."""
+import math
+
 import numpy as np
 import pytest
 
@@ -268,3 +270,53 @@ def test_a8_close_to_unquantised_product_sanity_band():
     _, y16, _ = oracle.matmul_a16(codes, scales, 128, 0, synth.f32_to_bf16_bits(X))
     rel_rms = np.sqrt(np.mean((y8 - y16) ** 2) / np.mean(y16 ** 2))
     assert rel_rms < 0.03
+
+
+# ------------------------------------------------------------------ fused epilogue (Sec. II-D)
+def test_epilogue_silu_closed_forms_and_identities():
+    z = np.array([[0.0, 1.0, -1.0, 30.0, -30.0, 0.5, -0.5, 2.0]], np.float64)
+    _, out = oracle.epilogue(z, act=1)
+    assert out[0, 0] == 0.0                                        # silu(0) = 0
+    assert abs(out[0, 1] - 1.0 / (1.0 + math.e ** -1.0)) < 1e-15   # silu(1) = 1 / (1 + 1/e)
+    assert abs(out[0, 3] - 30.0) < 1e-11 and abs(out[0, 4]) < 1e-11   # x for large x, 0 for very negative x
+    # silu(x) - silu(-x) = x, and silu(x) + silu(-x) = x tanh(x/2)
+    assert np.allclose(out[0, 1] - out[0, 2], 1.0, atol=1e-15) and np.allclose(out[0, 5] - out[0, 6], 0.5, atol=1e-15)
+    assert np.allclose(out[0, 1] + out[0, 2], np.tanh(0.5), atol=1e-15)
+    # slope 1/2 at the origin (a dropped factor or a sign error in the exponent changes it)
+    h = 1e-6
+    _, d = oracle.epilogue(np.array([[h, -h]], np.float64), act=1)
+    assert abs((d[0, 0] - d[0, 1]) / (2 * h) - 0.5) < 1e-9
+    # no activation: identity, one rounding to bf16
+    Y, same = oracle.epilogue(z, act=0)
+    assert np.array_equal(same, z) and np.array_equal(Y, oracle.f64_to_bf16(z))
+
+
+def test_epilogue_bias_and_gated_layout_by_brute_force():
+    rng = np.random.default_rng(5)
+    M, N = 3, 64
+    y = rng.standard_normal((M, N))
+    bias_f = rng.standard_normal(N).astype(np.float32)
+    bias = synth.f32_to_bf16_bits(bias_f)
+    b64 = synth.bf16_bits_to_f32(bias).astype(np.float64)
+    _, out = oracle.epilogue(y, bias=bias, act=0)
+    assert np.array_equal(out, y + b64[None, :])                   # bias is per column, added before anything else
+    Y, out = oracle.epilogue(y, bias=bias, act=2)
+    assert out.shape == (M, N // 2)
+    for m in range(M):
+        for no in range(N // 2):
+            b, l = divmod(no, 16)
+            g = y[m, 32 * b + l] + b64[32 * b + l]                 # gate: even 16-column block
+            u = y[m, 32 * b + 16 + l] + b64[32 * b + 16 + l]       # up: the odd block after it
+            ref = g / (1.0 + math.exp(-g)) * u
+            assert abs(out[m, no] - ref) <= 1e-15 * max(1.0, abs(ref))
+    assert np.array_equal(Y, oracle.f64_to_bf16(out))
+    # gate = 0 gives 0 whatever up is; swapping the two blocks changes the result (not symmetric)
+    y0 = y.copy(); y0[:, 0:16] = 0.0
+    _, o0 = oracle.epilogue(y0, act=2)
+    assert np.all(o0[:, 0:16] == 0.0)
+    ys = y.copy(); ys[:, 0:16], ys[:, 16:32] = y[:, 16:32].copy(), y[:, 0:16].copy()
+    _, o1 = oracle.epilogue(ys, act=2)
+    _, o2 = oracle.epilogue(y, act=2)
+    assert not np.allclose(o1[:, 0:16], o2[:, 0:16])
+    with pytest.raises(oracle.OracleError):
+        oracle.epilogue(np.zeros((1, 48)), act=2)                  # N must be a multiple of 32
