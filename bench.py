@@ -317,6 +317,43 @@ def main():
     torch.cuda.synchronize()
     two_call_ms = e0.elapsed_time(e1) / args.steps
 
+    # ---- the same layer as a dependent chain, one graph per pool entry: QKV -> (attention left out: the
+    # first 4096 outputs stand in for its result) -> O -> gate+up with the gated SiLU epilogue -> down.
+    # Every call takes the previous call's bf16 output and quantises it inside the kernel.
+    Kq, Nq = shapes["qkv"]
+    Ko, No = shapes["o"]
+    Kg, Ng = shapes["gate_up"]
+    Kdn, Ndn = shapes["down"]
+    assert Ko <= Nq and Kg == No and Kdn == Ng // 2
+    c_qkv = torch.empty((1, Nq), dtype=torch.bfloat16, device=dev)
+    c_o = torch.empty((1, No), dtype=torch.bfloat16, device=dev)
+    c_act = torch.empty((1, Ng // 2), dtype=torch.bfloat16, device=dev)
+    c_out = torch.empty((1, Ndn), dtype=torch.bfloat16, device=dev)
+
+    def step_chained(layer):
+        s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        rc = lib.w2_matmul_a8_fused(vp(layer["qkv"]), Kq, Nq, G, vp(Xd["qkv"]), w2.DT_F32, Kq, M, vp(c_qkv), Nq, None, 0, s)
+        assert rc == 0, lib.w2_last_error()
+        rc = lib.w2_matmul_a8_fused(vp(layer["o"]), Ko, No, G, vp(c_qkv), w2.DT_BF16, Nq, M, vp(c_o), No, None, 0, s)
+        assert rc == 0, lib.w2_last_error()
+        w2.matmul_a8_fused_epi(layer["gate_up"], Kg, Ng, G, c_o, act=w2.ACT_SILU_MUL, out=c_act)
+        rc = lib.w2_matmul_a8_fused(vp(layer["down"]), Kdn, Ndn, G, vp(c_act), w2.DT_BF16, Kdn, M, vp(c_out), Ndn, None, 0, s)
+        assert rc == 0, lib.w2_last_error()
+
+    step_chained(pool[0])
+    torch.cuda.synchronize()
+    graphs3 = [capture(lambda l=l: step_chained(l)) for l in pool] if use_graph else None
+    for i in range(args.warmup):
+        graphs3[i % n_pool].replay() if graphs3 else step_chained(pool[i % n_pool])
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(args.steps):
+        graphs3[i % n_pool].replay() if graphs3 else step_chained(pool[i % n_pool])
+    e1.record()
+    torch.cuda.synchronize()
+    chained_ms = e0.elapsed_time(e1) / args.steps
+    chained_bytes = step_bytes - 2 * M * (Ng // 2)           # the gated epilogue stores half the columns
+
     # ---- roofline of the dominant kernel: the GEMV on the largest projection (gate+up),
     # launched alone, back to back over the pool, timed with events on the launch stream
     Kd, Nd = shapes["gate_up"]
@@ -407,7 +444,11 @@ def main():
                                "QKV 4096x6144, O 4096x4096, gate+up 4096x28672, down 14336x4096",
                    "bytes_per_step": step_bytes, "pool_layers": n_pool, "hip_graph": bool(graphs),
                    "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
-                   "two_call_gpu_ms_per_step": round(two_call_ms, 5)},
+                   "two_call_gpu_ms_per_step": round(two_call_ms, 5),
+                   "chained_layer": {"what": "QKV -> O -> gate+up with fused silu(gate)*up -> down, each call fed by the "
+                                             "previous call's bf16 output (attention, norms and residuals left out)",
+                                     "gpu_ms_per_step": round(chained_ms, 5),
+                                     "GBps": round(chained_bytes / (chained_ms * 1e-3) / 1e9, 1)}},
         "roofline": {"bound": "hbm", "kernel": "a8_fusedq_kernel (quantise + int8 MFMA GEMV + dequant) on gate+up 4096x28672, M=1",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic("a8_fusedq gate_up M=1"),
