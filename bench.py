@@ -522,7 +522,8 @@ def main():
         out["prefill_a16"] = {"workload": "the same shape, w2a16 (bf16 activations, bf16 MFMA)", "us_per_launch": round(us16, 1),
                               "value": round(tf16, 1), "unit": "TFLOP/s",
                               "roofline": {"bound": "mfma", "achieved": round(tf16, 1), "peak": 2500.0, "unit": "TFLOP/s",
-                                           "frac": round(tf16 / 2500.0, 4), "traffic": None}}
+                                           "frac": round(tf16 / 2500.0, 4),
+                                           "traffic": read_traffic("a16_fold_tiled gate_up 70B M=2048")}}
         try:
             B16 = torch.randn(Np, Kp, device=dev, dtype=torch.bfloat16).t()
             for _ in range(15):
