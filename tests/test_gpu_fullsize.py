@@ -43,7 +43,12 @@ def weights(w2, K, N, G, codec, seed):
     return _weights[key]
 
 
-def check_a8(w2, M, K, N, G, codec, seed, ncols=256, acc_check=True):
+def workspace(w2, M, K, N, G, a16=False):
+    n = w2.workspace_size(M, K, N, G, a16=a16)
+    return torch.empty(n, dtype=torch.uint8, device="cuda") if n else None
+
+
+def check_a8(w2, M, K, N, G, codec, seed, ncols=256, acc_check=True, use_ws=False):
     codes, scales, packed = weights(w2, K, N, G, codec, seed)
     X = synth.make_activations(M, K, seed=seed + 1000 + M)
     xq, sx, _ = w2.quantize_rows(dev(X), G)
@@ -52,7 +57,7 @@ def check_a8(w2, M, K, N, G, codec, seed, ncols=256, acc_check=True):
     assert np.array_equal(sx.cpu().numpy().view(np.uint32), osx.view(np.uint32))
     cols = sample_cols(N, ncols, seed)
     cs, ss = np.ascontiguousarray(codes[:, cols]), np.ascontiguousarray(scales[:, cols])
-    Y = w2.matmul_a8(packed, K, N, G, xq, sx)
+    Y = w2.matmul_a8(packed, K, N, G, xq, sx, workspace=workspace(w2, M, K, N, G) if use_ws else None)
     Yo, y64 = oracle.matmul_a8(cs, ss, G, codec, oq, osx)
     mag = oracle.a8_term_magnitude(cs, ss, G, codec, oq, osx)
     check_y(bf16_bits(Y)[:, cols], Yo, y64, mag, f"a8 full M={M} K={K} N={N} G={G}")
@@ -64,12 +69,13 @@ def check_a8(w2, M, K, N, G, codec, seed, ncols=256, acc_check=True):
         assert np.array_equal(acc.cpu().numpy()[:, :, cols], oacc)
 
 
-def check_a16(w2, M, K, N, G, codec, seed, ncols=128):
+def check_a16(w2, M, K, N, G, codec, seed, ncols=128, use_ws=False):
     codes, scales, packed = weights(w2, K, N, G, codec, seed)
     Xb = synth.f32_to_bf16_bits(synth.make_activations(M, K, seed=seed + 2000 + M))
     cols = sample_cols(N, ncols, seed)
     cs, ss = np.ascontiguousarray(codes[:, cols]), np.ascontiguousarray(scales[:, cols])
-    Y = w2.matmul_a16(packed, K, N, G, dev(Xb).view(torch.bfloat16))
+    Y = w2.matmul_a16(packed, K, N, G, dev(Xb).view(torch.bfloat16),
+                      workspace=workspace(w2, M, K, N, G, a16=True) if use_ws else None)
     Yo, y64, mag = oracle.matmul_a16(cs, ss, G, codec, Xb)
     check_y(bf16_bits(Y)[:, cols], Yo, y64, mag, f"a16 full M={M} K={K} N={N} G={G}")
 
@@ -125,3 +131,40 @@ def test_70b_prefill_down(w2):
     K, N = synth.SHAPES_70B["down"]
     check_a8(w2, 512, K, N, 128, 0, seed=4, ncols=128)
     check_a16(w2, 256, K, N, 128, 0, seed=4, ncols=64)
+
+
+def test_70b_prefill_gate_up_a16(w2):
+    """The benchmark's w2a16 prefill launch: 8192 x 57344 at M = 2048 (128-row scale-folded tiles)."""
+    K, N = synth.SHAPES_70B["gate_up"]
+    check_a16(w2, 2048, K, N, 128, 0, seed=4, ncols=64)
+
+
+@pytest.mark.parametrize("name", list(synth.SHAPES_8B))
+def test_8b_between_decode_and_prefill(w2, name):
+    """8B-class projections at M = 32 (mid-M kernels) and M = 128 (tiled kernels; with the workspace
+    w2_workspace_size asks for, so K is split across workgroups where the planner wants it), both paths."""
+    K, N = synth.SHAPES_8B[name]
+    for M in (32, 128):
+        check_a8(w2, M, K, N, 128, 0, seed=1, ncols=64, acc_check=False, use_ws=True)
+        check_a16(w2, M, K, N, 128, 0, seed=1, ncols=64, use_ws=True)
+
+
+def test_8b_gate_up_gated_epilogue_m1(w2):
+    """The chained layer's gate+up call: bf16 row in, quantised in the kernel, silu(gate) * up out."""
+    K, N = synth.SHAPES_8B["gate_up"]
+    codes, scales, packed = weights(w2, K, N, 128, 0, 1)
+    Xb = synth.f32_to_bf16_bits(synth.make_activations(1, K, seed=78))
+    Y = w2.matmul_a8_fused_epi(packed, K, N, 128, dev(Xb).view(torch.bfloat16), act=w2.ACT_SILU_MUL)
+    oq, osx, _ = oracle.quantize_rows(Xb, 128, x_is_bf16=True, want_gsum=False)
+    blocks = np.unique(np.concatenate([np.arange(4), np.random.default_rng(9).choice(N // 32, 12), [N // 32 - 1]]))
+    cols = (blocks[:, None] * 32 + np.arange(32)[None, :]).reshape(-1)          # whole gate/up block pairs
+    cs, ss = np.ascontiguousarray(codes[:, cols]), np.ascontiguousarray(scales[:, cols])
+    _, y64 = oracle.matmul_a8(cs, ss, 128, 0, oq, osx)
+    mag = oracle.a8_term_magnitude(cs, ss, 128, 0, oq, osx)
+    _, out = oracle.epilogue(y64, act=2)
+    ocols = (blocks[:, None] * 16 + np.arange(16)[None, :]).reshape(-1)
+    yg = synth.bf16_bits_to_f32(bf16_bits(Y)[:, ocols]).astype(np.float64)
+    d = (1e-2 * np.abs(y64) + 2.0 ** -10 * mag).reshape(1, -1, 2, 16)
+    z = y64.reshape(1, -1, 2, 16)
+    tol = (1.1 * d[:, :, 0] * (np.abs(z[:, :, 1]) + d[:, :, 1]) + np.abs(z[:, :, 0]) * d[:, :, 1]).reshape(1, -1)
+    assert np.all(np.abs(yg - out) <= tol + 2.0 ** -8 * np.abs(out))
