@@ -66,14 +66,14 @@ typedef enum {
 
 /* Kernel families, for w2_matmul_a8_ex / w2_matmul_a16_ex and the debug export.
  * AUTO picks by M (w2a8: SMALLM for M <= 8 (M <= 3 when N >= 6144 or K > 16384), MIDM up to
- * M = 64, else TILED;
- * w2a16: SMALLM for M <= 8, MIDM up to M = 64, else the SCALED16 tiled kernel).
+ * M = 64 (M = 128 when N <= 8192), else TILED;
+ * w2a16: SMALLM for M <= 8, MIDM up to M = 64 (M = 128 when N <= 4096), else the SCALED16 tiled kernel).
  * DOT4: per-lane v_dot4_i32_i8
  * with split-K across the waves of a workgroup (M <= 4; kept as the dot-product form of the microkernel,
  * selectable here).  SMALLM: one 16-row int8 (bf16 for a16) MFMA tile per
  * wave, split-K across waves (M <= 16).  MIDM: the weight stream
- * is still read once; every streamed tile is multiplied into one to four
- * 16-row MFMA tiles (M <= 64; for w2a16 with the SCALED16 weight construction).
+ * is still read once per band of 64 rows; every streamed tile is multiplied into one to four
+ * 16-row MFMA tiles (M <= 256 = four bands; for w2a16 with the SCALED16 weight construction).
  * TILED: LDS-staged MFMA tiles (any M; for w2a16 the zero-point construction).
  * SCALED16 (w2a16 only): the weights are built as sw*q from code and group
  * scale (Sec. II-D, the alternative 16-bit construction) and go to the bf16

@@ -201,7 +201,11 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         // column blocks: it then splits K four ways with a barrier pair per tile), and is faster
         // than the tiled one up to M = 64
         const int dot4_max = env_int("W2_DOT4_MAX_M", 0);
-        const int midm_min = env_int("W2_MIDM_MIN_M", (a.n_cb >= 384 || a.n_kt > 64) ? 4 : 9), midm_max = env_int("W2_MIDM_MAX_M", 64);
+        // ... and, as two bands of 64 rows, up to M = 128 on projections of at most 8192 columns, where
+        // one band's workgroups leave CUs idle and the tiled kernel has too few tiles (10 against 19 us
+        // on 4096 x 4096)
+        const int midm_min = env_int("W2_MIDM_MIN_M", (a.n_cb >= 384 || a.n_kt > 64) ? 4 : 9);
+        const int midm_max = env_int("W2_MIDM_MAX_M", a.n_cb <= 512 ? 128 : 64);
         variant = M <= dot4_max && a8_dot4_supports(a)                       ? W2_VARIANT_DOT4
                 : M >= midm_min && M <= midm_max && a8_midm_supports(a)     ? W2_VARIANT_MIDM
                 : a8_smallm_supports(a)                                      ? W2_VARIANT_SMALLM
@@ -216,7 +220,7 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         if (!a8_smallm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: SMALLM needs M <= 16", fn);
         return launch_a8_smallm(a, s);
     case W2_VARIANT_MIDM:
-        if (!a8_midm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: MIDM needs M <= 64", fn);
+        if (!a8_midm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: MIDM needs M <= 256", fn);
         return launch_a8_midm(a, s);
     default:
         return launch_a8_tiled(a, s);
@@ -360,8 +364,7 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     if (variant == W2_VARIANT_SCALED16) {
         // the scale-folded construction: the small-M kernel with it, or the kernels built on it
         if (!a16_smallm_supports(a))
-            return a16_midm_supports(a) ? launch_a16_midm(a, (hipStream_t)stream)
-                                        : launch_a16_fold_tiled(a, (hipStream_t)stream);
+            return M <= 64 ? launch_a16_midm(a, (hipStream_t)stream) : launch_a16_fold_tiled(a, (hipStream_t)stream);
         variant = W2_VARIANT_SMALLM;
     }
     if (variant == W2_VARIANT_AUTO) {
@@ -370,12 +373,13 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         // above, 128-row tiles.  Both of the latter fold the scale into the weights: fewest vector
         // instructions per matrix instruction.
         const int midm_min = env_int("W2_A16_MIDM_MIN_M", 9);
-        if (M >= midm_min && a16_midm_supports(a)) return launch_a16_midm(a, (hipStream_t)stream);
+        const int midm_max = env_int("W2_A16_MIDM_MAX_M", a.n_cb <= 256 ? 128 : 64);   // two bands on small projections
+        if (M >= midm_min && M <= midm_max && a16_midm_supports(a)) return launch_a16_midm(a, (hipStream_t)stream);
         if (!a16_smallm_supports(a)) return launch_a16_fold_tiled(a, (hipStream_t)stream);
         variant = W2_VARIANT_SMALLM;
     }
     if (variant == W2_VARIANT_MIDM) {
-        if (!a16_midm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: MIDM needs M <= 64", fn);
+        if (!a16_midm_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: MIDM needs M <= 256", fn);
         return launch_a16_midm(a, (hipStream_t)stream);
     }
     if (variant == W2_VARIANT_SMALLM) {

@@ -28,6 +28,7 @@ constexpr int THREADS = 512;
 constexpr int CHUNK_TILES = 4;                                   // k tiles per LDS chunk
 constexpr int ROW_STRIDE = CHUNK_TILES * TILE_K * 2 + 32;        // bytes per LDS activation row (32 mod 64: conflict-free operand reads)
 constexpr int D = 8;                                             // weight tiles in flight per wave
+constexpr int ROWS_PER_BAND = 64;                                // rows one workgroup multiplies (RT <= 4 row tiles)
 
 // The four weights of one (group, column), low bytes and high bytes, indexed by the raw code
 // (00 -> 0, 01 -> +sw, 10 -> -2 sw: sign flipped and exponent + 1, 11 -> -sw).
@@ -66,8 +67,17 @@ __device__ __forceinline__ v4f mfma_bf16(const v4i& a, const v4i& b, const v4f& 
 
 template <int G, int RT, int TPC>
 __global__ void __launch_bounds__(THREADS)
-a16_midm_kernel(A16Args a)
+a16_midm_kernel(A16Args a_all)
 {
+    // More than 64 rows: blockIdx.y picks a band of 64 rows; the bands stream the same weights (the
+    // second one mostly out of L2), which pays when one band's workgroups would leave CUs idle.
+    A16Args a = a_all;
+    {
+        const int64_t m_off = (int64_t)blockIdx.y * ROWS_PER_BAND;
+        a.M = min((int64_t)ROWS_PER_BAND, a_all.M - m_off);
+        a.X += m_off * a.ldx;
+        a.Y += m_off * a.ldy;
+    }
     constexpr int KS = CHUNK_TILES / TPC;                    // k-splits
     constexpr int CBW = 8 / KS;                              // column blocks per workgroup
     constexpr int VPR = CHUNK_TILES * TILE_K / 8;            // 16-byte pieces (eight k) per full row: 128
@@ -243,10 +253,11 @@ template <int G, int RT, int TPC>
 static int launch_t(const A16Args& a, hipStream_t stream)
 {
     constexpr int CBW = 2 * TPC;
-    const size_t act = (size_t)a.M * ROW_STRIDE;
+    const int64_t band = a.M < ROWS_PER_BAND ? a.M : ROWS_PER_BAND;
+    const size_t act = (size_t)band * ROW_STRIDE;
     const size_t red = (size_t)8 * RT * 16 * 16 * sizeof(float);
     const size_t lds = act > red ? act : red;
-    const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW)), block(THREADS);
+    const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW), (unsigned)((a.M + ROWS_PER_BAND - 1) / ROWS_PER_BAND)), block(THREADS);
     auto kern = a16_midm_kernel<G, RT, TPC>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -281,7 +292,8 @@ static int launch_g(const A16Args& a, hipStream_t stream)
 
 }  // namespace midm16
 
-bool a16_midm_supports(const A16Args& a) { return a.M >= 1 && a.M <= 64; }
+// up to four bands of 64 rows
+bool a16_midm_supports(const A16Args& a) { return a.M >= 1 && a.M <= 4 * midm16::ROWS_PER_BAND; }
 
 int launch_a16_midm(const A16Args& a, hipStream_t stream)
 {

@@ -26,11 +26,23 @@ constexpr int THREADS = 512;
 constexpr int CHUNK_TILES = 4;                               // k tiles per LDS chunk
 constexpr int ROW_STRIDE = CHUNK_TILES * TILE_K + XS_PAD;    // bytes per LDS activation row
 constexpr int D = 8;                                         // weight tiles in flight per wave
+constexpr int ROWS_PER_BAND = 64;                            // rows one workgroup multiplies (RT <= 4 row tiles)
 
 template <int G, int RT, int TPC, bool DBG>
 __global__ void __launch_bounds__(THREADS)
-a8_midm_kernel(A8Args a)
+a8_midm_kernel(A8Args a_all)
 {
+    // More than 64 rows: blockIdx.y picks a band of 64 rows; the bands stream the same weights (the
+    // second one mostly out of L2), which pays when one band's workgroups would leave CUs idle.
+    A8Args a = a_all;
+    {
+        const int64_t m_off = (int64_t)blockIdx.y * ROWS_PER_BAND;
+        a.M = min((int64_t)ROWS_PER_BAND, a_all.M - m_off);
+        a.xq += m_off * a.K;
+        if (a.sx) a.sx += m_off;
+        if (a.Y) a.Y += m_off * a.ldy;
+        if (a.acc_out) a.acc_out += m_off * (a.K / G) * a.N;
+    }
     constexpr int KS = CHUNK_TILES / TPC;                    // k-splits
     constexpr int CBW = 8 / KS;                              // column blocks per workgroup
     constexpr int NS = 2 * RT;                               // 16-byte activation pieces per thread and chunk
@@ -244,10 +256,11 @@ template <int G, int RT, int TPC>
 static int launch_t(const A8Args& a, hipStream_t stream)
 {
     constexpr int CBW = 2 * TPC;
-    const size_t act = (size_t)a.M * ROW_STRIDE;
+    const int64_t band = a.M < ROWS_PER_BAND ? a.M : ROWS_PER_BAND;
+    const size_t act = (size_t)band * ROW_STRIDE;
     const size_t red = (size_t)8 * RT * 16 * 16 * sizeof(float);
     const size_t lds = act > red ? act : red;
-    const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW)), block(THREADS);
+    const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW), (unsigned)((a.M + ROWS_PER_BAND - 1) / ROWS_PER_BAND)), block(THREADS);
     auto go = [&](auto kern) {
         if (lds > 64 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -285,7 +298,8 @@ static int launch_g(const A8Args& a, hipStream_t stream)
 
 }  // namespace midm
 
-bool a8_midm_supports(const A8Args& a) { return a.M >= 1 && a.M <= 64; }
+// up to four bands of 64 rows (beyond that the tiled kernel's reuse of the weights wins everywhere)
+bool a8_midm_supports(const A8Args& a) { return a.M >= 1 && a.M <= 4 * midm::ROWS_PER_BAND; }
 
 int launch_a8_midm(const A8Args& a, hipStream_t stream)
 {

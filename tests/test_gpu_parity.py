@@ -161,11 +161,20 @@ def test_a8_midm(w2, M, K, N, G, cbw, monkeypatch):
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_MIDM, seed=M + K + N + G)
 
 
+@pytest.mark.parametrize("M", [65, 100, 128, 130, 256])
+@pytest.mark.parametrize("K,N,G", [(1024, 272, 128), (768, 48, 64)])
+def test_midm_row_bands(w2, M, K, N, G):
+    # more than 64 rows: bands of 64 rows on grid.y (ragged last band), both activation types, and the
+    # integer accumulators of every band bit for bit
+    run_a8_case(w2, M, K, N, G, M % 2, w2.VARIANT_MIDM, seed=M + K)
+    run_a16_case(w2, M, K, N, G, M % 2, w2.VARIANT_MIDM, seed=M + K)
+
+
 def test_a8_midm_long_k_and_limits(w2):
     run_a8_case(w2, 64, 8192, 48, 128, 0, w2.VARIANT_MIDM, seed=7)
     run_a8_case(w2, 40, 14336, 32, 64, 1, w2.VARIANT_MIDM, seed=8)
     run_a8_case(w2, 3, 512, 40, 128, 0, w2.VARIANT_MIDM, seed=9)       # small M is allowed, just not chosen
-    codes, scales, X = synth.make_problem(65, 256, 16, 128, 0, 9)
+    codes, scales, X = synth.make_problem(257, 256, 16, 128, 0, 9)      # more than four bands of 64 rows
     packed = w2.prepack(dev(codes), dev(scales), 128, 0)
     xq, sx, _ = w2.quantize_rows(dev(X), 128)
     with pytest.raises(w2.W2Error):
@@ -460,7 +469,7 @@ def test_a16_midm(w2, M, K, N, G, cbw, monkeypatch):
 def test_a16_midm_long_k_and_limits(w2):
     run_a16_case(w2, 40, 14336, 64, 128, 0, w2.VARIANT_MIDM, seed=3)
     K, N, G = 256, 16, 128
-    codes, scales, X = synth.make_problem(65, K, N, G, 0, 0)
+    codes, scales, X = synth.make_problem(257, K, N, G, 0, 0)          # more than four bands of 64 rows
     packed = w2.prepack(dev(codes), dev(scales), G, 0)
     with pytest.raises(w2.W2Error):
         w2.matmul_a16(packed, K, N, G, dev(synth.f32_to_bf16_bits(X)).view(torch.bfloat16), variant=w2.VARIANT_MIDM)
