@@ -54,7 +54,9 @@ stream_read_kernel(const uint4* __restrict__ src, size_t n_chunks, uint32_t* __r
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const size_t c = base + u < n_chunks ? base + u : n_chunks - 1;
-            v[u] = src[c * 64 + lane];
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // non-temporal, as the GEMV kernels load their weights
+            const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + c * 64 + lane));
+            v[u] = make_uint4(t[0], t[1], t[2], t[3]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;

@@ -15,6 +15,8 @@
 // loads and their first use, so nothing waits behind the weight stream.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "w2_small_common.h"
 
 namespace w2 {
@@ -46,7 +48,7 @@ struct FusedArgs {
     Epilogue epi;
 };
 
-template <int G, int TMAX, int RL, bool BF16IN>
+template <int G, int TMAX, int RL, bool BF16IN, int PRE = TMAX>
 __global__ void __launch_bounds__(1024)
 a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
 {
@@ -88,15 +90,25 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
     // 2. the wave's whole share of the weight stream
     int64_t kt0 = ks;
     const int64_t kt_end = a.n_kt;
-    auto load_batch = [&](int64_t kb, TileRegs (&tr)[TMAX]) {
+    auto load_range = [&](int64_t kb, TileRegs (&tr)[TMAX], auto first, auto last) {
 #pragma unroll
-        for (int i = 0; i < TMAX; ++i) {
+        for (int i = decltype(first)::value; i < decltype(last)::value; ++i) {
             const int64_t kt = kb + (int64_t)i * cfg.ks;
             tr[i] = load_tile<G>(a.codes, a.scales, cbc * a.n_kt + (kt < kt_end ? kt : kt_end - 1), lane);
         }
     };
+    auto load_batch = [&](int64_t kb, TileRegs (&tr)[TMAX]) {
+        load_range(kb, tr, std::integral_constant<int, 0>{}, std::integral_constant<int, TMAX>{});
+    };
+    // Only the first PRE tiles are requested before the activations are quantised.  With every
+    // load of a large projection issued up front the memory pipeline fills, the waves stall in
+    // the issue of their later loads, and the barriers below (hence the first matrix instruction)
+    // wait for the slowest of them: measured with in-kernel timestamps on 4096 x 28672, the
+    // quantised row was ready after 4.6 us (median over the waves) and most arithmetic ran
+    // after the weights had arrived; with the split it is ready after 3.2 us.  The first tiles
+    // keep the memory system busy while the rows are quantised; the rest is requested right after.
     TileRegs tr0[TMAX];
-    load_batch(kt0, tr0);
+    load_range(kt0, tr0, std::integral_constant<int, 0>{}, std::integral_constant<int, PRE>{});
 
     // 3. reduce abs-max per row; the pieces stay in registers (every piece has a slot: a launch condition)
     float amax[RL];
@@ -178,6 +190,7 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
         }
     }
     __syncthreads();
+    load_range(kt0, tr0, std::integral_constant<int, PRE>{}, std::integral_constant<int, TMAX>{});
 
     // 5. up-convert and compute, as in the small-M kernel
     float y[RL];
@@ -235,6 +248,10 @@ static int launch_fusedq_t(const FusedArgs& a, const SmallCfg& c, size_t lds, hi
     const char* what = "w2_matmul_a8_fused";
     if (tpw <= 2) return launch_small(a8_fusedq_kernel<G, 2, RL, BF16IN>, what, a, c, lds, stream);
     if (tpw <= 4) return launch_small(a8_fusedq_kernel<G, 4, RL, BF16IN>, what, a, c, lds, stream);
+    // every wave has more than four tiles: a large projection.  One row: half of the loads wait for
+    // the quantised row (measured 10.0 against 10.4 us on 4096 x 28672; with two rows it loses).
+    if (RL == 1 && env_int("W2_SMALL_PRE", 4) == 4)
+        return launch_small(a8_fusedq_kernel<G, TMAX, RL, BF16IN, 4>, what, a, c, lds, stream);
     return launch_small(a8_fusedq_kernel<G, TMAX, RL, BF16IN>, what, a, c, lds, stream);
 }
 

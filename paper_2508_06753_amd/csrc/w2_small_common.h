@@ -80,7 +80,11 @@ __device__ __forceinline__ TileRegs load_tile(const uint32_t* __restrict__ codes
                                               int lane)
 {
     TileRegs r;
-    r.w = *reinterpret_cast<const uint4*>(codes + (tile * 64 + lane) * 4);
+    // non-temporal: the weights are streamed once and should not displace anything in the caches
+    // (measured: the plain streaming read gains 10 % from the hint, the GEMV kernels 1-3 %)
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(codes + (tile * 64 + lane) * 4));
+    r.w = make_uint4(t[0], t[1], t[2], t[3]);
     if constexpr (G == 128) {
         r.s0 = *reinterpret_cast<const uint32_t*>(scales + (tile * TILE_N + (lane & 15)) * 2);
         r.s1 = 0;
