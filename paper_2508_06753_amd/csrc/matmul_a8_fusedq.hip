@@ -196,28 +196,48 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
     float y[RL];
 #pragma unroll
     for (int r = 0; r < RL; ++r) y[r] = 0.f;
-    v4i acc = {0, 0, 0, 0};
+    // Two accumulators alternate between groups, and a finished group is dequantised one group
+    // later, after the next group's matrix instructions have been issued: the int -> float
+    // conversion then never waits for the matrix pipe, and the next tile's activation operands
+    // are read from LDS while this tile is multiplied.  What a wave does after its last tile has
+    // arrived is the kernel's tail, so the length of this chain counts.
+    v4i acc[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    float pend_sw = 0.f;                                     // scale of the group waiting in acc[1]: none yet
+    auto dequant = [&](int b) {
+#pragma unroll
+        for (int r = 0; r < RL; ++r) y[r] = fmaf(pend_sw, (float)acc[b][r], y[r]);
+    };
+    auto read_aop = [&](int64_t kt, v4i (&aop)[4]) {
+        const int8_t* xrow = xs + arow * row_stride + (int)kt * TILE_K + q * 16;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) aop[t] = *reinterpret_cast<const v4i*>(xrow + t * 64);
+    };
     auto compute_batch = [&](int64_t kb, const TileRegs (&tr)[TMAX]) {
+        v4i aop[2][4];
+        read_aop(min(kb, kt_end - 1), aop[0]);
 #pragma unroll
         for (int i = 0; i < TMAX; ++i) {
             const int64_t kt = kb + (int64_t)i * cfg.ks;
             if (kt >= kt_end) break;
+            if (i + 1 < TMAX) read_aop(min(kt + cfg.ks, kt_end - 1), aop[(i + 1) & 1]);   // clamped: stays inside the rows
+            __builtin_amdgcn_sched_barrier(0);               // the reads stay here, a tile ahead of their use
             const TileRegs cur = tr[i];
-            const int8_t* xrow = xs + arow * row_stride + (int)kt * TILE_K + q * 16;
             const uint32_t wd[4] = {cur.w.x, cur.w.y, cur.w.z, cur.w.w};
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 int u[4];
                 upconvert(wd[t], u);
                 const v4i bop = {u[0], u[1], u[2], u[3]};
-                const v4i aop = *reinterpret_cast<const v4i*>(xrow + t * 64);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, bop, acc, 0, 0, 0);
-                if (G == 64 || (t & 1)) {
-                    const float sw = tile_scale<G>(cur, G == 64 ? t : t >> 1);
-#pragma unroll
-                    for (int r = 0; r < RL; ++r) y[r] = fmaf(sw, (float)acc[r], y[r]);
-                    acc = (v4i){0, 0, 0, 0};
+                const int gi = G == 64 ? t : t >> 1;         // group inside the tile
+                const int b = gi & 1;                        // its accumulator (groups per tile are even)
+                const bool first = G == 64 || !(t & 1);
+                const v4i zero = {0, 0, 0, 0};
+                acc[b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[i & 1][t], bop, first ? zero : acc[b], 0, 0, 0);
+                if (first) {
+                    __builtin_amdgcn_sched_barrier(0);       // ... after this group's first matrix instruction, not before
+                    dequant(b ^ 1);                          // the group before this one
                 }
+                if (G == 64 || (t & 1)) pend_sw = tile_scale<G>(cur, gi);
             }
         }
     };
@@ -227,6 +247,7 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
         load_batch(kt0, tr);
         compute_batch(kt0, tr);
     }
+    dequant(1);                                              // the last group (it sits in acc[1])
 
     __syncthreads();
     float* red = reinterpret_cast<float*>(smem + FQ_HDR);   // [waves][16 m][16 n]
