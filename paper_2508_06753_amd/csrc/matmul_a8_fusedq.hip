@@ -287,9 +287,9 @@ int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x
         return -2;
     }
     const int rows = (int)M;
-    SmallCfg c = pick_cfg(n_cb, n_kt, rows, 1, 16, epi.act == ACT_SILU_MUL);
     const int es = x_is_bf16 ? 2 : 4;
-    const int64_t pieces = M * K * es / 16;
+    const int64_t pieces = M * K * es / 16;                  // every piece needs a register slot of some thread
+    SmallCfg c = pick_cfg(n_cb, n_kt, rows, 1, 16, epi.act == ACT_SILU_MUL, (int)((pieces + FQ_PIECES - 1) / FQ_PIECES));
     const int threads = 64 * c.cbw * c.ks;
     const size_t xs_bytes = ((size_t)rows * (K + XS_PAD) + 15) & ~(size_t)15;
     size_t lds = FQ_HDR + xs_bytes;
