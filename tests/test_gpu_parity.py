@@ -4,6 +4,8 @@ int32 group accumulators) must match bit for bit; bf16 outputs must satisfy
 |Y - Yor| <= 1e-2*|Yor| + 2^-10 * sum|terms| (the second term is the floor for
 outputs that are a cancelling sum; fp32 vs fp64 association alone moves
 those)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -591,3 +593,66 @@ def test_argument_errors_write_nothing(w2):
     assert torch.all(Y == 7.0)
     with pytest.raises(w2.W2Error):
         w2.matmul_a8(packed, 256, 64, 128, xq.repeat(5, 1), sx.repeat(5), variant=w2.VARIANT_DOT4)
+
+
+# ------------------------------------------------------------------ HIP graph replays
+def test_graph_replays_match_eager(w2):
+    """The benchmark replays its steps from HIP graphs: a captured chain (fused call -> gated epilogue call ->
+    fused call with bf16 input, a split-K tiled call and a w2a16 call beside it) is replayed several times with
+    eager launches and synchronisations in between; every replay must reproduce the eager results bit for bit,
+    also after the inputs changed."""
+    K, N, G = 1024, 512, 128
+    codes, scales, X = synth.make_problem(1, K, N, G, 0, 11)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    codes2, scales2, _ = synth.make_problem(1, N // 2, 256, G, 0, 12)
+    packed2 = w2.prepack(dev(codes2), dev(scales2), G, 0)
+    Mt = 130
+    _, _, Xt = synth.make_problem(Mt, K, N, G, 0, 13)
+    x_in = dev(X)
+    xt = dev(Xt)
+    xtb = xt.to(torch.bfloat16)
+    ws = torch.empty(w2.workspace_size(Mt, K, N, G) + 4 * Mt * N * 4, dtype=torch.uint8, device="cuda")
+    ws16 = torch.empty(4 * Mt * N * 4, dtype=torch.uint8, device="cuda")
+    h = torch.empty((1, N // 2), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((1, 256), dtype=torch.bfloat16, device="cuda")
+    yt = torch.empty((Mt, N), dtype=torch.bfloat16, device="cuda")
+    y16 = torch.empty((Mt, N), dtype=torch.bfloat16, device="cuda")
+    os.environ["W2_SPLITK"] = "3"
+    try:
+        def step():
+            w2.matmul_a8_fused_epi(packed, K, N, G, x_in, act=w2.ACT_SILU_MUL, out=h)
+            w2.matmul_a8_fused(packed2, N // 2, 256, G, h, out=y)
+            w2.matmul_a8_fused(packed, K, N, G, xt, out=yt, workspace=ws)          # quantise + tiled split-K + reduce
+            w2.matmul_a16(packed, K, N, G, xtb, out=y16, workspace=ws16)
+
+        def eager():
+            step()
+            torch.cuda.synchronize()
+            return [t.clone() for t in (h, y, yt, y16)]
+
+        ref = eager()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            step()                                           # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(s)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for rep in range(4):
+            for t in (h, y, yt, y16):
+                t.zero_()                                    # eager work between the replays
+            if rep == 2:                                     # new inputs in the same buffers
+                x_in.mul_(-0.5)
+                xt.add_(0.25)
+                xtb.copy_(xt.to(torch.bfloat16))
+                ref = eager()
+                for t in (h, y, yt, y16):
+                    t.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for got, want, name in zip((h, y, yt, y16), ref, ("gated", "chained", "split-K a8", "a16")):
+                assert torch.equal(got.view(torch.int16), want.view(torch.int16)), f"replay {rep}: {name} differs from eager"
+    finally:
+        os.environ.pop("W2_SPLITK", None)
