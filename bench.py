@@ -576,7 +576,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         best = None
-        for _ in range(2):
+        for _ in range(10):
             t = time.perf_counter()
             for name in shapes:
                 codes, scales, X = host[name]
@@ -587,7 +587,7 @@ def main():
         out["cpu_baseline"] = {"value": round(step_bytes / best / 1e9, 3), "unit": "GB/s",
                                "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": "the full step (all four projections of the layer, M=1), "
-                                         "best of 2 runs; %.3f s per step" % best}
+                                         "best of 10 runs; %.3f s per step" % best}
     print(json.dumps(out))
 
 

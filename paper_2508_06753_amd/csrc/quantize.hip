@@ -45,8 +45,12 @@ __device__ __forceinline__ int quant1(float x, float inv)
     return (int)r;
 }
 
-// One workgroup per row.  Pass 1: abs-max (wave shuffles + LDS).  Pass 2:
-// re-read the row (L2-resident), quantise, store packed int8.
+// One workgroup per row.  Pass 1: abs-max (wave shuffles + LDS).  Pass 2: quantise and store packed
+// int8.  The first CR vectors of a thread stay in registers between the passes (with 1024 threads
+// that is a whole row of up to 16384 fp32 or 32768 bf16 values: one trip to memory instead of two);
+// longer rows re-read the rest (L2-resident).
+constexpr int CR = 4;
+
 template <bool BF16>
 __global__ void __launch_bounds__(1024)
 quantize_rows_kernel(const void* __restrict__ X, int64_t K, int64_t ldx, int G,
@@ -58,10 +62,26 @@ quantize_rows_kernel(const void* __restrict__ X, int64_t K, int64_t ldx, int G,
     const void* row = BF16 ? (const void*)((const uint16_t*)X + m * ldx)
                            : (const void*)((const float*)X + m * ldx);
     __shared__ float s_red[16];
-    __shared__ float s_amax;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t step = (int64_t)blockDim.x * EPT;
+
+    float cache[CR][EPT];
+#pragma unroll
+    for (int c = 0; c < CR; ++c) {
+        const int64_t k = (int64_t)threadIdx.x * EPT + c * step;
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) cache[c][i] = 0.0f;
+        if (k < K) L::load(row, k, cache[c]);
+    }
+    if (threadIdx.x < 16) s_red[threadIdx.x] = 0.0f;         // slots of waves that do not exist stay 0
+    __syncthreads();
 
     float amax = 0.0f;
-    for (int64_t k = (int64_t)threadIdx.x * EPT; k < K; k += (int64_t)blockDim.x * EPT) {
+#pragma unroll
+    for (int c = 0; c < CR; ++c)
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) amax = fmaxf(amax, fabsf(cache[c][i]));
+    for (int64_t k = (int64_t)threadIdx.x * EPT + CR * step; k < K; k += step) {
         float v[EPT];
         L::load(row, k, v);
 #pragma unroll
@@ -69,17 +89,11 @@ quantize_rows_kernel(const void* __restrict__ X, int64_t K, int64_t ldx, int G,
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     if (lane == 0) s_red[wave] = amax;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        float a = 0.0f;
-        const int nw = (blockDim.x + 63) >> 6;
-        for (int i = 0; i < nw; ++i) a = fmaxf(a, s_red[i]);
-        s_amax = a;
-    }
-    __syncthreads();
-    amax = s_amax;
+    amax = s_red[lane & 15];                                 // every wave reduces the (at most 16) partial maxima itself
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
     float inv = 0.0f, s = 0.0f;
     if (amax > 0.0f) {
         inv = __fdiv_rn(127.0f, amax);
@@ -88,9 +102,7 @@ quantize_rows_kernel(const void* __restrict__ X, int64_t K, int64_t ldx, int G,
     if (threadIdx.x == 0) sx[m] = s;
 
     const int lanes_per_group = G / EPT;      // 8..32, a power of two, divides 64
-    for (int64_t k = (int64_t)threadIdx.x * EPT; k < K; k += (int64_t)blockDim.x * EPT) {
-        float v[EPT];
-        L::load(row, k, v);
+    auto emit = [&](int64_t k, const float (&v)[EPT]) {
         int q[EPT];
         int sum = 0;
 #pragma unroll
@@ -110,6 +122,16 @@ quantize_rows_kernel(const void* __restrict__ X, int64_t K, int64_t ldx, int G,
             for (int off = 1; off < lanes_per_group; off <<= 1) sum += __shfl_xor(sum, off);
             if ((lane & (lanes_per_group - 1)) == 0) gsum[m * (K / G) + k / G] = sum;
         }
+    };
+#pragma unroll
+    for (int c = 0; c < CR; ++c) {
+        const int64_t k = (int64_t)threadIdx.x * EPT + c * step;
+        if (k < K) emit(k, cache[c]);                        // uniform per wave (K % 256 == 0)
+    }
+    for (int64_t k = (int64_t)threadIdx.x * EPT + CR * step; k < K; k += step) {
+        float v[EPT];
+        L::load(row, k, v);
+        emit(k, v);
     }
 }
 
