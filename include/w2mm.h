@@ -190,8 +190,8 @@ W2_API int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, c
  *                    w2_prepack), N % 32 == 0, and Y has N/2 columns:
  *                    Y[m,16b+l] = bf16( silu(z[m,32b+l]) * z[m,32b+16+l] ),
  *                    ldy >= N/2.
- * epi == NULL is W2_ACT_NONE without bias.  Everything else as w2_matmul_a8_ex
- * and w2_matmul_a8_fused. */
+ * epi == NULL is W2_ACT_NONE without bias.  Everything else as w2_matmul_a8_ex,
+ * w2_matmul_a8_fused and w2_matmul_a16_ex (declared below). */
 typedef enum { W2_ACT_NONE = 0, W2_ACT_SILU = 1, W2_ACT_SILU_MUL = 2 } w2_act_t;
 typedef struct {
     const uint16_t* bias;
@@ -220,6 +220,12 @@ W2_API int w2_matmul_a16(const void* packed, int64_t K, int64_t N, int G, const 
 W2_API int w2_matmul_a16_ex(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
                      int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                      size_t workspace_bytes, int variant, void* stream);
+
+/* w2_matmul_a16_ex with a fused epilogue (see w2_epilogue_t above). */
+W2_API int w2_matmul_a16_epi(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
+                             int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                             const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes,
+                             int variant, void* stream);
 
 /* Bytes of workspace (host out-pointer) with which the calls take their fastest
  * route for this problem.  a16 = 0 (w2_matmul_a8_fused; w2_matmul_a8 uses the

@@ -44,6 +44,7 @@ _SIGS = {
     "w2_debug_stream_read": [_vp, _sz, _vp, _vp],
     "w2_debug_int8_gemv": [_vp, _i64, _i64, _vp, _vp, _vp],
     "w2_matmul_a8_epi": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _int, _vp],
+    "w2_matmul_a16_epi": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _vp, _sz, _int, _vp],
     "w2_matmul_a8_fused_epi": [_vp, _i64, _i64, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp, _vp, _sz, _vp],
 }
 for _name, _args in _SIGS.items():
@@ -213,6 +214,23 @@ def matmul_a8_fused_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, w
     wp, wb = _ws(workspace)
     _check("w2_matmul_a8_fused_epi", _lib.w2_matmul_a8_fused_epi(_ptr(packed), K, N, G, _ptr(X), dt, ldx, M,
                                                                  _ptr(Y), ldy, ctypes.byref(e), wp, wb, _stream()))
+    return Y
+
+
+def matmul_a16_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, variant=VARIANT_AUTO, workspace=None):
+    """matmul_a16 with the fused epilogue."""
+    _dev(X, torch.bfloat16, "X")
+    M = X.shape[0]
+    if X.dim() != 2 or X.shape[1] != K or X.stride(1) != 1:
+        raise ValueError("X must be [M,K] with unit inner stride")
+    n_out = N // 2 if act == ACT_SILU_MUL else N
+    Y = out if out is not None else torch.empty((M, n_out), dtype=torch.bfloat16, device=X.device)
+    ldx = X.stride(0) if M > 1 else K
+    ldy = Y.stride(0) if M > 1 else n_out
+    e = _epi(bias, act, N)
+    wp, wb = _ws(workspace)
+    _check("w2_matmul_a16_epi", _lib.w2_matmul_a16_epi(_ptr(packed), K, N, G, _ptr(X), ldx, M, _ptr(Y), ldy,
+                                                       ctypes.byref(e), wp, wb, variant, _stream()))
     return Y
 
 

@@ -335,11 +335,15 @@ int w2_debug_group_acc_a8(const void* packed, int64_t K, int64_t N, int G, const
 
 static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, int G,
                       const uint16_t* X, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
-                      void* workspace, size_t workspace_bytes, int variant, void* stream)
+                      void* workspace, size_t workspace_bytes, int variant, void* stream,
+                      const Epilogue& epi = Epilogue())
 {
     int rc = check_shape(fn, K, N, G);
     if (rc) return rc;
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
+    rc = check_epilogue(fn, epi, N);
+    if (rc) return rc;
+    const int64_t n_out = epi.act == ACT_SILU_MUL ? N / 2 : N;
     if (variant != W2_VARIANT_AUTO && variant != W2_VARIANT_SMALLM && variant != W2_VARIANT_TILED &&
         variant != W2_VARIANT_SCALED16 && variant != W2_VARIANT_MIDM)
         return fail(W2_ERR_INVALID_ARG, "%s: variant %d not available for w2a16", fn, variant);
@@ -347,8 +351,8 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     if (!packed || !X || !Y) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
     if (!aligned16(packed) || !aligned16(X) || !aligned16(Y))
         return fail(W2_ERR_MISALIGNED, "%s: packed, X and Y must be 16-byte aligned", fn);
-    if (ldx < K || ldx % 8 || ldy < N || ldy % 8)
-        return fail(W2_ERR_MISALIGNED, "%s: ldx >= K, ldy >= N, both multiples of 8", fn);
+    if (ldx < K || ldx % 8 || ldy < n_out || ldy % 8)
+        return fail(W2_ERR_MISALIGNED, "%s: ldx >= K, ldy >= the number of output columns, both multiples of 8", fn);
     if (M > ((int64_t)1 << 24)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: M is limited to 2^24", fn);
     // the tiled kernel addresses a workgroup's 64 rows with 32-bit byte offsets
     if (ldx > ((int64_t)1 << 24)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: ldx is limited to 2^24", fn);
@@ -362,6 +366,7 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         return fail(W2_ERR_MISALIGNED, "%s: workspace must be 16-byte aligned", fn);
     a.part = (float*)workspace;                              // split-K partial results, if the kernel wants them
     a.part_bytes = workspace ? workspace_bytes : 0;
+    a.epi = epi;
     a.fold = variant == W2_VARIANT_SCALED16;
     if (variant == W2_VARIANT_SCALED16) {
         // the scale-folded construction: the small-M kernel with it, or the kernels built on it
@@ -397,6 +402,14 @@ int w2_matmul_a16_ex(const void* packed, int64_t K, int64_t N, int G, const uint
 {
     return a16_common("w2_matmul_a16", packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes, variant,
                       stream);
+}
+
+int w2_matmul_a16_epi(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X, int64_t ldx, int64_t M,
+                      uint16_t* Y, int64_t ldy, const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes,
+                      int variant, void* stream)
+{
+    return a16_common("w2_matmul_a16_epi", packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes, variant,
+                      stream, to_epilogue(epi));
 }
 
 int w2_matmul_a16(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,

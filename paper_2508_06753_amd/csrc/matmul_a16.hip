@@ -249,14 +249,12 @@ a16_smallm_kernel(A16Args a, SmallCfg cfg)
 #pragma unroll
     for (int r = 0; r < 4; ++r) red[(wave * 16 + 4 * q + r) * 16 + (lane & 15)] = FOLD ? acc[r] : y[r];
     __syncthreads();
-    const int outs = cfg.cbw * rows * 16;
-    for (int i = threadIdx.x; i < outs; i += blockDim.x) {
-        const int nl = i & 15, m = (i >> 4) % rows, ci = i / (16 * rows);
-        float s = 0.0f;
-        for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * 16 + m) * 16 + nl];
-        const int64_t nn = ((int64_t)blockIdx.x * cfg.cbw + ci) * TILE_N + nl;
-        if (nn < a.N) a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s);
-    }
+    store_outputs(a.epi, a.Y, a.ldy, a.N, (int64_t)blockIdx.x * cfg.cbw, cfg.cbw, rows,
+                  [&](int ci, int m, int nl, int) {
+                      float s = 0.0f;
+                      for (int k = 0; k < cfg.ks; ++k) s += red[((k * cfg.cbw + ci) * 16 + m) * 16 + nl];
+                      return s;
+                  });
 }
 
 bool a16_smallm_supports(const A16Args& a) { return a.M >= 1 && a.M <= 16; }
@@ -265,7 +263,7 @@ template <int G, bool FOLD>
 static int launch_a16_smallm_t(const A16Args& a, hipStream_t stream)
 {
     const int rows = (int)a.M;
-    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 2);
+    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 2, 16, a.epi.act == ACT_SILU_MUL);
     const size_t extra = (size_t)(c.kc / G) * 16 * sizeof(float);
     const size_t lds = small_lds_bytes(c, rows, 16, 2, extra);
     const int tpw = tiles_per_wave(a.n_kt, c);
@@ -494,10 +492,22 @@ a16_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m)
         for (int r = 0; r < 4; ++r) {
             const int64_t m = m0 + i * 16 + 4 * q + r;
             if (m >= a.M) continue;
+            // fused epilogue: bias, SiLU, or silu(even block) * (odd block) for the wave's pair of column blocks
+            float z[CJ];
 #pragma unroll
             for (int j = 0; j < CJ; ++j) {
                 const int64_t n = n0 + wn * WN + j * 16 + l16;
-                if (n < a.N) a.Y[m * a.ldy + n] = f32_to_bf16_rne(y[i][j][r]);
+                z[j] = y[i][j][r] + ((a.epi.bias && n < a.N) ? bf16_to_f32(a.epi.bias[n]) : 0.f);
+            }
+            if (a.epi.act == ACT_SILU_MUL) {
+                const int64_t no = (n0 + wn * WN) / 2 + l16;
+                if (no < a.N / 2) a.Y[m * a.ldy + no] = f32_to_bf16_rne(silu_f32(z[0]) * z[1]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) {
+                    const int64_t n = n0 + wn * WN + j * 16 + l16;
+                    if (n < a.N) a.Y[m * a.ldy + n] = f32_to_bf16_rne(a.epi.act == ACT_SILU ? silu_f32(z[j]) : z[j]);
+                }
             }
         }
     }

@@ -335,24 +335,41 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m, int spli
     // stage freed the activation buffers) and leaves as 16-byte stores, four lanes per 64-byte row piece.
     int8_t* ebase = smem + wn * (BM * E_STRIDE);
     uint16_t* eb = reinterpret_cast<uint16_t*>(ebase);
+    // Fused epilogue (Sec. II-D: bias and activation applied while the outputs are in registers).  The
+    // gated form combines the wave's two column blocks, an even (gate) and an odd (up) one, into one.
+    const bool gated = a.epi.act == ACT_SILU_MUL;
+    float bias[CJ];
+#pragma unroll
+    for (int j = 0; j < CJ; ++j) {
+        const int64_t n = n0 + wn * WN + j * 16 + l16;
+        bias[j] = (a.epi.bias && n < a.N) ? bf16_to_f32(a.epi.bias[n]) : 0.f;
+    }
 #pragma unroll
     for (int i = 0; i < RI; ++i)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = i * 16 + 4 * q + r;
-#pragma unroll
-            for (int j = 0; j < CJ; ++j) eb[row * (E_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(acc[i][j][r]);
+            const float z0 = acc[i][0][r] + bias[0], z1 = acc[i][1][r] + bias[1];
+            static_assert(CJ == 2, "the epilogue pairs the wave's two column blocks");
+            if (gated) {
+                eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(silu_f32(z0) * z1);
+            } else {
+                const bool act = a.epi.act == ACT_SILU;
+                eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(act ? silu_f32(z0) : z0);
+                eb[row * (E_STRIDE / 2) + 16 + l16] = f32_to_bf16_rne(act ? silu_f32(z1) : z1);
+            }
         }
     // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
-    constexpr int LPR = WN * 2 / 16;                         // lanes per row piece (16 bytes each)
-    constexpr int RPP = 64 / LPR;                            // rows per pass
-    const int64_t ncol = n0 + wn * WN + (lane % LPR) * 8;    // first of this lane's 8 columns
-#pragma unroll
-    for (int p = 0; p < BM / RPP; ++p) {
-        const int row = p * RPP + lane / LPR;
+    const int wcols = gated ? WN / 2 : WN;                   // output columns of this wave
+    const int lpr = wcols * 2 / 16;                          // lanes per row piece (16 bytes each): 4 or 2
+    const int rpp = 64 / lpr;                                // rows per pass
+    const int64_t ncol = (gated ? (n0 + wn * WN) / 2 : n0 + wn * WN) + (lane % lpr) * 8;   // first of this lane's 8 columns
+    const int64_t n_out = gated ? a.N / 2 : a.N;
+    for (int p = 0; p < BM / rpp; ++p) {
+        const int row = p * rpp + lane / lpr;
         const int64_t m = m0 + row;
-        const uint4 v = *reinterpret_cast<const uint4*>(ebase + row * E_STRIDE + (lane % LPR) * 16);
-        if (m < a.M && ncol < a.N) *reinterpret_cast<uint4*>(a.Y + m * a.ldy + ncol) = v;   // N % 8 == 0: all 8 or none
+        const uint4 v = *reinterpret_cast<const uint4*>(ebase + row * E_STRIDE + (lane % lpr) * 16);
+        if (m < a.M && ncol < n_out) *reinterpret_cast<uint4*>(a.Y + m * a.ldy + ncol) = v;   // N % 8 == 0: all 8 or none
     }
 }
 
@@ -383,7 +400,7 @@ static int launch_fold_bn(const A16Args& a_in, int splits, hipStream_t stream)
                        (int)grid.y);
     int rc = check_launch("w2_matmul_a16[scaled16 tiled]");
     if (rc || !a.part) return rc;
-    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, Epilogue(), stream);
+    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, a.epi, stream);
 }
 
 // 256 columns per workgroup (eight waves, one workgroup per CU) unless that leaves half the chip

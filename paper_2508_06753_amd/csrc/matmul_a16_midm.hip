@@ -238,15 +238,13 @@ a16_midm_kernel(A16Args a_all)
         for (int r = 0; r < 4; ++r)
             red[((wave * RT + rt) * 16 + 4 * q + r) * 16 + l16] = acc[0][rt][r] + acc[1][rt][r];
     __syncthreads();
-    const int outs = CBW * rows * 16;
-    for (int i = threadIdx.x; i < outs; i += THREADS) {
-        const int nl = i & 15, m = (i >> 4) % rows, ci = i / (16 * rows);
-        float s = 0.0f;
+    store_outputs(a.epi, a.Y, a.ldy, a.N, (int64_t)blockIdx.x * CBW, CBW, rows,
+                  [&](int ci, int m, int nl, int) {
+                      float s = 0.0f;
 #pragma unroll
-        for (int k = 0; k < KS; ++k) s += red[((k * CBW + ci) * (RT * 16) + m) * 16 + nl];
-        const int64_t nn = ((int64_t)blockIdx.x * CBW + ci) * TILE_N + nl;
-        if (nn < a.N) a.Y[(int64_t)m * a.ldy + nn] = f32_to_bf16_rne(s);
-    }
+                      for (int k = 0; k < KS; ++k) s += red[((k * CBW + ci) * (RT * 16) + m) * 16 + nl];
+                      return s;
+                  });
 }
 
 template <int G, int RT, int TPC>

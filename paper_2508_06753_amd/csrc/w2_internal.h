@@ -73,6 +73,7 @@ struct A16Args {
     int fold;       // build the weights as sw*q (scale folded in): no zero-point term, no dequant step
     float* part = nullptr;      // split-K workspace, as in A8Args (scale-folded tiled kernel only)
     size_t part_bytes = 0;
+    Epilogue epi;
 };
 
 bool a16_smallm_supports(const A16Args& a);

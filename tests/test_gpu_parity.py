@@ -416,6 +416,31 @@ def test_a8_fused_entry_with_epilogue_and_split_k(w2, M, act, monkeypatch):
     check_epilogue(bf16_bits(Y), y64, mag, bias, act, f"fused entry + epilogue M={M} act={act}")
 
 
+A16_EPI_VARIANTS = [("SMALLM", 2, [1, 5, 16]), ("SCALED16 small", 5, [3]), ("MIDM", 4, [9, 40, 100]),
+                    ("SCALED16 tiled", 5, [130]), ("TILED", 3, [70])]
+
+
+@pytest.mark.parametrize("with_bias,act", [(True, 0), (False, 1), (True, 2), (False, 2)])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(256, 32), (1024, 288)])
+def test_a16_fused_epilogues(w2, K, N, G, with_bias, act, monkeypatch):
+    # the same epilogues on the unquantised-activation path, every kernel family, split-K reduce included
+    monkeypatch.setenv("W2_SPLITK", "2")
+    rng = np.random.default_rng(K + N + G + act)
+    bias = synth.f32_to_bf16_bits(rng.standard_normal(N).astype(np.float32)) if with_bias else None
+    bias_d = dev(bias) if with_bias else None
+    for name, variant, Ms in A16_EPI_VARIANTS:
+        for M in Ms:
+            codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + N)
+            Xb = synth.f32_to_bf16_bits(X)
+            packed = w2.prepack(dev(codes), dev(scales), G, 0)
+            ws = torch.empty(4 * M * N * 4, dtype=torch.uint8, device="cuda")
+            Y = w2.matmul_a16_epi(packed, K, N, G, dev(Xb).view(torch.bfloat16), bias=bias_d, act=act, variant=variant,
+                                  workspace=ws)
+            _, y64, mag = oracle.matmul_a16(codes, scales, G, 0, Xb)
+            check_epilogue(bf16_bits(Y), y64, mag, bias, act, f"a16 epilogue {name} M={M} K={K} N={N} G={G} act={act}")
+
+
 def test_epilogue_argument_errors(w2):
     K, N, G = 256, 48, 128                                   # N % 32 != 0
     codes, scales, X = synth.make_problem(1, K, N, G, 0, 0)
