@@ -168,7 +168,9 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m, int spli
     const int64_t kt_b = a.n_kt * blockIdx.y / splits, kt_e = a.n_kt * (blockIdx.y + 1) / splits;
     const int64_t st_b = kt_b * 4, n_st = kt_e * 4;          // stages of 64 k: [st_b, n_st)
     // two register sets: a load has two stages to land before its data goes to LDS
-    uint4 ar0[NP], ar1[NP];
+    // (four-wave workgroups copy twice as much per thread and keep one set: the registers do not allow two)
+    constexpr bool TWO_SETS = NP <= 2;
+    uint4 ar0[NP], ar1[TWO_SETS ? NP : 1];
     auto load_a = [&](int64_t st, uint4 (&ar)[NP]) {
         st = min(st, n_st - 1);
         const char* p = cp_base + st * (BK * 2);             // uniform
@@ -221,7 +223,7 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m, int spli
         store_a(p, ar0);
     }
     load_a(st_b + WR, ar0);
-    load_a(st_b + WR + 1, ar1);
+    if constexpr (TWO_SETS) load_a(st_b + WR + 1, ar1);
     __syncthreads();
 
     const int8_t* a_base = smem + l16 * A_STRIDE + q * 16;
@@ -264,9 +266,11 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m, int spli
         const WTile<G>& wn_tile = t == 3 ? wnx : wc;         // where stage it+1 finds its weights
         const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;
         const int bufw = buf + WR >= NBUF ? buf + WR - NBUF : buf + WR;
-        store_a(bufw, (t & 1) ? ar1 : ar0);                  // activations of stage it+WR
+        if constexpr (TWO_SETS) store_a(bufw, (t & 1) ? ar1 : ar0);      // activations of stage it+WR
+        else store_a(bufw, ar0);
         if constexpr (t == 0) load_w((it >> 2) + 1, wnx);
-        load_a(it + WR + 2, (t & 1) ? ar1 : ar0);
+        if constexpr (TWO_SETS) load_a(it + WR + 2, (t & 1) ? ar1 : ar0);
+        else load_a(it + WR + 1, ar0);
         __builtin_amdgcn_sched_barrier(0);                   // all loads are issued up here, unconditionally
         const int8_t* ab = a_base + buf * A_BUF;
         const int8_t* abn = a_base + buf1 * A_BUF;
