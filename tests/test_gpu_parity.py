@@ -681,3 +681,42 @@ def test_graph_replays_match_eager(w2):
                 assert torch.equal(got.view(torch.int16), want.view(torch.int16)), f"replay {rep}: {name} differs from eager"
     finally:
         os.environ.pop("W2_SPLITK", None)
+
+
+# ------------------------------------------------------------------ row strides
+@pytest.mark.parametrize("M", [1, 5, 40, 100, 130, 300])
+def test_row_strides_of_inputs_and_outputs(w2, M):
+    """Y with a row stride above N (both paths, every kernel family AUTO reaches, split-K and the gated epilogue
+    included) and bf16 X with a row stride above K: the padding columns of Y must stay untouched."""
+    K, N, G = 1024, 272, 128
+    codes, scales, X = synth.make_problem(M, K, N, G, 0, 100 + M)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    oq, osx, _ = oracle.quantize_rows(X, G)
+    Yo, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+    ws = torch.empty(w2.workspace_size(M, K, N, G) + 3 * M * N * 4, dtype=torch.uint8, device="cuda")
+    ldy = N + 40
+    big = torch.full((M, ldy), 7.0, dtype=torch.bfloat16, device="cuda")
+    w2.matmul_a8(packed, K, N, G, xq, sx, out=big[:, :N], workspace=ws)
+    check_y(bf16_bits(big[:, :N].contiguous()), Yo, y64, mag, f"a8 strided Y M={M}")
+    assert torch.all(big[:, N:] == 7.0), "a8: columns past N were written"
+    # w2a16: strided X and strided Y
+    Xb = synth.f32_to_bf16_bits(X)
+    xw = torch.zeros((M, K + 64), dtype=torch.bfloat16, device="cuda")
+    xw[:, :K] = dev(Xb).view(torch.bfloat16)
+    big.fill_(7.0)
+    w2.matmul_a16(packed, K, N, G, xw[:, :K], out=big[:, :N], workspace=ws)
+    Yo16, y64_16, mag16 = oracle.matmul_a16(codes, scales, G, 0, Xb)
+    check_y(bf16_bits(big[:, :N].contiguous()), Yo16, y64_16, mag16, f"a16 strided X and Y M={M}")
+    assert torch.all(big[:, N:] == 7.0), "a16: columns past N were written"
+    # gated epilogue into a strided output of N/2 columns (N = 288 here: a multiple of 32)
+    N2 = 288
+    codes2, scales2, _ = synth.make_problem(1, K, N2, G, 0, 200 + M)
+    packed2 = w2.prepack(dev(codes2), dev(scales2), G, 0)
+    _, y64g = oracle.matmul_a8(codes2, scales2, G, 0, oq, osx)
+    magg = oracle.a8_term_magnitude(codes2, scales2, G, 0, oq, osx)
+    out = torch.full((M, N2 // 2 + 24), 7.0, dtype=torch.bfloat16, device="cuda")
+    w2.matmul_a8_epi(packed2, K, N2, G, xq, sx, act=w2.ACT_SILU_MUL, out=out[:, :N2 // 2], workspace=ws)
+    check_epilogue(bf16_bits(out[:, :N2 // 2].contiguous()), y64g, magg, None, 2, f"gated, strided Y M={M}")
+    assert torch.all(out[:, N2 // 2:] == 7.0), "gated epilogue: columns past N/2 were written"
