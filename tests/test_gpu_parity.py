@@ -720,3 +720,11 @@ def test_row_strides_of_inputs_and_outputs(w2, M):
     w2.matmul_a8_epi(packed2, K, N2, G, xq, sx, act=w2.ACT_SILU_MUL, out=out[:, :N2 // 2], workspace=ws)
     check_epilogue(bf16_bits(out[:, :N2 // 2].contiguous()), y64g, magg, None, 2, f"gated, strided Y M={M}")
     assert torch.all(out[:, N2 // 2:] == 7.0), "gated epilogue: columns past N/2 were written"
+
+
+@pytest.mark.parametrize("M,K,N", [(1000, 512, 136), (2049, 256, 8), (515, 768, 520)])
+def test_large_ragged_m_both_paths(w2, M, K, N):
+    # many row tiles with a ragged last one, narrow and ragged N, both tiled kernels (AUTO), G = 64
+    G = 64
+    run_a8_case(w2, M, K, N, G, 1, w2.VARIANT_AUTO, seed=M + N)
+    run_a16_case(w2, M, K, N, G, 1, w2.VARIANT_AUTO, seed=M + N)
