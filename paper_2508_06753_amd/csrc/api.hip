@@ -207,7 +207,10 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         // one band's workgroups leave CUs idle and the tiled kernel has too few tiles (10 against 19 us
         // on 4096 x 4096)
         const int midm_min = env_int("W2_MIDM_MIN_M", (a.n_cb >= 384 || a.n_kt > 64) ? 4 : 9);
-        const int midm_max = env_int("W2_MIDM_MAX_M", a.n_cb <= 512 ? 128 : 64);
+        // ... and only up to M = 48 on very wide projections (32768 columns and more), where every
+        // workgroup's re-read of the activation rows outweighs the weights (8192 x 57344 at M = 64:
+        // 66 us against 50 us through the tiled kernel)
+        const int midm_max = env_int("W2_MIDM_MAX_M", a.n_cb <= 512 ? 128 : a.n_cb >= 2048 ? 48 : 64);
         variant = M <= dot4_max && a8_dot4_supports(a)                       ? W2_VARIANT_DOT4
                 : M >= midm_min && M <= midm_max && a8_midm_supports(a)     ? W2_VARIANT_MIDM
                 : a8_smallm_supports(a)                                      ? W2_VARIANT_SMALLM
