@@ -67,7 +67,8 @@ typedef enum {
 /* Kernel families, for w2_matmul_a8_ex / w2_matmul_a16_ex and the debug export.
  * AUTO picks by M (w2a8: SMALLM for M <= 8 (M <= 3 when N >= 6144 or K > 16384), MIDM up to
  * M = 64 (M = 128 when N <= 8192, M = 48 when N >= 32768), else TILED;
- * w2a16: SMALLM for M <= 8, MIDM up to M = 64 (M = 128 when N <= 4096), else the SCALED16 tiled kernel).
+ * w2a16: SMALLM for M <= 8, MIDM up to M = 64 (M = 128 when N <= 4096, M = 40 when N >= 32768), else the
+ * SCALED16 tiled kernel).
  * DOT4: per-lane v_dot4_i32_i8
  * with split-K across the waves of a workgroup (M <= 4; kept as the dot-product form of the microkernel,
  * selectable here).  SMALLM: one 16-row int8 (bf16 for a16) MFMA tile per

@@ -383,7 +383,9 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         // above, 128-row tiles.  Both of the latter fold the scale into the weights: fewest vector
         // instructions per matrix instruction.
         const int midm_min = env_int("W2_A16_MIDM_MIN_M", 9);
-        const int midm_max = env_int("W2_A16_MIDM_MAX_M", a.n_cb <= 256 ? 128 : 64);   // two bands on small projections
+        // two bands on small projections; on very wide ones (32768 columns and more) the tiled kernel
+        // takes over at M = 41 (8192 x 57344 at M = 48: 94 against 104 us)
+        const int midm_max = env_int("W2_A16_MIDM_MAX_M", a.n_cb <= 256 ? 128 : a.n_cb >= 2048 ? 40 : 64);
         if (M >= midm_min && M <= midm_max && a16_midm_supports(a)) return launch_a16_midm(a, (hipStream_t)stream);
         if (!a16_smallm_supports(a)) return launch_a16_fold_tiled(a, (hipStream_t)stream);
         variant = W2_VARIANT_SMALLM;
