@@ -62,7 +62,7 @@ def pmc_mode(torch, w2, lib, vp, pool, shapes, Xd, Yd, dev):
     for _ in range(3):
         dst.copy_(src)                                   # calibration: reads 256 MiB, writes 256 MiB
     for l in pool:
-        lib.w2_debug_stream_read(vp(l["gate_up"]), l["gate_up"].numel(), vp(sink), s)
+        lib.w2_debug_stream_read(vp(l["gate_up"]), l["gate_up"].numel(), vp(sink), None, s)
     for l in pool:
         rc = lib.w2_matmul_a8_fused(vp(l["gate_up"]), Kd, Nd, G, vp(Xd["gate_up"]), w2.DT_F32, Kd, M,
                                     vp(Yd["gate_up"]), Nd, None, 0, s)
@@ -388,7 +388,7 @@ def main():
     def all_read():
         s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
         for l in pool:
-            lib.w2_debug_stream_read(vp(l["gate_up"]), l["gate_up"].numel(), vp(sink), s)
+            lib.w2_debug_stream_read(vp(l["gate_up"]), l["gate_up"].numel(), vp(sink), None, s)
 
     gr = capture(all_read) if use_graph else None
     for _ in range(3):

@@ -18,7 +18,8 @@
  *     the default stream) of the CURRENT device;
  *   - every buffer is owned by the caller; the library keeps no device state,
  *     allocates nothing and holds no handles, so calls from several host
- *     threads are independent;
+ *     threads are independent; which kernel runs depends on the arguments
+ *     alone (the process environment is never read);
  *   - "dev" pointers are device memory of the current device, "host" pointers
  *     are ordinary host memory;
  *   - arguments are validated before anything is launched: a call that returns
@@ -87,6 +88,29 @@ typedef enum {
 typedef enum { W2_VARIANT_AUTO = 0, W2_VARIANT_DOT4 = 1, W2_VARIANT_SMALLM = 2,
                W2_VARIANT_TILED = 3, W2_VARIANT_MIDM = 4, W2_VARIANT_SCALED16 = 5 } w2_variant_t;
 
+/* Overrides of the library's own choices, for tests and tuning sweeps; taken by
+ * the *_ex / *_epi entry points, the debug export and the probe.  A NULL pointer,
+ * or a field left 0, means the library's rule, which depends on the shape only.
+ * A value a field does not allow gives W2_ERR_INVALID_ARG (nothing launched).
+ * Fields that do not concern the kernel family that runs are ignored. */
+typedef struct {
+    int variant;          /* w2_variant_t: the kernel family */
+    int dot4_max_m;       /* w2a8 AUTO: largest M given to DOT4 (1..4; default: never) */
+    int midm_min_m;       /* AUTO: smallest / largest M given to MIDM (1..256) */
+    int midm_max_m;
+    int small_waves;      /* DOT4, SMALLM, fused kernel: waves per workgroup, 1..16 */
+    int small_cbw;        /* ... column blocks per workgroup: 1, 2, 4, 8 or 16, at most the waves */
+    int small_kc;         /* ... k per local-memory chunk of the activations: a multiple of 256 */
+    int fused_pre;        /* fused kernel, one row, large projections: weight tiles a wave requests before the row is quantised: 4 or 8 */
+    int midm_cbw;         /* MIDM: column blocks per workgroup: 2, 4 or 8 */
+    int tiled_bn;         /* TILED / SCALED16 tiled kernels: columns per workgroup: 128 or 256 */
+    int tiled_group_m;    /* ... row tiles per band of the workgroup order: 1..1024 */
+    int splitk;           /* tiled kernels: 1 = never split K, n = 2..16: n parts if the workspace holds them */
+    int splitk_min_tiles; /* ... planner: fewest 256-k tiles per part, 1..1024 */
+    int stream_unroll;    /* w2_debug_stream_read: 1 KiB chunks in flight per wave: 4, 8 or 16 */
+    int stream_blocks;    /* ... most workgroups launched: 1..65536 */
+} w2_tuning_t;
+
 /* ------------------------------------------------------------------------
  * Offline weight pre-formatting (Sec. II-B and II-D: the 2-bit weights are
  * packed into the instruction's layout once, before inference, at no run-time
@@ -149,11 +173,11 @@ W2_API int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const i
                  const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                  size_t workspace_bytes, void* stream);
 
-/* Same, with the kernel family forced (tests, tuning).  Returns
- * W2_ERR_UNSUPPORTED_SHAPE if the family does not cover M. */
+/* Same, with overrides (tests, tuning; tune == NULL: exactly w2_matmul_a8).  Returns
+ * W2_ERR_UNSUPPORTED_SHAPE if a forced kernel family does not cover M. */
 W2_API int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
                     const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
-                    size_t workspace_bytes, int variant, void* stream);
+                    size_t workspace_bytes, const w2_tuning_t* tune, void* stream);
 
 /* The int2 x {fp32, bf16} -> bf16 call (Sec. II-D: activation quantisation
  * fused into the GEMM; Sec. III-C: fusing wins for matrix-vector shapes, a
@@ -201,11 +225,11 @@ typedef struct {
 W2_API int w2_matmul_a8_epi(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
                             const float* sx, int64_t M, uint16_t* Y, int64_t ldy,
                             const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes,
-                            int variant, void* stream);
+                            const w2_tuning_t* tune, void* stream);
 W2_API int w2_matmul_a8_fused_epi(const void* packed, int64_t K, int64_t N, int G, const void* X,
                                   w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
                                   const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes,
-                                  void* stream);
+                                  const w2_tuning_t* tune, void* stream);
 
 /* ------------------------------------------------------------------------
  * w2a16 (Sec. II-D, "Alternative implementation": weights rebuilt as 16-bit
@@ -220,13 +244,13 @@ W2_API int w2_matmul_a16(const void* packed, int64_t K, int64_t N, int G, const 
 
 W2_API int w2_matmul_a16_ex(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
                      int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
-                     size_t workspace_bytes, int variant, void* stream);
+                     size_t workspace_bytes, const w2_tuning_t* tune, void* stream);
 
 /* w2_matmul_a16_ex with a fused epilogue (see w2_epilogue_t above). */
 W2_API int w2_matmul_a16_epi(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
                              int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
                              const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes,
-                             int variant, void* stream);
+                             const w2_tuning_t* tune, void* stream);
 
 /* Bytes of workspace (host out-pointer) with which the calls take their fastest
  * route for this problem.  a16 = 0 (w2_matmul_a8_fused; w2_matmul_a8 uses the
@@ -244,7 +268,7 @@ W2_API int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, si
  * w2_debug_unpack: inverse of w2_prepack: canonical codes [K][N] and scales
  *   [K/G][N] recovered from the blob (codec selects the code -> value map). */
 W2_API int w2_debug_group_acc_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
-                          int64_t M, int variant, int32_t* acc, void* stream);
+                          int64_t M, const w2_tuning_t* tune, int32_t* acc, void* stream);
 W2_API int w2_debug_unpack(const void* packed, int64_t K, int64_t N, int G, w2_codec_t codec,
                     uint8_t* codes_KN, uint16_t* scales, void* stream);
 
@@ -252,7 +276,8 @@ W2_API int w2_debug_unpack(const void* packed, int64_t K, int64_t N, int G, w2_c
  * into sink[0] (dev, uint32).  Used by the benchmark as the attainable
  * read-bandwidth ceiling the weight stream is compared with (the role the
  * int8-weight GEMV plays in Sec. III-B/III-C). */
-W2_API int w2_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+W2_API int w2_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, const w2_tuning_t* tune,
+                                void* stream);
 
 /* Comparator for the benchmark, not part of the method: an int8-weight GEMV
  * (Sec. III-B, III-C read the 2-bit GEMV against the int8 one, which moves

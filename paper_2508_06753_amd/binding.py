@@ -34,18 +34,18 @@ _SIGS = {
     "w2_prepack": [_vp, _vp, _i64, _i64, _int, _int, _vp, _sz, _vp, _vp],
     "w2_quantize_rows": [_vp, _int, _i64, _i64, _i64, _int, _vp, _vp, _vp, _vp],
     "w2_matmul_a8": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _sz, _vp],
-    "w2_matmul_a8_ex": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _sz, _int, _vp],
+    "w2_matmul_a8_ex": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _sz, _vp, _vp],
     "w2_matmul_a8_fused": [_vp, _i64, _i64, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp, _sz, _vp],
     "w2_matmul_a16": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _sz, _vp],
-    "w2_matmul_a16_ex": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _sz, _int, _vp],
+    "w2_matmul_a16_ex": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _sz, _vp, _vp],
     "w2_workspace_size": [_i64, _i64, _i64, _int, _int, ctypes.POINTER(_sz)],
-    "w2_debug_group_acc_a8": [_vp, _i64, _i64, _int, _vp, _i64, _int, _vp, _vp],
+    "w2_debug_group_acc_a8": [_vp, _i64, _i64, _int, _vp, _i64, _vp, _vp, _vp],
     "w2_debug_unpack": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp],
-    "w2_debug_stream_read": [_vp, _sz, _vp, _vp],
+    "w2_debug_stream_read": [_vp, _sz, _vp, _vp, _vp],
     "w2_debug_int8_gemv": [_vp, _i64, _i64, _vp, _vp, _vp],
-    "w2_matmul_a8_epi": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _int, _vp],
-    "w2_matmul_a16_epi": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _vp, _sz, _int, _vp],
-    "w2_matmul_a8_fused_epi": [_vp, _i64, _i64, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp, _vp, _sz, _vp],
+    "w2_matmul_a8_epi": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp, _vp],
+    "w2_matmul_a16_epi": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _vp, _sz, _vp, _vp],
+    "w2_matmul_a8_fused_epi": [_vp, _i64, _i64, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp, _vp, _sz, _vp, _vp],
 }
 for _name, _args in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -141,6 +141,34 @@ def quantize_rows(X, G=128, want_gsum=False):
     return xq, sx, gsum
 
 
+class Tuning(ctypes.Structure):
+    """w2_tuning_t: overrides for tests and sweeps; every field 0 = the library's own rule."""
+    _fields_ = [(n, ctypes.c_int) for n in (
+        "variant", "dot4_max_m", "midm_min_m", "midm_max_m", "small_waves", "small_cbw", "small_kc", "fused_pre",
+        "midm_cbw", "tiled_bn", "tiled_group_m", "splitk", "splitk_min_tiles", "stream_unroll", "stream_blocks")]
+
+
+def _tune(variant=VARIANT_AUTO, tune=None):
+    """NULL when nothing is overridden, else a Tuning (kept alive by the caller's frame)."""
+    if tune is None and variant == VARIANT_AUTO:
+        return None
+    t = Tuning()
+    if isinstance(tune, Tuning):
+        ctypes.memmove(ctypes.byref(t), ctypes.byref(tune), ctypes.sizeof(t))
+    elif tune:
+        for k, v in tune.items():
+            if not hasattr(t, k):
+                raise ValueError(f"w2_tuning_t has no field {k}")
+            setattr(t, k, int(v))
+    if variant != VARIANT_AUTO:
+        t.variant = int(variant)
+    return t
+
+
+def _tp(t):
+    return None if t is None else ctypes.byref(t)
+
+
 def _ws(workspace):
     if workspace is None:
         return None, 0
@@ -148,7 +176,7 @@ def _ws(workspace):
     return _ptr(workspace), workspace.numel()
 
 
-def matmul_a8(packed, K, N, G, xq, sx, out=None, variant=VARIANT_AUTO, workspace=None):
+def matmul_a8(packed, K, N, G, xq, sx, out=None, variant=VARIANT_AUTO, workspace=None, tune=None):
     """Y bf16 [M,N] = dequant-fused int8 matmul.  xq int8 [M,K], sx fp32 [M].  `workspace`: optional uint8
     device tensor; with workspace_size(M, K, N, G) bytes the tiled kernel may split K across workgroups."""
     _dev(xq, torch.int8, "xq")
@@ -159,8 +187,9 @@ def matmul_a8(packed, K, N, G, xq, sx, out=None, variant=VARIANT_AUTO, workspace
     Y = out if out is not None else torch.empty((M, N), dtype=torch.bfloat16, device=xq.device)
     ldy = Y.stride(0) if M > 1 else N
     wp, wb = _ws(workspace)
+    t = _tune(variant, tune)
     _check("w2_matmul_a8", _lib.w2_matmul_a8_ex(_ptr(packed), K, N, G, _ptr(xq), _ptr(sx), M,
-                                                _ptr(Y), ldy, wp, wb, variant, _stream()))
+                                                _ptr(Y), ldy, wp, wb, _tp(t), _stream()))
     return Y
 
 
@@ -178,7 +207,8 @@ def _epi(bias, act, N):
     return _Epilogue(bias.data_ptr() if bias is not None else None, int(act))
 
 
-def matmul_a8_epi(packed, K, N, G, xq, sx, bias=None, act=ACT_NONE, out=None, variant=VARIANT_AUTO, workspace=None):
+def matmul_a8_epi(packed, K, N, G, xq, sx, bias=None, act=ACT_NONE, out=None, variant=VARIANT_AUTO, workspace=None,
+                  tune=None):
     """matmul_a8 with the fused epilogue: bias (bf16 [N]) and activation; ACT_SILU_MUL gives N/2 columns."""
     _dev(xq, torch.int8, "xq")
     _dev(sx, torch.float32, "sx")
@@ -190,12 +220,13 @@ def matmul_a8_epi(packed, K, N, G, xq, sx, bias=None, act=ACT_NONE, out=None, va
     ldy = Y.stride(0) if M > 1 else n_out
     e = _epi(bias, act, N)
     wp, wb = _ws(workspace)
+    t = _tune(variant, tune)
     _check("w2_matmul_a8_epi", _lib.w2_matmul_a8_epi(_ptr(packed), K, N, G, _ptr(xq), _ptr(sx), M, _ptr(Y), ldy,
-                                                     ctypes.byref(e), wp, wb, variant, _stream()))
+                                                     ctypes.byref(e), wp, wb, _tp(t), _stream()))
     return Y
 
 
-def matmul_a8_fused_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, workspace=None):
+def matmul_a8_fused_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, workspace=None, tune=None):
     """matmul_a8_fused with the fused epilogue."""
     if X.dtype == torch.float32:
         dt = DT_F32
@@ -212,12 +243,15 @@ def matmul_a8_fused_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, w
     ldy = Y.stride(0) if M > 1 else n_out
     e = _epi(bias, act, N)
     wp, wb = _ws(workspace)
+    t = _tune(VARIANT_AUTO, tune)
     _check("w2_matmul_a8_fused_epi", _lib.w2_matmul_a8_fused_epi(_ptr(packed), K, N, G, _ptr(X), dt, ldx, M,
-                                                                 _ptr(Y), ldy, ctypes.byref(e), wp, wb, _stream()))
+                                                                 _ptr(Y), ldy, ctypes.byref(e), wp, wb, _tp(t),
+                                                                 _stream()))
     return Y
 
 
-def matmul_a16_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, variant=VARIANT_AUTO, workspace=None):
+def matmul_a16_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, variant=VARIANT_AUTO, workspace=None,
+                   tune=None):
     """matmul_a16 with the fused epilogue."""
     _dev(X, torch.bfloat16, "X")
     M = X.shape[0]
@@ -229,8 +263,9 @@ def matmul_a16_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, varian
     ldy = Y.stride(0) if M > 1 else n_out
     e = _epi(bias, act, N)
     wp, wb = _ws(workspace)
+    t = _tune(variant, tune)
     _check("w2_matmul_a16_epi", _lib.w2_matmul_a16_epi(_ptr(packed), K, N, G, _ptr(X), ldx, M, _ptr(Y), ldy,
-                                                       ctypes.byref(e), wp, wb, variant, _stream()))
+                                                       ctypes.byref(e), wp, wb, _tp(t), _stream()))
     return Y
 
 
@@ -255,7 +290,7 @@ def matmul_a8_fused(packed, K, N, G, X, out=None, workspace=None):
     return Y
 
 
-def matmul_a16(packed, K, N, G, X, out=None, variant=VARIANT_AUTO, workspace=None):
+def matmul_a16(packed, K, N, G, X, out=None, variant=VARIANT_AUTO, workspace=None, tune=None):
     """Y bf16 [M,N] from bf16 activations X [M,K] (unquantised).  `workspace`: as for matmul_a8
     (workspace_size(..., a16=True) bytes)."""
     _dev(X, torch.bfloat16, "X")
@@ -266,17 +301,19 @@ def matmul_a16(packed, K, N, G, X, out=None, variant=VARIANT_AUTO, workspace=Non
     ldx = X.stride(0) if M > 1 else K
     ldy = Y.stride(0) if M > 1 else N
     wp, wb = _ws(workspace)
+    t = _tune(variant, tune)
     _check("w2_matmul_a16", _lib.w2_matmul_a16_ex(_ptr(packed), K, N, G, _ptr(X), ldx, M, _ptr(Y),
-                                                  ldy, wp, wb, variant, _stream()))
+                                                  ldy, wp, wb, _tp(t), _stream()))
     return Y
 
 
-def debug_group_acc_a8(packed, K, N, G, xq, variant=VARIANT_AUTO):
+def debug_group_acc_a8(packed, K, N, G, xq, variant=VARIANT_AUTO, tune=None):
     _dev(xq, torch.int8, "xq")
     M = xq.shape[0]
     acc = torch.empty((M, K // G, N), dtype=torch.int32, device=xq.device)
+    t = _tune(variant, tune)
     _check("w2_debug_group_acc_a8", _lib.w2_debug_group_acc_a8(_ptr(packed), K, N, G, _ptr(xq), M,
-                                                               variant, _ptr(acc), _stream()))
+                                                               _tp(t), _ptr(acc), _stream()))
     return acc
 
 
@@ -301,9 +338,10 @@ def debug_int8_gemv(W8, xq, out=None):
     return out
 
 
-def debug_stream_read(buf, sink=None):
+def debug_stream_read(buf, sink=None, tune=None):
     if sink is None:
         sink = torch.zeros(1, dtype=torch.int32, device=buf.device)
+    t = _tune(VARIANT_AUTO, tune)
     _check("w2_debug_stream_read", _lib.w2_debug_stream_read(_ptr(buf), buf.numel() * buf.element_size(),
-                                                             _ptr(sink), _stream()))
+                                                             _ptr(sink), _tp(t), _stream()))
     return sink

@@ -6,6 +6,9 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "../../include/w2mm.h"
 #include "w2_internal.h"
 
@@ -31,11 +34,30 @@ int check_launch(const char* what)
     return W2_OK;
 }
 
-int env_int(const char* name, int dflt)
+namespace {
+struct LdsGrant { const void* kern; int dev; size_t bytes; };
+std::mutex g_lds_mutex;
+std::vector<LdsGrant> g_lds_grants;
+}  // namespace
+
+int ensure_dynamic_lds(const void* kern, size_t bytes, const char* what)
 {
-    const char* v = getenv(name);
-    if (!v || !*v) return dflt;
-    return atoi(v);
+    if (bytes <= 64 * 1024) return W2_OK;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) dev = 0;
+    std::lock_guard<std::mutex> lock(g_lds_mutex);
+    LdsGrant* g = nullptr;
+    for (auto& e : g_lds_grants)
+        if (e.kern == kern && e.dev == dev) { g = &e; break; }
+    if (g && g->bytes >= bytes) return W2_OK;
+    const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) {
+        set_error("%s: hipFuncSetAttribute(%zu bytes of LDS): %s", what, bytes, hipGetErrorString(e));
+        return W2_ERR_HIP;
+    }
+    if (g) g->bytes = bytes;
+    else g_lds_grants.push_back({kern, dev, bytes});
+    return W2_OK;
 }
 
 // Streaming-read probe.  Each wave reads U consecutive 1 KiB chunks (one
@@ -66,12 +88,12 @@ stream_read_kernel(const uint4* __restrict__ src, size_t n_chunks, uint32_t* __r
     if (lane == 0 && x == 0x9e3779b9u) atomicXor(sink, x);   // keeps the loads alive; rarely taken
 }
 
-int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream)
+int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, const w2_tuning_t& tune, hipStream_t stream)
 {
     const size_t n_chunks = bytes / 1024;
     if (n_chunks == 0) return W2_OK;
-    const int unroll = env_int("W2_STREAM_UNROLL", 8);
-    const size_t cap = (size_t)env_int("W2_STREAM_BLOCKS", 2048);
+    const int unroll = tune.stream_unroll ? tune.stream_unroll : 8;          // validated: 4, 8 or 16
+    const size_t cap = tune.stream_blocks ? (size_t)tune.stream_blocks : 2048;
     size_t blocks = (n_chunks + 4 * (size_t)unroll - 1) / (4 * (size_t)unroll);   // 4 waves per block
     if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned)blocks), block(256);
@@ -111,6 +133,36 @@ static int check_shape(const char* fn, int64_t K, int64_t N, int G)
     if (N % 8) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: N must be a multiple of 8", fn);
     if (K > (int64_t)1 << 24 || N > (int64_t)1 << 24)
         return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: K and N are limited to 2^24", fn);
+    return W2_OK;
+}
+
+// Copies *t (NULL: all defaults) after checking every field against the values the header allows.
+static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
+{
+    memset(out, 0, sizeof *out);
+    if (!t) return W2_OK;
+    auto in = [](int v, int lo, int hi) { return v == 0 || (v >= lo && v <= hi); };
+    auto one_of = [](int v, int a, int b, int c = 0, int d = 0, int e = 0) {
+        return v == 0 || v == a || v == b || (c && v == c) || (d && v == d) || (e && v == e);
+    };
+    const char* bad = nullptr;
+    if (t->variant < W2_VARIANT_AUTO || t->variant > W2_VARIANT_SCALED16) bad = "variant";
+    else if (!in(t->dot4_max_m, 1, 4)) bad = "dot4_max_m";
+    else if (!in(t->midm_min_m, 1, 256)) bad = "midm_min_m";
+    else if (!in(t->midm_max_m, 1, 256)) bad = "midm_max_m";
+    else if (!in(t->small_waves, 1, 16)) bad = "small_waves";
+    else if (!one_of(t->small_cbw, 1, 2, 4, 8, 16)) bad = "small_cbw";
+    else if (t->small_kc < 0 || t->small_kc % TILE_K) bad = "small_kc";
+    else if (!one_of(t->fused_pre, 4, 8)) bad = "fused_pre";
+    else if (!one_of(t->midm_cbw, 2, 4, 8)) bad = "midm_cbw";
+    else if (!one_of(t->tiled_bn, 128, 256)) bad = "tiled_bn";
+    else if (!in(t->tiled_group_m, 1, 1024)) bad = "tiled_group_m";
+    else if (!in(t->splitk, 1, 16)) bad = "splitk";
+    else if (!in(t->splitk_min_tiles, 1, 1024)) bad = "splitk_min_tiles";
+    else if (!one_of(t->stream_unroll, 4, 8, 16)) bad = "stream_unroll";
+    else if (!in(t->stream_blocks, 1, 65536)) bad = "stream_blocks";
+    if (bad) return fail(W2_ERR_INVALID_ARG, "%s: w2_tuning_t.%s is out of range", fn, bad);
+    *out = *t;
     return W2_OK;
 }
 
@@ -165,7 +217,7 @@ int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_t K, in
 
 static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, int G,
                      const int8_t* xq, const float* sx, int64_t M, uint16_t* Y, int64_t ldy,
-                     int32_t* acc_out, void* workspace, size_t workspace_bytes, int variant, void* stream,
+                     int32_t* acc_out, void* workspace, size_t workspace_bytes, const w2_tuning_t* tune, void* stream,
                      const Epilogue& epi = Epilogue())
 {
     int rc = check_shape(fn, K, N, G);
@@ -173,9 +225,13 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
     rc = check_epilogue(fn, epi, N);
     if (rc) return rc;
+    w2_tuning_t tn;
+    rc = check_tuning(fn, tune, &tn);
+    if (rc) return rc;
+    int variant = tn.variant;
     const int64_t n_out = epi.act == ACT_SILU_MUL ? N / 2 : N;
-    if (variant < W2_VARIANT_AUTO || variant > W2_VARIANT_MIDM)
-        return fail(W2_ERR_INVALID_ARG, "%s: unknown variant %d", fn, variant);
+    if (variant > W2_VARIANT_MIDM)
+        return fail(W2_ERR_INVALID_ARG, "%s: variant %d not available for w2a8", fn, variant);
     if (M == 0) return W2_OK;
     if (!packed || !xq) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
     if (!acc_out && (!sx || !Y)) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
@@ -196,21 +252,22 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     a.part = (float*)workspace;                              // split-K partial results, if the tiled kernel wants them
     a.part_bytes = workspace ? workspace_bytes : 0;
     a.epi = epi;
+    a.tune = tn;
     if (variant == W2_VARIANT_AUTO) {
         // measured: the MFMA form is at least as fast as dot4 from M = 1 on; the mid-M kernel (one
         // fma per accumulator in the dequant, rolling weight window; its time hardly grows with M)
         // overtakes the small-M one at M = 4 on wide or very deep projections and at M = 9 on narrow ones (few
         // column blocks: it then splits K four ways with a barrier pair per tile), and is faster
         // than the tiled one up to M = 64
-        const int dot4_max = env_int("W2_DOT4_MAX_M", 0);
+        const int dot4_max = tn.dot4_max_m;
         // ... and, as two bands of 64 rows, up to M = 128 on projections of at most 8192 columns, where
         // one band's workgroups leave CUs idle and the tiled kernel has too few tiles (10 against 19 us
         // on 4096 x 4096)
-        const int midm_min = env_int("W2_MIDM_MIN_M", (a.n_cb >= 384 || a.n_kt > 64) ? 4 : 9);
+        const int midm_min = tn.midm_min_m ? tn.midm_min_m : (a.n_cb >= 384 || a.n_kt > 64) ? 4 : 9;
         // ... and only up to M = 48 on very wide projections (32768 columns and more), where every
         // workgroup's re-read of the activation rows outweighs the weights (8192 x 57344 at M = 64:
         // 66 us against 50 us through the tiled kernel)
-        const int midm_max = env_int("W2_MIDM_MAX_M", a.n_cb <= 512 ? 128 : a.n_cb >= 2048 ? 48 : 64);
+        const int midm_max = tn.midm_max_m ? tn.midm_max_m : a.n_cb <= 512 ? 128 : a.n_cb >= 2048 ? 48 : 64;
         variant = M <= dot4_max && a8_dot4_supports(a)                       ? W2_VARIANT_DOT4
                 : M >= midm_min && M <= midm_max && a8_midm_supports(a)     ? W2_VARIANT_MIDM
                 : a8_smallm_supports(a)                                      ? W2_VARIANT_SMALLM
@@ -234,9 +291,9 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
 
 int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
                     const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
-                    size_t workspace_bytes, int variant, void* stream)
+                    size_t workspace_bytes, const w2_tuning_t* tune, void* stream)
 {
-    return a8_common("w2_matmul_a8", packed, K, N, G, xq, sx, M, Y, ldy, nullptr, workspace, workspace_bytes, variant,
+    return a8_common("w2_matmul_a8", packed, K, N, G, xq, sx, M, Y, ldy, nullptr, workspace, workspace_bytes, tune,
                      stream);
 }
 
@@ -244,8 +301,7 @@ int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* 
                  const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                  size_t workspace_bytes, void* stream)
 {
-    return w2_matmul_a8_ex(packed, K, N, G, xq, sx, M, Y, ldy, workspace, workspace_bytes,
-                           W2_VARIANT_AUTO, stream);
+    return w2_matmul_a8_ex(packed, K, N, G, xq, sx, M, Y, ldy, workspace, workspace_bytes, nullptr, stream);
 }
 
 // Workspace that lets w2_matmul_a8_fused take the two-kernel route: int8 rows + one scale per row
@@ -257,11 +313,15 @@ static size_t fused_workspace_bytes(int64_t M, int64_t K)
 
 static int a8_fused_common(const char* fn, const void* packed, int64_t K, int64_t N, int G, const void* X,
                            w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
-                           void* workspace, size_t workspace_bytes, void* stream, const Epilogue& epi)
+                           void* workspace, size_t workspace_bytes, const w2_tuning_t* tune, void* stream,
+                           const Epilogue& epi)
 {
     int rc = check_shape(fn, K, N, G);
     if (rc) return rc;
     rc = check_epilogue(fn, epi, N);
+    if (rc) return rc;
+    w2_tuning_t tn;
+    rc = check_tuning(fn, tune, &tn);
     if (rc) return rc;
     const int64_t n_out = epi.act == ACT_SILU_MUL ? N / 2 : N;
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
@@ -285,7 +345,7 @@ static int a8_fused_common(const char* fn, const void* packed, int64_t K, int64_
             return fail(W2_ERR_BUFFER_TOO_SMALL, "%s: M = %lld needs a workspace of %zu bytes (w2_workspace_size)",
                         fn, (long long)M, fused_workspace_bytes(M, K));
         rc = launch_a8_fusedq(packed, (const char*)packed + L.codes_bytes, X, x_dtype == W2_DT_BF16, ldx,
-                              M, K, N, G, L.n_cb, L.n_kt, Y, ldy, epi, (hipStream_t)stream);
+                              M, K, N, G, L.n_cb, L.n_kt, Y, ldy, epi, tn, (hipStream_t)stream);
         if (rc != W2_ERR_UNSUPPORTED_SHAPE || !ws_ok) return rc;
     }
     int8_t* xq = (int8_t*)workspace;
@@ -294,7 +354,7 @@ static int a8_fused_common(const char* fn, const void* packed, int64_t K, int64_
     if (rc) return rc;
     const size_t used = fused_workspace_bytes(M, K);
     return a8_common(fn, packed, K, N, G, xq, sx, M, Y, ldy, nullptr, (char*)workspace + used, workspace_bytes - used,
-                     W2_VARIANT_AUTO, stream, epi);
+                     tune, stream, epi);
 }
 
 static Epilogue to_epilogue(const w2_epilogue_t* e)
@@ -309,36 +369,37 @@ int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const vo
                        void* workspace, size_t workspace_bytes, void* stream)
 {
     return a8_fused_common("w2_matmul_a8_fused", packed, K, N, G, X, x_dtype, ldx, M, Y, ldy, workspace,
-                           workspace_bytes, stream, Epilogue());
+                           workspace_bytes, nullptr, stream, Epilogue());
 }
 
 int w2_matmul_a8_fused_epi(const void* packed, int64_t K, int64_t N, int G, const void* X,
                            w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
-                           const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes, void* stream)
+                           const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes,
+                           const w2_tuning_t* tune, void* stream)
 {
     return a8_fused_common("w2_matmul_a8_fused_epi", packed, K, N, G, X, x_dtype, ldx, M, Y, ldy, workspace,
-                           workspace_bytes, stream, to_epilogue(epi));
+                           workspace_bytes, tune, stream, to_epilogue(epi));
 }
 
 int w2_matmul_a8_epi(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq, const float* sx,
                      int64_t M, uint16_t* Y, int64_t ldy, const w2_epilogue_t* epi, void* workspace,
-                     size_t workspace_bytes, int variant, void* stream)
+                     size_t workspace_bytes, const w2_tuning_t* tune, void* stream)
 {
     return a8_common("w2_matmul_a8_epi", packed, K, N, G, xq, sx, M, Y, ldy, nullptr, workspace, workspace_bytes,
-                     variant, stream, to_epilogue(epi));
+                     tune, stream, to_epilogue(epi));
 }
 
 int w2_debug_group_acc_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
-                          int64_t M, int variant, int32_t* acc, void* stream)
+                          int64_t M, const w2_tuning_t* tune, int32_t* acc, void* stream)
 {
     if (!acc && M > 0) return fail(W2_ERR_INVALID_ARG, "w2_debug_group_acc_a8: acc is NULL");
     return a8_common("w2_debug_group_acc_a8", packed, K, N, G, xq, nullptr, M, nullptr, 0, acc, nullptr, 0,
-                     variant, stream);
+                     tune, stream);
 }
 
 static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, int G,
                       const uint16_t* X, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
-                      void* workspace, size_t workspace_bytes, int variant, void* stream,
+                      void* workspace, size_t workspace_bytes, const w2_tuning_t* tune, void* stream,
                       const Epilogue& epi = Epilogue())
 {
     int rc = check_shape(fn, K, N, G);
@@ -346,6 +407,10 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
     rc = check_epilogue(fn, epi, N);
     if (rc) return rc;
+    w2_tuning_t tn;
+    rc = check_tuning(fn, tune, &tn);
+    if (rc) return rc;
+    int variant = tn.variant;
     const int64_t n_out = epi.act == ACT_SILU_MUL ? N / 2 : N;
     if (variant != W2_VARIANT_AUTO && variant != W2_VARIANT_SMALLM && variant != W2_VARIANT_TILED &&
         variant != W2_VARIANT_SCALED16 && variant != W2_VARIANT_MIDM)
@@ -370,6 +435,7 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     a.part = (float*)workspace;                              // split-K partial results, if the kernel wants them
     a.part_bytes = workspace ? workspace_bytes : 0;
     a.epi = epi;
+    a.tune = tn;
     a.fold = variant == W2_VARIANT_SCALED16;
     if (variant == W2_VARIANT_SCALED16) {
         // the scale-folded construction: the small-M kernel with it, or the kernels built on it
@@ -382,10 +448,10 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         // weight stream is still read once; measured faster from M = 9 on every projection shape);
         // above, 128-row tiles.  Both of the latter fold the scale into the weights: fewest vector
         // instructions per matrix instruction.
-        const int midm_min = env_int("W2_A16_MIDM_MIN_M", 9);
+        const int midm_min = tn.midm_min_m ? tn.midm_min_m : 9;
         // two bands on small projections; on very wide ones (32768 columns and more) the tiled kernel
         // takes over at M = 41 (8192 x 57344 at M = 48: 94 against 104 us)
-        const int midm_max = env_int("W2_A16_MIDM_MAX_M", a.n_cb <= 256 ? 128 : a.n_cb >= 2048 ? 40 : 64);
+        const int midm_max = tn.midm_max_m ? tn.midm_max_m : a.n_cb <= 256 ? 128 : a.n_cb >= 2048 ? 40 : 64;
         if (M >= midm_min && M <= midm_max && a16_midm_supports(a)) return launch_a16_midm(a, (hipStream_t)stream);
         if (!a16_smallm_supports(a)) return launch_a16_fold_tiled(a, (hipStream_t)stream);
         variant = W2_VARIANT_SMALLM;
@@ -403,17 +469,17 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
 
 int w2_matmul_a16_ex(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X,
                      int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
-                     size_t workspace_bytes, int variant, void* stream)
+                     size_t workspace_bytes, const w2_tuning_t* tune, void* stream)
 {
-    return a16_common("w2_matmul_a16", packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes, variant,
+    return a16_common("w2_matmul_a16", packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes, tune,
                       stream);
 }
 
 int w2_matmul_a16_epi(const void* packed, int64_t K, int64_t N, int G, const uint16_t* X, int64_t ldx, int64_t M,
                       uint16_t* Y, int64_t ldy, const w2_epilogue_t* epi, void* workspace, size_t workspace_bytes,
-                      int variant, void* stream)
+                      const w2_tuning_t* tune, void* stream)
 {
-    return a16_common("w2_matmul_a16_epi", packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes, variant,
+    return a16_common("w2_matmul_a16_epi", packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes, tune,
                       stream, to_epilogue(epi));
 }
 
@@ -421,8 +487,7 @@ int w2_matmul_a16(const void* packed, int64_t K, int64_t N, int G, const uint16_
                   int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                   size_t workspace_bytes, void* stream)
 {
-    return w2_matmul_a16_ex(packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes,
-                            W2_VARIANT_AUTO, stream);
+    return w2_matmul_a16_ex(packed, K, N, G, X, ldx, M, Y, ldy, workspace, workspace_bytes, nullptr, stream);
 }
 
 int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* bytes)
@@ -434,9 +499,10 @@ int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* b
     // one or two rows of up to 64 KiB (as fp32) run as a single launch and need none
     const bool single = M <= 2 && M * K * 4 <= 64 * 1024;
     const Layout L = make_layout(K, N, G);
+    const w2_tuning_t dflt = {};
     if (M == 0) *bytes = 0;
-    else if (a16) *bytes = M > 64 ? a16_fold_splitk_bytes(M, N, L.n_kt) : 0;
-    else *bytes = (single ? 0 : fused_workspace_bytes(M, K)) + (M > 64 ? a8_tiled_splitk_bytes(M, N, L.n_kt) : 0);
+    else if (a16) *bytes = M > 64 ? a16_fold_splitk_bytes(M, N, L.n_kt, dflt) : 0;
+    else *bytes = (single ? 0 : fused_workspace_bytes(M, K)) + (M > 64 ? a8_tiled_splitk_bytes(M, N, L.n_kt, dflt) : 0);
     return W2_OK;
 }
 
@@ -452,11 +518,14 @@ int w2_debug_unpack(const void* packed, int64_t K, int64_t N, int G, w2_codec_t 
                          (hipStream_t)stream);
 }
 
-int w2_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream)
+int w2_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, const w2_tuning_t* tune, void* stream)
 {
     if (!src || !sink) return fail(W2_ERR_INVALID_ARG, "w2_debug_stream_read: NULL pointer");
     if (!aligned16(src)) return fail(W2_ERR_MISALIGNED, "w2_debug_stream_read: src must be 16-byte aligned");
-    return launch_stream_read(src, bytes, sink, (hipStream_t)stream);
+    w2_tuning_t tn;
+    const int rc = check_tuning("w2_debug_stream_read", tune, &tn);
+    if (rc) return rc;
+    return launch_stream_read(src, bytes, sink, tn, (hipStream_t)stream);
 }
 
 int w2_debug_int8_gemv(const int8_t* W8, int64_t K, int64_t N, const int8_t* xq, int32_t* out, void* stream)

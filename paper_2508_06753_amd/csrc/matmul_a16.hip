@@ -263,7 +263,7 @@ template <int G, bool FOLD>
 static int launch_a16_smallm_t(const A16Args& a, hipStream_t stream)
 {
     const int rows = (int)a.M;
-    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 2, 16, a.epi.act == ACT_SILU_MUL);
+    const SmallCfg c = pick_cfg(a.tune, a.n_cb, a.n_kt, rows, 2, 16, a.epi.act == ACT_SILU_MUL);
     const size_t extra = (size_t)(c.kc / G) * 16 * sizeof(float);
     const size_t lds = small_lds_bytes(c, rows, 16, 2, extra);
     const int tpw = tiles_per_wave(a.n_kt, c);
@@ -521,8 +521,7 @@ static int launch_a16_tiled_t(const A16Args& a, hipStream_t stream)
     using namespace tiled16;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
-    int group_m = env_int("W2_TILED_GROUP_M", 8);
-    if (group_m < 1) group_m = 1;
+    const int group_m = a.tune.tiled_group_m ? a.tune.tiled_group_m : 8;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(THREADS);
     hipLaunchKernelGGL(a16_tiled_kernel<G>, grid, block, LDS_BYTES, stream, a, tiles_m, tiles_n, group_m);
     return check_launch("w2_matmul_a16[tiled]");

@@ -388,18 +388,12 @@ static int launch_fold_bn(const A16Args& a_in, int splits, hipStream_t stream)
     if (splits < 2) a.part = nullptr;
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
-    int group_m = env_int("W2_TILED_GROUP_M", 8);
-    if (group_m < 1) group_m = 1;
+    const int group_m = a.tune.tiled_group_m ? a.tune.tiled_group_m : 8;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)(splits < 2 ? 1 : splits)), block(64 * waves_of(BN));
     constexpr int lds = lds_bytes(BN, BM);
-    if (lds > 64 * 1024) {                                   // more than 64 KiB of dynamic LDS needs the opt-in
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(a16_fold_tiled_kernel<G, BN, RI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) {
-            set_error("w2_matmul_a16[scaled16 tiled]: hipFuncSetAttribute(%d): %s", lds, hipGetErrorString(e));
-            return -5;
-        }
-    }
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(a16_fold_tiled_kernel<G, BN, RI>), lds,
+                                    "w2_matmul_a16[scaled16 tiled]"))
+        return rc;
     hipLaunchKernelGGL((a16_fold_tiled_kernel<G, BN, RI>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m,
                        (int)grid.y);
     int rc = check_launch("w2_matmul_a16[scaled16 tiled]");
@@ -409,33 +403,33 @@ static int launch_fold_bn(const A16Args& a_in, int splits, hipStream_t stream)
 
 // 256 columns per workgroup (eight waves, one workgroup per CU) unless that leaves half the chip
 // without a workgroup; then 128 columns (four waves)
-static int fold_bn(int64_t M, int64_t N)
+static int fold_bn(int64_t M, int64_t N, const w2_tuning_t& tune)
 {
     const int64_t wgs256 = ((M + 127) / 128) * ((N + 255) / 256);
-    return env_int("W2_FOLD_BN", wgs256 <= 128 ? 128 : 256);
+    return tune.tiled_bn ? tune.tiled_bn : wgs256 <= 128 ? 128 : 256;
 }
 
-static int fold_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap)
+static int fold_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap, const w2_tuning_t& tune)
 {
-    const int bn = fold_bn(M, N);
-    const int forced = env_int("W2_SPLITK", 0);              // tuning and tests: 1 = never, n = n parts if they fit
+    const int bn = fold_bn(M, N, tune);
+    const int forced = tune.splitk;                          // tuning and tests: 1 = never, n = n parts if they fit
     if (forced > 0) return (int)min((int64_t)forced, min(cap, n_kt));
     // two 128-column workgroups fit a CU, one 256-column one: count in CUs' worth
     const int64_t wgs = ((M + 127) / 128) * ((N + bn - 1) / bn);
-    return splitk_plan(bn == 128 ? (wgs + 1) / 2 : wgs, n_kt, env_int("W2_SPLITK_MIN_TILES", 4), M, N, cap);
+    return splitk_plan(bn == 128 ? (wgs + 1) / 2 : wgs, n_kt, tune.splitk_min_tiles ? tune.splitk_min_tiles : 4, M, N, cap);
 }
 
-size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt)
+size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune)
 {
-    const int s = fold_splits(M, N, n_kt, 16);
+    const int s = fold_splits(M, N, n_kt, 16, tune);
     return s < 2 ? 0 : (size_t)s * M * N * sizeof(float);
 }
 
 int launch_a16_fold_tiled(const A16Args& a, hipStream_t stream)
 {
-    const int bn = fold_bn(a.M, a.N);
+    const int bn = fold_bn(a.M, a.N, a.tune);
     const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
-    const int splits = fold_splits(a.M, a.N, a.n_kt, cap);
+    const int splits = fold_splits(a.M, a.N, a.n_kt, cap, a.tune);
     if (bn == 256)
         return a.G == 128 ? launch_fold_bn<128, 256, 8>(a, splits, stream) : launch_fold_bn<64, 256, 8>(a, splits, stream);
     return a.G == 128 ? launch_fold_bn<128, 128, 8>(a, splits, stream) : launch_fold_bn<64, 128, 8>(a, splits, stream);

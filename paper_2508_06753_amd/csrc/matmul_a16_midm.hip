@@ -257,13 +257,7 @@ static int launch_t(const A16Args& a, hipStream_t stream)
     const size_t lds = act > red ? act : red;
     const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW), (unsigned)((a.M + ROWS_PER_BAND - 1) / ROWS_PER_BAND)), block(THREADS);
     auto kern = a16_midm_kernel<G, RT, TPC>;
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) {
-            set_error("w2_matmul_a16[midm]: hipFuncSetAttribute(%zu): %s", lds, hipGetErrorString(e));
-            return -5;
-        }
-    }
+    if (int rc = ensure_dynamic_lds((const void*)kern, lds, "w2_matmul_a16[midm]")) return rc;
     hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
     return check_launch("w2_matmul_a16[midm]");
 }
@@ -273,7 +267,7 @@ static int launch_rt(const A16Args& a, hipStream_t stream)
 {
     // column blocks per workgroup: as many as still leave at least 128 workgroups, since every
     // workgroup reads all M rows of the activations
-    int cbw = env_int("W2_MIDM_CBW", 0);
+    int cbw = a.tune.midm_cbw;
     if (cbw != 2 && cbw != 4 && cbw != 8) cbw = a.n_cb >= 8 * 128 ? 8 : a.n_cb >= 4 * 128 ? 4 : 2;
     if (cbw == 8) return launch_t<G, RT, 4>(a, stream);
     if (cbw == 4) return launch_t<G, RT, 2>(a, stream);

@@ -263,7 +263,7 @@ a8_fusedq_kernel(FusedArgs a, SmallCfg cfg)
 }
 
 template <int G, int RL, bool BF16IN>
-static int launch_fusedq_t(const FusedArgs& a, const SmallCfg& c, size_t lds, hipStream_t stream)
+static int launch_fusedq_t(const FusedArgs& a, const SmallCfg& c, size_t lds, int pre, hipStream_t stream)
 {
     const int tpw = (int)((a.n_kt + c.ks - 1) / c.ks);
     const char* what = "w2_matmul_a8_fused";
@@ -271,7 +271,7 @@ static int launch_fusedq_t(const FusedArgs& a, const SmallCfg& c, size_t lds, hi
     if (tpw <= 4) return launch_small(a8_fusedq_kernel<G, 4, RL, BF16IN>, what, a, c, lds, stream);
     // every wave has more than four tiles: a large projection.  One row: half of the loads wait for
     // the quantised row (measured 10.0 against 10.4 us on 4096 x 28672; with two rows it loses).
-    if (RL == 1 && env_int("W2_SMALL_PRE", 4) == 4)
+    if (RL == 1 && pre != 8)
         return launch_small(a8_fusedq_kernel<G, TMAX, RL, BF16IN, 4>, what, a, c, lds, stream);
     return launch_small(a8_fusedq_kernel<G, TMAX, RL, BF16IN>, what, a, c, lds, stream);
 }
@@ -280,7 +280,7 @@ static int launch_fusedq_t(const FusedArgs& a, const SmallCfg& c, size_t lds, hi
 // per-workgroup budget; the caller then uses w2_quantize_rows + w2_matmul_a8.
 int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x_is_bf16, int64_t ldx,
                      int64_t M, int64_t K, int64_t N, int G, int64_t n_cb, int64_t n_kt, uint16_t* Y,
-                     int64_t ldy, const Epilogue& epi, hipStream_t stream)
+                     int64_t ldy, const Epilogue& epi, const w2_tuning_t& tune, hipStream_t stream)
 {
     if (M < 1 || M > 4) {
         set_error("w2_matmul_a8_fused: M must be 1..4 (use w2_quantize_rows + w2_matmul_a8)");
@@ -289,7 +289,7 @@ int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x
     const int rows = (int)M;
     const int es = x_is_bf16 ? 2 : 4;
     const int64_t pieces = M * K * es / 16;                  // every piece needs a register slot of some thread
-    SmallCfg c = pick_cfg(n_cb, n_kt, rows, 1, 16, epi.act == ACT_SILU_MUL, (int)((pieces + FQ_PIECES - 1) / FQ_PIECES));
+    SmallCfg c = pick_cfg(tune, n_cb, n_kt, rows, 1, 16, epi.act == ACT_SILU_MUL, (int)((pieces + FQ_PIECES - 1) / FQ_PIECES));
     const int threads = 64 * c.cbw * c.ks;
     const size_t xs_bytes = ((size_t)rows * (K + XS_PAD) + 15) & ~(size_t)15;
     size_t lds = FQ_HDR + xs_bytes;
@@ -305,8 +305,8 @@ int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x
     a.epi = epi;
     const int rl = M <= 1 ? 1 : M <= 2 ? 2 : 4;
 #define W2_FQ(GG, RLL)                                                                         \
-    return x_is_bf16 ? launch_fusedq_t<GG, RLL, true>(a, c, lds, stream)                       \
-                     : launch_fusedq_t<GG, RLL, false>(a, c, lds, stream)
+    return x_is_bf16 ? launch_fusedq_t<GG, RLL, true>(a, c, lds, tune.fused_pre, stream)       \
+                     : launch_fusedq_t<GG, RLL, false>(a, c, lds, tune.fused_pre, stream)
     if (G == 128) {
         if (rl == 1) { W2_FQ(128, 1); }
         if (rl == 2) { W2_FQ(128, 2); }

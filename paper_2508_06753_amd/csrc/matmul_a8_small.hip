@@ -319,7 +319,7 @@ template <int MT, int G>
 static int launch_dot4_t(const A8Args& a, hipStream_t stream)
 {
     const int rows = MT < (int)a.M ? MT : (int)a.M;
-    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 1, 16, a.epi.act == ACT_SILU_MUL);
+    const SmallCfg c = pick_cfg(a.tune, a.n_cb, a.n_kt, rows, 1, 16, a.epi.act == ACT_SILU_MUL);
     const size_t lds = small_lds_bytes(c, rows, MT, 1, 0);
     if (a.acc_out) return launch_small(a8_dot4_kernel<MT, G, TMAX, true>, "w2_matmul_a8[dot4]", a, c, lds, stream);
     // in-flight depth = tiles per wave, so that no load slot re-reads a tile
@@ -346,7 +346,7 @@ template <int G, int RL>
 static int launch_smallm_t(const A8Args& a, hipStream_t stream)
 {
     const int rows = (int)a.M;
-    const SmallCfg c = pick_cfg(a.n_cb, a.n_kt, rows, 1, 16, a.epi.act == ACT_SILU_MUL);
+    const SmallCfg c = pick_cfg(a.tune, a.n_cb, a.n_kt, rows, 1, 16, a.epi.act == ACT_SILU_MUL);
     const size_t lds = small_lds_bytes(c, rows, 16, 1, 0);
     if (a.acc_out) return launch_small(a8_smallm_kernel<G, TMAX, 4, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
     const int tpw = tiles_per_wave(a.n_kt, c);

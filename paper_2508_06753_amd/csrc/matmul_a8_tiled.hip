@@ -386,8 +386,7 @@ static int launch_tiled(const A8Args& a_in, int splits, hipStream_t stream)
     const int tiles_n = (int)((a.N + BN - 1) / BN);
     const size_t act = 3 * A_BUF, epi = (size_t)WAVES * BM * E_STRIDE;   // three activation stages; the epilogue regions reuse them
     const size_t lds = act > epi ? act : epi;
-    int group_m = env_int("W2_TILED_GROUP_M", 8);
-    if (group_m < 1) group_m = 1;
+    const int group_m = a.tune.tiled_group_m ? a.tune.tiled_group_m : 8;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)splits), block(THREADS);
     hipLaunchKernelGGL((a8_tiled_kernel<G, DBG, BN>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m, splits);
     int rc = check_launch("w2_matmul_a8[tiled]");
@@ -396,36 +395,36 @@ static int launch_tiled(const A8Args& a_in, int splits, hipStream_t stream)
 }
 
 // 256 columns per workgroup unless that leaves the chip's 512 workgroup slots clearly underfilled
-static int tiled_bn(int64_t M, int64_t N)
+static int tiled_bn(int64_t M, int64_t N, const w2_tuning_t& tune)
 {
     const int64_t wgs256 = ((M + tiled::BM - 1) / tiled::BM) * ((N + 255) / 256);
-    int bn = env_int("W2_TILED_BN", 0);
+    int bn = tune.tiled_bn;
     if (bn != 128 && bn != 256) bn = wgs256 < 400 ? 128 : 256;
     return bn;
 }
 
-static int tiled_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap)
+static int tiled_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap, const w2_tuning_t& tune)
 {
-    const int bn = tiled_bn(M, N);
-    const int forced = env_int("W2_SPLITK", 0);              // tuning and tests: 1 = never, n = n parts if they fit
+    const int bn = tiled_bn(M, N, tune);
+    const int forced = tune.splitk;                          // tuning and tests: 1 = never, n = n parts if they fit
     if (forced > 0) return (int)min((int64_t)forced, min(cap, n_kt));
     // four 128-column workgroups fit a CU, two 256-column ones: count in units of half a CU's worth
     const int64_t wgs = ((M + tiled::BM - 1) / tiled::BM) * ((N + bn - 1) / bn);
-    return splitk_plan(bn == 128 ? (wgs + 1) / 2 : wgs, n_kt, env_int("W2_SPLITK_MIN_TILES", 12), M, N, cap);
+    return splitk_plan(bn == 128 ? (wgs + 1) / 2 : wgs, n_kt, tune.splitk_min_tiles ? tune.splitk_min_tiles : 12, M, N, cap);
 }
 
-size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt)
+size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune)
 {
-    const int s = tiled_splits(M, N, n_kt, 16);
+    const int s = tiled_splits(M, N, n_kt, 16, tune);
     return s < 2 ? 0 : (size_t)s * M * N * sizeof(float);
 }
 
 template <int G, bool DBG>
 static int launch_tiled_bn(const A8Args& a, hipStream_t stream)
 {
-    const int bn = tiled_bn(a.M, a.N);
+    const int bn = tiled_bn(a.M, a.N, a.tune);
     const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
-    const int splits = DBG ? 1 : tiled_splits(a.M, a.N, a.n_kt, cap);
+    const int splits = DBG ? 1 : tiled_splits(a.M, a.N, a.n_kt, cap, a.tune);
     return bn == 128 ? launch_tiled<G, DBG, 128>(a, splits, stream) : launch_tiled<G, DBG, 256>(a, splits, stream);
 }
 

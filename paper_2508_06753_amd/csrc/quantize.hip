@@ -117,8 +117,9 @@ quantize_rows_kernel(const void* __restrict__ X, int64_t K, int64_t ldx, int G,
             *reinterpret_cast<uint2*>(xq + m * K + k) = make_uint2(p0, p1);
         }
         if (gsum) {
-            // K % 256 == 0 and blockDim % 64 == 0: whole waves are active here and
-            // each group occupies lanes_per_group consecutive, aligned lanes.
+            // Each group occupies lanes_per_group (at most 32) consecutive, aligned lanes, and K % 256 == 0
+            // makes the active lanes of a wave a whole number of such runs (a bf16 row of 256 values fills
+            // half a wave: lanes 0..31): a lane only ever reads lanes of its own, fully active, run.
             for (int off = 1; off < lanes_per_group; off <<= 1) sum += __shfl_xor(sum, off);
             if ((lane & (lanes_per_group - 1)) == 0) gsum[m * (K / G) + k / G] = sum;
         }
@@ -126,7 +127,7 @@ quantize_rows_kernel(const void* __restrict__ X, int64_t K, int64_t ldx, int G,
 #pragma unroll
     for (int c = 0; c < CR; ++c) {
         const int64_t k = (int64_t)threadIdx.x * EPT + c * step;
-        if (k < K) emit(k, cache[c]);                        // uniform per wave (K % 256 == 0)
+        if (k < K) emit(k, cache[c]);                        // whole groups of lanes (K % 256 == 0)
     }
     for (int64_t k = (int64_t)threadIdx.x * EPT + CR * step; k < K; k += step) {
         float v[EPT];

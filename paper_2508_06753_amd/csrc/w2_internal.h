@@ -2,7 +2,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
+#include "../../include/w2mm.h"
 #include "w2_layout.h"
 
 namespace w2 {
@@ -18,7 +20,7 @@ int launch_unpack(const void* packed, const Layout& L, int codec, uint8_t* codes
                   uint16_t* scales, hipStream_t stream);
 int launch_quantize(const void* X, int x_is_bf16, int64_t M, int64_t K, int64_t ldx, int G,
                     int8_t* xq, float* sx, int32_t* gsum, hipStream_t stream);
-int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
+int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, const w2_tuning_t& tune, hipStream_t stream);
 
 // Work fused into the store of the result (Sec. II-D: bias addition and post-GEMM activation
 // functions are applied while the outputs are still in registers).  z = fp32 result + bias[n];
@@ -48,6 +50,7 @@ struct A8Args {
     float* part = nullptr;
     size_t part_bytes = 0;
     Epilogue epi;
+    w2_tuning_t tune = {};      // overrides from the caller (all 0: the library's rules)
 };
 
 bool a8_dot4_supports(const A8Args& a);
@@ -60,7 +63,7 @@ int launch_a8_tiled(const A8Args& a, hipStream_t stream);
 
 int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x_is_bf16, int64_t ldx,
                      int64_t M, int64_t K, int64_t N, int G, int64_t n_cb, int64_t n_kt, uint16_t* Y,
-                     int64_t ldy, const Epilogue& epi, hipStream_t stream);
+                     int64_t ldy, const Epilogue& epi, const w2_tuning_t& tune, hipStream_t stream);
 
 struct A16Args {
     const uint32_t* codes;
@@ -74,6 +77,7 @@ struct A16Args {
     float* part = nullptr;      // split-K workspace, as in A8Args (scale-folded tiled kernel only)
     size_t part_bytes = 0;
     Epilogue epi;
+    w2_tuning_t tune = {};
 };
 
 bool a16_smallm_supports(const A16Args& a);
@@ -89,15 +93,17 @@ int launch_a16_midm(const A16Args& a, hipStream_t stream);
 // for `cap` fp32 copies of the M x N output.
 int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t N, int64_t cap);
 // Bytes of workspace with which the tiled kernels would split K for this problem (0: they would not).
-size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt);
-size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt);
+size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune);
+size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune);
 // Y[m][n] = bf16(sum_s part[s][m][n]), a fixed order of summation
 int launch_splitk_reduce(const float* part, int splits, int64_t M, int64_t N, uint16_t* Y, int64_t ldy,
                          const Epilogue& epi, hipStream_t stream);
 
 int launch_int8_gemv(const int8_t* W8, const int8_t* xq, int32_t* out, int64_t K, int64_t N, hipStream_t stream);
 
-// Environment override for tuning sweeps (read once per call on the host).
-int env_int(const char* name, int dflt);
+// Opts a kernel in to more than 64 KiB of dynamic LDS.  The library remembers, per kernel and device,
+// the largest size it has asked for: the attribute is set when a launch needs more than any earlier
+// one did, not on every launch (host-side bookkeeping only; no device state).
+int ensure_dynamic_lds(const void* kern, size_t bytes, const char* what);
 
 }  // namespace w2

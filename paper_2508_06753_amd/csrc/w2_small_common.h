@@ -144,16 +144,16 @@ constexpr int64_t LDS_BUDGET = 128 * 1024;   // activation chunk + reduction scr
 // workgroups of these kernels at a time; on wide projections the finer grain
 // fills the chip better: measured 13.5 against 15.6 us on 5120 x 34816 and 26.1
 // against 29.7 us on 8192 x 57344 at M = 1, no change on 4096 x 28672).
-static SmallCfg pick_cfg(int64_t n_cb, int64_t n_kt, int rows, int bytes_per_k, int max_waves = 16,
-                         bool even_cbw = false, int min_threads = 0)
+static SmallCfg pick_cfg(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, int rows, int bytes_per_k,
+                         int max_waves = 16, bool even_cbw = false, int min_threads = 0)
 {
     SmallCfg c;
-    int waves = env_int("W2_SMALL_WAVES", 0);
+    int waves = tune.small_waves;                            // validated by the entry point: 0 or 1..16
     const bool auto_waves = waves <= 0;
     if (auto_waves) waves = 8;
     if (waves > max_waves) waves = max_waves;
     if (waves < 1) waves = 1;
-    const int cbw_env = env_int("W2_SMALL_CBW", 0);
+    const int cbw_env = tune.small_cbw;                      // 0 or a power of two <= 16
     auto choose = [&](int w) {
         int cb = w;
         // split K until a wave has at most TMAX tiles, while there are waves to split over
@@ -175,7 +175,7 @@ static SmallCfg pick_cfg(int64_t n_cb, int64_t n_kt, int rows, int bytes_per_k, 
     if (c.ks < 1) c.ks = 1;
     int64_t kc = n_kt * TILE_K;
     while (kc > TILE_K && (int64_t)rows * (kc * bytes_per_k + XS_PAD) > LDS_BUDGET) kc -= TILE_K;
-    const int force = env_int("W2_SMALL_KC", 0);
+    const int force = tune.small_kc;
     if (force >= TILE_K && force % TILE_K == 0 && force < kc) kc = force;
     c.kc = (int)kc;
     return c;
@@ -200,13 +200,7 @@ template <typename Kern, typename Args>
 static int launch_small(Kern kern, const char* what, const Args& a, const SmallCfg& c, size_t lds,
                         hipStream_t stream)
 {
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) {
-            set_error("%s: hipFuncSetAttribute(%zu): %s", what, lds, hipGetErrorString(e));
-            return -5;
-        }
-    }
+    if (int rc = ensure_dynamic_lds((const void*)kern, lds, what)) return rc;
     const dim3 grid((unsigned)((a.n_cb + c.cbw - 1) / c.cbw)), block(64 * c.cbw * c.ks);
     hipLaunchKernelGGL(kern, grid, block, lds, stream, a, c);
     return check_launch(what);

@@ -128,9 +128,32 @@ def test_70b_prefill_gate_up(w2):
 
 
 def test_70b_prefill_down(w2):
+    """70B-class down 28672 x 8192 at M = 2048 and M = 512 (w2a8), and w2a16."""
     K, N = synth.SHAPES_70B["down"]
+    check_a8(w2, 2048, K, N, 128, 0, seed=4, ncols=64, acc_check=False)
     check_a8(w2, 512, K, N, 128, 0, seed=4, ncols=128)
     check_a16(w2, 256, K, N, 128, 0, seed=4, ncols=64)
+
+
+@pytest.mark.parametrize("name", ["gate_up", "down"])
+def test_70b_prefill_tiled_kernel_accumulators(w2, name):
+    """The int32 group accumulators of the PREFILL kernel at the full K of the 70B-class shapes (8192 and
+    28672: 64 and 224 groups, the long pipelines and every periodic bias settlement), bit for bit, on a
+    band of rows that spans two row tiles with a ragged second one.  The kernel family is forced: AUTO
+    would send so few rows to the mid-M kernel."""
+    K, N = synth.SHAPES_70B[name]
+    G, rows = 128, 80
+    codes, scales, packed = weights(w2, K, N, G, 0, 4)
+    X = synth.make_activations(rows, K, seed=4321)
+    xq, _, _ = w2.quantize_rows(dev(X), G)
+    oq, _, _ = oracle.quantize_rows(X, G, want_gsum=False)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    cols = sample_cols(N, 192, 17)
+    acc = w2.debug_group_acc_a8(packed, K, N, G, xq, variant=w2.VARIANT_TILED)        # [rows][K/G][N] on the device
+    got = acc[:, :, torch.from_numpy(cols).cuda()].cpu().numpy()
+    del acc
+    oacc = oracle.group_acc(np.ascontiguousarray(codes[:, cols]), G, 0, oq)
+    assert np.array_equal(got, oacc)
 
 
 def test_70b_prefill_gate_up_a16(w2):

@@ -4,8 +4,6 @@ int32 group accumulators) must match bit for bit; bf16 outputs must satisfy
 |Y - Yor| <= 1e-2*|Yor| + 2^-10 * sum|terms| (the second term is the floor for
 outputs that are a cancelling sum; fp32 vs fp64 association alone moves
 those)."""
-import os
-
 import numpy as np
 import pytest
 
@@ -116,18 +114,33 @@ def test_quantize_ties_and_bf16_and_stride(w2):
     assert np.array_equal(xq.cpu().numpy(), oq)
 
 
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("M", [1, 3])
+def test_quantize_bf16_single_tile_row_with_group_sums(w2, M, G):
+    # K = 256 in bf16 is half of what one wave covers at eight elements per lane: the lanes past the
+    # end of the row must contribute neither to the abs-max nor to the group sums
+    Xb = synth.f32_to_bf16_bits(synth.make_activations(M, 256, seed=40 + M))
+    xq, sx, gs = w2.quantize_rows(dev(Xb).view(torch.bfloat16), G, want_gsum=True)
+    oq, os_, og = oracle.quantize_rows(Xb, G, x_is_bf16=True)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), os_.view(np.uint32))
+    assert np.array_equal(gs.cpu().numpy(), og)
+
+
 # ------------------------------------------------------------------ w2a8
-def run_a8_case(w2, M, K, N, G, codec, variant, seed):
+def run_a8_case(w2, M, K, N, G, codec, variant, seed, tune=None):
+    """`tune`: overrides (w2_tuning_t fields) passed with every call, so that the case runs the
+    workgroup shape it names whatever the library would pick by itself."""
     codes, scales, X = synth.make_problem(M, K, N, G, codec, seed)
     packed = w2.prepack(dev(codes), dev(scales), G, codec)
     xq, sx, _ = w2.quantize_rows(dev(X), G)
     oq, osx, _ = oracle.quantize_rows(X, G)
     assert np.array_equal(xq.cpu().numpy(), oq)
-    acc = w2.debug_group_acc_a8(packed, K, N, G, xq, variant)
+    acc = w2.debug_group_acc_a8(packed, K, N, G, xq, variant, tune=tune)
     oacc = oracle.group_acc(codes, G, codec, oq)
     assert np.array_equal(acc.cpu().numpy(), oacc), "int32 group accumulators differ"
-    Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=variant)
-    Y2 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=variant)
+    Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=variant, tune=tune)
+    Y2 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=variant, tune=tune)
     assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "not deterministic"
     Yo, y64 = oracle.matmul_a8(codes, scales, G, codec, oq, osx)
     mag = oracle.a8_term_magnitude(codes, scales, G, codec, oq, osx)
@@ -156,11 +169,10 @@ def test_a8_smallm(w2, M, K, N, G):
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (2304, 1032), (768, 8)])
 @pytest.mark.parametrize("M", [9, 16, 17, 31, 32, 33, 50, 64])
-def test_a8_midm(w2, M, K, N, G, cbw, monkeypatch):
+def test_a8_midm(w2, M, K, N, G, cbw):
     # one / two / four 16-row tiles per streamed weight tile; every split of the eight waves
     # into column blocks x k-splits; K of one chunk, of a ragged last chunk (2304 = 2 x 1024 + 256)
-    monkeypatch.setenv("W2_MIDM_CBW", str(cbw))
-    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_MIDM, seed=M + K + N + G)
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_MIDM, seed=M + K + N + G, tune={"midm_cbw": cbw})
 
 
 @pytest.mark.parametrize("M", [65, 100, 128, 130, 256])
@@ -187,10 +199,9 @@ def test_a8_midm_long_k_and_limits(w2):
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (512, 1032)])
 @pytest.mark.parametrize("M", [1, 17, 127, 128, 200])
-def test_a8_tiled(w2, M, K, N, G, bn, monkeypatch):
+def test_a8_tiled(w2, M, K, N, G, bn):
     # both workgroup widths (four and eight waves); ragged M, N; one to four stages of K
-    monkeypatch.setenv("W2_TILED_BN", str(bn))
-    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G)
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G, tune={"tiled_bn": bn})
 
 
 @pytest.mark.parametrize("M", [1, 4, 8, 9, 16, 17, 64, 65, 130])
@@ -322,22 +333,22 @@ def test_workspace_size_rule(w2):
 @pytest.mark.parametrize("splitk", [0, 2, 3, 5])
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("M,K,N", [(65, 1024, 272), (130, 2304, 48), (200, 512, 1032)])
-def test_tiled_split_k(w2, M, K, N, G, splitk, monkeypatch):
+def test_tiled_split_k(w2, M, K, N, G, splitk):
     # K cut into ranges computed by different workgroups, fp32 partial results summed by a second launch:
     # forced numbers of parts (uneven ranges included) and the planner's own choice (0), both kernels
-    monkeypatch.setenv("W2_SPLITK", str(splitk))
+    tune = {"splitk": splitk}
     codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + N + G)
     packed = w2.prepack(dev(codes), dev(scales), G, 0)
     ws = torch.empty(16 * M * N * 4, dtype=torch.uint8, device="cuda")
     xq, sx, _ = w2.quantize_rows(dev(X), G)
-    Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED, workspace=ws)
+    Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED, workspace=ws, tune=tune)
     oq, osx, _ = oracle.quantize_rows(X, G)
     assert np.array_equal(xq.cpu().numpy(), oq)
     Yo, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
     mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
     check_y(bf16_bits(Y), Yo, y64, mag, f"a8 split-K {splitk} M={M} K={K} N={N} G={G}")
     Xb = synth.f32_to_bf16_bits(X)
-    Y16 = w2.matmul_a16(packed, K, N, G, dev(Xb).view(torch.bfloat16), workspace=ws)
+    Y16 = w2.matmul_a16(packed, K, N, G, dev(Xb).view(torch.bfloat16), workspace=ws, tune=tune)
     Yo, y64, mag = oracle.matmul_a16(codes, scales, G, 0, Xb)
     check_y(bf16_bits(Y16), Yo, y64, mag, f"a16 split-K {splitk} M={M} K={K} N={N} G={G}")
     if splitk >= 2:
@@ -399,17 +410,16 @@ def test_a8_fused_epilogues(w2, K, N, G, with_bias, act):
 
 @pytest.mark.parametrize("act", [1, 2])
 @pytest.mark.parametrize("M", [1, 2, 4, 40, 130])
-def test_a8_fused_entry_with_epilogue_and_split_k(w2, M, act, monkeypatch):
+def test_a8_fused_entry_with_epilogue_and_split_k(w2, M, act):
     # the one-call entry point (quantisation fused or through the workspace) with bias + activation; for the large M
     # the tiled kernel splits K and the epilogue runs in the reduce launch
     K, N, G = 1024, 320, 128
-    if M > 64:
-        monkeypatch.setenv("W2_SPLITK", "3")
+    tune = {"splitk": 3} if M > 64 else None
     codes, scales, X = synth.make_problem(M, K, N, G, 0, M + act)
     bias = synth.f32_to_bf16_bits(np.random.default_rng(M).standard_normal(N).astype(np.float32))
     packed = w2.prepack(dev(codes), dev(scales), G, 0)
     ws = torch.empty(w2.workspace_size(M, K, N, G) + 4 * M * N * 4, dtype=torch.uint8, device="cuda")
-    Y = w2.matmul_a8_fused_epi(packed, K, N, G, dev(X), bias=dev(bias), act=act, workspace=ws)
+    Y = w2.matmul_a8_fused_epi(packed, K, N, G, dev(X), bias=dev(bias), act=act, workspace=ws, tune=tune)
     oq, osx, _ = oracle.quantize_rows(X, G)
     _, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
     mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
@@ -423,9 +433,8 @@ A16_EPI_VARIANTS = [("SMALLM", 2, [1, 5, 16]), ("SCALED16 small", 5, [3]), ("MID
 @pytest.mark.parametrize("with_bias,act", [(True, 0), (False, 1), (True, 2), (False, 2)])
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(256, 32), (1024, 288)])
-def test_a16_fused_epilogues(w2, K, N, G, with_bias, act, monkeypatch):
+def test_a16_fused_epilogues(w2, K, N, G, with_bias, act):
     # the same epilogues on the unquantised-activation path, every kernel family, split-K reduce included
-    monkeypatch.setenv("W2_SPLITK", "2")
     rng = np.random.default_rng(K + N + G + act)
     bias = synth.f32_to_bf16_bits(rng.standard_normal(N).astype(np.float32)) if with_bias else None
     bias_d = dev(bias) if with_bias else None
@@ -436,7 +445,7 @@ def test_a16_fused_epilogues(w2, K, N, G, with_bias, act, monkeypatch):
             packed = w2.prepack(dev(codes), dev(scales), G, 0)
             ws = torch.empty(4 * M * N * 4, dtype=torch.uint8, device="cuda")
             Y = w2.matmul_a16_epi(packed, K, N, G, dev(Xb).view(torch.bfloat16), bias=bias_d, act=act, variant=variant,
-                                  workspace=ws)
+                                  workspace=ws, tune={"splitk": 2})
             _, y64, mag = oracle.matmul_a16(codes, scales, G, 0, Xb)
             check_epilogue(bf16_bits(Y), y64, mag, bias, act, f"a16 epilogue {name} M={M} K={K} N={N} G={G} act={act}")
 
@@ -457,13 +466,13 @@ def test_epilogue_argument_errors(w2):
 
 
 # ------------------------------------------------------------------ w2a16
-def run_a16_case(w2, M, K, N, G, codec, variant, seed):
+def run_a16_case(w2, M, K, N, G, codec, variant, seed, tune=None):
     codes, scales, X = synth.make_problem(M, K, N, G, codec, seed)
     Xb = synth.f32_to_bf16_bits(X)
     packed = w2.prepack(dev(codes), dev(scales), G, codec)
     Xd = dev(Xb).view(torch.bfloat16)
-    Y = w2.matmul_a16(packed, K, N, G, Xd, variant=variant)
-    Y2 = w2.matmul_a16(packed, K, N, G, Xd, variant=variant)
+    Y = w2.matmul_a16(packed, K, N, G, Xd, variant=variant, tune=tune)
+    Y2 = w2.matmul_a16(packed, K, N, G, Xd, variant=variant, tune=tune)
     assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "not deterministic"
     Yo, y64, mag = oracle.matmul_a16(codes, scales, G, codec, Xb)
     check_y(bf16_bits(Y), Yo, y64, mag, f"a16 M={M} K={K} N={N} G={G} codec={codec} variant={variant}")
@@ -487,10 +496,9 @@ def test_a16_tiled(w2, M, K, N, G):
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (768, 1032), (2304, 48)])
 @pytest.mark.parametrize("M", [1, 9, 16, 17, 31, 32, 33, 50, 64])
-def test_a16_midm(w2, M, K, N, G, cbw, monkeypatch):
+def test_a16_midm(w2, M, K, N, G, cbw):
     # weight stream read once, scale-folded weights; every workgroup shape; K = 768, 2304: chunks that overlap
-    monkeypatch.setenv("W2_MIDM_CBW", str(cbw))
-    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_MIDM, seed=M + K + N + G)
+    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_MIDM, seed=M + K + N + G, tune={"midm_cbw": cbw})
 
 
 def test_a16_midm_long_k_and_limits(w2):
@@ -519,10 +527,9 @@ def test_a16_scale_folded_weights(w2, M, K, N, G):
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (768, 1032)])
 @pytest.mark.parametrize("M", [17, 127, 128, 129, 300])
-def test_a16_scale_folded_weights_large_m(w2, M, K, N, G, bn, monkeypatch):
+def test_a16_scale_folded_weights_large_m(w2, M, K, N, G, bn):
     # the same construction in the tiled kernel; both workgroup widths; K = 768 is an odd number of tiles
-    monkeypatch.setenv("W2_FOLD_BN", str(bn))
-    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SCALED16, seed=M + K + N + G)
+    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SCALED16, seed=M + K + N + G, tune={"tiled_bn": bn})
 
 
 def test_a16_scale_folded_zero_scales_and_exact_integers(w2):
@@ -611,7 +618,18 @@ def test_argument_errors_write_nothing(w2):
                             ctypes.c_void_p(Y.data_ptr() + 2), 64, None, 0, s) == w2.ERR_MISALIGNED
     assert lib.w2_matmul_a8(p(packed), 256, 64, 128, p(xq), p(sx), 1, p(Y), 32, None, 0, s) == w2.ERR_MISALIGNED
     assert lib.w2_matmul_a8(p(packed), 256, 64, 128, None, p(sx), 1, p(Y), 64, None, 0, s) == w2.ERR_INVALID_ARG
-    assert lib.w2_matmul_a8_ex(p(packed), 256, 64, 128, p(xq), p(sx), 1, p(Y), 64, None, 0, 9, s) == w2.ERR_INVALID_ARG
+    # overrides outside what the header allows are refused, field by field, before anything is launched
+    for field, value in (("variant", 9), ("variant", w2.VARIANT_SCALED16), ("small_waves", 17), ("small_cbw", 3),
+                         ("small_kc", 100), ("midm_cbw", 3), ("tiled_bn", 64), ("splitk", 17), ("stream_unroll", 1),
+                         ("tiled_group_m", -1)):
+        t = w2.Tuning()
+        setattr(t, field, value)
+        assert lib.w2_matmul_a8_ex(p(packed), 256, 64, 128, p(xq), p(sx), 1, p(Y), 64, None, 0, ctypes.byref(t),
+                                   s) == w2.ERR_INVALID_ARG, field
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    t = w2.Tuning()
+    t.stream_blocks = 70000
+    assert lib.w2_debug_stream_read(p(packed), 1024, p(sink), ctypes.byref(t), s) == w2.ERR_INVALID_ARG
     # M == 0 is a no-op
     assert lib.w2_matmul_a8(p(packed), 256, 64, 128, p(xq), p(sx), 0, p(Y), 64, None, 0, s) == 0
     torch.cuda.synchronize()
@@ -642,13 +660,13 @@ def test_graph_replays_match_eager(w2):
     y = torch.empty((1, 256), dtype=torch.bfloat16, device="cuda")
     yt = torch.empty((Mt, N), dtype=torch.bfloat16, device="cuda")
     y16 = torch.empty((Mt, N), dtype=torch.bfloat16, device="cuda")
-    os.environ["W2_SPLITK"] = "3"
-    try:
+    if True:
         def step():
             w2.matmul_a8_fused_epi(packed, K, N, G, x_in, act=w2.ACT_SILU_MUL, out=h)
             w2.matmul_a8_fused(packed2, N // 2, 256, G, h, out=y)
-            w2.matmul_a8_fused(packed, K, N, G, xt, out=yt, workspace=ws)          # quantise + tiled split-K + reduce
-            w2.matmul_a16(packed, K, N, G, xtb, out=y16, workspace=ws16)
+            # quantise + tiled split-K + reduce
+            w2.matmul_a8_fused_epi(packed, K, N, G, xt, out=yt, workspace=ws, tune={"splitk": 3})
+            w2.matmul_a16(packed, K, N, G, xtb, out=y16, workspace=ws16, tune={"splitk": 3})
 
         def eager():
             step()
@@ -679,8 +697,6 @@ def test_graph_replays_match_eager(w2):
             torch.cuda.synchronize()
             for got, want, name in zip((h, y, yt, y16), ref, ("gated", "chained", "split-K a8", "a16")):
                 assert torch.equal(got.view(torch.int16), want.view(torch.int16)), f"replay {rep}: {name} differs from eager"
-    finally:
-        os.environ.pop("W2_SPLITK", None)
 
 
 # ------------------------------------------------------------------ row strides

@@ -55,6 +55,9 @@ def test_worked_example(worked_example, codec, name):
     np.testing.assert_allclose(y64, _floats(w[f"y_a8_{name}"]), rtol=0, atol=6e-7)
     if name == "int2":
         assert np.array_equal(Y, _hex16(w["Y_a8_int2_bf16"]))
+    # the tolerance floor: hand-worked values (numerators over 127; sx is 4/127, 1/127 rounded to fp32)
+    tm = oracle.a8_term_magnitude(codes, scales, G, codec, xq, sx)
+    np.testing.assert_allclose(tm, _floats(w[f"mag_a8_{name}_times127"]) / 127.0, rtol=1e-7, atol=0)
     Y16, y16, _ = oracle.matmul_a16(codes, scales, G, codec, _exact_bf16_bits(X))
     assert np.array_equal(y16, _floats(w[f"y_a16_{name}"]))        # exact dyadics
     if name == "int2":
@@ -206,6 +209,19 @@ def test_a8_against_numpy_fp64_dequantised_matmul(codec):
         assert np.array_equal(Y, oracle.f64_to_bf16(y64))
         tm = oracle.a8_term_magnitude(codes, scales, G, codec, xq, sx)
         assert np.all(tm <= mag * (1 + 1e-12)) and np.all(tm >= np.abs(y64) * (1 - 1e-12))
+        # ... and it IS |sx| * sum_g |sw_g * acc_g|, recomputed with numpy from the integer group sums
+        # (checked above against numpy int64); every product sw*acc is exact in fp64 (8 x 17 bits), so only
+        # the order of the fp64 additions could differ: g ascending on both sides -> equal to the last bit
+        acc = oracle.group_acc(codes, G, codec, xq).astype(np.float64)            # [M][K/G][N]
+        terms = np.abs(sw[None, :, :] * acc)
+        ref_tm = np.zeros((M, N))
+        for g in range(K // G):
+            ref_tm += terms[:, g, :]
+        ref_tm *= np.abs(sx.astype(np.float64))[:, None]
+        assert np.array_equal(tm, ref_tm)
+        # the two plausible mistakes do not pass: |.| of the whole sum, |.| per k
+        if K // G > 1 and N > 8:
+            assert np.any(tm > np.abs(y64) * 1.01) and np.any(tm < mag * 0.99)
 
 
 @pytest.mark.parametrize("codec", [0, 1])
