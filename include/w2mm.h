@@ -16,9 +16,10 @@
  *     aborts, never synchronises the device;
  *   - all work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) of the CURRENT device;
- *   - every buffer is owned by the caller; the library keeps no device state,
- *     allocates nothing and holds no handles, so calls from several host
- *     threads are independent; which kernel runs depends on the arguments
+ *   - every buffer is owned by the caller; the library keeps no device state
+ *     (w2_matmul_a8_fused_noalloc, with its built-in scratch buffer, is the one
+ *     exception), allocates nothing and holds no handles, so calls from several
+ *     host threads are independent; which kernel runs depends on the arguments
  *     alone (the process environment is never read);
  *   - "dev" pointers are device memory of the current device, "host" pointers
  *     are ordinary host memory;
@@ -200,6 +201,29 @@ W2_API int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, cons
 W2_API int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const void* X,
                               w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it): w2_matmul_a8_fused with the
+ * workspace replaced by a buffer built into the library, W2_NOALLOC_SCRATCH_MIB
+ * MiB of device memory per GPU that exists from the moment the library is loaded
+ * on that GPU until the process ends.  The call itself allocates nothing, on the
+ * device or on the host.  Same arguments, same results as w2_matmul_a8_fused
+ * called with a workspace of that size (bit for bit).
+ *   - The int8 rows and their scales must fit: M*K + 4*M (rounded up to 256)
+ *     <= W2_NOALLOC_SCRATCH_MIB MiB, else W2_ERR_BUFFER_TOO_SMALL and nothing is
+ *     launched.  What remains is offered to the tiled kernel for split-K.
+ *   - Every call on a GPU shares that GPU's buffer: calls that may overlap on one
+ *     GPU (different streams, different host threads) race; calls on one stream,
+ *     or ordered by events, do not.  The buffer keeps the last call's contents;
+ *     nothing in it needs clearing, every byte read was written by the same call.
+ *   - The buffer's address is looked up once per GPU, by the first call there or
+ *     by w2_init() (call it, with the device current, before a graph capture that
+ *     contains the first call). */
+#define W2_NOALLOC_SCRATCH_MIB 24
+W2_API int w2_init(void);
+W2_API int w2_matmul_a8_fused_noalloc(const void* packed, int64_t K, int64_t N, int G, const void* X,
+                                      w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                                      void* stream);
 
 /* Fused epilogues (Sec. II-D: further operations such as a bias addition or a
  * post-GEMM activation function are applied while the outputs are still in

@@ -36,6 +36,8 @@ _SIGS = {
     "w2_matmul_a8": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _sz, _vp],
     "w2_matmul_a8_ex": [_vp, _i64, _i64, _int, _vp, _vp, _i64, _vp, _i64, _vp, _sz, _vp, _vp],
     "w2_matmul_a8_fused": [_vp, _i64, _i64, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp, _sz, _vp],
+    "w2_init": [],
+    "w2_matmul_a8_fused_noalloc": [_vp, _i64, _i64, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp],
     "w2_matmul_a16": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _sz, _vp],
     "w2_matmul_a16_ex": [_vp, _i64, _i64, _int, _vp, _i64, _i64, _vp, _i64, _vp, _sz, _vp, _vp],
     "w2_workspace_size": [_i64, _i64, _i64, _int, _int, ctypes.POINTER(_sz)],
@@ -288,6 +290,34 @@ def matmul_a8_fused(packed, K, N, G, X, out=None, workspace=None):
     _check("w2_matmul_a8_fused", _lib.w2_matmul_a8_fused(_ptr(packed), K, N, G, _ptr(X), dt, ldx, M,
                                                          _ptr(Y), ldy, ws, ws_bytes, _stream()))
     return Y
+
+
+NOALLOC_SCRATCH_BYTES = 24 << 20
+
+
+def init():
+    """Resolves the built-in scratch buffer's address on the current device (optional; see the header)."""
+    _check("w2_init", _lib.w2_init())
+
+
+def matmul_a8_fused_noalloc(packed, K, N, G, X, out):
+    """matmul_a8_fused out of the library's built-in scratch buffer: the call allocates nothing, so `out`
+    (bf16 [M,N]) is required."""
+    if X.dtype == torch.float32:
+        dt = DT_F32
+    elif X.dtype == torch.bfloat16:
+        dt = DT_BF16
+    else:
+        raise ValueError("X must be float32 or bfloat16")
+    if not X.is_cuda or X.dim() != 2 or X.shape[1] != K or X.stride(1) != 1:
+        raise ValueError("X must be a device tensor [M,K] with unit inner stride")
+    M = X.shape[0]
+    _dev(out, torch.bfloat16, "out")
+    ldx = X.stride(0) if M > 1 else K
+    ldy = out.stride(0) if M > 1 else N
+    _check("w2_matmul_a8_fused_noalloc", _lib.w2_matmul_a8_fused_noalloc(_ptr(packed), K, N, G, _ptr(X), dt, ldx, M,
+                                                                         _ptr(out), ldy, _stream()))
+    return out
 
 
 def matmul_a16(packed, K, N, G, X, out=None, variant=VARIANT_AUTO, workspace=None, tune=None):

@@ -7,7 +7,6 @@
 #include <string.h>
 
 #include <mutex>
-#include <vector>
 
 #include "../../include/w2mm.h"
 #include "w2_internal.h"
@@ -37,7 +36,9 @@ int check_launch(const char* what)
 namespace {
 struct LdsGrant { const void* kern; int dev; size_t bytes; };
 std::mutex g_lds_mutex;
-std::vector<LdsGrant> g_lds_grants;
+constexpr int MAX_LDS_GRANTS = 512;         // fixed table: the bookkeeping never allocates
+LdsGrant g_lds_grants[MAX_LDS_GRANTS];
+int g_n_lds_grants = 0;
 }  // namespace
 
 int ensure_dynamic_lds(const void* kern, size_t bytes, const char* what)
@@ -47,8 +48,8 @@ int ensure_dynamic_lds(const void* kern, size_t bytes, const char* what)
     if (hipGetDevice(&dev) != hipSuccess) dev = 0;
     std::lock_guard<std::mutex> lock(g_lds_mutex);
     LdsGrant* g = nullptr;
-    for (auto& e : g_lds_grants)
-        if (e.kern == kern && e.dev == dev) { g = &e; break; }
+    for (int i = 0; i < g_n_lds_grants; ++i)
+        if (g_lds_grants[i].kern == kern && g_lds_grants[i].dev == dev) { g = &g_lds_grants[i]; break; }
     if (g && g->bytes >= bytes) return W2_OK;
     const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) {
@@ -56,8 +57,8 @@ int ensure_dynamic_lds(const void* kern, size_t bytes, const char* what)
         return W2_ERR_HIP;
     }
     if (g) g->bytes = bytes;
-    else g_lds_grants.push_back({kern, dev, bytes});
-    return W2_OK;
+    else if (g_n_lds_grants < MAX_LDS_GRANTS) g_lds_grants[g_n_lds_grants++] = {kern, dev, bytes};
+    return W2_OK;                                            // a full table only means the call is repeated next time
 }
 
 // Streaming-read probe.  Each wave reads U consecutive 1 KiB chunks (one
@@ -370,6 +371,68 @@ int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const vo
 {
     return a8_fused_common("w2_matmul_a8_fused", packed, K, N, G, X, x_dtype, ldx, M, Y, ldy, workspace,
                            workspace_bytes, nullptr, stream, Epilogue());
+}
+
+// ---- the entry point that allocates nothing -------------------------------------------------
+// The scratch memory w2_matmul_a8_fused otherwise takes from the caller's workspace (the int8 rows,
+// their scales, split-K partial results) lives in this array: device memory that exists from the
+// moment the library's code object is loaded on a GPU until the process ends, one copy per GPU.
+// In host code the array's name is only a handle for hipGetSymbolAddress; the address it returns
+// (per device) is what kernels and copies get.
+constexpr size_t W2_SCRATCH_BYTES = (size_t)W2_NOALLOC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[W2_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+}  // namespace
+
+// Device address of `scratch` on the current device, resolved once per device.
+static int scratch_address(const char* fn, void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(W2_ERR_HIP, "%s: hipGetDevice: %s", fn, hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(W2_ERR_HIP, "%s: device ordinal %d not supported", fn, dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(W2_ERR_HIP, "%s: hipGetSymbolAddress(scratch): %s", fn, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return W2_OK;
+}
+
+int w2_init(void)
+{
+    void* p;
+    return scratch_address("w2_init", &p);
+}
+
+int w2_matmul_a8_fused_noalloc(const void* packed, int64_t K, int64_t N, int G, const void* X,
+                               w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
+                               void* stream)
+{
+    const char* fn = "w2_matmul_a8_fused_noalloc";
+    int rc = check_shape(fn, K, N, G);
+    if (rc) return rc;
+    if (M < 0) return fail(W2_ERR_INVALID_ARG, "%s: M < 0", fn);
+    if (M > ((int64_t)1 << 24)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: M is limited to 2^24", fn);
+    // the quantised rows and their scales must fit the built-in scratch (what is left goes to split-K)
+    const size_t need = M > 0 ? fused_workspace_bytes(M, K) : 0;
+    if (need > W2_SCRATCH_BYTES)
+        return fail(W2_ERR_BUFFER_TOO_SMALL,
+                    "%s: M*K = %lld needs %zu bytes of scratch, the built-in buffer holds %zu "
+                    "(use w2_matmul_a8_fused with a workspace)", fn, (long long)(M * K), need, W2_SCRATCH_BYTES);
+    void* ws = nullptr;
+    rc = scratch_address(fn, &ws);
+    if (rc) return rc;
+    return a8_fused_common(fn, packed, K, N, G, X, x_dtype, ldx, M, Y, ldy, ws, W2_SCRATCH_BYTES, nullptr, stream,
+                           Epilogue());
 }
 
 int w2_matmul_a8_fused_epi(const void* packed, int64_t K, int64_t N, int G, const void* X,
