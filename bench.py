@@ -449,9 +449,9 @@ def main():
                                              "previous call's bf16 output (attention, norms and residuals left out)",
                                      "gpu_ms_per_step": round(chained_ms, 5),
                                      "GBps": round(chained_bytes / (chained_ms * 1e-3) / 1e9, 1)}},
-        "roofline": {"bound": "hbm", "kernel": "a8_fusedq_kernel (quantise + int8 MFMA GEMV + dequant) on gate+up 4096x28672, M=1",
+        "roofline": {"bound": "hbm", "kernel": "a8_gemv_kernel, fp32 row in (quantise + int8 MFMA GEMV + dequant) on gate+up 4096x28672, M=1",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic("a8_fusedq gate_up M=1"),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic("a8_gemv gate_up M=1"),
                      "us_per_launch": round(gemv_us, 3), "bytes_per_launch": gemv_bytes,
                      "stream_read_us_same_bytes": round(read_us, 3),
                      "frac_of_stream_read": round(read_us / gemv_us, 4),

@@ -87,7 +87,8 @@ typedef enum {
  * AUTO's choice for prefill.  Needs bf16 scales with an exponent field below
  * 254 (-2 sw is made by raising the exponent by one). */
 typedef enum { W2_VARIANT_AUTO = 0, W2_VARIANT_DOT4 = 1, W2_VARIANT_SMALLM = 2,
-               W2_VARIANT_TILED = 3, W2_VARIANT_MIDM = 4, W2_VARIANT_SCALED16 = 5 } w2_variant_t;
+               W2_VARIANT_TILED = 3, W2_VARIANT_MIDM = 4, W2_VARIANT_SCALED16 = 5,
+               W2_VARIANT_GEMV = 6 } w2_variant_t;
 
 /* Overrides of the library's own choices, for tests and tuning sweeps; taken by
  * the *_ex / *_epi entry points, the debug export and the probe.  A NULL pointer,
@@ -99,10 +100,10 @@ typedef struct {
     int dot4_max_m;       /* w2a8 AUTO: largest M given to DOT4 (1..4; default: never) */
     int midm_min_m;       /* AUTO: smallest / largest M given to MIDM (1..256) */
     int midm_max_m;
-    int small_waves;      /* DOT4, SMALLM, fused kernel: waves per workgroup, 1..16 */
+    int small_waves;      /* GEMV, DOT4, SMALLM: waves per workgroup, 1..16 */
     int small_cbw;        /* ... column blocks per workgroup: 1, 2, 4, 8 or 16, at most the waves */
     int small_kc;         /* ... k per local-memory chunk of the activations: a multiple of 256 */
-    int fused_pre;        /* fused kernel, one row, large projections: weight tiles a wave requests before the row is quantised: 4 or 8 */
+    int gemv_window;      /* GEMV: weight tiles a wave keeps in flight: 2, 4 or 8 */
     int midm_cbw;         /* MIDM: column blocks per workgroup: 2, 4 or 8 */
     int tiled_bn;         /* TILED / SCALED16 tiled kernels: columns per workgroup: 128 or 256 */
     int tiled_group_m;    /* ... row tiles per band of the workgroup order: 1..1024 */

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libw2mm.so")
 CODEC_INT2, CODEC_TERNARY = 0, 1
 DT_F32, DT_BF16 = 0, 1
 VARIANT_AUTO, VARIANT_DOT4, VARIANT_SMALLM, VARIANT_TILED, VARIANT_MIDM, VARIANT_SCALED16 = 0, 1, 2, 3, 4, 5
+VARIANT_GEMV = 6
 
 OK = 0
 ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED = -1, -2, -3
@@ -146,7 +147,7 @@ def quantize_rows(X, G=128, want_gsum=False):
 class Tuning(ctypes.Structure):
     """w2_tuning_t: overrides for tests and sweeps; every field 0 = the library's own rule."""
     _fields_ = [(n, ctypes.c_int) for n in (
-        "variant", "dot4_max_m", "midm_min_m", "midm_max_m", "small_waves", "small_cbw", "small_kc", "fused_pre",
+        "variant", "dot4_max_m", "midm_min_m", "midm_max_m", "small_waves", "small_cbw", "small_kc", "gemv_window",
         "midm_cbw", "tiled_bn", "tiled_group_m", "splitk", "splitk_min_tiles", "stream_unroll", "stream_blocks")]
 
 

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libw2mm.so")
 SOURCES = ["api.hip", "prepack.hip", "quantize.hip", "matmul_a8_small.hip",
-           "matmul_a8_midm.hip", "matmul_a8_tiled.hip", "matmul_a8_fusedq.hip", "matmul_a16.hip", "matmul_a16_fold.hip", "matmul_a16_midm.hip",
+           "matmul_a8_midm.hip", "matmul_a8_tiled.hip", "matmul_a8_gemv.hip", "matmul_a16.hip", "matmul_a16_fold.hip", "matmul_a16_midm.hip",
            "comparators.hip", "splitk.hip"]
 HEADERS = ["w2_layout.h", "w2_internal.h", "w2_small_common.h", os.path.join("..", "..", "include", "w2mm.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -147,14 +147,14 @@ static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
         return v == 0 || v == a || v == b || (c && v == c) || (d && v == d) || (e && v == e);
     };
     const char* bad = nullptr;
-    if (t->variant < W2_VARIANT_AUTO || t->variant > W2_VARIANT_SCALED16) bad = "variant";
+    if (t->variant < W2_VARIANT_AUTO || t->variant > W2_VARIANT_GEMV) bad = "variant";
     else if (!in(t->dot4_max_m, 1, 4)) bad = "dot4_max_m";
     else if (!in(t->midm_min_m, 1, 256)) bad = "midm_min_m";
     else if (!in(t->midm_max_m, 1, 256)) bad = "midm_max_m";
     else if (!in(t->small_waves, 1, 16)) bad = "small_waves";
     else if (!one_of(t->small_cbw, 1, 2, 4, 8, 16)) bad = "small_cbw";
     else if (t->small_kc < 0 || t->small_kc % TILE_K) bad = "small_kc";
-    else if (!one_of(t->fused_pre, 4, 8)) bad = "fused_pre";
+    else if (!one_of(t->gemv_window, 2, 4, 8)) bad = "gemv_window";
     else if (!one_of(t->midm_cbw, 2, 4, 8)) bad = "midm_cbw";
     else if (!one_of(t->tiled_bn, 128, 256)) bad = "tiled_bn";
     else if (!in(t->tiled_group_m, 1, 1024)) bad = "tiled_group_m";
@@ -231,7 +231,7 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     if (rc) return rc;
     int variant = tn.variant;
     const int64_t n_out = epi.act == ACT_SILU_MUL ? N / 2 : N;
-    if (variant > W2_VARIANT_MIDM)
+    if (variant == W2_VARIANT_SCALED16)
         return fail(W2_ERR_INVALID_ARG, "%s: variant %d not available for w2a8", fn, variant);
     if (M == 0) return W2_OK;
     if (!packed || !xq) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
@@ -270,12 +270,20 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         // 66 us against 50 us through the tiled kernel)
         const int midm_max = tn.midm_max_m ? tn.midm_max_m : a.n_cb <= 512 ? 128 : a.n_cb >= 2048 ? 48 : 64;
         variant = M <= dot4_max && a8_dot4_supports(a)                       ? W2_VARIANT_DOT4
+                : a8_gemv_supports(M)                                        ? W2_VARIANT_GEMV
                 : M >= midm_min && M <= midm_max && a8_midm_supports(a)     ? W2_VARIANT_MIDM
                 : a8_smallm_supports(a)                                      ? W2_VARIANT_SMALLM
                                                                              : W2_VARIANT_TILED;
     }
     hipStream_t s = (hipStream_t)stream;
     switch (variant) {
+    case W2_VARIANT_GEMV: {
+        if (!a8_gemv_supports(M)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: GEMV needs M <= 4", fn);
+        rc = launch_a8_gemv(a, xq, 0, K, s);
+        // rows too long for one workgroup's local memory: the small-M kernel stages them in chunks
+        if (rc != W2_ERR_UNSUPPORTED_SHAPE || tn.variant == W2_VARIANT_GEMV) return rc;
+        return launch_a8_smallm(a, s);
+    }
     case W2_VARIANT_DOT4:
         if (!a8_dot4_supports(a)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: DOT4 needs M <= 4", fn);
         return launch_a8_dot4(a, s);
@@ -345,8 +353,13 @@ static int a8_fused_common(const char* fn, const void* packed, int64_t K, int64_
         if (M > 4 && workspace)
             return fail(W2_ERR_BUFFER_TOO_SMALL, "%s: M = %lld needs a workspace of %zu bytes (w2_workspace_size)",
                         fn, (long long)M, fused_workspace_bytes(M, K));
-        rc = launch_a8_fusedq(packed, (const char*)packed + L.codes_bytes, X, x_dtype == W2_DT_BF16, ldx,
-                              M, K, N, G, L.n_cb, L.n_kt, Y, ldy, epi, tn, (hipStream_t)stream);
+        A8Args a;
+        a.codes = (const uint32_t*)packed;
+        a.scales = (const uint16_t*)((const char*)packed + L.codes_bytes);
+        a.xq = nullptr; a.sx = nullptr; a.Y = Y; a.acc_out = nullptr;
+        a.M = M; a.K = K; a.N = N; a.ldy = ldy; a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
+        a.epi = epi; a.tune = tn;
+        rc = launch_a8_gemv(a, X, x_dtype == W2_DT_BF16 ? 2 : 1, ldx, (hipStream_t)stream);
         if (rc != W2_ERR_UNSUPPORTED_SHAPE || !ws_ok) return rc;
     }
     int8_t* xq = (int8_t*)workspace;

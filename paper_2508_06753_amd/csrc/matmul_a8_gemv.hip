@@ -1,0 +1,522 @@
+// w2a8 for one to four rows (decode): the memory-bound regime, where time
+// tracks the bytes of weight streamed (Sec. I, II-A) and the job of the kernel
+// is to keep the vector work per streamed code word below what the memory
+// system delivers (Sec. II-E: effective bandwidth = min(beta, B / gamma)).
+// One kernel serves both entry points:
+//   - int8 rows in (w2_matmul_a8, after w2_quantize_rows);
+//   - fp32 / bf16 rows in, quantised in the kernel (w2_matmul_a8_fused; Sec.
+//     II-D: on a GPU the separate quantise -> GEMM -> dequantise sequence costs
+//     launches and passes, so the abs-max is computed per workgroup,
+//     redundantly, kept in local memory, the rows are quantised in the kernel
+//     and the result is dequantised before the store; Sec. III-C: fusing wins
+//     for matrix-vector shapes).  The arithmetic is that of w2_quantize_rows
+//     value for value (one rounded multiply by 127/amax, round half to even),
+//     so both routes give the same bits.
+//
+// "Up-convert and compute" (Sec. II-C): a lane reads 128 bits of packed 2-bit
+// weights, one shift + one mask per four weights make int8 operands, and
+// v_mfma_i32_16x16x64_i8 multiplies them with the (at most four live) rows.
+//
+// Schedule.  A wave owns one 16-column block and a CONTIGUOUS run of its 256-k
+// tiles (K is split across the waves of a workgroup, Sec. II-D; partial sums
+// meet in LDS in a fixed order).  The tiles of the run pass through a rolling
+// window of W register slots: the load of tile i+W is issued the moment tile i
+// has been consumed, so the arithmetic of a tile runs while the following ones
+// are in flight and what remains after the last byte has arrived is one tile's
+// work.  Every load is unconditional, so the compiler can count the loads in
+// flight and waits for exactly the slot it needs; they are buffer loads whose
+// resource spans exactly the wave's run (the row, for the activations): a slot
+// past the end is out of range, which the hardware answers with zeros without
+// touching memory (measured: dummy loads aimed at one shared line instead cost
+// a microsecond, every wave of the grid queueing on it).  Addresses are
+// "resource + scalar offset + lane offset": the loop needs no vector address
+// arithmetic and no division.
+#include <hip/hip_runtime.h>
+
+#include "w2_small_common.h"
+
+// Timeline probe for instrumented builds (a working build defines it to record a timestamp per wave);
+// expands to nothing in the library.
+#ifndef W2_GEMV_MARK
+#define W2_GEMV_MARK(i)
+#define W2_GEMV_MARK_DECL
+#endif
+
+namespace w2 {
+
+namespace gemv {
+
+constexpr int HDR = 512;          // LDS: abs-max partials [16 waves][4 rows] fp32, then padding
+constexpr int XSLOTS = 8;         // most 16-byte pieces of the activation rows a thread holds in registers
+
+struct Args {
+    const uint32_t* codes;
+    const uint16_t* scales;
+    const void* X;                // XT 0: int8 [M][K] dense; 1: fp32 rows; 2: bf16 rows (row stride ldx elements)
+    const float* sx;              // XT 0: activation scales [M]
+    uint16_t* Y;
+    int32_t* acc_out;             // debug export (XT 0)
+    int64_t ldx, ldy, N;
+    int K, M, n_cb, n_kt;
+    int cbw_shift, cbw, ks;       // waves of a workgroup = cbw column blocks x ks k-ranges
+    int t_lo, t_rem;              // tiles per k-range: t_lo, and one more for the first t_rem ranges
+    int red_off;                  // LDS offset of the reduction scratch
+    int sc_off;                   // LDS offset of the waves' scale slices
+    Epilogue epi;
+};
+
+constexpr int MAX_RUN = 16;       // most tiles in a wave's run: their scales are fetched in one go
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Raw buffer resource over [base, base + bytes): loads at or past `bytes` return zeros and move nothing.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+constexpr int AUX_NT = 2;         // non-temporal: the weights are streamed once
+
+__device__ __forceinline__ u32x4 load_tile(__amdgpu_buffer_rsrc_t wr, int w_lane, int i)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(wr, w_lane, i * TILE_BYTES, AUX_NT);
+}
+
+// x * inv, one rounding, then round half to even by adding 1.5 * 2^23 (one more rounding: exact for
+// |t| < 2^22): the low byte of the sum's bit pattern is the int8 code.  |x * inv| never exceeds
+// 127.00001 for finite inputs (|x| <= amax, inv = RN(127 / amax)), so the clamp of the definition
+// never acts and is left out.
+__device__ __forceinline__ uint32_t quant_bits(float x, float inv)
+{
+#pragma clang fp contract(off)                               // two roundings, as defined: never one fused multiply-add
+    const float t = x * inv;
+    return __float_as_uint(t + 12582912.0f);
+}
+
+__device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    // low bytes of a, b, c, d -> one dword
+    const uint32_t lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);   // {a.b0, b.b0, 0, 0}
+    const uint32_t hi = __builtin_amdgcn_perm(d, c, 0x04000c0cu);   // {0, 0, c.b0, d.b0}
+    return lo | hi;
+}
+
+// NP: 16-byte pieces per row and thread (a launch-time choice: the row's pieces / the workgroup's threads, rounded up)
+template <int G, int RL, int XT, int W, int NP, bool DBG>
+__global__ void __launch_bounds__(1024)
+a8_gemv_kernel(Args a)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    constexpr int GPT = TILE_K / G;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_waves = __builtin_amdgcn_readfirstlane((int)blockDim.x >> 6);
+    const int threads = n_waves * 64;
+    const int cbi = wave & (a.cbw - 1), ksi = wave >> a.cbw_shift;
+    const int q = lane >> 4, l16 = lane & 15;
+    const int cb = (int)blockIdx.x * a.cbw + cbi;
+    const bool cb_ok = cb < a.n_cb;
+    const int cbc = cb_ok ? cb : a.n_cb - 1;                 // clamp: keeps loads in bounds
+    const int kt_b = ksi * a.t_lo + min(ksi, a.t_rem);       // this wave's run of tiles
+    const int T = a.t_lo + (ksi < a.t_rem ? 1 : 0);
+    const int row_stride = a.K + XS_PAD;
+    float* s_red = reinterpret_cast<float*>(smem);           // [16 waves][4 rows]
+    int8_t* xs = smem + HDR;                                 // int8 rows
+
+    W2_GEMV_MARK_DECL;
+    W2_GEMV_MARK(0);
+    // ---- 1. the activation rows: unconditional vector loads, issued before the weight loads
+    constexpr int ES = XT == 1 ? 4 : XT == 2 ? 2 : 1;        // bytes per source element
+    constexpr int PR = NP;                                   // register slots per row
+    static_assert(NP * RL <= XSLOTS, "too many register slots");
+    const int ppr = a.K * ES / 16;                           // 16-byte pieces per row
+    uint4 pc[RL][PR];
+#pragma unroll
+    for (int r = 0; r < RL; ++r) {
+        const int rr = r < a.M ? r : a.M - 1;
+        const __amdgpu_buffer_rsrc_t xr =
+            make_rsrc(reinterpret_cast<const char*>(a.X) + (int64_t)rr * a.ldx * ES, (uint32_t)a.K * ES);
+#pragma unroll
+        for (int j = 0; j < PR; ++j) {                       // pieces past the end of the row: out of range, zeros
+            const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(xr, (tid + j * threads) * 16, 0, 0);
+            pc[r][j] = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+    }
+    float sxv[RL];
+    if constexpr (XT == 0) {
+#pragma unroll
+        for (int r = 0; r < RL; ++r) sxv[r] = DBG ? 0.f : a.sx[r < a.M ? r : a.M - 1];
+    }
+
+    // ---- 2. the first W tiles of the weight stream
+    const int64_t tile0 = (int64_t)cbc * a.n_kt + kt_b;
+    const __amdgpu_buffer_rsrc_t wr =                        // exactly this wave's run: tiles [0, T)
+        make_rsrc(reinterpret_cast<const char*>(a.codes) + tile0 * TILE_BYTES, (uint32_t)T * TILE_BYTES);
+    // The scales of the whole run, [T][16 columns][GPT] bf16, are contiguous: one 16-byte load per lane
+    // (two for G = 64) fetches up to 16 tiles' worth, parked in this wave's LDS slice and read back per tile
+    // (measured: one small scale load per tile, a second memory request per KiB of codes, cost 0.4 to 0.9 us
+    // on 4096 x 28672).
+    constexpr int SPT = TILE_N * GPT * 2;                    // bytes of scales per tile: 64 or 128
+    constexpr int NSL = MAX_RUN * SPT / 1024;                // 16-byte loads per lane: 1 or 2
+    const __amdgpu_buffer_rsrc_t sr =
+        make_rsrc(reinterpret_cast<const char*>(a.scales) + tile0 * SPT, (uint32_t)T * SPT);
+    const int w_lane = lane * 16;
+    u32x4 tr[W];
+    auto issue = [&](int i, u32x4& dst) {                    // i: tile of the run (uniform); past the end: zeros, no traffic
+        dst = load_tile(wr, w_lane, i);
+    };
+    u32x4 sc_regs[NSL];
+#pragma unroll
+    for (int j = 0; j < NSL; ++j) sc_regs[j] = __builtin_amdgcn_raw_buffer_load_b128(sr, w_lane + j * 1024, 0, 0);
+#pragma unroll
+    for (int u = 0; u < W; ++u) issue(u, tr[u]);
+    W2_GEMV_MARK(1);
+
+    // ---- 3. quantise (or copy) the rows into LDS
+    if constexpr (XT == 0) {
+#pragma unroll
+        for (int r = 0; r < RL; ++r)
+#pragma unroll
+            for (int j = 0; j < PR; ++j) {
+                const int i = tid + j * threads;
+                if (i < ppr && r < a.M) *reinterpret_cast<uint4*>(xs + r * row_stride + i * 16) = pc[r][j];
+            }
+    } else {
+        float amax[RL];
+#pragma unroll
+        for (int r = 0; r < RL; ++r) {
+            float m = 0.f;
+#pragma unroll
+            for (int j = 0; j < PR; ++j) {
+                const uint32_t d[4] = {pc[r][j].x, pc[r][j].y, pc[r][j].z, pc[r][j].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if constexpr (XT == 2) {
+                        m = fmaxf(m, fabsf(__uint_as_float(d[e] << 16)));
+                        m = fmaxf(m, fabsf(__uint_as_float(d[e] & 0xffff0000u)));
+                    } else {
+                        m = fmaxf(m, fabsf(__uint_as_float(d[e])));
+                    }
+                }
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+            amax[r] = m;
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int r = 0; r < RL; ++r) s_red[wave * 4 + r] = amax[r];
+        }
+        __syncthreads();
+        float inv[RL];
+#pragma unroll
+        for (int r = 0; r < RL; ++r) {
+            float m = 0.f;
+            for (int w = 0; w < n_waves; ++w) m = fmaxf(m, s_red[w * 4 + r]);
+            inv[r] = 0.f; sxv[r] = 0.f;
+            if (m > 0.f) {
+                inv[r] = __fdiv_rn(127.0f, m);
+                sxv[r] = __fdiv_rn(m, 127.0f);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RL; ++r)
+#pragma unroll
+            for (int j = 0; j < PR; ++j) {
+                const int i = tid + j * threads;
+                if (i < ppr && r < a.M) {
+                    const uint32_t d[4] = {pc[r][j].x, pc[r][j].y, pc[r][j].z, pc[r][j].w};
+                    if constexpr (XT == 2) {
+                        uint32_t b[8];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            b[2 * e] = quant_bits(__uint_as_float(d[e] << 16), inv[r]);
+                            b[2 * e + 1] = quant_bits(__uint_as_float(d[e] & 0xffff0000u), inv[r]);
+                        }
+                        *reinterpret_cast<uint2*>(xs + r * row_stride + i * 8) =
+                            make_uint2(pack4(b[0], b[1], b[2], b[3]), pack4(b[4], b[5], b[6], b[7]));
+                    } else {
+                        *reinterpret_cast<uint32_t*>(xs + r * row_stride + i * 4) =
+                            pack4(quant_bits(__uint_as_float(d[0]), inv[r]), quant_bits(__uint_as_float(d[1]), inv[r]),
+                                  quant_bits(__uint_as_float(d[2]), inv[r]), quant_bits(__uint_as_float(d[3]), inv[r]));
+                    }
+                }
+            }
+    }
+    // this wave's scales -> its LDS slice (read back by the same wave only: LDS operations of a wave complete in order)
+    int8_t* sc_lds = smem + a.sc_off + wave * (MAX_RUN * SPT);
+#pragma unroll
+    for (int j = 0; j < NSL; ++j) *reinterpret_cast<u32x4*>(sc_lds + j * 1024 + w_lane) = sc_regs[j];
+    __syncthreads();
+    W2_GEMV_MARK(2);
+
+    // ---- 4. the stream: up-convert and compute
+    float y[RL];
+#pragma unroll
+    for (int r = 0; r < RL; ++r) y[r] = 0.f;
+    // Two accumulators alternate between groups; a finished group is dequantised after the next
+    // group's first matrix instruction has been issued, so its int -> float conversion does not wait
+    // for the matrix pipe.
+    v4i acc[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    float pend_sw = 0.f;                                     // scale of the group waiting in acc[1]: none yet
+    int pend_g = -1;                                         // its index (debug export)
+    auto dequant = [&](int b) {
+#pragma unroll
+        for (int r = 0; r < RL; ++r) {
+            if constexpr (DBG) {
+                const int64_t n = (int64_t)cb * TILE_N + l16;
+                if (pend_g >= 0 && q == 0 && cb_ok && n < a.N && r < a.M)
+                    a.acc_out[((int64_t)r * (a.K / G) + pend_g) * a.N + n] = acc[b][r] >> 6;
+            }
+            y[r] = fmaf(pend_sw, (float)acc[b][r], y[r]);
+        }
+    };
+    // LDS address of this lane's A operand: row (lane & 15, padded rows repeat the last), 16-byte piece lane >> 4
+    const int arow = l16 < a.M ? l16 : a.M - 1;
+    const uint32_t a_lane = (uint32_t)(HDR + arow * row_stride + q * 16);
+    auto read_aop = [&](int kt, v4i (&aop)[4]) {
+        const int8_t* p = smem + a_lane + (uint32_t)kt * TILE_K;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) aop[t] = *reinterpret_cast<const v4i*>(p + t * 64);
+    };
+    const int8_t* sc_lane = sc_lds + l16 * (GPT * 2);
+    auto read_scales = [&](int i, uint32_t (&sc)[2]) {       // tile i of the run
+        if constexpr (G == 128) {
+            sc[0] = *reinterpret_cast<const uint32_t*>(sc_lane + i * SPT);
+            sc[1] = 0;
+        } else {
+            const uint2 t = *reinterpret_cast<const uint2*>(sc_lane + i * SPT);
+            sc[0] = t.x; sc[1] = t.y;
+        }
+    };
+    auto compute = [&](int kt, const u32x4& cur, const uint32_t (&sc)[2], const v4i (&aop)[4]) {
+        const uint32_t wd[4] = {cur[0], cur[1], cur[2], cur[3]};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            int u[4];
+            upconvert(wd[t], u);
+            const v4i bop = {u[0], u[1], u[2], u[3]};
+            const int gi = G == 64 ? t : t >> 1;             // group inside the tile
+            const int b = gi & 1;                            // its accumulator (groups per tile are even)
+            const bool first = G == 64 || !(t & 1);
+            const v4i zero = {0, 0, 0, 0};
+            acc[b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[t], bop, first ? zero : acc[b], 0, 0, 0);
+            if (first) dequant(b ^ 1);                       // the group before this one
+            if (G == 64 || (t & 1)) {
+                const uint32_t pair = (G == 128 || gi < 2) ? sc[0] : sc[1];
+                pend_sw = (gi & 1) ? __uint_as_float(pair & 0xffff0000u) : __uint_as_float(pair << 16);
+                pend_g = kt * GPT + gi;
+            }
+        }
+    };
+    v4i aop[2][4];
+    uint32_t scl[2][2];
+    read_aop(kt_b, aop[0]);
+    read_scales(0, scl[0]);
+    for (int base = 0; base < T; base += W) {
+#pragma unroll
+        for (int u = 0; u < W; ++u) {
+            const int i = base + u;
+            // the slot is refilled before its tile is multiplied (the tile moves to other registers): a wave's
+            // requests stay W deep while it computes, instead of W - 1 and a gap
+            const u32x4 cur = tr[u];
+            issue(i + W, tr[u]);                             // unconditional: keeps the count of loads in flight static
+            if (i < T) {                                     // uniform
+                read_aop(kt_b + min(i + 1, T - 1), aop[(u + 1) & 1]);     // a tile ahead; clamped: stays inside the rows
+                read_scales(min(i + 1, T - 1), scl[(u + 1) & 1]);
+                compute(kt_b + i, cur, scl[u & 1], aop[u & 1]);
+                if (i == 0) { W2_GEMV_MARK(3); }
+            }
+        }
+    }
+    dequant(1);                                              // the last group (it sits in acc[1])
+    W2_GEMV_MARK(4);
+    if constexpr (DBG) return;
+
+    // ---- 5. reduce the k-ranges through LDS (fixed order), dequantise, store
+    float* red = reinterpret_cast<float*>(smem + a.red_off);   // [waves][RL][16]; its own region: no barrier before the writes
+    if (q == 0) {
+#pragma unroll
+        for (int r = 0; r < RL; ++r) red[(wave * RL + r) * 16 + l16] = y[r];
+    }
+    __syncthreads();
+    W2_GEMV_MARK(5);
+    const bool gated = a.epi.act == ACT_SILU_MUL;
+    const int outs = gated ? (a.cbw >> 1) * 16 : a.cbw * 16;
+    if (tid < outs) {
+        const int nl = tid & 15, ci = tid >> 4;
+        auto z = [&](int c, int r) {                         // finished fp32 result of column block c, row r
+            float s = 0.f;
+            for (int k = 0; k < a.ks; ++k) s += red[(((k << a.cbw_shift) + c) * RL + r) * 16 + nl];
+            return s * (sxv[r] * 0.015625f);
+        };
+        if (!gated) {
+            const int64_t nn = ((int64_t)blockIdx.x * a.cbw + ci) * TILE_N + nl;
+            if (nn < a.N) {
+                const float bias = a.epi.bias ? bf16_to_f32(a.epi.bias[nn]) : 0.f;
+#pragma unroll
+                for (int r = 0; r < RL; ++r) {
+                    if (r < a.M) {
+                        float v = z(ci, r) + bias;
+                        if (a.epi.act == ACT_SILU) v = silu_f32(v);
+                        a.Y[(int64_t)r * a.ldy + nn] = f32_to_bf16_rne(v);
+                    }
+                }
+            }
+        } else {
+            const int64_t first_cb = (int64_t)blockIdx.x * a.cbw;           // even
+            const int64_t ng = (first_cb + 2 * ci) * TILE_N + nl, nu = ng + TILE_N;
+            if (nu < a.N) {                                  // N % 32 == 0: both or neither
+                const float bg = a.epi.bias ? bf16_to_f32(a.epi.bias[ng]) : 0.f;
+                const float bu = a.epi.bias ? bf16_to_f32(a.epi.bias[nu]) : 0.f;
+#pragma unroll
+                for (int r = 0; r < RL; ++r) {
+                    if (r < a.M) {
+                        const float g = z(2 * ci, r) + bg, u = z(2 * ci + 1, r) + bu;
+                        a.Y[(int64_t)r * a.ldy + ((first_cb >> 1) + ci) * TILE_N + nl] = f32_to_bf16_rne(silu_f32(g) * u);
+                    }
+                }
+            }
+        }
+    }
+    W2_GEMV_MARK(6);
+}
+
+// Workgroup shape: waves = cbw column blocks x ks k-ranges.  Rules from graph-timed sweeps over the 8B-
+// and 27B-class projections at M = 1 (waves per workgroup 4 / 8 / 16, every split, windows 2 / 4 / 8):
+//   - K is split (ks, a power of two) until the grid has at least 2048 waves, two per SIMD: 4096 x 4096 and
+//     4096 x 6144 want ks = 8 (runs of two tiles), 4096 x 28672 ks = 2 (runs of eight), 14336 x 4096 ks = 8
+//     (runs of seven); more waves than that only add per-wave fixed work, fewer leave the memory system short
+//     of requests;
+//   - eight waves per workgroup (sixteen when ks = 16, or when the rows need the threads);
+//   - window 2 for runs of up to four tiles, 4 above (8 was never better: the stream is the bound, not depth).
+struct Cfg { int cbw, ks, window; };
+
+static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_cbw, int min_threads)
+{
+    Cfg c;
+    if (tune.small_waves || tune.small_cbw) {                // forced shape (tests, sweeps)
+        int waves = tune.small_waves ? tune.small_waves : 8;
+        int p = 1;
+        while (p * 2 <= waves) p <<= 1;                      // powers of two only
+        waves = p;
+        c.cbw = tune.small_cbw ? tune.small_cbw : waves;
+        if (c.cbw > waves) c.cbw = waves;
+        c.ks = waves / c.cbw;
+    } else {
+        int ks = 1;
+        while (ks < 16 && n_cb * ks < 2048 && n_kt / (ks * 2) >= 1) ks <<= 1;
+        while (ks < 16 && (n_kt + ks - 1) / ks > MAX_RUN) ks <<= 1;
+        c.ks = ks;
+        c.cbw = ks >= 8 ? 1 : 8 / ks;                        // eight waves; sixteen when ks = 16
+    }
+    if (even_cbw && (c.cbw & 1)) c.cbw = 2;                  // the gated epilogue pairs adjacent column blocks
+    while (c.cbw * c.ks > 16) {                              // at most 16 waves
+        if (c.ks > 1) c.ks >>= 1; else c.cbw >>= 1;
+    }
+    while (c.cbw * c.ks * 64 < min_threads && c.cbw * c.ks < 16) c.cbw <<= 1;   // the rows need the threads
+    if (c.ks > n_kt) {
+        c.ks = 1;
+        while (c.ks * 2 <= n_kt) c.ks <<= 1;
+    }
+    // a run is at most MAX_RUN tiles: split K further (fewer column blocks per workgroup, then more waves)
+    while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw > 1 && !(even_cbw && c.cbw == 2)) { c.cbw >>= 1; c.ks <<= 1; }
+    while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw * c.ks < 16) c.ks <<= 1;
+    const int64_t run = (n_kt + c.ks - 1) / c.ks;
+    c.window = tune.gemv_window ? tune.gemv_window : run > 4 ? 4 : 2;
+    return c;
+}
+
+template <int G, int RL, int XT, int NP, bool DBG>
+static int launch_w(const Args& a, const Cfg& c, size_t lds, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((a.n_cb + c.cbw - 1) / c.cbw)), block(64 * c.cbw * c.ks);
+    auto go = [&](auto kern) {
+        if (int rc = ensure_dynamic_lds((const void*)kern, lds, "w2_matmul_a8[gemv]")) return rc;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
+        return check_launch("w2_matmul_a8[gemv]");
+    };
+    if (c.window >= 8) return go(a8_gemv_kernel<G, RL, XT, 8, NP, DBG>);
+    if (c.window >= 4) return go(a8_gemv_kernel<G, RL, XT, 4, NP, DBG>);
+    return go(a8_gemv_kernel<G, RL, XT, 2, NP, DBG>);
+}
+
+template <int G, int RL, int XT, bool DBG>
+static int launch_np(const Args& a, const Cfg& c, size_t lds, int np, hipStream_t stream)
+{
+    constexpr int MAXNP = XSLOTS / RL;
+    if (np <= 1) return launch_w<G, RL, XT, 1, DBG>(a, c, lds, stream);
+    if constexpr (MAXNP >= 2) { if (np <= 2) return launch_w<G, RL, XT, 2, DBG>(a, c, lds, stream); }
+    if constexpr (MAXNP >= 4) { if (np <= 4) return launch_w<G, RL, XT, 4, DBG>(a, c, lds, stream); }
+    return launch_w<G, RL, XT, MAXNP, DBG>(a, c, lds, stream);
+}
+
+}  // namespace gemv
+
+bool a8_gemv_supports(int64_t M) { return M >= 1 && M <= 4; }
+
+// xt: 0 = int8 rows (X = xq, sx given), 1 = fp32 rows, 2 = bf16 rows.  Returns W2_ERR_UNSUPPORTED_SHAPE
+// (with a message, nothing launched) when the rows do not fit a workgroup.
+int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStream_t stream)
+{
+    using namespace gemv;
+    const int64_t M = a8.M, K = a8.K;
+    if (!a8_gemv_supports(M)) {
+        set_error("w2_matmul_a8[gemv]: M must be 1..4");
+        return W2_ERR_UNSUPPORTED_SHAPE;
+    }
+    const int rl = M <= 1 ? 1 : M <= 2 ? 2 : 4;
+    const int es = xt == 1 ? 4 : xt == 2 ? 2 : 1;
+    const int64_t ppr = K * es / 16;                         // 16-byte pieces per row
+    const int pr = XSLOTS / rl;                              // register slots per row and thread
+    const int min_threads = (int)((ppr + pr - 1) / pr);
+    const size_t xs_bytes = ((size_t)rl * (K + XS_PAD) + 15) & ~(size_t)15;
+    if (min_threads > 1024 || HDR + xs_bytes + 16 * 4 * 16 * sizeof(float) + 16 * MAX_RUN * 128 > 150 * 1024) {
+        set_error("w2_matmul_a8[gemv]: M*K too large for one workgroup (use w2_quantize_rows + w2_matmul_a8)");
+        return W2_ERR_UNSUPPORTED_SHAPE;
+    }
+    const Cfg c = pick(a8.tune, a8.n_cb, a8.n_kt, a8.epi.act == ACT_SILU_MUL, min_threads);
+    const int waves = c.cbw * c.ks;
+    if (waves * 64 < min_threads) {
+        set_error("w2_matmul_a8[gemv]: the forced workgroup shape cannot hold the activation rows");
+        return W2_ERR_UNSUPPORTED_SHAPE;
+    }
+    if ((a8.n_kt + c.ks - 1) / c.ks > MAX_RUN) {
+        set_error("w2_matmul_a8[gemv]: K too deep for this workgroup shape (a wave's run is limited to %d tiles)", MAX_RUN);
+        return W2_ERR_UNSUPPORTED_SHAPE;
+    }
+    Args a;
+    a.codes = a8.codes; a.scales = a8.scales; a.X = X; a.sx = a8.sx; a.Y = a8.Y; a.acc_out = a8.acc_out;
+    a.ldx = ldx; a.ldy = a8.ldy; a.N = a8.N; a.K = (int)K; a.M = (int)M;
+    a.n_cb = (int)a8.n_cb; a.n_kt = (int)a8.n_kt;
+    a.cbw = c.cbw; a.ks = c.ks;
+    a.cbw_shift = 0;
+    while ((1 << a.cbw_shift) < c.cbw) ++a.cbw_shift;
+    a.t_lo = (int)(a8.n_kt / c.ks); a.t_rem = (int)(a8.n_kt % c.ks);
+    a.red_off = (int)(HDR + xs_bytes);
+    a.sc_off = a.red_off + waves * rl * 16 * (int)sizeof(float);
+    a.epi = a8.epi;
+    const size_t lds = a.sc_off + (size_t)waves * MAX_RUN * (TILE_N * (TILE_K / a8.G) * 2);
+    const bool dbg = a8.acc_out != nullptr;
+    const int np = (int)((ppr + waves * 64 - 1) / (waves * 64));       // pieces per row and thread (<= XSLOTS / rl: checked above)
+#define W2_GEMV(GG, RLL)                                                                               \
+    do {                                                                                               \
+        if (dbg) return launch_np<GG, RLL, 0, true>(a, c, lds, np, stream);                            \
+        if (xt == 0) return launch_np<GG, RLL, 0, false>(a, c, lds, np, stream);                       \
+        if (xt == 1) return launch_np<GG, RLL, 1, false>(a, c, lds, np, stream);                       \
+        return launch_np<GG, RLL, 2, false>(a, c, lds, np, stream);                                    \
+    } while (0)
+    if (a8.G == 128) {
+        if (rl == 1) W2_GEMV(128, 1);
+        if (rl == 2) W2_GEMV(128, 2);
+        W2_GEMV(128, 4);
+    }
+    if (rl == 1) W2_GEMV(64, 1);
+    if (rl == 2) W2_GEMV(64, 2);
+    W2_GEMV(64, 4);
+#undef W2_GEMV
+}
+
+}  // namespace w2

@@ -348,8 +348,13 @@ static int launch_smallm_t(const A8Args& a, hipStream_t stream)
     const int rows = (int)a.M;
     const SmallCfg c = pick_cfg(a.tune, a.n_cb, a.n_kt, rows, 1, 16, a.epi.act == ACT_SILU_MUL);
     const size_t lds = small_lds_bytes(c, rows, 16, 1, 0);
-    if (a.acc_out) return launch_small(a8_smallm_kernel<G, TMAX, 4, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
     const int tpw = tiles_per_wave(a.n_kt, c);
+    // the debug export runs the instantiation (in-flight depth, live rows) the same call without it would run
+    if (a.acc_out) {
+        if (tpw <= 2) return launch_small(a8_smallm_kernel<G, 2, RL, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+        if (tpw <= 4) return launch_small(a8_smallm_kernel<G, 4, RL, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+        return launch_small(a8_smallm_kernel<G, TMAX, RL, true>, "w2_matmul_a8[smallm]", a, c, lds, stream);
+    }
     if (tpw <= 2) return launch_small(a8_smallm_kernel<G, 2, RL, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
     if (tpw <= 4) return launch_small(a8_smallm_kernel<G, 4, RL, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);
     return launch_small(a8_smallm_kernel<G, TMAX, RL, false>, "w2_matmul_a8[smallm]", a, c, lds, stream);

@@ -61,9 +61,10 @@ bool a8_midm_supports(const A8Args& a);
 int launch_a8_midm(const A8Args& a, hipStream_t stream);
 int launch_a8_tiled(const A8Args& a, hipStream_t stream);
 
-int launch_a8_fusedq(const void* codes, const void* scales, const void* X, int x_is_bf16, int64_t ldx,
-                     int64_t M, int64_t K, int64_t N, int G, int64_t n_cb, int64_t n_kt, uint16_t* Y,
-                     int64_t ldy, const Epilogue& epi, const w2_tuning_t& tune, hipStream_t stream);
+// The decode kernel (M <= 4): xt 0 = int8 rows (a.xq / a.sx), 1 = fp32 rows, 2 = bf16 rows quantised in the kernel.
+bool a8_gemv_supports(int64_t M);
+int launch_a8_gemv(const A8Args& a, const void* X, int xt, int64_t ldx, hipStream_t stream);
+
 
 struct A16Args {
     const uint32_t* codes;

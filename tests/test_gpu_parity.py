@@ -165,6 +165,50 @@ def test_a8_smallm(w2, M, K, N, G):
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SMALLM, seed=M + K + N + G)
 
 
+@pytest.mark.parametrize("shape", [None, (4, 1, 2), (8, 8, 4), (16, 2, 8), (8, 1, 8), (2, 2, 2), (16, 16, 2)])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", SMALL_SHAPES + [(5120, 48)])
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+def test_a8_gemv(w2, M, K, N, G, shape):
+    # the decode kernel: the library's own workgroup shape and forced ones (waves, column blocks, window):
+    # runs of one tile, runs shorter and longer than the window, uneven runs (20 tiles over 8 ranges)
+    tune = None if shape is None else {"small_waves": shape[0], "small_cbw": shape[1], "gemv_window": shape[2]}
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_GEMV, seed=M + K + N + G, tune=tune)
+
+
+@pytest.mark.parametrize("bf16_in", [False, True])
+@pytest.mark.parametrize("M", [1, 2, 4, 8])
+def test_production_kernels_hold_exact_group_sums(w2, M, bf16_in):
+    """The int32 group accumulators of the kernels the benchmark times, read through Y itself (no debug
+    instantiation): activations in {-1, 0, 1} plus one 127 per row on a k whose weights are all zero, so that
+    the quantisation is the identity (inv = 1, sx = 1); scales 1.0 in ONE group and 0 elsewhere, so that
+    Y[m][n] = acc[m][g][n], a small integer that bf16 holds exactly.  Every group in turn, K = 4096, through the
+    fused entry point (one launch for M <= 2) and through quantise + matmul."""
+    K, N, G = 4096, 80, 128
+    rng = np.random.default_rng(77 + M)
+    codes = rng.integers(0, 4, size=(K, N), dtype=np.uint8)
+    codes[5, :] = 2                                          # q = 0 under the int2 codec
+    X = rng.integers(-1, 2, size=(M, K)).astype(np.float32)
+    X[:, 5] = 127.0
+    oq, osx, _ = oracle.quantize_rows(X, G)
+    assert np.array_equal(oq, X.astype(np.int8)) and np.all(osx == 1.0)
+    oacc = oracle.group_acc(codes, G, 0, oq)                 # [M][K/G][N]
+    assert np.abs(oacc).max() <= 256
+    Xd = dev(X).to(torch.bfloat16) if bf16_in else dev(X)
+    ws = torch.empty(max(w2.workspace_size(M, K, N, G), 16), dtype=torch.uint8, device="cuda")
+    xq, sx, _ = w2.quantize_rows(Xd, G)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    for g in range(K // G):
+        scales = np.zeros((K // G, N), np.uint16)
+        scales[g, :] = 0x3F80
+        packed = w2.prepack(dev(codes), dev(scales), G, 0)
+        want = oacc[:, g, :].astype(np.float64)
+        Yf = w2.matmul_a8_fused(packed, K, N, G, Xd, workspace=ws)
+        assert np.array_equal(bits_to_f64(bf16_bits(Yf)), want), f"fused entry, group {g}"
+        Y2 = w2.matmul_a8(packed, K, N, G, xq, sx)
+        assert np.array_equal(bits_to_f64(bf16_bits(Y2)), want), f"quantise + matmul, group {g}"
+
+
 @pytest.mark.parametrize("cbw", [0, 2, 4, 8])
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (2304, 1032), (768, 8)])
