@@ -105,6 +105,7 @@ typedef struct {
     int small_kc;         /* ... k per local-memory chunk of the activations: a multiple of 256 */
     int gemv_window;      /* GEMV: weight tiles a wave keeps in flight: 2, 4 or 8 */
     int midm_cbw;         /* MIDM: column blocks per workgroup: 2, 4 or 8 */
+    int tiled_bm;         /* w2a8 TILED: rows per workgroup: 64 or 128 (128: G = 128, K not split) */
     int tiled_bn;         /* TILED / SCALED16 tiled kernels: columns per workgroup: 128 or 256 */
     int tiled_group_m;    /* ... row tiles per band of the workgroup order: 1..1024 */
     int splitk;           /* tiled kernels: 1 = never split K, n = 2..16: n parts if the workspace holds them */
@@ -161,6 +162,9 @@ W2_API int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_
  *   acc[m,g,n] = sum_{k in group g} xq[m,k] * q[k,n]            (int32, exact)
  *   Y[m,n]     = bf16( sx[m] * sum_g sw[g,n] * float(acc[m,g,n]) )   (fp32)
  * packed  dev, from w2_prepack with the same K, N, G
+ *         Weight scales: finite bf16 with |sw| < 2^63 (for M > 8 the kernels
+ *         multiply by sw * 2^64 in fp32); results below the fp32 normal range
+ *         (|sx * sw * acc| < 2^-126) may lose precision.
  * xq, sx  dev, as produced by w2_quantize_rows ([M][K] dense, [M])
  * Y       dev, bf16 bit patterns [M][N], row stride ldy
  * workspace  optional (NULL / 0: none), dev, 16-byte aligned, contents

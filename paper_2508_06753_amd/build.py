@@ -12,12 +12,15 @@ CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libw2mm.so")
 SOURCES = ["api.hip", "prepack.hip", "quantize.hip", "matmul_a8_small.hip",
-           "matmul_a8_midm.hip", "matmul_a8_tiled.hip", "matmul_a8_gemv.hip", "matmul_a16.hip", "matmul_a16_fold.hip", "matmul_a16_midm.hip",
+           "matmul_a8_midm.hip", "matmul_a8_tiled.hip", "matmul_a8_tiled128.hip", "matmul_a8_gemv.hip", "matmul_a16.hip", "matmul_a16_fold.hip", "matmul_a16_midm.hip",
            "comparators.hip", "splitk.hip"]
 HEADERS = ["w2_layout.h", "w2_internal.h", "w2_small_common.h", os.path.join("..", "..", "include", "w2mm.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Wall", "-Wno-unused-function",
+         # the mid-M and prefill w2a8 kernels read int32 accumulators as fp32 denormals (one-fma dequant):
+         # denormals must be kept (HIP's default), never flushed; the sources refuse -ffast-math as well
+         "-fno-gpu-flush-denormals-to-zero",
          # packed-fp32 VALU forms are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

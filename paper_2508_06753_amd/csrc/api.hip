@@ -156,6 +156,7 @@ static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
     else if (t->small_kc < 0 || t->small_kc % TILE_K) bad = "small_kc";
     else if (!one_of(t->gemv_window, 2, 4, 8)) bad = "gemv_window";
     else if (!one_of(t->midm_cbw, 2, 4, 8)) bad = "midm_cbw";
+    else if (!one_of(t->tiled_bm, 64, 128)) bad = "tiled_bm";
     else if (!one_of(t->tiled_bn, 128, 256)) bad = "tiled_bn";
     else if (!in(t->tiled_group_m, 1, 1024)) bad = "tiled_group_m";
     else if (!in(t->splitk, 1, 16)) bad = "splitk";

@@ -18,6 +18,10 @@
 
 #include "w2_small_common.h"
 
+#if defined(__HIP_DEVICE_COMPILE__) && defined(__FAST_MATH__)
+#error "the one-fma dequant reads int32 accumulators as fp32 denormals: do not build with fast-math / flush-to-zero"
+#endif
+
 namespace w2 {
 
 namespace midm {

@@ -36,6 +36,10 @@
 
 #include "w2_internal.h"
 
+#if defined(__HIP_DEVICE_COMPILE__) && defined(__FAST_MATH__)
+#error "the one-fma dequant reads int32 accumulators as fp32 denormals: do not build with fast-math / flush-to-zero"
+#endif
+
 namespace w2 {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -430,6 +434,16 @@ static int launch_tiled_bn(const A8Args& a, hipStream_t stream)
 
 int launch_a8_tiled(const A8Args& a, hipStream_t stream)
 {
+    // 128-row tiles (half the up-convert work per matrix instruction) where the problem has the rows for
+    // them and K is not split across workgroups
+    {
+        const int bn = tiled_bn(a.M, a.N, a.tune);
+        const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
+        const int splits = a.acc_out ? 1 : tiled_splits(a.M, a.N, a.n_kt, cap, a.tune);
+        (void)bn;
+        const bool want128 = a.tune.tiled_bm ? a.tune.tiled_bm == 128 : a.M >= 1024;
+        if (want128 && splits < 2 && a8_tiled128_supports(a)) return launch_a8_tiled128(a, stream);
+    }
     if (a.G == 128)
         return a.acc_out ? launch_tiled_bn<128, true>(a, stream) : launch_tiled_bn<128, false>(a, stream);
     return a.acc_out ? launch_tiled_bn<64, true>(a, stream) : launch_tiled_bn<64, false>(a, stream);

@@ -1,0 +1,401 @@
+// w2a8 for prefill, 128-row tiles: the compute-bound regime (Sec. III-C, GEMM
+// results) on the int8 matrix cores.  Measured on MI355X, what limits this
+// method there is vector-instruction issue: a SIMD issues one vector
+// instruction, matrix ones included, about every four clocks, and per matrix
+// instruction (16 clocks of matrix pipe) the method needs 256/G fmas to apply
+// the group scales (Sec. II-D dequant, per group) plus 7/RI shift/mask
+// instructions to up-convert (Sec. II-C), RI = row tiles that share a weight
+// operand.  The 64-row kernel (RI = 4) runs at 5.2 vector instructions per
+// matrix instruction; this one halves the up-convert share with 128-row wave
+// tiles (RI = 8 x CJ = 2 column blocks of v_mfma_i32_16x16x64_i8) and spreads
+// the remaining vector work evenly under the matrix instructions:
+//   - workgroup 128 rows x 256 columns (eight waves of 128 x 32, one workgroup
+//     per CU) or 128 x 128 (four waves, two per CU); a stage is 128 k = one
+//     group of G = 128, 32 matrix instructions per wave;
+//   - activations go through three LDS buffers (row stride 160 B: conflict-free
+//     operand reads): stage s reads buffers s and s+1 and writes the rows of
+//     stage s+2, which were loaded from global memory two stages earlier; one
+//     barrier per stage;
+//   - the weights go from global memory to registers (the packed dword IS the
+//     matrix operand), one 16-byte load per lane, column block and 256-k tile,
+//     a tile ahead;
+//   - every wave is software-pipelined on its own: under a stage's matrix
+//     instructions it reads the second k-step's operands and the next stage's
+//     first ones, up-converts one operand ahead, and dequantises a finished
+//     column block in two halves (16 fmas per eight matrix instructions);
+//   - dequant in ONE fma per accumulator: a group starts from BIAS = 2^21 (the
+//     third MFMA operand), so acc = BIAS + 64*sum is positive and below 2^23 and
+//     its bit pattern read as binary32 is the denormal acc * 2^-149:
+//     y += as_float(acc) * (sw * 2^64); the bias term is taken out every 16
+//     stages and at the end.  Requires fp32 denormals (checked at build time:
+//     the library is never built with flush-to-zero) and |sw| < 2^63.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "w2_small_common.h"
+
+#if defined(__HIP_DEVICE_COMPILE__) && defined(__FAST_MATH__)
+#error "the one-fma dequant reads int32 accumulators as fp32 denormals: do not build with fast-math / flush-to-zero"
+#endif
+
+namespace w2 {
+
+namespace t128 {
+
+constexpr int RI = 8;                              // 16-row tiles per wave
+constexpr int CJ = 2;                              // 16-column blocks per wave
+constexpr int BM = 16 * RI, BK = 128;
+constexpr int WN = 16 * CJ;
+constexpr int A_STRIDE = BK + 32;                  // 32 mod 64 bytes: conflict-free A-operand reads
+constexpr int A_BUF = BM * A_STRIDE;
+constexpr int NBUF = 3;
+constexpr int E_STRIDE = WN * 2 + 16;              // epilogue: bytes per LDS row of a wave's result
+constexpr int BIAS = 1 << 21;                      // > 64 * 127 * 2 * 128 = 2 080 768
+constexpr int waves_of(int bn) { return bn / WN; }
+constexpr int lds_bytes(int bn)
+{
+    return NBUF * A_BUF > waves_of(bn) * BM * E_STRIDE ? NBUF * A_BUF : waves_of(bn) * BM * E_STRIDE;
+}
+
+__device__ __forceinline__ v4i upconvert4(uint32_t w)
+{
+    v4i u;
+    u[0] = (int)((w << 6) & 0xC0C0C0C0u);
+    u[1] = (int)((w << 4) & 0xC0C0C0C0u);
+    u[2] = (int)((w << 2) & 0xC0C0C0C0u);
+    u[3] = (int)(w & 0xC0C0C0C0u);
+    return u;
+}
+
+template <int G>
+struct WTile {
+    uint4 w[CJ];                                   // 16 bytes of codes per column block: dword t = k 64t .. 64t+63
+    uint32_t s[CJ][G == 128 ? 1 : 2];              // the lane's column: 2 (G=128) or 4 (G=64) bf16 group scales
+};
+
+template <int G, bool DBG, int BN>
+__global__ void __launch_bounds__(64 * waves_of(BN), BN >= 256 ? 1 : 2)
+a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
+{
+    constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
+    constexpr int GPT = TILE_K / G;
+    constexpr int CPT = THREADS / BM;              // threads per activation row: 4 or 2
+    constexpr int NV = BK / CPT / 16;              // 16-byte pieces per thread and stage: 2 or 4
+    constexpr bool TWO_SETS = NV <= 2;             // two register sets: a load has two stages to land
+    extern __shared__ __align__(16) int8_t smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wn = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane >> 4, l16 = lane & 15;
+
+    // workgroup -> tile: one contiguous chunk of ids per XCD (consecutive ids go to different XCDs),
+    // bands of group_m row tiles inside, so that the workgroups resident on an XCD share activation rows
+    // and weight columns through that XCD's L2
+    const int64_t total = (int64_t)tiles_m * tiles_n;
+    int64_t id = blockIdx.x;
+    if (total % 8 == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int64_t band = id / ((int64_t)group_m * tiles_n);
+    const int64_t first_m = band * group_m;
+    const int gm = (int)min((int64_t)group_m, tiles_m - first_m);
+    const int64_t in_band = id - band * group_m * tiles_n;
+    const int64_t tile_m = first_m + in_band % gm;
+    const int64_t tile_n = in_band / gm;
+    const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const char* wb[CJ];
+    const char* sb[CJ];
+#pragma unroll
+    for (int j = 0; j < CJ; ++j) {
+        int64_t c = tile_n * (BN / TILE_N) + wn * CJ + j;
+        c = c < a.n_cb ? c : a.n_cb - 1;                     // clamp: loads stay in bounds
+        wb[j] = reinterpret_cast<const char*>(a.codes + c * a.n_kt * 256);
+        sb[j] = reinterpret_cast<const char*>(a.scales + c * a.n_kt * TILE_N * GPT);
+    }
+    uint32_t w_lane = (uint32_t)lane * 16u;
+    uint32_t s_lane = (uint32_t)l16 * (GPT * 2u);
+
+    // global -> LDS copy: CPT threads per row, NV 16-byte pieces each; rows past M repeat the last row.
+    // Lane offsets stay below 128 * K <= 2^31.
+    const int cp_row = tid / CPT, cp_seg = tid % CPT;
+    int64_t cp_m = m0 + cp_row;
+    if (cp_m >= a.M) cp_m = a.M - 1;
+    const char* cp_base = reinterpret_cast<const char*>(a.xq) + m0 * a.K;                 // uniform
+    uint32_t cp_lane = (uint32_t)((cp_m - m0) * a.K) + (uint32_t)cp_seg * (NV * 16);
+    const int cp_dst = cp_row * A_STRIDE + cp_seg * (NV * 16);
+
+    v4i acc[RI][CJ];
+    float y[RI][CJ][4];
+    float ssum[CJ] = {};                                     // sum of sw * 2^64 over the groups folded into y
+    const v4i biasv = {BIAS, BIAS, BIAS, BIAS};
+#pragma unroll
+    for (int i = 0; i < RI; ++i)
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) {
+            acc[i][j] = biasv;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) y[i][j][r] = 0.0f;
+        }
+
+    const int64_t n_st = a.n_kt * 2;                         // stages of 128 k
+    // plain named registers (arrays and structs of them ended up in scratch memory)
+    uint4 p00, p01, p02 = make_uint4(0, 0, 0, 0), p03 = p02;         // set 0
+    uint4 p10 = p02, p11 = p02;                                      // set 1 (eight-wave workgroups)
+    auto load_a = [&](int64_t st, uint4& v0, uint4& v1, uint4& v2, uint4& v3) {
+        st = min(st, n_st - 1);                              // past the end: re-read the last stage (never used)
+        const char* p = cp_base + st * BK;                   // uniform
+        asm volatile("" : "+v"(cp_lane));                    // keeps "scalar base + 32-bit offset" addressing
+        v0 = *reinterpret_cast<const uint4*>(p + cp_lane);
+        v1 = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
+        if constexpr (NV > 2) {
+            v2 = *reinterpret_cast<const uint4*>(p + cp_lane + 32);
+            v3 = *reinterpret_cast<const uint4*>(p + cp_lane + 48);
+        }
+    };
+    auto store_a = [&](int buf, const uint4& v0, const uint4& v1, const uint4& v2, const uint4& v3) {
+        int8_t* dst = smem + buf * A_BUF + cp_dst;
+        *reinterpret_cast<uint4*>(dst) = v0;
+        *reinterpret_cast<uint4*>(dst + 16) = v1;
+        if constexpr (NV > 2) {
+            *reinterpret_cast<uint4*>(dst + 32) = v2;
+            *reinterpret_cast<uint4*>(dst + 48) = v3;
+        }
+    };
+    auto load_w = [&](int64_t kt, WTile<G>& r) {
+        kt = min(kt, a.n_kt - 1);
+        const int64_t w_off = kt * 1024;
+        const int64_t s_off = kt * (TILE_N * GPT * 2);
+        asm volatile("" : "+v"(w_lane), "+v"(s_lane));
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) {
+            r.w[j] = *reinterpret_cast<const uint4*>(wb[j] + w_off + w_lane);
+            if constexpr (G == 128) {
+                r.s[j][0] = *reinterpret_cast<const uint32_t*>(sb[j] + s_off + s_lane);
+            } else {
+                const uint2 v = *reinterpret_cast<const uint2*>(sb[j] + s_off + s_lane);
+                r.s[j][0] = v.x;
+                r.s[j][1] = v.y;
+            }
+        }
+    };
+
+    // prologue: stages 0 and 1 go to LDS; the registers then hold stage 2 (and 3)
+    WTile<G> w0, w1;
+    load_w(0, w0);
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        load_a(p, p00, p01, p02, p03);
+        store_a(p, p00, p01, p02, p03);
+    }
+    load_a(2, p00, p01, p02, p03);
+    if constexpr (TWO_SETS) load_a(3, p10, p11, p02, p03);
+    __syncthreads();
+
+    const int8_t* a_base = smem + l16 * A_STRIDE + q * 16;
+
+    // y += as_float(acc) * (sw * 2^64) for rows [i0, i0 + 4) of column block j
+    auto dequant_half = [&](int j, int i0, float swS, int64_t g) {
+#pragma unroll
+        for (int i = i0; i < i0 + RI / 2; ++i) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if constexpr (DBG) {
+                    const int64_t m = m0 + i * 16 + 4 * q + r;
+                    const int64_t n = n0 + wn * WN + j * 16 + l16;
+                    if (g >= 0 && m < a.M && n < a.N)
+                        a.acc_out[(m * (a.K / G) + g) * a.N + n] = (acc[i][j][r] - BIAS) >> 6;
+                }
+                y[i][j][r] = fmaf(__int_as_float(acc[i][j][r]), swS, y[i][j][r]);
+            }
+        }
+    };
+    auto scale_of = [&](const WTile<G>& w, int j, int h, int t) -> float {
+        // G = 128: the stage's group is group h of the tile; G = 64: k-step t of stage h is group 2h + t
+        const uint32_t pair = G == 128 ? w.s[j][0] : w.s[j][h];
+        const int hi = G == 128 ? h : t;
+        return __uint_as_float(hi ? (pair & 0xffff0000u) : (pair << 16)) * 0x1p64f;
+    };
+    auto dword_of = [&](const WTile<G>& w, int j, int h, int t) -> uint32_t {
+        const int d = 2 * h + t;
+        return d == 0 ? w.w[j].x : d == 1 ? w.w[j].y : d == 2 ? w.w[j].z : w.w[j].w;
+    };
+
+    v4i a0[RI], a1[RI];
+#pragma unroll
+    for (int i = 0; i < RI; ++i) a0[i] = *reinterpret_cast<const v4i*>(a_base + i * 16 * A_STRIDE);
+    v4i b_next = upconvert4(w0.w[0].x);                      // operand (k-step 0, column block 0) of the coming stage
+    float pend_sw = 0.f;                                     // column block 1 of the previous stage: nothing yet
+    int64_t pend_g = -1;
+    int buf = 0;
+
+    // One stage (G = 128: one group).  Order of the matrix instructions: column block 0, k-steps 0 and 1
+    // (blocks A, B), then column block 1 (blocks C, D).  Vector work under them:
+    //   A: second k-step's operands from LDS, up-convert (1,0), dequant the previous stage's column 1, rows 0..63
+    //   B: up-convert (0,1), dequant the previous stage's column 1, rows 64..127
+    //   C: up-convert (1,1), dequant this stage's column 0, rows 0..63
+    //   D: next stage's first operands from LDS, up-convert its (0,0), dequant column 0, rows 64..127
+    auto stage = [&](int64_t it, auto hc, const WTile<G>& wc, WTile<G>& wnx) {
+        constexpr int h = decltype(hc)::value;
+        const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;
+        const int bufw = buf1 == NBUF - 1 ? 0 : buf1 + 1;
+        if constexpr (TWO_SETS && h == 1) {                  // activations of stage it+2
+            store_a(bufw, p10, p11, p02, p03);
+            load_a(it + 4, p10, p11, p02, p03);
+        } else {
+            store_a(bufw, p00, p01, p02, p03);
+            load_a(it + (TWO_SETS ? 4 : 3), p00, p01, p02, p03);
+        }
+        if constexpr (h == 0) load_w((it >> 1) + 1, wnx);
+        __builtin_amdgcn_sched_barrier(0);                   // all loads are issued up here, unconditionally
+        const int8_t* ab = a_base + buf * A_BUF;
+        const int8_t* abn = a_base + buf1 * A_BUF;
+        const WTile<G>& wn_tile = h == 1 ? wnx : wc;         // where the next stage finds its weights
+        static_assert(G == 128, "this schedule is written for one group per stage");
+        const float sw0 = scale_of(wc, 0, h, 0), sw1 = scale_of(wc, 1, h, 0);
+        const int64_t g = it;                                // group index = stage index (G = 128)
+
+        const v4i b00 = b_next;
+        // block A
+#pragma unroll
+        for (int i = 0; i < RI; ++i) a1[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE + 64);
+        const v4i b10 = upconvert4(dword_of(wc, 0, h, 1));
+#pragma unroll
+        for (int i = 0; i < RI; ++i) acc[i][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0[i], b00, biasv, 0, 0, 0);
+        dequant_half(1, 0, pend_sw, pend_g);
+        // block B
+        const v4i b01 = upconvert4(dword_of(wc, 1, h, 0));
+#pragma unroll
+        for (int i = 0; i < RI; ++i) acc[i][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1[i], b10, acc[i][0], 0, 0, 0);
+        dequant_half(1, RI / 2, pend_sw, pend_g);
+        ssum[1] += pend_sw;
+        // block C
+        const v4i b11 = upconvert4(dword_of(wc, 1, h, 1));
+#pragma unroll
+        for (int i = 0; i < RI; ++i) acc[i][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0[i], b01, biasv, 0, 0, 0);
+        dequant_half(0, 0, sw0, g);
+        // block D
+#pragma unroll
+        for (int i = 0; i < RI; ++i) a0[i] = *reinterpret_cast<const v4i*>(abn + i * 16 * A_STRIDE);
+        b_next = upconvert4(dword_of(wn_tile, 0, h ^ 1, 0));
+#pragma unroll
+        for (int i = 0; i < RI; ++i) acc[i][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1[i], b11, acc[i][1], 0, 0, 0);
+        dequant_half(0, RI / 2, sw0, g);
+        ssum[0] += sw0;
+        pend_sw = DBG ? 1.0f : sw1;
+        pend_g = g;
+        // issue order: one matrix instruction, then the LDS read (blocks A and D) and the vector instructions it hides
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk) {
+#pragma unroll
+            for (int k = 0; k < RI; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (blk == 0 || blk == 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            }
+        }
+        buf = buf1;
+        __syncthreads();
+    };
+
+    // one 256-k tile (two stages) per iteration; the next tile's weights arrive in w1 meanwhile and move
+    // to w0 at the end (every load and every register write is unconditional: registers written under a
+    // condition end up in scratch memory)
+    for (int64_t kt = 0; kt < a.n_kt; ++kt) {
+        stage(kt * 2, std::integral_constant<int, 0>{}, w0, w1);
+        stage(kt * 2 + 1, std::integral_constant<int, 1>{}, w0, w1);
+        w0 = w1;
+        if ((kt & 7) == 7) {
+            // take the accumulated bias term out every 16 stages, so that the running sums never carry
+            // more than 16 stages of it (the rounding error stays near 2^-14 of the result, whatever K is)
+#pragma unroll
+            for (int j = 0; j < CJ; ++j) {
+                // column 1 of the stage just finished is still pending: its scale is not in ssum[1] yet
+                const float corr = ssum[j] * 0x1p-128f;      // BIAS * 2^-149 = 2^-128
+                ssum[j] = 0.f;
+#pragma unroll
+                for (int i = 0; i < RI; ++i)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) y[i][j][r] -= corr;
+            }
+        }
+    }
+    // the very last stage's column block 1
+    dequant_half(1, 0, pend_sw, pend_g);
+    dequant_half(1, RI / 2, pend_sw, pend_g);
+    ssum[1] += pend_sw;
+    if constexpr (DBG) return;
+
+    // y_true = (y - BIAS*2^-149 * ssum) * 2^(149-64) * 2^-6 * sx.  The wave's 128 x 32 result goes through
+    // LDS (its own region; the barrier at the end of the last stage freed the activation buffers) and
+    // leaves as 16-byte stores.
+    int8_t* ebase = smem + wn * (BM * E_STRIDE);
+    uint16_t* eb = reinterpret_cast<uint16_t*>(ebase);
+    const bool gated = a.epi.act == ACT_SILU_MUL;
+    float bias[CJ];
+#pragma unroll
+    for (int j = 0; j < CJ; ++j) {
+        const int64_t n = n0 + wn * WN + j * 16 + l16;
+        bias[j] = (a.epi.bias && n < a.N) ? bf16_to_f32(a.epi.bias[n]) : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < RI; ++i) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = i * 16 + 4 * q + r;
+            const int64_t m = m0 + row;
+            const float s = a.sx[m < a.M ? m : a.M - 1];
+            float z[CJ];
+#pragma unroll
+            for (int j = 0; j < CJ; ++j) z[j] = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f * s + bias[j];
+            if (gated) {
+                eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(silu_f32(z[0]) * z[1]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < CJ; ++j)
+                    eb[row * (E_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(a.epi.act == ACT_SILU ? silu_f32(z[j]) : z[j]);
+            }
+        }
+    }
+    // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
+    const int wcols = gated ? WN / 2 : WN;                   // output columns of this wave
+    const int lpr = wcols * 2 / 16;                          // lanes per row piece (16 bytes each): 4 or 2
+    const int rpp = 64 / lpr;                                // rows per pass
+    const int64_t ncol = (gated ? (n0 + wn * WN) / 2 : n0 + wn * WN) + (lane % lpr) * 8;   // first of this lane's 8 columns
+    const int64_t n_out = gated ? a.N / 2 : a.N;
+    for (int p = 0; p < BM / rpp; ++p) {
+        const int row = p * rpp + lane / lpr;
+        const int64_t m = m0 + row;
+        const uint4 v = *reinterpret_cast<const uint4*>(ebase + row * E_STRIDE + (lane % lpr) * 16);
+        if (m < a.M && ncol < n_out) *reinterpret_cast<uint4*>(a.Y + m * a.ldy + ncol) = v;   // N % 8 == 0: all 8 or none
+    }
+}
+
+template <bool DBG, int BN>
+static int launch(const A8Args& a, hipStream_t stream)
+{
+    constexpr int WAVES = waves_of(BN);
+    const int tiles_m = (int)((a.M + BM - 1) / BM);
+    const int tiles_n = (int)((a.N + BN - 1) / BN);
+    const int group_m = a.tune.tiled_group_m ? a.tune.tiled_group_m : 8;
+    constexpr int lds = lds_bytes(BN);
+    auto kern = a8_tiled128_kernel<128, DBG, BN>;
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, "w2_matmul_a8[tiled 128]")) return rc;
+    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(64 * WAVES);
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
+    return check_launch("w2_matmul_a8[tiled 128]");
+}
+
+}  // namespace t128
+
+// G = 128 only (a stage is one group); K splitting across workgroups stays with the 64-row kernel.
+bool a8_tiled128_supports(const A8Args& a) { return a.G == 128; }
+
+int launch_a8_tiled128(const A8Args& a, hipStream_t stream)
+{
+    const int64_t wgs256 = ((a.M + 127) / 128) * ((a.N + 255) / 256);
+    const int bn = a.tune.tiled_bn ? a.tune.tiled_bn : wgs256 <= 128 ? 128 : 256;
+    if (a.acc_out) return bn == 128 ? t128::launch<true, 128>(a, stream) : t128::launch<true, 256>(a, stream);
+    return bn == 128 ? t128::launch<false, 128>(a, stream) : t128::launch<false, 256>(a, stream);
+}
+
+}  // namespace w2

@@ -60,6 +60,8 @@ int launch_a8_smallm(const A8Args& a, hipStream_t stream);
 bool a8_midm_supports(const A8Args& a);
 int launch_a8_midm(const A8Args& a, hipStream_t stream);
 int launch_a8_tiled(const A8Args& a, hipStream_t stream);
+bool a8_tiled128_supports(const A8Args& a);
+int launch_a8_tiled128(const A8Args& a, hipStream_t stream);
 
 // The decode kernel (M <= 4): xt 0 = int8 rows (a.xq / a.sx), 1 = fp32 rows, 2 = bf16 rows quantised in the kernel.
 bool a8_gemv_supports(int64_t M);

@@ -248,6 +248,34 @@ def test_a8_tiled(w2, M, K, N, G, bn):
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G, tune={"tiled_bn": bn})
 
 
+@pytest.mark.parametrize("bn", [128, 256])
+@pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (512, 1032), (4608, 48)])
+@pytest.mark.parametrize("M", [1, 17, 127, 128, 129, 300])
+def test_a8_tiled_128_row_tiles(w2, M, K, N, bn):
+    # the prefill kernel with 128-row tiles: both workgroup widths; ragged M and N; one stage pair up to 36
+    # stages (K = 4608: two periodic bias settlements); accumulators bit for bit, outputs to tolerance
+    run_a8_case(w2, M, K, N, 128, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N, tune={"tiled_bm": 128, "tiled_bn": bn})
+
+
+@pytest.mark.parametrize("M", [20, 100, 300])
+def test_a8_one_fma_dequant_keeps_denormals(w2, M):
+    # the mid-M and prefill kernels read BIAS + 64*sum as an fp32 denormal and multiply by sw * 2^64: a build
+    # that flushed denormals would return zeros here.  Unit scales, xq = small integers, sx = 1: exact results.
+    K, N, G = 512, 48, 128
+    rng = np.random.default_rng(M)
+    codes = rng.integers(0, 4, size=(K, N), dtype=np.uint8)
+    scales = np.full((K // G, N), 0x3F80, np.uint16)
+    xq = rng.integers(-2, 3, size=(M, K)).astype(np.int8)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    want = (xq.astype(np.int64) @ (codes.astype(np.int64) - 2)).astype(np.float64)
+    assert np.abs(want).max() <= 256 and np.abs(want).max() > 8
+    for variant, tune in ((w2.VARIANT_MIDM, None), (w2.VARIANT_TILED, {"tiled_bm": 64}), (w2.VARIANT_TILED, {"tiled_bm": 128})):
+        if variant == w2.VARIANT_MIDM and M > 256:
+            continue
+        Y = w2.matmul_a8(packed, K, N, G, torch.from_numpy(xq).cuda(), torch.ones(M, device="cuda"), variant=variant, tune=tune)
+        assert np.array_equal(bits_to_f64(bf16_bits(Y)), want), (variant, tune)
+
+
 @pytest.mark.parametrize("M", [1, 4, 8, 9, 16, 17, 64, 65, 130])
 def test_a8_auto_dispatch(w2, M):
     run_a8_case(w2, M, 1024, 528, 128, 0, w2.VARIANT_AUTO, seed=M)
