@@ -12,10 +12,13 @@
 //   - workgroup 128 rows x 256 columns (eight waves of 128 x 32, one workgroup
 //     per CU) or 128 x 128 (four waves, two per CU); a stage is 128 k = one
 //     group of G = 128, 32 matrix instructions per wave;
-//   - activations go through three LDS buffers (row stride 160 B: conflict-free
-//     operand reads): stage s reads buffers s and s+1 and writes the rows of
-//     stage s+2, which were loaded from global memory two stages earlier; one
-//     barrier per stage;
+//   - activations go through LDS (row stride 160 B: conflict-free operand
+//     reads).  Three buffers: stage s reads buffers s and s+1 and writes the rows
+//     of stage s+2, one barrier per stage.  Five buffers (eight-wave workgroups):
+//     the pair of stages (2S, 2S+1) reads stages 2S .. 2S+2 and writes stages
+//     2S+3 and 2S+4, five different buffers, one barrier per pair, so the waves
+//     of a workgroup may be a stage apart inside a pair.  Rows are loaded from
+//     global memory two stages before they go to LDS;
 //   - the weights go from global memory to registers (the packed dword IS the
 //     matrix operand), one 16-byte load per lane, column block and 256-k tile,
 //     a tile ahead;
@@ -27,8 +30,11 @@
 //     third MFMA operand), so acc = BIAS + 64*sum is positive and below 2^23 and
 //     its bit pattern read as binary32 is the denormal acc * 2^-149:
 //     y += as_float(acc) * (sw * 2^64); the bias term is taken out every 16
-//     stages and at the end.  Requires fp32 denormals (checked at build time:
-//     the library is never built with flush-to-zero) and |sw| < 2^63.
+//     stages and at the end.  Requires fp32 denormals (the build keeps them and
+//     the source refuses fast-math) and |sw| < 2^63.  (Starting from the bit
+//     pattern of 1.5 * 2^23 instead, a normal number, is no faster -- denormal
+//     operands cost the fma nothing here -- and carries six times the bias,
+//     which costs the near-zero outputs their accuracy.)
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -49,13 +55,16 @@ constexpr int BM = 16 * RI, BK = 128;
 constexpr int WN = 16 * CJ;
 constexpr int A_STRIDE = BK + 32;                  // 32 mod 64 bytes: conflict-free A-operand reads
 constexpr int A_BUF = BM * A_STRIDE;
-constexpr int NBUF = 3;
+// LDS buffers: 3 with a barrier after every stage; 5 with a barrier after every other stage (eight-wave
+// workgroups, one per CU: the waves of a workgroup may then drift a stage apart inside a pair)
+constexpr int nbuf_of(int bn) { return bn >= 256 ? 5 : 3; }
 constexpr int E_STRIDE = WN * 2 + 16;              // epilogue: bytes per LDS row of a wave's result
 constexpr int BIAS = 1 << 21;                      // > 64 * 127 * 2 * 128 = 2 080 768
+constexpr float BIAS_F = 0x1p-128f;                // BIAS read as a float: 2^21 * 2^-149
 constexpr int waves_of(int bn) { return bn / WN; }
 constexpr int lds_bytes(int bn)
 {
-    return NBUF * A_BUF > waves_of(bn) * BM * E_STRIDE ? NBUF * A_BUF : waves_of(bn) * BM * E_STRIDE;
+    return nbuf_of(bn) * A_BUF > waves_of(bn) * BM * E_STRIDE ? nbuf_of(bn) * A_BUF : waves_of(bn) * BM * E_STRIDE;
 }
 
 __device__ __forceinline__ v4i upconvert4(uint32_t w)
@@ -83,6 +92,9 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     constexpr int CPT = THREADS / BM;              // threads per activation row: 4 or 2
     constexpr int NV = BK / CPT / 16;              // 16-byte pieces per thread and stage: 2 or 4
     constexpr bool TWO_SETS = NV <= 2;             // two register sets: a load has two stages to land
+    constexpr int NBUF = nbuf_of(BN);
+    constexpr int WR = NBUF == 3 ? 2 : 3;          // stage s writes the activations of stage s + WR
+    static_assert(NBUF == 3 || TWO_SETS, "five buffers go with two register sets");
     extern __shared__ __align__(16) int8_t smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -121,8 +133,12 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     int64_t cp_m = m0 + cp_row;
     if (cp_m >= a.M) cp_m = a.M - 1;
     const char* cp_base = reinterpret_cast<const char*>(a.xq) + m0 * a.K;                 // uniform
-    uint32_t cp_lane = (uint32_t)((cp_m - m0) * a.K) + (uint32_t)cp_seg * (NV * 16);
-    const int cp_dst = cp_row * A_STRIDE + cp_seg * (NV * 16);
+    // piece v of a thread is the row's 16-byte piece v * CPT + cp_seg: the CPT threads of a row store CPT
+    // consecutive pieces per instruction, so eight lanes (two or four rows) never share an LDS bank
+    // (with NV consecutive pieces per thread a row's last piece fell on the next row's first bank)
+    uint32_t cp_lane = (uint32_t)((cp_m - m0) * a.K) + (uint32_t)cp_seg * 16u;
+    const int cp_dst = cp_row * A_STRIDE + cp_seg * 16;
+    constexpr int CP_STEP = CPT * 16;              // bytes between a thread's pieces
 
     v4i acc[RI][CJ];
     float y[RI][CJ][4];
@@ -146,19 +162,19 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         const char* p = cp_base + st * BK;                   // uniform
         asm volatile("" : "+v"(cp_lane));                    // keeps "scalar base + 32-bit offset" addressing
         v0 = *reinterpret_cast<const uint4*>(p + cp_lane);
-        v1 = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
+        v1 = *reinterpret_cast<const uint4*>(p + cp_lane + CP_STEP);
         if constexpr (NV > 2) {
-            v2 = *reinterpret_cast<const uint4*>(p + cp_lane + 32);
-            v3 = *reinterpret_cast<const uint4*>(p + cp_lane + 48);
+            v2 = *reinterpret_cast<const uint4*>(p + cp_lane + 2 * CP_STEP);
+            v3 = *reinterpret_cast<const uint4*>(p + cp_lane + 3 * CP_STEP);
         }
     };
     auto store_a = [&](int buf, const uint4& v0, const uint4& v1, const uint4& v2, const uint4& v3) {
         int8_t* dst = smem + buf * A_BUF + cp_dst;
         *reinterpret_cast<uint4*>(dst) = v0;
-        *reinterpret_cast<uint4*>(dst + 16) = v1;
+        *reinterpret_cast<uint4*>(dst + CP_STEP) = v1;
         if constexpr (NV > 2) {
-            *reinterpret_cast<uint4*>(dst + 32) = v2;
-            *reinterpret_cast<uint4*>(dst + 48) = v3;
+            *reinterpret_cast<uint4*>(dst + 2 * CP_STEP) = v2;
+            *reinterpret_cast<uint4*>(dst + 3 * CP_STEP) = v3;
         }
     };
     auto load_w = [&](int64_t kt, WTile<G>& r) {
@@ -183,12 +199,12 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     WTile<G> w0, w1;
     load_w(0, w0);
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < WR; ++p) {
         load_a(p, p00, p01, p02, p03);
         store_a(p, p00, p01, p02, p03);
     }
-    load_a(2, p00, p01, p02, p03);
-    if constexpr (TWO_SETS) load_a(3, p10, p11, p02, p03);
+    load_a(WR, p00, p01, p02, p03);
+    if constexpr (TWO_SETS) load_a(WR + 1, p10, p11, p02, p03);
     __syncthreads();
 
     const int8_t* a_base = smem + l16 * A_STRIDE + q * 16;
@@ -237,13 +253,13 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     auto stage = [&](int64_t it, auto hc, const WTile<G>& wc, WTile<G>& wnx) {
         constexpr int h = decltype(hc)::value;
         const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;
-        const int bufw = buf1 == NBUF - 1 ? 0 : buf1 + 1;
+        const int bufw = buf + WR >= NBUF ? buf + WR - NBUF : buf + WR;
         if constexpr (TWO_SETS && h == 1) {                  // activations of stage it+2
             store_a(bufw, p10, p11, p02, p03);
-            load_a(it + 4, p10, p11, p02, p03);
+            load_a(it + WR + 2, p10, p11, p02, p03);
         } else {
             store_a(bufw, p00, p01, p02, p03);
-            load_a(it + (TWO_SETS ? 4 : 3), p00, p01, p02, p03);
+            load_a(it + WR + (TWO_SETS ? 2 : 1), p00, p01, p02, p03);
         }
         if constexpr (h == 0) load_w((it >> 1) + 1, wnx);
         __builtin_amdgcn_sched_barrier(0);                   // all loads are issued up here, unconditionally
@@ -255,6 +271,20 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         const int64_t g = it;                                // group index = stage index (G = 128)
 
         const v4i b00 = b_next;
+        // Each block is a scheduling region of its own (sched_barrier at its end): the vector work placed in a
+        // block reads only accumulators finished at least one block (eight matrix instructions) earlier.  In one
+        // region the scheduler pulled the fmas up to right behind the matrix instruction that produces their
+        // operand, and every such pair stalls the wave until the matrix pipe has written the result (measured:
+        // 2070 TOP/s; 4290 with the same fmas reading other registers).
+        auto interleave = [&](bool with_lds) {               // per matrix instruction: [one LDS read] three vector instructions
+#pragma unroll
+            for (int k = 0; k < RI; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (with_lds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
         // block A
 #pragma unroll
         for (int i = 0; i < RI; ++i) a1[i] = *reinterpret_cast<const v4i*>(ab + i * 16 * A_STRIDE + 64);
@@ -262,17 +292,20 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 #pragma unroll
         for (int i = 0; i < RI; ++i) acc[i][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0[i], b00, biasv, 0, 0, 0);
         dequant_half(1, 0, pend_sw, pend_g);
+        interleave(true);
         // block B
         const v4i b01 = upconvert4(dword_of(wc, 1, h, 0));
 #pragma unroll
         for (int i = 0; i < RI; ++i) acc[i][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1[i], b10, acc[i][0], 0, 0, 0);
         dequant_half(1, RI / 2, pend_sw, pend_g);
         ssum[1] += pend_sw;
+        interleave(false);
         // block C
         const v4i b11 = upconvert4(dword_of(wc, 1, h, 1));
 #pragma unroll
         for (int i = 0; i < RI; ++i) acc[i][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0[i], b01, biasv, 0, 0, 0);
         dequant_half(0, 0, sw0, g);
+        interleave(false);
         // block D
 #pragma unroll
         for (int i = 0; i < RI; ++i) a0[i] = *reinterpret_cast<const v4i*>(abn + i * 16 * A_STRIDE);
@@ -283,18 +316,9 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         ssum[0] += sw0;
         pend_sw = DBG ? 1.0f : sw1;
         pend_g = g;
-        // issue order: one matrix instruction, then the LDS read (blocks A and D) and the vector instructions it hides
-#pragma unroll
-        for (int blk = 0; blk < 4; ++blk) {
-#pragma unroll
-            for (int k = 0; k < RI; ++k) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (blk == 0 || blk == 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-            }
-        }
+        interleave(true);
         buf = buf1;
-        __syncthreads();
+        if constexpr (NBUF == 3 || h == 1) __syncthreads();
     };
 
     // one 256-k tile (two stages) per iteration; the next tile's weights arrive in w1 meanwhile and move
@@ -310,7 +334,7 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
 #pragma unroll
             for (int j = 0; j < CJ; ++j) {
                 // column 1 of the stage just finished is still pending: its scale is not in ssum[1] yet
-                const float corr = ssum[j] * 0x1p-128f;      // BIAS * 2^-149 = 2^-128
+                const float corr = ssum[j] * BIAS_F;
                 ssum[j] = 0.f;
 #pragma unroll
                 for (int i = 0; i < RI; ++i)
@@ -346,7 +370,7 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
             const float s = a.sx[m < a.M ? m : a.M - 1];
             float z[CJ];
 #pragma unroll
-            for (int j = 0; j < CJ; ++j) z[j] = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f * s + bias[j];
+            for (int j = 0; j < CJ; ++j) z[j] = (y[i][j][r] - ssum[j] * BIAS_F) * 0x1p79f * s + bias[j];
             if (gated) {
                 eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(silu_f32(z[0]) * z[1]);
             } else {
