@@ -83,6 +83,57 @@ def pmc_mode(torch, w2, lib, vp, pool, shapes, Xd, Yd, dev):
           "x3 (w2a16)" % len(pool))
 
 
+def gamma_mode(torch, w2, synth, dev, timing):
+    """The small-batch sweep (gate+up 4096 x 28672, M in {1,2,4,8,16}, G in {64,128}) through every w2a8 kernel
+    family that covers the M.  With `timing` each case is graph-timed over a pool of weight copies (one line
+    per case); without it each case is launched eagerly three times, in the same order, for `rocprofv3 --pmc`
+    to count its instructions (the line then carries the case's position in the dispatch order)."""
+    K, N = synth.SHAPES_8B["gate_up"]
+    fam = [("gemv", w2.VARIANT_GEMV, 4), ("dot4", w2.VARIANT_DOT4, 4), ("smallm", w2.VARIANT_SMALLM, 16),
+           ("midm", w2.VARIANT_MIDM, 64)]
+    pos = 0
+    for g in (128, 64):
+        nb = w2.packed_size(K, N, g)
+        n = max(2, -(-POOL_BYTES // nb)) if timing else 1
+        base = torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev)
+        base[K * N // 4:].view(torch.int16)[:] = 0x3C00
+        pool = [base] + [base.clone() for _ in range(n - 1)]
+        for M in (1, 2, 4, 8, 16):
+            X = torch.randn(M, K, device=dev)
+            xq, sx, _ = w2.quantize_rows(X, g)
+            Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            pos += 1                                          # the quantise launch
+            for name, variant, m_max in fam:
+                if M > m_max:
+                    continue
+                words = K * N // 16                           # 32-bit code words per launch
+                if timing:
+                    gr = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gr):
+                        for l in pool:
+                            w2.matmul_a8(l, K, N, g, xq, sx, out=Y, variant=variant)
+                    t_end = time.perf_counter() + 0.1
+                    while time.perf_counter() < t_end:
+                        gr.replay()
+                        torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(6):
+                        gr.replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    us = e0.elapsed_time(e1) * 1e3 / (6 * len(pool))
+                    by = algorithmic_bytes(M, K, N, g)
+                    print("gamma G=%3d M=%2d %-6s %8.2f us %8.1f GB/s  code words %d" % (g, M, name, us, by / us / 1e3, words),
+                          flush=True)
+                else:
+                    for _ in range(3):
+                        w2.matmul_a8(pool[0], K, N, g, xq, sx, out=Y, variant=variant)
+                    print("gamma G=%3d M=%2d %-6s dispatches %d..%d  code words %d" % (g, M, name, pos, pos + 2, words), flush=True)
+                    pos += 3
+    torch.cuda.synchronize()
+
+
 def sweep_mode(torch, w2, synth, dev):
     """One line per (configuration, projection, M, call): microseconds per launch, the method's own
     bytes / time (GB/s, % of 8 TB/s) for M <= 64, ops / time (TOP/s, % of the MFMA peak) above."""
@@ -195,6 +246,10 @@ def main():
                     help="counter-collection mode for `rocprofv3 --pmc`: launch, eagerly and a few times each, a plain "
                          "256 MiB device copy (the calibration kernel), the streaming read, the dominant GEMV over "
                          "the pool and the prefill kernel; print no bench line")
+    ap.add_argument("--gamma", choices=["time", "count"],
+                    help="the small-batch sweep on gate+up (M = 1..16, G = 64 and 128, every w2a8 kernel family): "
+                         "`time` prints graph-timed microseconds per launch, `count` launches each case eagerly "
+                         "three times for `rocprofv3 --pmc` (vector instructions per 32-bit code word)")
     ap.add_argument("--sweep", action="store_true",
                     help="time every configuration BASELINE.json lists (decode shapes from HIP graphs over a pool "
                          "of distinct weight copies, prefill shapes under sustained launches) and print a table "
@@ -213,6 +268,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.sweep:
         return sweep_mode(torch, w2, synth, dev)
+    if args.gamma:
+        return gamma_mode(torch, w2, synth, dev, args.gamma == "time")
     M = 1
     shapes = synth.SHAPES_8B
 
