@@ -83,6 +83,36 @@ def pmc_mode(torch, w2, lib, vp, pool, shapes, Xd, Yd, dev):
           "x3 (w2a16)" % len(pool))
 
 
+def probe_sweep_mode(torch, w2, synth, dev):
+    """Launch-shape sweep of the streaming-read probe (the ceiling the decode kernels are compared with) on the
+    four 8B-class blobs: chunks in flight per wave x most workgroups, graph-timed over a pool of copies."""
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    for name, (K, N) in synth.SHAPES_8B.items():
+        nb = w2.packed_size(K, N, G)
+        n = max(2, -(-POOL_BYTES // nb))
+        base = torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev)
+        pool = [base] + [base.clone() for _ in range(n - 1)]
+        for u in (4, 8, 16):
+            for b in (256, 512, 1024, 2048, 4096, 8192, 16384):
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr):
+                    for l in pool:
+                        w2.debug_stream_read(l, sink, tune={"stream_unroll": u, "stream_blocks": b})
+                t_end = time.perf_counter() + 0.05
+                while time.perf_counter() < t_end:
+                    gr.replay()
+                    torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(6):
+                    gr.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / (6 * len(pool))
+                print("probe %-8s %9d B unroll=%2d blocks=%5d %7.2f us %7.1f GB/s" % (name, nb, u, b, us, nb / us / 1e3), flush=True)
+        del pool
+
+
 def gamma_mode(torch, w2, synth, dev, timing):
     """The small-batch sweep (gate+up 4096 x 28672, M in {1,2,4,8,16}, G in {64,128}) through every w2a8 kernel
     family that covers the M.  With `timing` each case is graph-timed over a pool of weight copies (one line
@@ -246,6 +276,8 @@ def main():
                     help="counter-collection mode for `rocprofv3 --pmc`: launch, eagerly and a few times each, a plain "
                          "256 MiB device copy (the calibration kernel), the streaming read, the dominant GEMV over "
                          "the pool and the prefill kernel; print no bench line")
+    ap.add_argument("--probe-sweep", action="store_true",
+                    help="launch-shape sweep of the streaming-read probe on the 8B-class blobs (a table, no bench line)")
     ap.add_argument("--gamma", choices=["time", "count"],
                     help="the small-batch sweep on gate+up (M = 1..16, G = 64 and 128, every w2a8 kernel family): "
                          "`time` prints graph-timed microseconds per launch, `count` launches each case eagerly "
@@ -268,6 +300,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.sweep:
         return sweep_mode(torch, w2, synth, dev)
+    if args.probe_sweep:
+        return probe_sweep_mode(torch, w2, synth, dev)
     if args.gamma:
         return gamma_mode(torch, w2, synth, dev, args.gamma == "time")
     M = 1
