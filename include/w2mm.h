@@ -108,7 +108,7 @@ typedef struct {
     int tiled_bm;         /* w2a8 TILED: rows per workgroup: 64 or 128 (128: G = 128, K not split) */
     int tiled_bn;         /* TILED / SCALED16 tiled kernels: columns per workgroup: 128 or 256 */
     int tiled_group_m;    /* ... row tiles per band of the workgroup order: 1..1024 */
-    int splitk;           /* tiled kernels: 1 = never split K, n = 2..16: n parts if the workspace holds them */
+    int splitk;           /* tiled and mid-M kernels: 1 = never split K, n = 2..16: n parts if the workspace holds them */
     int splitk_min_tiles; /* ... planner: fewest 256-k tiles per part, 1..1024 */
     int stream_unroll;    /* w2_debug_stream_read: 1 KiB chunks in flight per wave: 4, 8 or 16 */
     int stream_blocks;    /* ... most workgroups launched: 1..65536 */
@@ -168,13 +168,14 @@ W2_API int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_
  * xq, sx  dev, as produced by w2_quantize_rows ([M][K] dense, [M])
  * Y       dev, bf16 bit patterns [M][N], row stride ldy
  * workspace  optional (NULL / 0: none), dev, 16-byte aligned, contents
- *            undefined before and after: for M > 64 on shapes with few
- *            output tiles and a deep K the tiled kernel splits K across
- *            workgroups (Sec. II-D, K-splitting for the smaller GEMM
- *            shapes) if it is given room for the fp32 partial results
- *            (w2_workspace_size; less room = fewer parts or none, same
- *            result contract).  A second launch on `stream` sums the parts
- *            in a fixed order.  Not touched otherwise. */
+ *            undefined before and after: on shapes with few output tiles
+ *            and a deep K (M > 64: the tiled kernel; 4 <= M <= 128 and
+ *            K >= 13568: the mid-M kernel) K is split across workgroups
+ *            (Sec. II-D, K-splitting for the smaller GEMM shapes) if there
+ *            is room for the fp32 partial results (w2_workspace_size; less
+ *            room = fewer parts or none, same result contract).  A second
+ *            launch on `stream` sums the parts in a fixed order.  Not
+ *            touched otherwise. */
 W2_API int w2_matmul_a8(const void* packed, int64_t K, int64_t N, int G, const int8_t* xq,
                  const float* sx, int64_t M, uint16_t* Y, int64_t ldy, void* workspace,
                  size_t workspace_bytes, void* stream);
@@ -189,10 +190,10 @@ W2_API int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, cons
  * fused into the GEMM; Sec. III-C: fusing wins for matrix-vector shapes, a
  * separate abs-max pass for multi-row activations).  Takes the unquantised
  * activations (fp32 or bf16, row stride ldx) and produces exactly what
- * w2_quantize_rows followed by w2_matmul_a8 produces, bit for bit (where the
- * tiled kernel splits K, i.e. M > 64 with room in the workspace beyond the
- * int8 rows, the fp32 sums are taken in another order and the two agree to the
- * tolerance of the result contract instead).
+ * w2_quantize_rows followed by w2_matmul_a8 produces, bit for bit (where a
+ * kernel splits K, see w2_matmul_a8's workspace, with room in the workspace
+ * beyond the int8 rows, the fp32 sums are taken in another order and the two
+ * agree to the tolerance of the result contract instead).
  *   M <= 2: one launch; the abs-max is reduced per workgroup, redundantly, and
  *           kept in local memory.
  *   M >= 3: with a workspace of w2_workspace_size(M, K, N, G, 0) bytes (dev,
@@ -285,7 +286,7 @@ W2_API int w2_matmul_a16_epi(const void* packed, int64_t K, int64_t N, int G, co
  * route for this problem.  a16 = 0 (w2_matmul_a8_fused; w2_matmul_a8 uses the
  * split-K part only and accepts the same buffer): room for the int8 rows and
  * their scales, rounded up to 256 bytes (0 where one launch covers the
- * quantisation: one or two rows of up to 64 KiB as fp32), plus, where the tiled
+ * quantisation: one or two rows of up to 64 KiB as fp32), plus, where a
  * kernel would split K, 2..16 fp32 copies of the M x N output.  a16 = 1
  * (w2_matmul_a16): the split-K part alone.  0 means no workspace is used. */
 W2_API int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* bytes);

@@ -251,7 +251,7 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     a.n_cb = L.n_cb; a.n_kt = L.n_kt; a.G = G;
     if (workspace && !aligned16(workspace))
         return fail(W2_ERR_MISALIGNED, "%s: workspace must be 16-byte aligned", fn);
-    a.part = (float*)workspace;                              // split-K partial results, if the tiled kernel wants them
+    a.part = (float*)workspace;                              // split-K partial results, if the kernel wants them
     a.part_bytes = workspace ? workspace_bytes : 0;
     a.epi = epi;
     a.tune = tn;
@@ -269,7 +269,10 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         // ... and only up to M = 48 on very wide projections (32768 columns and more), where every
         // workgroup's re-read of the activation rows outweighs the weights (8192 x 57344 at M = 64:
         // 66 us against 50 us through the tiled kernel)
-        const int midm_max = tn.midm_max_m ? tn.midm_max_m : a.n_cb <= 512 ? 128 : a.n_cb >= 2048 ? 48 : 64;
+        // (with room for split-K partial results the tiled kernel is the faster one there once K passes
+        // 16384: 31 against 43 us on 17408 x 5120 at M = 128)
+        const int midm_max = tn.midm_max_m ? tn.midm_max_m
+                           : a.n_cb <= 512 ? (a.part_bytes && a.n_kt > 64 ? 64 : 128) : a.n_cb >= 2048 ? 48 : 64;
         variant = M <= dot4_max && a8_dot4_supports(a)                       ? W2_VARIANT_DOT4
                 : a8_gemv_supports(M)                                        ? W2_VARIANT_GEMV
                 : M >= midm_min && M <= midm_max && a8_midm_supports(a)     ? W2_VARIANT_MIDM
@@ -579,7 +582,13 @@ int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* b
     const w2_tuning_t dflt = {};
     if (M == 0) *bytes = 0;
     else if (a16) *bytes = M > 64 ? a16_fold_splitk_bytes(M, N, L.n_kt, dflt) : 0;
-    else *bytes = (single ? 0 : fused_workspace_bytes(M, K)) + (M > 64 ? a8_tiled_splitk_bytes(M, N, L.n_kt, dflt) : 0);
+    else {
+        // split-K partial results: the tiled kernel's above 64 rows, the mid-M kernel's on deep projections
+        // (whichever of the two the call would pick, the larger need covers it)
+        const size_t tiled = M > 64 ? a8_tiled_splitk_bytes(M, N, L.n_kt, dflt) : 0;
+        const size_t midm = M >= 4 && M <= 128 ? a8_midm_splitk_bytes(M, N, L.n_cb, L.n_kt, dflt) : 0;
+        *bytes = (single ? 0 : fused_workspace_bytes(M, K)) + (tiled > midm ? tiled : midm);
+    }
     return W2_OK;
 }
 

@@ -29,8 +29,8 @@
 // past the end is out of range, which the hardware answers with zeros without
 // touching memory (measured: dummy loads aimed at one shared line instead cost
 // a microsecond, every wave of the grid queueing on it).  Addresses are
-// "resource + scalar offset + lane offset": the loop needs no vector address
-// arithmetic and no division.
+// "resource + lane offset + tile offset", one vector add per load (the range
+// check covers the vector offset only), and no division.
 #include <hip/hip_runtime.h>
 
 #include "w2_small_common.h"
@@ -80,7 +80,8 @@ constexpr int AUX_NT = 2;         // non-temporal: the weights are streamed once
 
 __device__ __forceinline__ u32x4 load_tile(__amdgpu_buffer_rsrc_t wr, int w_lane, int i)
 {
-    return __builtin_amdgcn_raw_buffer_load_b128(wr, w_lane, i * TILE_BYTES, AUX_NT);
+    // the tile's offset goes into the vector offset: the range check covers that one, not the scalar offset
+    return __builtin_amdgcn_raw_buffer_load_b128(wr, w_lane + i * TILE_BYTES, 0, AUX_NT);
 }
 
 // x * inv, one rounding, then round half to even by adding 1.5 * 2^23 (one more rounding: exact for

@@ -34,7 +34,7 @@ constexpr int ROWS_PER_BAND = 64;                            // rows one workgro
 
 template <int G, int RT, int TPC, bool DBG>
 __global__ void __launch_bounds__(THREADS)
-a8_midm_kernel(A8Args a_all)
+a8_midm_kernel(A8Args a_all, int splits)
 {
     // More than 64 rows: blockIdx.y picks a band of 64 rows; the bands stream the same weights (the
     // second one mostly out of L2), which pays when one band's workgroups would leave CUs idle.
@@ -46,6 +46,7 @@ a8_midm_kernel(A8Args a_all)
         if (a.sx) a.sx += m_off;
         if (a.Y) a.Y += m_off * a.ldy;
         if (a.acc_out) a.acc_out += m_off * (a.K / G) * a.N;
+        if (a.part) a.part += ((int64_t)blockIdx.z * a_all.M + m_off) * a.N;
     }
     constexpr int KS = CHUNK_TILES / TPC;                    // k-splits
     constexpr int CBW = 8 / KS;                              // column blocks per workgroup
@@ -62,6 +63,11 @@ a8_midm_kernel(A8Args a_all)
     const int64_t n = cb * TILE_N + l16;
     const int rows = (int)a.M;                               // 1..16*RT
     const int n_chunks = (int)((a.n_kt + CHUNK_TILES - 1) / CHUNK_TILES);
+    // split-K across workgroups (Sec. II-D): blockIdx.z picks one of `splits` near-equal ranges of whole
+    // chunks [c_b, c_e); the workgroup stages only that K range of the activation rows
+    const int c_b = (int)((int64_t)n_chunks * blockIdx.z / splits);
+    const int c_e = (int)((int64_t)n_chunks * (blockIdx.z + 1) / splits);
+    const int64_t kt_hi = min(a.n_kt, (int64_t)c_e * CHUNK_TILES);
     (void)n;
 
     int arow[RT];                                            // padded rows repeat the last
@@ -137,7 +143,7 @@ a8_midm_kernel(A8Args a_all)
     uint32_t w_lane = (uint32_t)lane * 16u, s_lane = (uint32_t)l16 * (GPT * 2u);
     auto load_w = [&](int64_t s) {
         int64_t kt = ks + s * KS;
-        kt = kt < a.n_kt ? kt : a.n_kt - 1;
+        kt = kt < kt_hi ? kt : kt_hi - 1;                    // past this workgroup's range: its last tile again
         const int64_t tile = cbc * a.n_kt + kt;
         const char* wbase = reinterpret_cast<const char*>(a.codes) + tile * (TILE_N * TILE_K / 4);
         const char* sbase = reinterpret_cast<const char*>(a.scales) + tile * (TILE_N * GPT * 2);
@@ -210,27 +216,27 @@ a8_midm_kernel(A8Args a_all)
 
     // activation loads first, then the weight window: vector memory returns in order, so the
     // wait for the activations does not wait for the weights behind them
-    load_x(0, true);
+    load_x(c_b, true);
     TileRegs tr[D];
+    const int64_t s_b = (int64_t)c_b * TPC, s_e = (int64_t)c_e * TPC;    // the same for every wave: barriers match
 #pragma unroll
-    for (int i = 0; i < D; ++i) tr[i] = load_w(i);
+    for (int i = 0; i < D; ++i) tr[i] = load_w(s_b + i);
     __builtin_amdgcn_sched_barrier(0);
 
-    const int64_t s_total = (int64_t)n_chunks * TPC;         // the same for every wave: barriers match
-    for (int64_t s0 = 0; s0 < s_total; s0 += D) {
+    for (int64_t s0 = s_b; s0 < s_e; s0 += D) {
 #pragma unroll
         for (int i = 0; i < D; ++i) {
             const int64_t s = s0 + i;
             const int c = (int)(s / TPC);
             if (i % TPC == 0) {
-                if (c >= n_chunks) break;
-                if (c > 0) __syncthreads();                  // everyone is done reading chunk c-1
+                if (c >= c_e) break;
+                if (c > c_b) __syncthreads();                // everyone is done reading chunk c-1
                 store_x();
                 __syncthreads();
-                load_x(c + 1, c + 1 < n_chunks);
+                load_x(c + 1, c + 1 < c_e);
             }
             const int64_t kt = ks + s * KS;
-            if (kt < a.n_kt) compute(tr[i], kt, (int)(kt - chunk_base(c)));
+            if (kt < kt_hi) compute(tr[i], kt, (int)(kt - chunk_base(c)));
             if ((i & 3) == 3) settle();                      // every 8 (G=128) or 16 (G=64) groups
             tr[i] = load_w(s + D);                           // past the end: re-reads the last tile
             __builtin_amdgcn_sched_barrier(0);
@@ -247,6 +253,20 @@ a8_midm_kernel(A8Args a_all)
 #pragma unroll
         for (int r = 0; r < 4; ++r) red[((wave * RT + rt) * 16 + 4 * q + r) * 16 + l16] = y[rt][r] * 0x1p79f;   // 2^(149-64-6)
     __syncthreads();
+    if (a.part) {
+        // this K range's share of the result, as fp32 [m][n] rows of the workspace (16 * CBW adjacent
+        // columns per row); a second launch adds the ranges in a fixed order and applies the epilogue
+        for (int i = threadIdx.x; i < CBW * rows * 16; i += THREADS) {
+            const int nl = i & 15, ci = (i >> 4) % CBW, m = i / (16 * CBW);
+            const int64_t nn = ((int64_t)blockIdx.x * CBW + ci) * TILE_N + nl;
+            if (nn >= a.N) continue;
+            float s = 0.0f;
+#pragma unroll
+            for (int k = 0; k < KS; ++k) s += red[((k * CBW + ci) * (RT * 16) + m) * 16 + nl];
+            a.part[(int64_t)m * a.N + nn] = s * a.sx[m];
+        }
+        return;
+    }
     store_outputs(a.epi, a.Y, a.ldy, a.N, (int64_t)blockIdx.x * CBW, CBW, rows,
                   [&](int ci, int m, int nl, int) {
                       float s = 0.0f;
@@ -257,33 +277,68 @@ a8_midm_kernel(A8Args a_all)
 }
 
 template <int G, int RT, int TPC>
-static int launch_t(const A8Args& a, hipStream_t stream)
+static int launch_t(const A8Args& a_in, int splits, hipStream_t stream)
 {
     constexpr int CBW = 2 * TPC;
+    A8Args a = a_in;
+    if (splits < 2 || a.acc_out) { a.part = nullptr; splits = 1; }
     const int64_t band = a.M < ROWS_PER_BAND ? a.M : ROWS_PER_BAND;
     const size_t act = (size_t)band * ROW_STRIDE;
     const size_t red = (size_t)8 * RT * 16 * 16 * sizeof(float);
     const size_t lds = act > red ? act : red;
-    const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW), (unsigned)((a.M + ROWS_PER_BAND - 1) / ROWS_PER_BAND)), block(THREADS);
+    const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW), (unsigned)((a.M + ROWS_PER_BAND - 1) / ROWS_PER_BAND),
+                    (unsigned)splits), block(THREADS);
     auto go = [&](auto kern) {
         if (int rc = ensure_dynamic_lds((const void*)kern, lds, "w2_matmul_a8[midm]")) return rc;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, a, splits);
         return check_launch("w2_matmul_a8[midm]");
     };
     if (a.acc_out) return go(a8_midm_kernel<G, RT, TPC, true>);
-    return go(a8_midm_kernel<G, RT, TPC, false>);
+    if (int rc = go(a8_midm_kernel<G, RT, TPC, false>)) return rc;
+    if (splits < 2) return W2_OK;
+    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, a.epi, stream);
+}
+
+// (column blocks per workgroup, K ranges) for a problem with room for `cap` fp32 copies of the output
+struct Plan { int cbw, splits; };
+static Plan plan(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, int64_t cap, const w2_tuning_t& tune)
+{
+    (void)N;
+    const int64_t bands = (M + ROWS_PER_BAND - 1) / ROWS_PER_BAND;
+    const int64_t n_chunks = (n_kt + CHUNK_TILES - 1) / CHUNK_TILES;
+    const int forced_cbw = tune.midm_cbw == 2 || tune.midm_cbw == 4 || tune.midm_cbw == 8 ? tune.midm_cbw : 0;
+    Plan p;
+    // Deep K (14 chunks and more) and room for partial results: about 64 workgroups across the columns,
+    // each as wide as that allows (every workgroup reads all M rows of its K range of the activations:
+    // fewer, wider workgroups move less through L2), times enough K ranges for one workgroup per CU.
+    // Measured at M = 64: 28672 x 8192 34 us against 57 us unsplit, 14336 x 4096 17 against 22 us; at
+    // 8 chunks and fewer the partial results and the second launch cost more than they save.
+    int64_t s = 1;
+    p.cbw = forced_cbw;
+    if (tune.splitk != 1 && cap >= 2 && (tune.splitk > 1 || n_chunks >= 14)) {
+        if (!p.cbw) p.cbw = n_cb >= 8 * 64 ? 8 : n_cb >= 4 * 64 ? 4 : 2;
+        const int64_t wgs = (n_cb + p.cbw - 1) / p.cbw * bands;
+        s = tune.splitk > 1 ? tune.splitk : (256 + wgs / 2) / wgs;
+        if (tune.splitk == 0) s = min(s, n_chunks / 3);
+        s = min(min(s, n_chunks), min((int64_t)16, cap));
+    }
+    if (s < 2) {
+        // K in one piece: as many column blocks per workgroup as still leave about one workgroup per CU
+        s = 1;
+        p.cbw = forced_cbw ? forced_cbw : n_cb >= 8 * 224 ? 8 : n_cb >= 4 * 224 ? 4 : 2;
+    }
+    p.splits = (int)s;
+    return p;
 }
 
 template <int G, int RT>
 static int launch_rt(const A8Args& a, hipStream_t stream)
 {
-    // column blocks per workgroup: as many as still leave at least 128 workgroups, since every
-    // workgroup reads all M rows of the activations (fewer, wider workgroups move less through L2)
-    int cbw = a.tune.midm_cbw;
-    if (cbw != 2 && cbw != 4 && cbw != 8) cbw = a.n_cb >= 8 * 128 ? 8 : a.n_cb >= 4 * 128 ? 4 : 2;
-    if (cbw == 8) return launch_t<G, RT, 4>(a, stream);
-    if (cbw == 4) return launch_t<G, RT, 2>(a, stream);
-    return launch_t<G, RT, 1>(a, stream);
+    const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
+    const Plan p = plan(a.M, a.N, a.n_cb, a.n_kt, cap, a.tune);
+    if (p.cbw == 8) return launch_t<G, RT, 4>(a, p.splits, stream);
+    if (p.cbw == 4) return launch_t<G, RT, 2>(a, p.splits, stream);
+    return launch_t<G, RT, 1>(a, p.splits, stream);
 }
 
 template <int G>
@@ -298,6 +353,12 @@ static int launch_g(const A8Args& a, hipStream_t stream)
 
 // up to four bands of 64 rows (beyond that the tiled kernel's reuse of the weights wins everywhere)
 bool a8_midm_supports(const A8Args& a) { return a.M >= 1 && a.M <= 4 * midm::ROWS_PER_BAND; }
+
+size_t a8_midm_splitk_bytes(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, const w2_tuning_t& tune)
+{
+    const int s = midm::plan(M, N, n_cb, n_kt, 16, tune).splits;
+    return s < 2 ? 0 : (size_t)s * M * N * sizeof(float);
+}
 
 int launch_a8_midm(const A8Args& a, hipStream_t stream)
 {

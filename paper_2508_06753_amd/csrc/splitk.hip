@@ -24,21 +24,35 @@ int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t
     return s < 2 ? 1 : (int)s;
 }
 
+// Sum over the parts of eight adjacent columns, part 0 first.  All SMAX loads are issued before the
+// first addition (a loop with a run-time trip count would wait for each part's round trip in turn);
+// slots past the last part re-read it and are left out of the sum.
+template <int SMAX>
 __device__ __forceinline__ void sum8(const float* __restrict__ part, int splits, int64_t M, int64_t N, int64_t m,
                                      int64_t n, float (&acc)[8])
 {
+    float4 a[SMAX], b[SMAX];
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
+        const int se = s < splits ? s : splits - 1;
+        const float4* p = reinterpret_cast<const float4*>(part + ((int64_t)se * M + m) * N + n);
+        a[s] = p[0];
+        b[s] = p[1];
+    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int s = 0; s < splits; ++s) {
-        const float4* p = reinterpret_cast<const float4*>(part + ((int64_t)s * M + m) * N + n);
-        const float4 a = p[0], b = p[1];
-        acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
-        acc[4] += b.x; acc[5] += b.y; acc[6] += b.z; acc[7] += b.w;
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
+        if (s < splits) {
+            acc[0] += a[s].x; acc[1] += a[s].y; acc[2] += a[s].z; acc[3] += a[s].w;
+            acc[4] += b[s].x; acc[5] += b[s].y; acc[6] += b[s].z; acc[7] += b[s].w;
+        }
     }
 }
 
 // One thread per eight adjacent output columns.  The fused epilogue is applied here, after the sum:
 // bias, SiLU, or (gated) silu(gate block) * (up block) for the pairs of adjacent 16-column blocks.
+template <int SMAX>
 __global__ void __launch_bounds__(256)
 splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t M, int64_t N, uint16_t* __restrict__ Y,
                      int64_t ldy, Epilogue epi)
@@ -51,7 +65,7 @@ splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t M, int6
     const int64_t m = i / n8, no = (i - m * n8) * 8;
     float acc[8];
     if (!gated) {
-        sum8(part, splits, M, N, m, no, acc);
+        sum8<SMAX>(part, splits, M, N, m, no, acc);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             if (epi.bias) acc[e] += __uint_as_float((uint32_t)epi.bias[no + e] << 16);
@@ -60,8 +74,8 @@ splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t M, int6
     } else {
         const int64_t ng = (no / 16) * 32 + (no % 16);       // the gate columns of these outputs; up: 16 further
         float up[8];
-        sum8(part, splits, M, N, m, ng, acc);
-        sum8(part, splits, M, N, m, ng + 16, up);
+        sum8<SMAX>(part, splits, M, N, m, ng, acc);
+        sum8<SMAX>(part, splits, M, N, m, ng + 16, up);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             if (epi.bias) {
@@ -86,8 +100,11 @@ int launch_splitk_reduce(const float* part, int splits, int64_t M, int64_t N, ui
                          const Epilogue& epi, hipStream_t stream)
 {
     const int64_t items = M * ((epi.act == ACT_SILU_MUL ? N / 2 : N) / 8);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, part,
-                       splits, M, N, Y, ldy, epi);
+    const dim3 grid((unsigned)((items + 255) / 256)), block(256);
+    if (splits < 1 || splits > 16) { set_error("split-K reduce: %d parts", splits); return W2_ERR_INVALID_ARG; }
+    if (splits <= 4) hipLaunchKernelGGL(splitk_reduce_kernel<4>, grid, block, 0, stream, part, splits, M, N, Y, ldy, epi);
+    else if (splits <= 8) hipLaunchKernelGGL(splitk_reduce_kernel<8>, grid, block, 0, stream, part, splits, M, N, Y, ldy, epi);
+    else hipLaunchKernelGGL(splitk_reduce_kernel<16>, grid, block, 0, stream, part, splits, M, N, Y, ldy, epi);
     return check_launch("split-K reduce");
 }
 

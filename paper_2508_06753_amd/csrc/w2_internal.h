@@ -45,7 +45,7 @@ struct A8Args {
     int64_t M, K, N, ldy;
     int64_t n_cb, n_kt;
     int G;
-    // split-K across workgroups (tiled kernel only): fp32 partial results [splits][M][N] in a caller's
+    // split-K across workgroups (tiled and mid-M kernels): fp32 partial results [splits][M][N] in a caller's
     // workspace, summed and rounded by a second launch; nullptr / 0 = not available
     float* part = nullptr;
     size_t part_bytes = 0;
@@ -97,6 +97,7 @@ int launch_a16_midm(const A16Args& a, hipStream_t stream);
 int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t N, int64_t cap);
 // Bytes of workspace with which the tiled kernels would split K for this problem (0: they would not).
 size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune);
+size_t a8_midm_splitk_bytes(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, const w2_tuning_t& tune);
 size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune);
 // Y[m][n] = bf16(sum_s part[s][m][n]), a fixed order of summation
 int launch_splitk_reduce(const float* part, int splits, int64_t M, int64_t N, uint16_t* Y, int64_t ldy,

@@ -400,6 +400,10 @@ def test_workspace_size_rule(w2):
     for a16 in (False, True):
         extra = w2.workspace_size(128, 14336, 4096, 128, a16=a16) - (0 if a16 else quant(128, 14336))
         assert extra > 0 and extra % (128 * 4096 * 4) == 0 and 2 <= extra // (128 * 4096 * 4) <= 16
+    # the mid-M kernel splits a deep K too (14 chunks of 1024 k and more), not a shallow one
+    extra = w2.workspace_size(16, 28672, 8192, 128) - quant(16, 28672)
+    assert extra > 0 and extra % (16 * 8192 * 4) == 0 and 2 <= extra // (16 * 8192 * 4) <= 16
+    assert w2.workspace_size(16, 4096, 28672, 128) == quant(16, 4096)
 
 
 @pytest.mark.parametrize("splitk", [0, 2, 3, 5])
@@ -428,6 +432,34 @@ def test_tiled_split_k(w2, M, K, N, G, splitk):
         small = torch.empty(M * N * 4, dtype=torch.uint8, device="cuda")
         Y1 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED, workspace=small)
         Y0 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED)
+        assert torch.equal(Y1.view(torch.int16), Y0.view(torch.int16))
+
+
+@pytest.mark.parametrize("cbw,splitk", [(2, 2), (4, 3), (8, 2), (2, 5), (0, 0)])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("M,K,N", [(9, 2304, 272), (33, 5376, 48), (64, 3072, 1032), (100, 2048, 272), (16, 14336, 64)])
+def test_midm_split_k(w2, M, K, N, G, cbw, splitk):
+    # the mid-M kernel with K cut into ranges of whole 1024-k chunks across workgroups: every workgroup
+    # width, forced part counts (uneven ranges, more parts than chunks: clamped), a ragged last chunk that
+    # overlaps its predecessor (2304, 5376), two bands of rows, and the planner's own choice (deep K: splits)
+    tune = {"midm_cbw": cbw, "splitk": splitk}
+    codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + N + G + cbw)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    ws = torch.empty(16 * M * N * 4, dtype=torch.uint8, device="cuda")
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_MIDM, workspace=ws, tune=tune)
+    Y2 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_MIDM, workspace=ws, tune=tune)
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "not deterministic"
+    oq, osx, _ = oracle.quantize_rows(X, G)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    Yo, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+    check_y(bf16_bits(Y), Yo, y64, mag, f"a8 mid-M split-K {splitk} cbw={cbw} M={M} K={K} N={N} G={G}")
+    if splitk >= 2:
+        # a workspace too small for two parts: no split, the unsplit kernel's bits
+        small = torch.empty(M * N * 4, dtype=torch.uint8, device="cuda")
+        Y1 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_MIDM, workspace=small, tune=tune)
+        Y0 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_MIDM, tune={"midm_cbw": cbw})
         assert torch.equal(Y1.view(torch.int16), Y0.view(torch.int16))
 
 
