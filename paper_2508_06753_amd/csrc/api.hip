@@ -531,7 +531,10 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         const int midm_min = tn.midm_min_m ? tn.midm_min_m : 9;
         // two bands on small projections; on very wide ones (32768 columns and more) the tiled kernel
         // takes over at M = 41 (8192 x 57344 at M = 48: 94 against 104 us)
-        const int midm_max = tn.midm_max_m ? tn.midm_max_m : a.n_cb <= 256 ? 128 : a.n_cb >= 2048 ? 40 : 64;
+        // (and with room for split-K partial results the tiled kernel wins above 64 rows once K passes 8192:
+        // 28 against 35 us on 14336 x 4096 at M = 128)
+        const int midm_max = tn.midm_max_m ? tn.midm_max_m
+                           : a.n_cb <= 256 ? (a.part_bytes && a.n_kt > 32 ? 64 : 128) : a.n_cb >= 2048 ? 40 : 64;
         if (M >= midm_min && M <= midm_max && a16_midm_supports(a)) return launch_a16_midm(a, (hipStream_t)stream);
         if (!a16_smallm_supports(a)) return launch_a16_fold_tiled(a, (hipStream_t)stream);
         variant = W2_VARIANT_SMALLM;
@@ -581,7 +584,11 @@ int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* b
     const Layout L = make_layout(K, N, G);
     const w2_tuning_t dflt = {};
     if (M == 0) *bytes = 0;
-    else if (a16) *bytes = M > 64 ? a16_fold_splitk_bytes(M, N, L.n_kt, dflt) : 0;
+    else if (a16) {
+        const size_t tiled = M > 64 ? a16_fold_splitk_bytes(M, N, L.n_kt, dflt) : 0;
+        const size_t midm = M >= 9 && M <= 128 ? a16_midm_splitk_bytes(M, N, L.n_cb, L.n_kt, dflt) : 0;
+        *bytes = tiled > midm ? tiled : midm;
+    }
     else {
         // split-K partial results: the tiled kernel's above 64 rows, the mid-M kernel's on deep projections
         // (whichever of the two the call would pick, the larger need covers it)

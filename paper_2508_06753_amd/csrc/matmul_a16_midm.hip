@@ -67,7 +67,7 @@ __device__ __forceinline__ v4f mfma_bf16(const v4i& a, const v4i& b, const v4f& 
 
 template <int G, int RT, int TPC>
 __global__ void __launch_bounds__(THREADS)
-a16_midm_kernel(A16Args a_all)
+a16_midm_kernel(A16Args a_all, int splits)
 {
     // More than 64 rows: blockIdx.y picks a band of 64 rows; the bands stream the same weights (the
     // second one mostly out of L2), which pays when one band's workgroups would leave CUs idle.
@@ -77,6 +77,7 @@ a16_midm_kernel(A16Args a_all)
         a.M = min((int64_t)ROWS_PER_BAND, a_all.M - m_off);
         a.X += m_off * a.ldx;
         a.Y += m_off * a.ldy;
+        if (a.part) a.part += ((int64_t)blockIdx.z * a_all.M + m_off) * a.N;
     }
     constexpr int KS = CHUNK_TILES / TPC;                    // k-splits
     constexpr int CBW = 8 / KS;                              // column blocks per workgroup
@@ -92,6 +93,11 @@ a16_midm_kernel(A16Args a_all)
     const int64_t cbc = cb < a.n_cb ? cb : a.n_cb - 1;       // clamp: keeps loads in bounds
     const int rows = (int)a.M;                               // 1..16*RT
     const int n_chunks = (int)((a.n_kt + CHUNK_TILES - 1) / CHUNK_TILES);
+    // split-K across workgroups (Sec. II-D): blockIdx.z picks one of `splits` near-equal ranges of whole
+    // chunks [c_b, c_e); the workgroup stages only that K range of the activation rows
+    const int c_b = (int)((int64_t)n_chunks * blockIdx.z / splits);
+    const int c_e = (int)((int64_t)n_chunks * (blockIdx.z + 1) / splits);
+    const int64_t kt_hi = min(a.n_kt, (int64_t)c_e * CHUNK_TILES);
 
     int arow[RT];                                            // padded rows repeat the last
 #pragma unroll
@@ -156,7 +162,7 @@ a16_midm_kernel(A16Args a_all)
     uint32_t w_lane = (uint32_t)lane * 16u, s_lane = (uint32_t)l16 * (GPT * 2u);
     auto load_w = [&](int64_t s) {
         int64_t kt = ks + s * KS;
-        kt = kt < a.n_kt ? kt : a.n_kt - 1;
+        kt = kt < kt_hi ? kt : kt_hi - 1;                    // past this workgroup's range: its last tile again
         const int64_t tile = cbc * a.n_kt + kt;
         const char* wbase = reinterpret_cast<const char*>(a.codes) + tile * (TILE_N * TILE_K / 4);
         const char* sbase = reinterpret_cast<const char*>(a.scales) + tile * (TILE_N * GPT * 2);
@@ -204,27 +210,27 @@ a16_midm_kernel(A16Args a_all)
 
     // activation loads first, then the weight window: vector memory returns in order, so the
     // wait for the activations does not wait for the weights behind them
-    load_x(0, true);
+    load_x(c_b, true);
     TileRegs tr[D];
+    const int64_t s_b = (int64_t)c_b * TPC, s_e = (int64_t)c_e * TPC;    // the same for every wave: barriers match
 #pragma unroll
-    for (int i = 0; i < D; ++i) tr[i] = load_w(i);
+    for (int i = 0; i < D; ++i) tr[i] = load_w(s_b + i);
     __builtin_amdgcn_sched_barrier(0);
 
-    const int64_t s_total = (int64_t)n_chunks * TPC;         // the same for every wave: barriers match
-    for (int64_t s0 = 0; s0 < s_total; s0 += D) {
+    for (int64_t s0 = s_b; s0 < s_e; s0 += D) {
 #pragma unroll
         for (int i = 0; i < D; ++i) {
             const int64_t s = s0 + i;
             const int c = (int)(s / TPC);
             if (i % TPC == 0) {
-                if (c >= n_chunks) break;
-                if (c > 0) __syncthreads();                  // everyone is done reading chunk c-1
+                if (c >= c_e) break;
+                if (c > c_b) __syncthreads();                // everyone is done reading chunk c-1
                 store_x();
                 __syncthreads();
-                load_x(c + 1, c + 1 < n_chunks);
+                load_x(c + 1, c + 1 < c_e);
             }
             const int64_t kt = ks + s * KS;
-            if (kt < a.n_kt) compute(tr[i], (int)(kt - chunk_base(c)));
+            if (kt < kt_hi) compute(tr[i], (int)(kt - chunk_base(c)));
             tr[i] = load_w(s + D);                           // past the end: re-reads the last tile
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -238,6 +244,20 @@ a16_midm_kernel(A16Args a_all)
         for (int r = 0; r < 4; ++r)
             red[((wave * RT + rt) * 16 + 4 * q + r) * 16 + l16] = acc[0][rt][r] + acc[1][rt][r];
     __syncthreads();
+    if (a.part) {
+        // this K range's share of the result, as fp32 [m][n] rows of the workspace; a second launch adds
+        // the ranges in a fixed order and applies the epilogue
+        for (int i = threadIdx.x; i < CBW * rows * 16; i += THREADS) {
+            const int nl = i & 15, ci = (i >> 4) % CBW, m = i / (16 * CBW);
+            const int64_t nn = ((int64_t)blockIdx.x * CBW + ci) * TILE_N + nl;
+            if (nn >= a.N) continue;
+            float s = 0.0f;
+#pragma unroll
+            for (int k = 0; k < KS; ++k) s += red[((k * CBW + ci) * (RT * 16) + m) * 16 + nl];
+            a.part[(int64_t)m * a.N + nn] = s;
+        }
+        return;
+    }
     store_outputs(a.epi, a.Y, a.ldy, a.N, (int64_t)blockIdx.x * CBW, CBW, rows,
                   [&](int ci, int m, int nl, int) {
                       float s = 0.0f;
@@ -248,30 +268,34 @@ a16_midm_kernel(A16Args a_all)
 }
 
 template <int G, int RT, int TPC>
-static int launch_t(const A16Args& a, hipStream_t stream)
+static int launch_t(const A16Args& a_in, int splits, hipStream_t stream)
 {
     constexpr int CBW = 2 * TPC;
+    A16Args a = a_in;
+    if (splits < 2) { a.part = nullptr; splits = 1; }
     const int64_t band = a.M < ROWS_PER_BAND ? a.M : ROWS_PER_BAND;
     const size_t act = (size_t)band * ROW_STRIDE;
     const size_t red = (size_t)8 * RT * 16 * 16 * sizeof(float);
     const size_t lds = act > red ? act : red;
-    const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW), (unsigned)((a.M + ROWS_PER_BAND - 1) / ROWS_PER_BAND)), block(THREADS);
+    const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW), (unsigned)((a.M + ROWS_PER_BAND - 1) / ROWS_PER_BAND),
+                    (unsigned)splits), block(THREADS);
     auto kern = a16_midm_kernel<G, RT, TPC>;
     if (int rc = ensure_dynamic_lds((const void*)kern, lds, "w2_matmul_a16[midm]")) return rc;
-    hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
-    return check_launch("w2_matmul_a16[midm]");
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, splits);
+    if (int rc = check_launch("w2_matmul_a16[midm]")) return rc;
+    if (splits < 2) return W2_OK;
+    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, a.epi, stream);
 }
 
 template <int G, int RT>
 static int launch_rt(const A16Args& a, hipStream_t stream)
 {
-    // column blocks per workgroup: as many as still leave at least 128 workgroups, since every
-    // workgroup reads all M rows of the activations
-    int cbw = a.tune.midm_cbw;
-    if (cbw != 2 && cbw != 4 && cbw != 8) cbw = a.n_cb >= 8 * 128 ? 8 : a.n_cb >= 4 * 128 ? 4 : 2;
-    if (cbw == 8) return launch_t<G, RT, 4>(a, stream);
-    if (cbw == 4) return launch_t<G, RT, 2>(a, stream);
-    return launch_t<G, RT, 1>(a, stream);
+    // the same launch shape as the int8-activation kernel's (workgroup width, K ranges)
+    const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
+    const MidmPlan p = midm_plan(a.M, a.n_cb, a.n_kt, cap, a.tune);
+    if (p.cbw == 8) return launch_t<G, RT, 4>(a, p.splits, stream);
+    if (p.cbw == 4) return launch_t<G, RT, 2>(a, p.splits, stream);
+    return launch_t<G, RT, 1>(a, p.splits, stream);
 }
 
 template <int G>
@@ -286,6 +310,12 @@ static int launch_g(const A16Args& a, hipStream_t stream)
 
 // up to four bands of 64 rows
 bool a16_midm_supports(const A16Args& a) { return a.M >= 1 && a.M <= 4 * midm16::ROWS_PER_BAND; }
+
+size_t a16_midm_splitk_bytes(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, const w2_tuning_t& tune)
+{
+    const int s = midm_plan(M, n_cb, n_kt, 16, tune).splits;
+    return s < 2 ? 0 : (size_t)s * M * N * sizeof(float);
+}
 
 int launch_a16_midm(const A16Args& a, hipStream_t stream)
 {

@@ -24,6 +24,37 @@
 
 namespace w2 {
 
+// (column blocks per workgroup, K ranges) for a problem with room for `cap` fp32 copies of the output
+MidmPlan midm_plan(int64_t M, int64_t n_cb, int64_t n_kt, int64_t cap, const w2_tuning_t& tune)
+{
+    constexpr int ROWS_PER_BAND = 64, CHUNK_TILES = 4;
+    const int64_t bands = (M + ROWS_PER_BAND - 1) / ROWS_PER_BAND;
+    const int64_t n_chunks = (n_kt + CHUNK_TILES - 1) / CHUNK_TILES;
+    const int forced_cbw = tune.midm_cbw == 2 || tune.midm_cbw == 4 || tune.midm_cbw == 8 ? tune.midm_cbw : 0;
+    MidmPlan p;
+    // Deep K (14 chunks and more) and room for partial results: about 64 workgroups across the columns,
+    // each as wide as that allows (every workgroup reads all M rows of its K range of the activations:
+    // fewer, wider workgroups move less through L2), times enough K ranges for one workgroup per CU.
+    // Measured at M = 64: 28672 x 8192 34 us against 57 us unsplit, 14336 x 4096 17 against 22 us; at
+    // 8 chunks and fewer the partial results and the second launch cost more than they save.
+    int64_t s = 1;
+    p.cbw = forced_cbw;
+    if (tune.splitk != 1 && cap >= 2 && (tune.splitk > 1 || n_chunks >= 14)) {
+        if (!p.cbw) p.cbw = n_cb >= 8 * 64 ? 8 : n_cb >= 4 * 64 ? 4 : 2;
+        const int64_t wgs = (n_cb + p.cbw - 1) / p.cbw * bands;
+        s = tune.splitk > 1 ? tune.splitk : (256 + wgs / 2) / wgs;
+        if (tune.splitk == 0) s = min(s, n_chunks / 3);
+        s = min(min(s, n_chunks), min((int64_t)16, cap));
+    }
+    if (s < 2) {
+        // K in one piece: as many column blocks per workgroup as still leave about one workgroup per CU
+        s = 1;
+        p.cbw = forced_cbw ? forced_cbw : n_cb >= 8 * 224 ? 8 : n_cb >= 4 * 224 ? 4 : 2;
+    }
+    p.splits = (int)s;
+    return p;
+}
+
 namespace midm {
 
 constexpr int THREADS = 512;
@@ -299,43 +330,11 @@ static int launch_t(const A8Args& a_in, int splits, hipStream_t stream)
     return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, a.epi, stream);
 }
 
-// (column blocks per workgroup, K ranges) for a problem with room for `cap` fp32 copies of the output
-struct Plan { int cbw, splits; };
-static Plan plan(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, int64_t cap, const w2_tuning_t& tune)
-{
-    (void)N;
-    const int64_t bands = (M + ROWS_PER_BAND - 1) / ROWS_PER_BAND;
-    const int64_t n_chunks = (n_kt + CHUNK_TILES - 1) / CHUNK_TILES;
-    const int forced_cbw = tune.midm_cbw == 2 || tune.midm_cbw == 4 || tune.midm_cbw == 8 ? tune.midm_cbw : 0;
-    Plan p;
-    // Deep K (14 chunks and more) and room for partial results: about 64 workgroups across the columns,
-    // each as wide as that allows (every workgroup reads all M rows of its K range of the activations:
-    // fewer, wider workgroups move less through L2), times enough K ranges for one workgroup per CU.
-    // Measured at M = 64: 28672 x 8192 34 us against 57 us unsplit, 14336 x 4096 17 against 22 us; at
-    // 8 chunks and fewer the partial results and the second launch cost more than they save.
-    int64_t s = 1;
-    p.cbw = forced_cbw;
-    if (tune.splitk != 1 && cap >= 2 && (tune.splitk > 1 || n_chunks >= 14)) {
-        if (!p.cbw) p.cbw = n_cb >= 8 * 64 ? 8 : n_cb >= 4 * 64 ? 4 : 2;
-        const int64_t wgs = (n_cb + p.cbw - 1) / p.cbw * bands;
-        s = tune.splitk > 1 ? tune.splitk : (256 + wgs / 2) / wgs;
-        if (tune.splitk == 0) s = min(s, n_chunks / 3);
-        s = min(min(s, n_chunks), min((int64_t)16, cap));
-    }
-    if (s < 2) {
-        // K in one piece: as many column blocks per workgroup as still leave about one workgroup per CU
-        s = 1;
-        p.cbw = forced_cbw ? forced_cbw : n_cb >= 8 * 224 ? 8 : n_cb >= 4 * 224 ? 4 : 2;
-    }
-    p.splits = (int)s;
-    return p;
-}
-
 template <int G, int RT>
 static int launch_rt(const A8Args& a, hipStream_t stream)
 {
     const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
-    const Plan p = plan(a.M, a.N, a.n_cb, a.n_kt, cap, a.tune);
+    const MidmPlan p = midm_plan(a.M, a.n_cb, a.n_kt, cap, a.tune);
     if (p.cbw == 8) return launch_t<G, RT, 4>(a, p.splits, stream);
     if (p.cbw == 4) return launch_t<G, RT, 2>(a, p.splits, stream);
     return launch_t<G, RT, 1>(a, p.splits, stream);
@@ -356,7 +355,7 @@ bool a8_midm_supports(const A8Args& a) { return a.M >= 1 && a.M <= 4 * midm::ROW
 
 size_t a8_midm_splitk_bytes(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, const w2_tuning_t& tune)
 {
-    const int s = midm::plan(M, N, n_cb, n_kt, 16, tune).splits;
+    const int s = midm_plan(M, n_cb, n_kt, 16, tune).splits;
     return s < 2 ? 0 : (size_t)s * M * N * sizeof(float);
 }
 

@@ -77,7 +77,7 @@ struct A16Args {
     int64_t n_cb, n_kt;
     int G;
     int fold;       // build the weights as sw*q (scale folded in): no zero-point term, no dequant step
-    float* part = nullptr;      // split-K workspace, as in A8Args (scale-folded tiled kernel only)
+    float* part = nullptr;      // split-K workspace, as in A8Args (scale-folded tiled kernel and mid-M kernel)
     size_t part_bytes = 0;
     Epilogue epi;
     w2_tuning_t tune = {};
@@ -98,7 +98,11 @@ int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t
 // Bytes of workspace with which the tiled kernels would split K for this problem (0: they would not).
 size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune);
 size_t a8_midm_splitk_bytes(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, const w2_tuning_t& tune);
+// The mid-M kernels' launch shape (both activation types): column blocks per workgroup and K ranges.
+struct MidmPlan { int cbw, splits; };
+MidmPlan midm_plan(int64_t M, int64_t n_cb, int64_t n_kt, int64_t cap, const w2_tuning_t& tune);
 size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune);
+size_t a16_midm_splitk_bytes(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, const w2_tuning_t& tune);
 // Y[m][n] = bf16(sum_s part[s][m][n]), a fixed order of summation
 int launch_splitk_reduce(const float* part, int splits, int64_t M, int64_t N, uint16_t* Y, int64_t ldy,
                          const Epilogue& epi, hipStream_t stream);

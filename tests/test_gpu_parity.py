@@ -455,6 +455,10 @@ def test_midm_split_k(w2, M, K, N, G, cbw, splitk):
     Yo, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
     mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
     check_y(bf16_bits(Y), Yo, y64, mag, f"a8 mid-M split-K {splitk} cbw={cbw} M={M} K={K} N={N} G={G}")
+    Xb = synth.f32_to_bf16_bits(X)
+    Y16 = w2.matmul_a16(packed, K, N, G, dev(Xb).view(torch.bfloat16), variant=w2.VARIANT_MIDM, workspace=ws, tune=tune)
+    Yo, y64, mag = oracle.matmul_a16(codes, scales, G, 0, Xb)
+    check_y(bf16_bits(Y16), Yo, y64, mag, f"a16 mid-M split-K {splitk} cbw={cbw} M={M} K={K} N={N} G={G}")
     if splitk >= 2:
         # a workspace too small for two parts: no split, the unsplit kernel's bits
         small = torch.empty(M * N * 4, dtype=torch.uint8, device="cuda")
