@@ -155,6 +155,7 @@ static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
     else if (!one_of(t->small_cbw, 1, 2, 4, 8, 16)) bad = "small_cbw";
     else if (t->small_kc < 0 || t->small_kc % TILE_K) bad = "small_kc";
     else if (!one_of(t->gemv_window, 2, 4, 8)) bad = "gemv_window";
+    else if (!in(t->gemv_max_m, 1, 16)) bad = "gemv_max_m";
     else if (!one_of(t->midm_cbw, 2, 4, 8)) bad = "midm_cbw";
     else if (!one_of(t->tiled_bm, 64, 128)) bad = "tiled_bm";
     else if (!one_of(t->tiled_bn, 128, 256)) bad = "tiled_bn";
@@ -255,6 +256,7 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     a.part_bytes = workspace ? workspace_bytes : 0;
     a.epi = epi;
     a.tune = tn;
+    int fallback = W2_VARIANT_SMALLM;                        // where the decode kernel cannot hold the rows
     if (variant == W2_VARIANT_AUTO) {
         // measured: the MFMA form is at least as fast as dot4 from M = 1 on; the mid-M kernel (one
         // fma per accumulator in the dequant, rolling weight window; its time hardly grows with M)
@@ -273,19 +275,34 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         // 16384: 31 against 43 us on 17408 x 5120 at M = 128)
         const int midm_max = tn.midm_max_m ? tn.midm_max_m
                            : a.n_cb <= 512 ? (a.part_bytes && a.n_kt > 64 ? 64 : 128) : a.n_cb >= 2048 ? 48 : 64;
-        variant = M <= dot4_max && a8_dot4_supports(a)                       ? W2_VARIANT_DOT4
-                : a8_gemv_supports(M)                                        ? W2_VARIANT_GEMV
-                : M >= midm_min && M <= midm_max && a8_midm_supports(a)     ? W2_VARIANT_MIDM
-                : a8_smallm_supports(a)                                      ? W2_VARIANT_SMALLM
-                                                                             : W2_VARIANT_TILED;
+        fallback = M >= midm_min && M <= midm_max && a8_midm_supports(a) ? W2_VARIANT_MIDM
+                 : a8_smallm_supports(a)                                   ? W2_VARIANT_SMALLM
+                                                                           : W2_VARIANT_TILED;
+        // The decode kernel keeps whole rows in local memory and reads the weights once, like the mid-M
+        // kernel, without that kernel's barrier pair per 1024 k: measured faster up to 8 rows wherever the
+        // rows fit (4096 x 28672 at M = 8: 7.4 against 10.1 us; 8192 x 8192: 5.9 against 7.8), up to 12 rows
+        // while two workgroups share a CU (rows of at most 64 KiB) or the projection is narrow (8192 x 8192:
+        // 6.5 against 8.5 us; 8192 x 57344 loses: 33 against 28), and up to 16 on the narrowest ones
+        // (4096 x 4096: 4.1 against 5.4 us; wider ones lose there: 4096 x 28672 11.6 against 10.3).
+        const int64_t row_bytes = M * (K + 32);
+        const int gemv_max = tn.gemv_max_m                               ? tn.gemv_max_m
+                           : M <= 8                                      ? 8
+                           : M <= 12 && (row_bytes <= 64 * 1024 || a.n_cb <= 512) ? 12
+                           : a.n_cb <= 256 && row_bytes <= 68 * 1024     ? 16
+                                                                         : 8;
+        variant = M <= dot4_max && a8_dot4_supports(a)     ? W2_VARIANT_DOT4
+                : M <= gemv_max && a8_gemv_supports(M)     ? W2_VARIANT_GEMV
+                                                           : fallback;
     }
     hipStream_t s = (hipStream_t)stream;
     switch (variant) {
     case W2_VARIANT_GEMV: {
-        if (!a8_gemv_supports(M)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: GEMV needs M <= 4", fn);
+        if (!a8_gemv_supports(M)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: GEMV needs M <= 16", fn);
         rc = launch_a8_gemv(a, xq, 0, K, s);
-        // rows too long for one workgroup's local memory: the small-M kernel stages them in chunks
+        // rows too long for one workgroup's local memory: the kernels that stage them in chunks
         if (rc != W2_ERR_UNSUPPORTED_SHAPE || tn.variant == W2_VARIANT_GEMV) return rc;
+        if (fallback == W2_VARIANT_MIDM) return launch_a8_midm(a, s);
+        if (fallback == W2_VARIANT_TILED) return launch_a8_tiled(a, s);
         return launch_a8_smallm(a, s);
     }
     case W2_VARIANT_DOT4:

@@ -46,8 +46,12 @@ namespace w2 {
 
 namespace gemv {
 
-constexpr int HDR = 512;          // LDS: abs-max partials [16 waves][4 rows] fp32, then padding
-constexpr int XSLOTS = 8;         // most 16-byte pieces of the activation rows a thread holds in registers
+constexpr int HDR = 512;          // LDS: abs-max partials [16 waves][4 rows] fp32, the rows' scales, padding
+constexpr int SX_SLOT = 64;       // ... the scales' first float
+// most 16-byte pieces of the activation rows a thread holds in registers: 8 for up to four rows (workgroups of
+// up to 16 waves, 128 registers a lane), 32 for the wide form (up to 8 waves, 256 registers)
+constexpr int xslots(int RL) { return RL > 4 ? 32 : 8; }
+constexpr int max_waves(int RL) { return RL > 4 ? 8 : 16; }
 
 struct Args {
     const uint32_t* codes;
@@ -103,11 +107,17 @@ __device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, ui
     return lo | hi;
 }
 
+// RL: rows staged (M <= RL).  Up to four rows sit in accumulator rows 0..3, which the lanes of the first
+// quarter of a wave hold (one, two or four values each); the wide form (RL = 8 or 16, int8 rows only) uses
+// every accumulator row: lane (q, l) holds rows 4q..4q+3 of column l.
 // NP: 16-byte pieces per row and thread (a launch-time choice: the row's pieces / the workgroup's threads, rounded up)
 template <int G, int RL, int XT, int W, int NP, bool DBG>
-__global__ void __launch_bounds__(1024)
+__global__ void __launch_bounds__(64 * max_waves(RL))
 a8_gemv_kernel(Args a)
 {
+    constexpr bool WIDE = RL > 4;
+    constexpr int RA = WIDE ? 4 : RL;                        // accumulator rows a lane folds into y
+    static_assert(!WIDE || XT == 0, "the wide form takes int8 rows");
     extern __shared__ __align__(16) int8_t smem[];
     constexpr int GPT = TILE_K / G;
     const int tid = threadIdx.x;
@@ -131,24 +141,33 @@ a8_gemv_kernel(Args a)
     // ---- 1. the activation rows: unconditional vector loads, issued before the weight loads
     constexpr int ES = XT == 1 ? 4 : XT == 2 ? 2 : 1;        // bytes per source element
     constexpr int PR = NP;                                   // register slots per row
-    static_assert(NP * RL <= XSLOTS, "too many register slots");
+    static_assert(NP * RL <= xslots(RL), "too many register slots");
     const int ppr = a.K * ES / 16;                           // 16-byte pieces per row
     uint4 pc[RL][PR];
 #pragma unroll
     for (int r = 0; r < RL; ++r) {
         const int rr = r < a.M ? r : a.M - 1;
         const __amdgpu_buffer_rsrc_t xr =
-            make_rsrc(reinterpret_cast<const char*>(a.X) + (int64_t)rr * a.ldx * ES, (uint32_t)a.K * ES);
+            make_rsrc(reinterpret_cast<const char*>(a.X) + (int64_t)rr * a.ldx * ES, r < a.M ? (uint32_t)a.K * ES : 0u);   // rows past M: nothing to fetch
 #pragma unroll
         for (int j = 0; j < PR; ++j) {                       // pieces past the end of the row: out of range, zeros
             const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(xr, (tid + j * threads) * 16, 0, 0);
             pc[r][j] = make_uint4(t[0], t[1], t[2], t[3]);
         }
     }
-    float sxv[RL];
-    if constexpr (XT == 0) {
+
+    // The rows' scales for the epilogue.  One or two rows: in registers (scalar loads).  More: the scale of
+    // row `tid`, parked in LDS below; unconditional like every load here (past M it is out of range).
+    constexpr bool SX_IN_REGS = RL <= 2;
+    float sxv[SX_IN_REGS ? RL : 1] = {};
+    float sx_mine = 0.f;
+    if constexpr (XT == 0 && !DBG) {
+        if constexpr (SX_IN_REGS) {
 #pragma unroll
-        for (int r = 0; r < RL; ++r) sxv[r] = DBG ? 0.f : a.sx[r < a.M ? r : a.M - 1];
+            for (int r = 0; r < RL; ++r) sxv[r] = a.sx[r < a.M ? r : a.M - 1];
+        } else {
+            sx_mine = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(a.sx, (uint32_t)a.M * 4u), tid * 4, 0, 0));
+        }
     }
 
     // ---- 2. the first W tiles of the weight stream
@@ -184,6 +203,8 @@ a8_gemv_kernel(Args a)
                 const int i = tid + j * threads;
                 if (i < ppr && r < a.M) *reinterpret_cast<uint4*>(xs + r * row_stride + i * 16) = pc[r][j];
             }
+        // (here, not at the load: a store right behind it would hold up the weight loads)
+        if (!DBG && !SX_IN_REGS && tid < a.M) s_red[SX_SLOT + tid] = sx_mine;
     } else {
         float amax[RL];
 #pragma unroll
@@ -216,11 +237,11 @@ a8_gemv_kernel(Args a)
         for (int r = 0; r < RL; ++r) {
             float m = 0.f;
             for (int w = 0; w < n_waves; ++w) m = fmaxf(m, s_red[w * 4 + r]);
-            inv[r] = 0.f; sxv[r] = 0.f;
-            if (m > 0.f) {
-                inv[r] = __fdiv_rn(127.0f, m);
-                sxv[r] = __fdiv_rn(m, 127.0f);
-            }
+            inv[r] = m > 0.f ? __fdiv_rn(127.0f, m) : 0.f;
+            // the row's scale, for the epilogue (LDS: another slot of the header than the partial maxima being read)
+            const float sxr = m > 0.f ? __fdiv_rn(m, 127.0f) : 0.f;
+            if constexpr (SX_IN_REGS) sxv[r] = sxr;
+            else if (tid == 0) s_red[SX_SLOT + r] = sxr;
         }
 #pragma unroll
         for (int r = 0; r < RL; ++r)
@@ -254,9 +275,9 @@ a8_gemv_kernel(Args a)
     W2_GEMV_MARK(2);
 
     // ---- 4. the stream: up-convert and compute
-    float y[RL];
+    float y[RA];
 #pragma unroll
-    for (int r = 0; r < RL; ++r) y[r] = 0.f;
+    for (int r = 0; r < RA; ++r) y[r] = 0.f;
     // Two accumulators alternate between groups; a finished group is dequantised after the next
     // group's first matrix instruction has been issued, so its int -> float conversion does not wait
     // for the matrix pipe.
@@ -265,11 +286,12 @@ a8_gemv_kernel(Args a)
     int pend_g = -1;                                         // its index (debug export)
     auto dequant = [&](int b) {
 #pragma unroll
-        for (int r = 0; r < RL; ++r) {
+        for (int r = 0; r < RA; ++r) {
             if constexpr (DBG) {
                 const int64_t n = (int64_t)cb * TILE_N + l16;
-                if (pend_g >= 0 && q == 0 && cb_ok && n < a.N && r < a.M)
-                    a.acc_out[((int64_t)r * (a.K / G) + pend_g) * a.N + n] = acc[b][r] >> 6;
+                const int row = WIDE ? 4 * q + r : r;
+                if (pend_g >= 0 && (WIDE || q == 0) && cb_ok && n < a.N && row < a.M)
+                    a.acc_out[((int64_t)row * (a.K / G) + pend_g) * a.N + n] = acc[b][r] >> 6;
             }
             y[r] = fmaf(pend_sw, (float)acc[b][r], y[r]);
         }
@@ -338,47 +360,97 @@ a8_gemv_kernel(Args a)
 
     // ---- 5. reduce the k-ranges through LDS (fixed order), dequantise, store
     float* red = reinterpret_cast<float*>(smem + a.red_off);   // [waves][RL][16]; its own region: no barrier before the writes
-    if (q == 0) {
+    if (WIDE ? 4 * q < RL : q == 0) {
 #pragma unroll
-        for (int r = 0; r < RL; ++r) red[(wave * RL + r) * 16 + l16] = y[r];
+        for (int r = 0; r < RA; ++r) red[(wave * RL + (WIDE ? 4 * q : 0) + r) * 16 + l16] = y[r];
     }
     __syncthreads();
     W2_GEMV_MARK(5);
     const bool gated = a.epi.act == ACT_SILU_MUL;
     const int outs = gated ? (a.cbw >> 1) * 16 : a.cbw * 16;
-    if (tid < outs) {
-        const int nl = tid & 15, ci = tid >> 4;
-        auto z = [&](int c, int r) {                         // finished fp32 result of column block c, row r
+    if constexpr (SX_IN_REGS) {
+        // one or two rows: a thread per output column, the rows in turn
+        if (tid < outs) {
+            const int nl = tid & 15, ci = tid >> 4;
+            const int kstride = (RL * 16) << a.cbw_shift;    // floats between two k-ranges' partial sums
+            auto z = [&](int c, int r) {                     // finished fp32 result of column block c, row r
+                const float* p0 = red + (c * RL + r) * 16 + nl;
+                float s = 0.f;
+                for (int k0 = 0; k0 < a.ks; k0 += 4) {       // four reads in flight, added in order
+                    float part[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) part[j] = p0[min(k0 + j, a.ks - 1) * kstride];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) s = k0 + j < a.ks ? s + part[j] : s;
+                }
+                return s * (sxv[r] * 0.015625f);
+            };
+            if (!gated) {
+                const int64_t nn = ((int64_t)blockIdx.x * a.cbw + ci) * TILE_N + nl;
+                if (nn < a.N) {
+                    const float bias = a.epi.bias ? bf16_to_f32(a.epi.bias[nn]) : 0.f;
+#pragma unroll
+                    for (int r = 0; r < RL; ++r) {
+                        if (r < a.M) {
+                            float v = z(ci, r) + bias;
+                            if (a.epi.act == ACT_SILU) v = silu_f32(v);
+                            a.Y[(int64_t)r * a.ldy + nn] = f32_to_bf16_rne(v);
+                        }
+                    }
+                }
+            } else {
+                const int64_t first_cb = (int64_t)blockIdx.x * a.cbw;       // even
+                const int64_t ng = (first_cb + 2 * ci) * TILE_N + nl, nu = ng + TILE_N;
+                if (nu < a.N) {                              // N % 32 == 0: both or neither
+                    const float bg = a.epi.bias ? bf16_to_f32(a.epi.bias[ng]) : 0.f;
+                    const float bu = a.epi.bias ? bf16_to_f32(a.epi.bias[nu]) : 0.f;
+#pragma unroll
+                    for (int r = 0; r < RL; ++r) {
+                        if (r < a.M) {
+                            const float g = z(2 * ci, r) + bg, u = z(2 * ci + 1, r) + bu;
+                            a.Y[(int64_t)r * a.ldy + ((first_cb >> 1) + ci) * TILE_N + nl] = f32_to_bf16_rne(silu_f32(g) * u);
+                        }
+                    }
+                }
+            }
+        }
+        W2_GEMV_MARK(6);
+        return;
+    }
+    // one output per thread and step: column `item % outs` (a power of two), row `item / outs`; the k-ranges'
+    // partial sums are fetched four at a time, then added in a fixed order
+    const int outs_shift = a.cbw_shift + (gated ? 3 : 4);
+    const int kstride = (RL * 16) << a.cbw_shift;            // floats between two k-ranges' partial sums
+    for (int item = tid; item < (a.M << outs_shift); item += threads) {
+        const int r = item >> outs_shift, col = item & (outs - 1);
+        const int nl = col & 15, ci = col >> 4;
+        const float sxr = s_red[SX_SLOT + r] * 0.015625f;
+        auto z = [&](int c) {                                // finished fp32 result of column block c, row r
+            const float* p0 = red + (c * RL + r) * 16 + nl;
             float s = 0.f;
-            for (int k = 0; k < a.ks; ++k) s += red[(((k << a.cbw_shift) + c) * RL + r) * 16 + nl];
-            return s * (sxv[r] * 0.015625f);
+            for (int k0 = 0; k0 < a.ks; k0 += 4) {           // four reads in flight, added in order
+                float part[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) part[j] = p0[min(k0 + j, a.ks - 1) * kstride];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) s = k0 + j < a.ks ? s + part[j] : s;
+            }
+            return s * sxr;
         };
         if (!gated) {
             const int64_t nn = ((int64_t)blockIdx.x * a.cbw + ci) * TILE_N + nl;
             if (nn < a.N) {
-                const float bias = a.epi.bias ? bf16_to_f32(a.epi.bias[nn]) : 0.f;
-#pragma unroll
-                for (int r = 0; r < RL; ++r) {
-                    if (r < a.M) {
-                        float v = z(ci, r) + bias;
-                        if (a.epi.act == ACT_SILU) v = silu_f32(v);
-                        a.Y[(int64_t)r * a.ldy + nn] = f32_to_bf16_rne(v);
-                    }
-                }
+                float v = z(ci) + (a.epi.bias ? bf16_to_f32(a.epi.bias[nn]) : 0.f);
+                if (a.epi.act == ACT_SILU) v = silu_f32(v);
+                a.Y[(int64_t)r * a.ldy + nn] = f32_to_bf16_rne(v);
             }
         } else {
             const int64_t first_cb = (int64_t)blockIdx.x * a.cbw;           // even
             const int64_t ng = (first_cb + 2 * ci) * TILE_N + nl, nu = ng + TILE_N;
             if (nu < a.N) {                                  // N % 32 == 0: both or neither
-                const float bg = a.epi.bias ? bf16_to_f32(a.epi.bias[ng]) : 0.f;
-                const float bu = a.epi.bias ? bf16_to_f32(a.epi.bias[nu]) : 0.f;
-#pragma unroll
-                for (int r = 0; r < RL; ++r) {
-                    if (r < a.M) {
-                        const float g = z(2 * ci, r) + bg, u = z(2 * ci + 1, r) + bu;
-                        a.Y[(int64_t)r * a.ldy + ((first_cb >> 1) + ci) * TILE_N + nl] = f32_to_bf16_rne(silu_f32(g) * u);
-                    }
-                }
+                const float g = z(2 * ci) + (a.epi.bias ? bf16_to_f32(a.epi.bias[ng]) : 0.f);
+                const float u = z(2 * ci + 1) + (a.epi.bias ? bf16_to_f32(a.epi.bias[nu]) : 0.f);
+                a.Y[(int64_t)r * a.ldy + ((first_cb >> 1) + ci) * TILE_N + nl] = f32_to_bf16_rne(silu_f32(g) * u);
             }
         }
     }
@@ -392,10 +464,13 @@ a8_gemv_kernel(Args a)
 //     (runs of seven); more waves than that only add per-wave fixed work, fewer leave the memory system short
 //     of requests;
 //   - eight waves per workgroup (sixteen when ks = 16, or when the rows need the threads);
-//   - window 2 for runs of up to four tiles, 4 above (8 was never better: the stream is the bound, not depth).
+//   - window 2 for runs of up to four tiles.  Longer runs: 4 in grids of more than 768 workgroups (8192 x
+//     57344 gains 10 %) and of up to 256 (14336 x 4096: 5 %), 2 between (5120 x 34816 loses 11 to 15 % to the
+//     deeper window, 4096 x 28672 3 % with int8 rows and gains 1 % with rows quantised in the kernel: more
+//     bytes in flight than about 10 MB over the chip does not pay); 8 was never better.
 struct Cfg { int cbw, ks, window; };
 
-static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_cbw, int min_threads)
+static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_cbw, int min_threads, int max_w, int xt)
 {
     Cfg c;
     if (tune.small_waves || tune.small_cbw) {                // forced shape (tests, sweeps)
@@ -408,25 +483,27 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
         c.ks = waves / c.cbw;
     } else {
         int ks = 1;
-        while (ks < 16 && n_cb * ks < 2048 && n_kt / (ks * 2) >= 1) ks <<= 1;
-        while (ks < 16 && (n_kt + ks - 1) / ks > MAX_RUN) ks <<= 1;
+        while (ks < max_w && n_cb * ks < 2048 && n_kt / (ks * 2) >= 1) ks <<= 1;
+        while (ks < max_w && (n_kt + ks - 1) / ks > MAX_RUN) ks <<= 1;
         c.ks = ks;
         c.cbw = ks >= 8 ? 1 : 8 / ks;                        // eight waves; sixteen when ks = 16
     }
     if (even_cbw && (c.cbw & 1)) c.cbw = 2;                  // the gated epilogue pairs adjacent column blocks
-    while (c.cbw * c.ks > 16) {                              // at most 16 waves
+    while (c.cbw * c.ks > max_w) {                           // at most 16 waves (8 in the wide form)
         if (c.ks > 1) c.ks >>= 1; else c.cbw >>= 1;
     }
-    while (c.cbw * c.ks * 64 < min_threads && c.cbw * c.ks < 16) c.cbw <<= 1;   // the rows need the threads
+    while (c.cbw * c.ks * 64 < min_threads && c.cbw * c.ks < max_w) c.cbw <<= 1;   // the rows need the threads
     if (c.ks > n_kt) {
         c.ks = 1;
         while (c.ks * 2 <= n_kt) c.ks <<= 1;
     }
     // a run is at most MAX_RUN tiles: split K further (fewer column blocks per workgroup, then more waves)
     while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw > 1 && !(even_cbw && c.cbw == 2)) { c.cbw >>= 1; c.ks <<= 1; }
-    while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw * c.ks < 16) c.ks <<= 1;
+    while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw * c.ks < max_w) c.ks <<= 1;
     const int64_t run = (n_kt + c.ks - 1) / c.ks;
-    c.window = tune.gemv_window ? tune.gemv_window : run > 4 ? 4 : 2;
+    const int64_t wgs = (n_cb + c.cbw - 1) / c.cbw;
+    (void)xt;
+    c.window = tune.gemv_window ? tune.gemv_window : run > 4 && (wgs > 768 || wgs <= 256) ? 4 : 2;
     return c;
 }
 
@@ -447,7 +524,7 @@ static int launch_w(const Args& a, const Cfg& c, size_t lds, hipStream_t stream)
 template <int G, int RL, int XT, bool DBG>
 static int launch_np(const Args& a, const Cfg& c, size_t lds, int np, hipStream_t stream)
 {
-    constexpr int MAXNP = XSLOTS / RL;
+    constexpr int MAXNP = xslots(RL) / RL;
     if (np <= 1) return launch_w<G, RL, XT, 1, DBG>(a, c, lds, stream);
     if constexpr (MAXNP >= 2) { if (np <= 2) return launch_w<G, RL, XT, 2, DBG>(a, c, lds, stream); }
     if constexpr (MAXNP >= 4) { if (np <= 4) return launch_w<G, RL, XT, 4, DBG>(a, c, lds, stream); }
@@ -456,7 +533,8 @@ static int launch_np(const Args& a, const Cfg& c, size_t lds, int np, hipStream_
 
 }  // namespace gemv
 
-bool a8_gemv_supports(int64_t M) { return M >= 1 && M <= 4; }
+// int8 rows: up to 16 (the wide form from five rows on); rows quantised in the kernel: up to four
+bool a8_gemv_supports(int64_t M) { return M >= 1 && M <= 16; }
 
 // xt: 0 = int8 rows (X = xq, sx given), 1 = fp32 rows, 2 = bf16 rows.  Returns W2_ERR_UNSUPPORTED_SHAPE
 // (with a message, nothing launched) when the rows do not fit a workgroup.
@@ -464,22 +542,31 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
 {
     using namespace gemv;
     const int64_t M = a8.M, K = a8.K;
-    if (!a8_gemv_supports(M)) {
-        set_error("w2_matmul_a8[gemv]: M must be 1..4");
+    if (!a8_gemv_supports(M) || (xt != 0 && M > 4)) {
+        set_error("w2_matmul_a8[gemv]: M must be 1..16 (1..4 for rows quantised in the kernel)");
         return W2_ERR_UNSUPPORTED_SHAPE;
     }
-    const int rl = M <= 1 ? 1 : M <= 2 ? 2 : 4;
+    const int rl = M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : M <= 8 ? 8 : 16;
+    const int max_w = rl > 4 ? 8 : 16;                       // max_waves(rl)
     const int es = xt == 1 ? 4 : xt == 2 ? 2 : 1;
     const int64_t ppr = K * es / 16;                         // 16-byte pieces per row
-    const int pr = XSLOTS / rl;                              // register slots per row and thread
+    const int pr = (rl > 4 ? 32 : 8) / rl;                   // register slots per row and thread: xslots(rl) / rl
     const int min_threads = (int)((ppr + pr - 1) / pr);
-    const size_t xs_bytes = ((size_t)rl * (K + XS_PAD) + 15) & ~(size_t)15;
-    if (min_threads > 1024 || HDR + xs_bytes + 16 * 4 * 16 * sizeof(float) + 16 * MAX_RUN * 128 > 150 * 1024) {
-        set_error("w2_matmul_a8[gemv]: M*K too large for one workgroup (use w2_quantize_rows + w2_matmul_a8)");
+    const size_t xs_bytes = ((size_t)(M < rl ? M : rl) * (K + XS_PAD) + 15) & ~(size_t)15;
+    const char* too_large = "w2_matmul_a8[gemv]: M*K too large for one workgroup (use w2_quantize_rows + w2_matmul_a8)";
+    if (min_threads > 64 * max_w || xs_bytes > 160 * 1024) {
+        set_error(too_large);
         return W2_ERR_UNSUPPORTED_SHAPE;
     }
-    const Cfg c = pick(a8.tune, a8.n_cb, a8.n_kt, a8.epi.act == ACT_SILU_MUL, min_threads);
+    const Cfg c = pick(a8.tune, a8.n_cb, a8.n_kt, a8.epi.act == ACT_SILU_MUL, min_threads, max_w, xt);
     const int waves = c.cbw * c.ks;
+    // local memory: header, rows, reduction scratch, the waves' scale slices; a CU has 160 KiB
+    const size_t lds_need = HDR + xs_bytes + (size_t)waves * rl * 16 * sizeof(float) +
+                            (size_t)waves * MAX_RUN * (TILE_N * (TILE_K / a8.G) * 2);
+    if (lds_need > 160 * 1024) {
+        set_error(too_large);
+        return W2_ERR_UNSUPPORTED_SHAPE;
+    }
     if (waves * 64 < min_threads) {
         set_error("w2_matmul_a8[gemv]: the forced workgroup shape cannot hold the activation rows");
         return W2_ERR_UNSUPPORTED_SHAPE;
@@ -499,7 +586,7 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
     a.red_off = (int)(HDR + xs_bytes);
     a.sc_off = a.red_off + waves * rl * 16 * (int)sizeof(float);
     a.epi = a8.epi;
-    const size_t lds = a.sc_off + (size_t)waves * MAX_RUN * (TILE_N * (TILE_K / a8.G) * 2);
+    const size_t lds = lds_need;
     const bool dbg = a8.acc_out != nullptr;
     const int np = (int)((ppr + waves * 64 - 1) / (waves * 64));       // pieces per row and thread (<= XSLOTS / rl: checked above)
 #define W2_GEMV(GG, RLL)                                                                               \
@@ -509,14 +596,24 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
         if (xt == 1) return launch_np<GG, RLL, 1, false>(a, c, lds, np, stream);                       \
         return launch_np<GG, RLL, 2, false>(a, c, lds, np, stream);                                    \
     } while (0)
+#define W2_GEMV_WIDE(GG, RLL)                                                                          \
+    do {                                                                                               \
+        if (dbg) return launch_np<GG, RLL, 0, true>(a, c, lds, np, stream);                            \
+        return launch_np<GG, RLL, 0, false>(a, c, lds, np, stream);                                    \
+    } while (0)
     if (a8.G == 128) {
         if (rl == 1) W2_GEMV(128, 1);
         if (rl == 2) W2_GEMV(128, 2);
-        W2_GEMV(128, 4);
+        if (rl == 4) W2_GEMV(128, 4);
+        if (rl == 8) W2_GEMV_WIDE(128, 8);
+        W2_GEMV_WIDE(128, 16);
     }
     if (rl == 1) W2_GEMV(64, 1);
     if (rl == 2) W2_GEMV(64, 2);
-    W2_GEMV(64, 4);
+    if (rl == 4) W2_GEMV(64, 4);
+    if (rl == 8) W2_GEMV_WIDE(64, 8);
+    W2_GEMV_WIDE(64, 16);
+#undef W2_GEMV_WIDE
 #undef W2_GEMV
 }
 
