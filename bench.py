@@ -63,10 +63,12 @@ def pmc_mode(torch, w2, lib, vp, pool, shapes, Xd, Yd, dev):
         dst.copy_(src)                                   # calibration: reads 256 MiB, writes 256 MiB
     for l in pool:
         lib.w2_debug_stream_read(vp(l["gate_up"]), l["gate_up"].numel(), vp(sink), None, s)
-    for l in pool:
-        rc = lib.w2_matmul_a8_fused(vp(l["gate_up"]), Kd, Nd, G, vp(Xd["gate_up"]), w2.DT_F32, Kd, M,
-                                    vp(Yd["gate_up"]), Nd, None, 0, s)
-        assert rc == 0, lib.w2_last_error()
+    for name in ("gate_up", "down", "qkv", "o"):             # the step's four fused launches, one projection at a time
+        Kq, Nq = shapes[name]
+        for l in pool:
+            rc = lib.w2_matmul_a8_fused(vp(l[name]), Kq, Nq, G, vp(Xd[name]), w2.DT_F32, Kq, M,
+                                        vp(Yd[name]), Nq, None, 0, s)
+            assert rc == 0, lib.w2_last_error()
     Kp, Np, Mp = 8192, 57344, 2048
     pk = torch.randint(0, 255, (w2.packed_size(Kp, Np, G),), dtype=torch.uint8, device=dev)
     pk[Kp * Np // 4:].view(torch.int16)[:] = 0x3C00
@@ -79,8 +81,8 @@ def pmc_mode(torch, w2, lib, vp, pool, shapes, Xd, Yd, dev):
     for _ in range(3):
         w2.matmul_a16(pk, Kp, Np, G, xbp, out=Yp)
     torch.cuda.synchronize()
-    print("bench.py --pmc: launched copy x3 (256 MiB), stream read and fused GEMV x%d, prefill x3 (w2a8), "
-          "x3 (w2a16)" % len(pool))
+    print("bench.py --pmc: launched copy x3 (256 MiB), stream read x%d, fused GEMV x%d on gate+up, down, QKV, O, "
+          "prefill x3 (w2a8), x3 (w2a16)" % (len(pool), len(pool)))
 
 
 def probe_sweep_mode(torch, w2, synth, dev):
@@ -119,7 +121,7 @@ def gamma_mode(torch, w2, synth, dev, timing):
     per case); without it each case is launched eagerly three times, in the same order, for `rocprofv3 --pmc`
     to count its instructions (the line then carries the case's position in the dispatch order)."""
     K, N = synth.SHAPES_8B["gate_up"]
-    fam = [("gemv", w2.VARIANT_GEMV, 4), ("dot4", w2.VARIANT_DOT4, 4), ("smallm", w2.VARIANT_SMALLM, 16),
+    fam = [("gemv", w2.VARIANT_GEMV, 16), ("dot4", w2.VARIANT_DOT4, 4), ("smallm", w2.VARIANT_SMALLM, 16),
            ("midm", w2.VARIANT_MIDM, 64)]
     pos = 0
     for g in (128, 64):

@@ -348,21 +348,29 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m, int spli
         const int64_t n = n0 + wn * WN + j * 16 + l16;
         bias[j] = (a.epi.bias && n < a.N) ? bf16_to_f32(a.epi.bias[n]) : 0.f;
     }
+    // (one copy of the loop per epilogue, picked here: a choice per element would have the compiler
+    // evaluate the SiLU for every output and select afterwards)
+    auto emit = [&](auto mode_c) {
+        constexpr int MODE = decltype(mode_c)::value;        // ACT_NONE, ACT_SILU, ACT_SILU_MUL
+        static_assert(CJ == 2, "the epilogue pairs the wave's two column blocks");
 #pragma unroll
-    for (int i = 0; i < RI; ++i)
+        for (int i = 0; i < RI; ++i)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = i * 16 + 4 * q + r;
-            const float z0 = acc[i][0][r] + bias[0], z1 = acc[i][1][r] + bias[1];
-            static_assert(CJ == 2, "the epilogue pairs the wave's two column blocks");
-            if (gated) {
-                eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(silu_f32(z0) * z1);
-            } else {
-                const bool act = a.epi.act == ACT_SILU;
-                eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(act ? silu_f32(z0) : z0);
-                eb[row * (E_STRIDE / 2) + 16 + l16] = f32_to_bf16_rne(act ? silu_f32(z1) : z1);
+            for (int r = 0; r < 4; ++r) {
+                const int row = i * 16 + 4 * q + r;
+                const float z0 = acc[i][0][r] + bias[0], z1 = acc[i][1][r] + bias[1];
+                if constexpr (MODE == ACT_SILU_MUL) {
+                    eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(silu_f32(z0) * z1);
+                } else {
+                    const uint32_t pk = MODE == ACT_SILU ? pack_bf16x2(silu_f32(z0), silu_f32(z1)) : pack_bf16x2(z0, z1);
+                    eb[row * (E_STRIDE / 2) + l16] = (uint16_t)pk;
+                    eb[row * (E_STRIDE / 2) + 16 + l16] = (uint16_t)(pk >> 16);
+                }
             }
-        }
+    };
+    if (gated) emit(std::integral_constant<int, ACT_SILU_MUL>{});
+    else if (a.epi.act == ACT_SILU) emit(std::integral_constant<int, ACT_SILU>{});
+    else emit(std::integral_constant<int, ACT_NONE>{});
     // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
     const int wcols = gated ? WN / 2 : WN;                   // output columns of this wave
     const int lpr = wcols * 2 / 16;                          // lanes per row piece (16 bytes each): 4 or 2

@@ -34,6 +34,8 @@
 //   - results leave through LDS as 16-byte stores.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "w2_internal.h"
 
 #if defined(__HIP_DEVICE_COMPILE__) && defined(__FAST_MATH__)
@@ -342,27 +344,35 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
         const int64_t n = n0 + wn * WN + j * 16 + l16;
         bias[j] = (a.epi.bias && n < a.N) ? __uint_as_float((uint32_t)a.epi.bias[n] << 16) : 0.f;
     }
+    // (one copy of the loop per epilogue, picked here: a choice per element would have the compiler
+    // evaluate the SiLU for every output and select afterwards)
+    auto emit = [&](auto mode_c) {
+        constexpr int MODE = decltype(mode_c)::value;        // ACT_NONE, ACT_SILU, ACT_SILU_MUL
 #pragma unroll
-    for (int i = 0; i < RI; ++i) {
+        for (int i = 0; i < RI; ++i) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = i * 16 + 4 * q + r;
-            const int64_t m = m0 + row;
-            const float s = a.sx[m < a.M ? m : a.M - 1];
-            float z[CJ];
+            for (int r = 0; r < 4; ++r) {
+                const int row = i * 16 + 4 * q + r;
+                const int64_t m = m0 + row;
+                const float s = a.sx[m < a.M ? m : a.M - 1];
+                float z[CJ];
 #pragma unroll
-            for (int j = 0; j < CJ; ++j) z[j] = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f * s + bias[j];
-            if (CJ == 2 && gated) {
-                eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(z[0] / (1.0f + __expf(-z[0])) * z[1]);
-            } else {
+                for (int j = 0; j < CJ; ++j) z[j] = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f * s + bias[j];
+                if constexpr (CJ == 2 && MODE == ACT_SILU_MUL) {
+                    eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(z[0] / (1.0f + __expf(-z[0])) * z[1]);
+                } else {
 #pragma unroll
-                for (int j = 0; j < CJ; ++j) {
-                    const float v = a.epi.act == ACT_SILU ? z[j] / (1.0f + __expf(-z[j])) : z[j];
-                    eb[row * (E_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(v);
+                    for (int j = 0; j < CJ; ++j) {
+                        const float v = MODE == ACT_SILU ? z[j] / (1.0f + __expf(-z[j])) : z[j];
+                        eb[row * (E_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(v);
+                    }
                 }
             }
         }
-    }
+    };
+    if (gated) emit(std::integral_constant<int, ACT_SILU_MUL>{});
+    else if (a.epi.act == ACT_SILU) emit(std::integral_constant<int, ACT_SILU>{});
+    else emit(std::integral_constant<int, ACT_NONE>{});
     // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
     const int wcols = gated ? WN / 2 : WN;                   // output columns of this wave
     const int lpr = wcols * 2 / 16;                          // lanes per row piece (16 bytes each): 4 or 2

@@ -62,6 +62,7 @@ constexpr int E_STRIDE = WN * 2 + 16;              // epilogue: bytes per LDS ro
 constexpr int BIAS = 1 << 21;                      // > 64 * 127 * 2 * 128 = 2 080 768
 constexpr float BIAS_F = 0x1p-128f;                // BIAS read as a float: 2^21 * 2^-149
 constexpr int waves_of(int bn) { return bn / WN; }
+constexpr int SX_BYTES = BM * 4;                   // the tile's activation scales, parked for the epilogue
 constexpr int lds_bytes(int bn)
 {
     return nbuf_of(bn) * A_BUF > waves_of(bn) * BM * E_STRIDE ? nbuf_of(bn) * A_BUF : waves_of(bn) * BM * E_STRIDE;
@@ -195,6 +196,11 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         }
     };
 
+    // the tile's activation scales, fetched now (unconditionally) and parked in LDS for the epilogue: loaded
+    // there they would cost every workgroup a memory round trip with nothing to hide it
+    float* sx_lds = reinterpret_cast<float*>(smem + lds_bytes(BN));
+    const float sx_mine = DBG ? 0.f : a.sx[min(m0 + (tid & (BM - 1)), a.M - 1)];
+
     // prologue: stages 0 and 1 go to LDS; the registers then hold stage 2 (and 3)
     WTile<G> w0, w1;
     load_w(0, w0);
@@ -203,6 +209,7 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         load_a(p, p00, p01, p02, p03);
         store_a(p, p00, p01, p02, p03);
     }
+    if (tid < BM) sx_lds[tid] = sx_mine;
     load_a(WR, p00, p01, p02, p03);
     if constexpr (TWO_SETS) load_a(WR + 1, p10, p11, p02, p03);
     __syncthreads();
@@ -361,25 +368,38 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         const int64_t n = n0 + wn * WN + j * 16 + l16;
         bias[j] = (a.epi.bias && n < a.N) ? bf16_to_f32(a.epi.bias[n]) : 0.f;
     }
+    // (one copy of the loop per epilogue, picked here: a choice per element would have the compiler
+    // evaluate the SiLU for every output and select afterwards)
+    float cj[CJ];
 #pragma unroll
-    for (int i = 0; i < RI; ++i) {
+    for (int j = 0; j < CJ; ++j) cj[j] = ssum[j] * BIAS_F;
+    auto emit = [&](auto mode_c) {
+        constexpr int MODE = decltype(mode_c)::value;        // ACT_NONE, ACT_SILU, ACT_SILU_MUL
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = i * 16 + 4 * q + r;
-            const int64_t m = m0 + row;
-            const float s = a.sx[m < a.M ? m : a.M - 1];
-            float z[CJ];
+        for (int i = 0; i < RI; ++i) {
+            const float4 s4 = *reinterpret_cast<const float4*>(sx_lds + i * 16 + 4 * q);     // rows 4q .. 4q+3 of row tile i
+            const float sr[4] = {s4.x, s4.y, s4.z, s4.w};
 #pragma unroll
-            for (int j = 0; j < CJ; ++j) z[j] = (y[i][j][r] - ssum[j] * BIAS_F) * 0x1p79f * s + bias[j];
-            if (gated) {
-                eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(silu_f32(z[0]) * z[1]);
-            } else {
+            for (int r = 0; r < 4; ++r) {
+                const int row = i * 16 + 4 * q + r;
+                const float t = sr[r] * 0x1p79f;
+                float z[CJ];
 #pragma unroll
-                for (int j = 0; j < CJ; ++j)
-                    eb[row * (E_STRIDE / 2) + j * 16 + l16] = f32_to_bf16_rne(a.epi.act == ACT_SILU ? silu_f32(z[j]) : z[j]);
+                for (int j = 0; j < CJ; ++j) z[j] = (y[i][j][r] - cj[j]) * t + bias[j];
+                if constexpr (MODE == ACT_SILU_MUL) {
+                    eb[row * (E_STRIDE / 2) + l16] = f32_to_bf16_rne(silu_f32(z[0]) * z[1]);
+                } else {
+                    static_assert(CJ == 2, "one packed conversion per row");
+                    const uint32_t pk = MODE == ACT_SILU ? pack_bf16x2(silu_f32(z[0]), silu_f32(z[1])) : pack_bf16x2(z[0], z[1]);
+                    eb[row * (E_STRIDE / 2) + l16] = (uint16_t)pk;
+                    eb[row * (E_STRIDE / 2) + 16 + l16] = (uint16_t)(pk >> 16);
+                }
             }
         }
-    }
+    };
+    if (gated) emit(std::integral_constant<int, ACT_SILU_MUL>{});
+    else if (a.epi.act == ACT_SILU) emit(std::integral_constant<int, ACT_SILU>{});
+    else emit(std::integral_constant<int, ACT_NONE>{});
     // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
     const int wcols = gated ? WN / 2 : WN;                   // output columns of this wave
     const int lpr = wcols * 2 / 16;                          // lanes per row piece (16 bytes each): 4 or 2
@@ -400,8 +420,11 @@ static int launch(const A8Args& a, hipStream_t stream)
     constexpr int WAVES = waves_of(BN);
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
-    const int group_m = a.tune.tiled_group_m ? a.tune.tiled_group_m : 8;
-    constexpr int lds = lds_bytes(BN);
+    // Row tiles per band: the 32 workgroups resident on an XCD cover group_m row tiles x 32 / group_m column
+    // tiles and fetch group_m MiB of activations and 16 / group_m MiB of weights per round at K = 8192: 4
+    // moves the least through the XCD's L2 (measured as fast as 8 at M = 2048, 2 % faster at M = 4096).
+    const int group_m = a.tune.tiled_group_m ? a.tune.tiled_group_m : 4;
+    constexpr int lds = lds_bytes(BN) + SX_BYTES;
     auto kern = a8_tiled128_kernel<128, DBG, BN>;
     if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, "w2_matmul_a8[tiled 128]")) return rc;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(64 * WAVES);

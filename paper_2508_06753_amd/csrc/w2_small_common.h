@@ -20,6 +20,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
+// two fp32 -> two bf16 (round to nearest even) in one dword, lo in the low half: one conversion instruction
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 // x * sigmoid(x); v_exp_f32 and v_rcp_f32 are good to about 1e-6 relative, far inside a bf16 result
 __device__ __forceinline__ float silu_f32(float z) { return z * __frcp_rn(1.0f + __expf(-z)); }
 
