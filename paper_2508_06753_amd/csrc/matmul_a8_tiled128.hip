@@ -204,14 +204,21 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     // prologue: stages 0 and 1 go to LDS; the registers then hold stage 2 (and 3)
     WTile<G> w0, w1;
     load_w(0, w0);
-#pragma unroll
-    for (int p = 0; p < WR; ++p) {
-        load_a(p, p00, p01, p02, p03);
-        store_a(p, p00, p01, p02, p03);
+    {
+        // every load of the prologue is issued before the first store waits: one memory round trip, not one
+        // per stage (nothing else runs on the CU meanwhile: a workgroup has it to itself)
+        const uint4 zero4 = make_uint4(0, 0, 0, 0);
+        uint4 t0a, t0b, t0c = zero4, t0d = zero4, t1a, t1b, t1c = zero4, t1d = zero4, t2a = zero4, t2b = zero4, t2c = zero4, t2d = zero4;
+        load_a(0, t0a, t0b, t0c, t0d);
+        load_a(1, t1a, t1b, t1c, t1d);
+        if constexpr (WR == 3) load_a(2, t2a, t2b, t2c, t2d);
+        load_a(WR, p00, p01, p02, p03);
+        if constexpr (TWO_SETS) load_a(WR + 1, p10, p11, p02, p03);
+        store_a(0, t0a, t0b, t0c, t0d);
+        store_a(1, t1a, t1b, t1c, t1d);
+        if constexpr (WR == 3) store_a(2, t2a, t2b, t2c, t2d);
     }
     if (tid < BM) sx_lds[tid] = sx_mine;
-    load_a(WR, p00, p01, p02, p03);
-    if constexpr (TWO_SETS) load_a(WR + 1, p10, p11, p02, p03);
     __syncthreads();
 
     const int8_t* a_base = smem + l16 * A_STRIDE + q * 16;
