@@ -195,16 +195,17 @@ W2_API int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, cons
  * kernel splits K, see w2_matmul_a8's workspace, with room in the workspace
  * beyond the int8 rows, the fp32 sums are taken in another order and the two
  * agree to the tolerance of the result contract instead).
- *   M <= 2: one launch; the abs-max is reduced per workgroup, redundantly, and
- *           kept in local memory.
- *   M >= 3: with a workspace of w2_workspace_size(M, K, N, G, 0) bytes (dev,
+ *   M <= 4: one launch where a workgroup can hold the rows (M', M rounded up
+ *           to a power of two: M'*K*elem_size up to 128 KiB in registers and
+ *           M*K up to about 150 KB of int8 rows in local memory): the abs-max
+ *           is reduced per workgroup, redundantly, and the rows are quantised
+ *           into local memory.
+ *   Otherwise, with a workspace of w2_workspace_size(M, K, N, G, 0) bytes (dev,
  *           16-byte aligned; holds the int8 rows and their scales, contents
  *           undefined afterwards) two launches: quantise, then the kernel family
- *           w2_matmul_a8 picks for M.  Without one, M <= 4 still runs as one
- *           launch (slower than two from M = 3 on) as long as the rows fit a
- *           workgroup's local memory (M*K*elem_size up to about 64 KiB);
- *           otherwise W2_ERR_UNSUPPORTED_SHAPE, nothing launched.  A workspace
- *           that is too small for M > 4 gives W2_ERR_BUFFER_TOO_SMALL. */
+ *           w2_matmul_a8 picks for M.  Without one: W2_ERR_UNSUPPORTED_SHAPE,
+ *           nothing launched; with one that is too small for M > 4:
+ *           W2_ERR_BUFFER_TOO_SMALL. */
 W2_API int w2_matmul_a8_fused(const void* packed, int64_t K, int64_t N, int G, const void* X,
                               w2_dtype_t x_dtype, int64_t ldx, int64_t M, uint16_t* Y, int64_t ldy,
                               void* workspace, size_t workspace_bytes, void* stream);

@@ -366,11 +366,12 @@ static int a8_fused_common(const char* fn, const void* packed, int64_t K, int64_
     if (workspace && !aligned16(workspace))
         return fail(W2_ERR_MISALIGNED, "%s: workspace must be 16-byte aligned", fn);
     const Layout L = make_layout(K, N, G);
-    // Measured: one launch with the abs-max reduced per workgroup wins for one or two rows; from
-    // three rows on every workgroup re-reading and re-quantising all rows costs more than a
-    // separate quantise launch (the paper's finding for multi-row activations, Sec. III-C).
+    // Measured: one launch with the abs-max reduced per workgroup is at least as fast as quantise + matmul
+    // up to four rows wherever a workgroup can hold the rows (4096 x 28672 at M = 4: 10.2 against 11.0 us,
+    // 4096 x 4096: 5.3 against 6.3); beyond, every workgroup re-reading and re-quantising all rows costs
+    // more than a separate quantise launch (the paper's finding for multi-row activations, Sec. III-C).
     const bool ws_ok = workspace && workspace_bytes >= fused_workspace_bytes(M, K);
-    if (M <= 2 || !ws_ok) {
+    if (M <= 4 || !ws_ok) {
         if (M > 4 && workspace)
             return fail(W2_ERR_BUFFER_TOO_SMALL, "%s: M = %lld needs a workspace of %zu bytes (w2_workspace_size)",
                         fn, (long long)M, fused_workspace_bytes(M, K));
