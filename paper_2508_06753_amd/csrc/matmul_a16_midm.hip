@@ -65,9 +65,9 @@ __device__ __forceinline__ v4f mfma_bf16(const v4i& a, const v4i& b, const v4f& 
                                                    __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
 }
 
-template <int G, int RT, int TPC>
+template <int G, int RT, int TPC, bool SPLIT>
 __global__ void __launch_bounds__(THREADS)
-a16_midm_kernel(A16Args a_all, int splits)
+a16_midm_kernel(A16Args a_all, int c_lo, int c_rem)
 {
     // More than 64 rows: blockIdx.y picks a band of 64 rows; the bands stream the same weights (the
     // second one mostly out of L2), which pays when one band's workgroups would leave CUs idle.
@@ -92,12 +92,29 @@ a16_midm_kernel(A16Args a_all, int splits)
     const int64_t cb = (int64_t)blockIdx.x * CBW + cbi;
     const int64_t cbc = cb < a.n_cb ? cb : a.n_cb - 1;       // clamp: keeps loads in bounds
     const int rows = (int)a.M;                               // 1..16*RT
+    // Split-K across workgroups (Sec. II-D): blockIdx.z picks one of the near-equal ranges of whole 1024-k
+    // chunks (c_lo chunks each, one more for the first c_rem ranges: no division here, ahead of the first
+    // loads), and the workgroup stages only that K range of the activation rows.  The range is entered by
+    // moving the base pointers: from here on the kernel sees a problem of n_kt tiles that starts at tile 0,
+    // and the loop the compiler builds is the unsplit kernel's (around a run-time first chunk it was 5 %
+    // slower on every shape).
+    const int64_t kt_stride = a.n_kt;                        // tiles per column block in memory
+    int64_t kt0 = 0;                                         // first tile of this workgroup's range
+    if constexpr (SPLIT) {
+        const int z = (int)blockIdx.z;
+        const int c_first = z * c_lo + min(z, c_rem);
+        const int c_count = c_lo + (z < c_rem ? 1 : 0);
+        kt0 = (int64_t)c_first * CHUNK_TILES;
+        a.n_kt = min(a.n_kt - kt0, (int64_t)c_count * CHUNK_TILES);
+        a.K = a.n_kt * TILE_K;                               // (the rows keep their stride ldx)
+        a.X += kt0 * TILE_K;
+    } else {
+        a.part = nullptr;
+    }
     const int n_chunks = (int)((a.n_kt + CHUNK_TILES - 1) / CHUNK_TILES);
-    // split-K across workgroups (Sec. II-D): blockIdx.z picks one of `splits` near-equal ranges of whole
-    // chunks [c_b, c_e); the workgroup stages only that K range of the activation rows
-    const int c_b = (int)((int64_t)n_chunks * blockIdx.z / splits);
-    const int c_e = (int)((int64_t)n_chunks * (blockIdx.z + 1) / splits);
-    const int64_t kt_hi = min(a.n_kt, (int64_t)c_e * CHUNK_TILES);
+    const int c_b = 0, c_e = n_chunks;
+    const int64_t kt_hi = a.n_kt;
+    if constexpr (!SPLIT) a.part = nullptr;
 
     int arow[RT];                                            // padded rows repeat the last
 #pragma unroll
@@ -163,7 +180,7 @@ a16_midm_kernel(A16Args a_all, int splits)
     auto load_w = [&](int64_t s) {
         int64_t kt = ks + s * KS;
         kt = kt < kt_hi ? kt : kt_hi - 1;                    // past this workgroup's range: its last tile again
-        const int64_t tile = cbc * a.n_kt + kt;
+        const int64_t tile = cbc * kt_stride + kt0 + kt;
         const char* wbase = reinterpret_cast<const char*>(a.codes) + tile * (TILE_N * TILE_K / 4);
         const char* sbase = reinterpret_cast<const char*>(a.scales) + tile * (TILE_N * GPT * 2);
         asm volatile("" : "+v"(w_lane), "+v"(s_lane));
@@ -277,13 +294,16 @@ static int launch_t(const A16Args& a_in, int splits, hipStream_t stream)
     const size_t act = (size_t)band * ROW_STRIDE;
     const size_t red = (size_t)8 * RT * 16 * 16 * sizeof(float);
     const size_t lds = act > red ? act : red;
+    const int n_chunks = (int)((a.n_kt + CHUNK_TILES - 1) / CHUNK_TILES);
     const dim3 grid((unsigned)((a.n_cb + CBW - 1) / CBW), (unsigned)((a.M + ROWS_PER_BAND - 1) / ROWS_PER_BAND),
                     (unsigned)splits), block(THREADS);
-    auto kern = a16_midm_kernel<G, RT, TPC>;
-    if (int rc = ensure_dynamic_lds((const void*)kern, lds, "w2_matmul_a16[midm]")) return rc;
-    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, splits);
-    if (int rc = check_launch("w2_matmul_a16[midm]")) return rc;
-    if (splits < 2) return W2_OK;
+    auto go = [&](auto kern) {
+        if (int rc = ensure_dynamic_lds((const void*)kern, lds, "w2_matmul_a16[midm]")) return rc;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, a, n_chunks / splits, n_chunks % splits);
+        return check_launch("w2_matmul_a16[midm]");
+    };
+    if (splits < 2) return go(a16_midm_kernel<G, RT, TPC, false>);
+    if (int rc = go(a16_midm_kernel<G, RT, TPC, true>)) return rc;
     return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, a.epi, stream);
 }
 
