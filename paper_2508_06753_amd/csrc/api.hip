@@ -280,25 +280,24 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
                                                                            : W2_VARIANT_TILED;
         // The decode kernel keeps whole rows in local memory and reads the weights once, like the mid-M
         // kernel, without that kernel's barrier pair per 1024 k: measured faster up to 8 rows wherever the
-        // rows fit (4096 x 28672 at M = 8: 7.4 against 10.1 us; 8192 x 8192: 5.9 against 7.8), up to 12 rows
-        // while two workgroups share a CU (rows of at most 64 KiB) or the projection is narrow (8192 x 8192:
-        // 6.5 against 8.5 us; 8192 x 57344 loses: 33 against 28), and up to 16 on the narrowest ones
-        // (4096 x 4096: 4.1 against 5.4 us; wider ones lose there: 4096 x 28672 11.6 against 10.3).
+        // rows fit (4096 x 28672 at M = 8: 7.4 against 10.1 us; 8192 x 8192: 5.9 against 7.8), and up to 16 rows
+        // while two workgroups share a CU (rows of at most 64 to 68 KiB: 4096 x 28672 at M = 16 10.1 against
+        // 10.5 us, 4096 x 6144 5.2 against 6.0) or the projection is narrow (8192 x 8192 at M = 16: 7.5 against
+        // 9.4 us); wide projections with long rows lose (8192 x 57344 at M = 12: 33 against 28 us).
         // Rows of more than 72 KiB leave room for one workgroup per CU only: then the grid must fit the chip
         // in one round (17408 x 5120 at M = 8, 320 workgroups: 15.3 against 10.4 us through the mid-M kernel;
-        // 14336 x 4096, 256 workgroups: 6.4 against 8.1).  The grid: eight waves as column blocks x k-ranges,
-        // K split until there are 2048 waves and no range is longer than 16 tiles (the decode kernel's rule).
+        // 14336 x 4096, 256 workgroups: 6.4 against 8.1).
         const int64_t row_bytes = M * (K + 32);
-        int ks = 1;
-        while (ks < 8 && (a.n_cb * ks < 2048 || (a.n_kt + ks - 1) / ks > 16)) ks <<= 1;
-        const int64_t gemv_wgs = (a.n_cb + 8 / ks - 1) / (8 / ks);
+        int gcbw = M > 12 ? 8 : 4;                              // (the decode kernel's rule for five rows and more)
+        while (gcbw > 1 && (a.n_cb / gcbw < 192 || (a.n_kt + 8 / gcbw - 1) / (8 / gcbw) > 16)) gcbw >>= 1;
+        const int64_t gemv_wgs = (a.n_cb + gcbw - 1) / gcbw;
         const bool one_round = row_bytes <= 72 * 1024 || gemv_wgs <= 256;
         const int gemv_max = tn.gemv_max_m                               ? tn.gemv_max_m
                            : M <= 4                                      ? 4
                            : !one_round                                  ? 4
                            : M <= 8                                      ? 8
                            : M <= 12 && (row_bytes <= 64 * 1024 || a.n_cb <= 512) ? 12
-                           : a.n_cb <= 256 && row_bytes <= 68 * 1024     ? 16
+                           : row_bytes <= 68 * 1024 || a.n_cb <= 512     ? 16
                                                                          : 8;
         variant = M <= dot4_max && a8_dot4_supports(a)     ? W2_VARIANT_DOT4
                 : M <= gemv_max && a8_gemv_supports(M)     ? W2_VARIANT_GEMV

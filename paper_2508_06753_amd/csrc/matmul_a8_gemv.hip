@@ -464,13 +464,16 @@ a8_gemv_kernel(Args a)
 //     (runs of seven); more waves than that only add per-wave fixed work, fewer leave the memory system short
 //     of requests;
 //   - eight waves per workgroup (sixteen when ks = 16, or when the rows need the threads);
+//   - five rows and more (the wide form): the rows re-read by every workgroup weigh as much as the weights, so
+//     the workgroups are as wide as still leaves about 192 of them (4096 x 28672 at M = 16: 10.1 us with 8 x 1
+//     against 12.5 with 4 x 2; 4096 x 6144: 5.2 with 2 x 4 against 7.5 with 1 x 8);
 //   - window 2 for runs of up to four tiles.  Longer runs: 4 in grids of more than 768 workgroups (8192 x
 //     57344 gains 10 %) and of up to 256 (14336 x 4096: 5 %), 2 between (5120 x 34816 loses 11 to 15 % to the
 //     deeper window, 4096 x 28672 3 % with int8 rows and gains 1 % with rows quantised in the kernel: more
 //     bytes in flight than about 10 MB over the chip does not pay); 8 was never better.
 struct Cfg { int cbw, ks, window; };
 
-static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_cbw, int min_threads, int max_w, int xt)
+static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_cbw, int min_threads, int max_w, int rows)
 {
     Cfg c;
     if (tune.small_waves || tune.small_cbw) {                // forced shape (tests, sweeps)
@@ -481,6 +484,13 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
         c.cbw = tune.small_cbw ? tune.small_cbw : waves;
         if (c.cbw > waves) c.cbw = waves;
         c.ks = waves / c.cbw;
+    } else if (rows > 4) {
+        // the wide form: every workgroup stages all rows, so as many column blocks per workgroup (up to 4;
+        // 8 from 13 rows on) as leave about 192 workgroups; eight waves
+        int cbw = rows > 12 ? 8 : 4;
+        while (cbw > 1 && n_cb / cbw < 192) cbw >>= 1;
+        c.cbw = cbw;
+        c.ks = 8 / cbw;
     } else {
         int ks = 1;
         while (ks < max_w && n_cb * ks < 2048 && n_kt / (ks * 2) >= 1) ks <<= 1;
@@ -502,7 +512,6 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
     while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw * c.ks < max_w) c.ks <<= 1;
     const int64_t run = (n_kt + c.ks - 1) / c.ks;
     const int64_t wgs = (n_cb + c.cbw - 1) / c.cbw;
-    (void)xt;
     c.window = tune.gemv_window ? tune.gemv_window : run > 4 && (wgs > 768 || wgs <= 256) ? 4 : 2;
     return c;
 }
@@ -558,7 +567,7 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
         set_error(too_large);
         return W2_ERR_UNSUPPORTED_SHAPE;
     }
-    const Cfg c = pick(a8.tune, a8.n_cb, a8.n_kt, a8.epi.act == ACT_SILU_MUL, min_threads, max_w, xt);
+    const Cfg c = pick(a8.tune, a8.n_cb, a8.n_kt, a8.epi.act == ACT_SILU_MUL, min_threads, max_w, (int)M);
     const int waves = c.cbw * c.ks;
     // local memory: header, rows, reduction scratch, the waves' scale slices; a CU has 160 KiB
     const size_t lds_need = HDR + xs_bytes + (size_t)waves * rl * 16 * sizeof(float) +
