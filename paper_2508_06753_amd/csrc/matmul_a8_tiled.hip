@@ -451,7 +451,14 @@ int launch_a8_tiled(const A8Args& a, hipStream_t stream)
         const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
         const int splits = a.acc_out ? 1 : tiled_splits(a.M, a.N, a.n_kt, cap, a.tune);
         (void)bn;
-        const bool want128 = a.tune.tiled_bm ? a.tune.tiled_bm == 128 : a.M >= 1024;
+        // 128-row tiles run one workgroup per CU, so a last round of workgroups that fills less than half the
+        // chip costs a whole round (64-row workgroups share a CU in pairs and speed up when alone); with 224
+        // tiles and more and a last round at least half full they win from M = 128 on (8192 x 57344 at M = 128:
+        // 71 against 84 us; 4096 x 28672 at M = 384, 1.3 rounds: 66 against 57)
+        const int64_t t128 = (a.M + 127) / 128 * ((a.N + 255) / 256);
+        const bool fill_ok = t128 >= 768 || t128 % 256 == 0 || t128 % 256 >= 128;
+        const bool want128 = a.tune.tiled_bm ? a.tune.tiled_bm == 128
+                                             : a.M >= 1024 || (a.M >= 128 && t128 >= 224 && fill_ok);
         if (want128 && splits < 2 && a8_tiled128_supports(a)) return launch_a8_tiled128(a, stream);
     }
     if (a.G == 128)
