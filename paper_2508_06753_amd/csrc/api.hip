@@ -159,6 +159,7 @@ static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
     else if (!one_of(t->midm_cbw, 2, 4, 8)) bad = "midm_cbw";
     else if (!one_of(t->tiled_bm, 64, 128)) bad = "tiled_bm";
     else if (!one_of(t->tiled_bn, 128, 256)) bad = "tiled_bn";
+    else if (!one_of(t->tiled_kw, 1, 2, 4)) bad = "tiled_kw";
     else if (!in(t->tiled_group_m, 1, 1024)) bad = "tiled_group_m";
     else if (!in(t->splitk, 1, 16)) bad = "splitk";
     else if (!in(t->splitk_min_tiles, 1, 1024)) bad = "splitk_min_tiles";
@@ -264,17 +265,16 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         // column blocks: it then splits K four ways with a barrier pair per tile), and is faster
         // than the tiled one up to M = 64
         const int dot4_max = tn.dot4_max_m;
-        // ... and, as two bands of 64 rows, up to M = 128 on projections of at most 8192 columns, where
-        // one band's workgroups leave CUs idle and the tiled kernel has too few tiles (10 against 19 us
-        // on 4096 x 4096)
         const int midm_min = tn.midm_min_m ? tn.midm_min_m : (a.n_cb >= 384 || a.n_kt > 64) ? 4 : 9;
-        // ... and only up to M = 48 on very wide projections (32768 columns and more), where every
-        // workgroup's re-read of the activation rows outweighs the weights (8192 x 57344 at M = 64:
-        // 66 us against 50 us through the tiled kernel)
-        // (with room for split-K partial results the tiled kernel is the faster one there once K passes
-        // 16384: 31 against 43 us on 17408 x 5120 at M = 128)
+        // Upper end.  Two bands of 64 rows (up to M = 128) on the narrowest projections only (up to 4096
+        // columns, where the tiled kernel has too few tiles: 4096 x 4096 at M = 128 10 against 14.7 us; with room
+        // for split-K partial results the tiled kernel is the faster one there once K passes 16384).  Wider:
+        // 8192 x 8192 at M = 128 runs 23.5 us through the tiled kernel with K split inside its workgroups
+        // against 33 in two bands, 4096 x 6144 15.0 against 18.7.  On wide projections (24576 columns and more)
+        // the tiled kernel takes over at M = 33, where the mid-M kernel goes to four row tiles per wave and its
+        // LDS operand reads bound it (4096 x 28672 at M = 48: 15.8 against 19.0 us; 5120 x 34816: 27 against 40).
         const int midm_max = tn.midm_max_m ? tn.midm_max_m
-                           : a.n_cb <= 512 ? (a.part_bytes && a.n_kt > 64 ? 64 : 128) : a.n_cb >= 2048 ? 48 : 64;
+                           : a.n_cb <= 256 ? (a.part_bytes && a.n_kt > 64 ? 64 : 128) : a.n_cb >= 1536 ? 32 : 64;
         fallback = M >= midm_min && M <= midm_max && a8_midm_supports(a) ? W2_VARIANT_MIDM
                  : a8_smallm_supports(a)                                   ? W2_VARIANT_SMALLM
                                                                            : W2_VARIANT_TILED;
@@ -619,7 +619,7 @@ int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* b
     else {
         // split-K partial results: the tiled kernel's above 64 rows, the mid-M kernel's on deep projections
         // (whichever of the two the call would pick, the larger need covers it)
-        const size_t tiled = M > 64 ? a8_tiled_splitk_bytes(M, N, L.n_kt, dflt) : 0;
+        const size_t tiled = M > 32 ? a8_tiled_splitk_bytes(M, N, L.n_kt, dflt) : 0;
         const size_t midm = M >= 4 && M <= 128 ? a8_midm_splitk_bytes(M, N, L.n_cb, L.n_kt, dflt) : 0;
         *bytes = (single ? 0 : fused_workspace_bytes(M, K)) + (tiled > midm ? tiled : midm);
     }

@@ -107,17 +107,24 @@ __device__ __forceinline__ void load_w(const char* const (&wb)[CJ], const char* 
     }
 }
 
-template <int G, bool DBG, int BN>
-__global__ void __launch_bounds__(64 * waves_of(BN), wgs_per_cu(64 * waves_of(BN)))
+// KW > 1: K-splitting inside the workgroup (Sec. II-D) for problems with too few output tiles to give
+// every SIMD a wave: KW groups of waves_of(BN) waves each run this kernel on their own K range (the
+// group index extends the split coordinate; the host guarantees equal ranges, so every group meets
+// the same barriers) with activation buffers of their own; the partial results meet in LDS, group 0
+// adds them in a fixed order and stores.
+template <int G, bool DBG, int BN, int KW>
+__global__ void __launch_bounds__(64 * waves_of(BN) * KW, wgs_per_cu(64 * waves_of(BN) * KW))
 a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
 {
-    constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
+    constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;      // per group
     (void)WAVES;
-    extern __shared__ __align__(16) int8_t smem[];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = 0, wn = wave;
+    extern __shared__ __align__(16) int8_t smem_all[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int grp = KW > 1 ? wave / WAVES : 0;
+    const int tid = (int)threadIdx.x - grp * THREADS;              // thread index inside the group
+    int8_t* const smem = smem_all + grp * (3 * A_BUF);             // this group's activation buffers
+    const int wm = 0, wn = KW > 1 ? wave % WAVES : wave;
     const int q = lane >> 4, l16 = lane & 15;
 
     // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (round
@@ -178,8 +185,9 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
     // the top of stage it into the other of two register sets.  Every global load has a whole
     // stage to land before anything waits for it.
     // this workgroup's K range (split-K: blockIdx.y of `splits` near-equal ranges of whole 256-k tiles)
-    const int64_t it_b = a.n_kt * blockIdx.y / splits * 2;
-    const int64_t n_it = a.n_kt * (blockIdx.y + 1) / splits * 2;   // stages [it_b, n_it): an even number, >= 2
+    const int64_t sy = (int64_t)blockIdx.y * KW + grp, ns = (int64_t)splits * KW;
+    const int64_t it_b = a.n_kt * sy / ns * 2;
+    const int64_t n_it = a.n_kt * (sy + 1) / ns * 2;               // stages [it_b, n_it): an even number, >= 2
     // The empty asm statements keep the zero-extension of a lane offset next to its load, which is
     // what lets the compiler pick the "scalar base + 32-bit vector offset" addressing mode.
     auto load_a = [&](int64_t it, uint4& r0, uint4& r1) {
@@ -308,6 +316,31 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
     }
     if constexpr (CJ > 1) dequant_col(CJ - 1, pend_sw, pend_g);   // the very last group's last column
     if constexpr (DBG) return;
+    if constexpr (KW > 1) {
+        // the groups' partial results (bias term taken out) meet in LDS, behind the epilogue's regions;
+        // element e of a wave's 64 x 32 tile sits at [e][lane]: conflict-free both ways
+        float* pr = reinterpret_cast<float*>(smem_all + WAVES * BM * E_STRIDE) + (int64_t)wn * (RI * 4 * CJ * 64) + lane;
+#pragma unroll
+        for (int i = 0; i < RI; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) {
+                    y[i][j][r] -= ssum[j] * 0x1p-128f;
+                    if (grp > 0) pr[((grp - 1) * WAVES * (RI * 4 * CJ) + (i * 4 + r) * CJ + j) * 64] = y[i][j][r];
+                }
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) ssum[j] = 0.f;
+        __syncthreads();
+        if (grp > 0) return;
+        for (int g = 0; g < KW - 1; ++g)
+#pragma unroll
+            for (int i = 0; i < RI; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int j = 0; j < CJ; ++j) y[i][j][r] += pr[(g * WAVES * (RI * 4 * CJ) + (i * 4 + r) * CJ + j) * 64];
+    }
 
     // y_true = (y - BIAS*2^-149 * ssum) * 2^(149-64) * 2^-6 * sx   (2^-128 = BIAS * 2^-149)
     // Each lane holds single columns of four rows per tile, which would make 2-byte stores in
@@ -332,7 +365,7 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
             }
         return;
     }
-    int8_t* ebase = smem + wn * (BM * E_STRIDE);
+    int8_t* ebase = smem_all + wn * (BM * E_STRIDE);
     uint16_t* eb = reinterpret_cast<uint16_t*>(ebase);
     // fused epilogue (Sec. II-D: bias and activation applied while the outputs are in registers).
     // The gated form combines the wave's two column blocks, an even (gate) and an odd (up) one,
@@ -389,20 +422,24 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
 
 }  // namespace tiled
 
-template <int G, bool DBG, int BN>
+template <int G, bool DBG, int BN, int KW = 1>
 static int launch_tiled(const A8Args& a_in, int splits, hipStream_t stream)
 {
     using namespace tiled;
-    constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
+    constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES * KW;
     A8Args a = a_in;
     if (splits < 2 || DBG) { a.part = nullptr; splits = 1; }
     const int tiles_m = (int)((a.M + BM - 1) / BM);
     const int tiles_n = (int)((a.N + BN - 1) / BN);
-    const size_t act = 3 * A_BUF, epi = (size_t)WAVES * BM * E_STRIDE;   // three activation stages; the epilogue regions reuse them
+    // three activation stages per group; the epilogue regions (and behind them the groups' partial results) reuse them
+    const size_t act = (size_t)KW * 3 * A_BUF;
+    const size_t epi = (size_t)WAVES * BM * E_STRIDE + (size_t)(KW - 1) * WAVES * BM * WN * sizeof(float);
     const size_t lds = act > epi ? act : epi;
     const int group_m = a.tune.tiled_group_m ? a.tune.tiled_group_m : 8;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)splits), block(THREADS);
-    hipLaunchKernelGGL((a8_tiled_kernel<G, DBG, BN>), grid, block, lds, stream, a, tiles_m, tiles_n, group_m, splits);
+    auto kern = a8_tiled_kernel<G, DBG, BN, KW>;
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, "w2_matmul_a8[tiled]")) return rc;
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, tiles_m, tiles_n, group_m, splits);
     int rc = check_launch("w2_matmul_a8[tiled]");
     if (rc || !a.part) return rc;
     return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, a.epi, stream);
@@ -439,6 +476,16 @@ static int launch_tiled_bn(const A8Args& a, hipStream_t stream)
     const int bn = tiled_bn(a.M, a.N, a.tune);
     const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
     const int splits = DBG ? 1 : tiled_splits(a.M, a.N, a.n_kt, cap, a.tune);
+    if (bn == 128 && !DBG) {
+        // K split inside the workgroup, only where every group gets the same number of 256-k tiles: four
+        // groups (16 waves, one workgroup per CU) while the workgroups fit the chip in one round, two (two
+        // workgroups per CU) up to two per CU.  Measured at M = 64: 4096 x 28672 16.1 us against 19.6 unsplit
+        // (and 20.4 through the mid-M kernel), 5120 x 34816 (272 workgroups) 27.4 with two groups, 33.3 with four.
+        const int64_t wgs = (a.M + tiled::BM - 1) / tiled::BM * ((a.N + 127) / 128) * (splits < 2 ? 1 : splits);
+        const int kw = a.tune.tiled_kw ? a.tune.tiled_kw : wgs <= 256 ? 4 : wgs <= 512 ? 2 : 1;
+        if (kw == 4 && a.n_kt % (4 * (splits < 2 ? 1 : splits)) == 0) return launch_tiled<G, DBG, 128, 4>(a, splits, stream);
+        if (kw >= 2 && a.n_kt % (2 * (splits < 2 ? 1 : splits)) == 0) return launch_tiled<G, DBG, 128, 2>(a, splits, stream);
+    }
     return bn == 128 ? launch_tiled<G, DBG, 128>(a, splits, stream) : launch_tiled<G, DBG, 256>(a, splits, stream);
 }
 

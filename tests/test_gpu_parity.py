@@ -249,6 +249,28 @@ def test_a8_tiled(w2, M, K, N, G, bn):
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G, tune={"tiled_bn": bn})
 
 
+@pytest.mark.parametrize("kw", [2, 4])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(1024, 272), (2048, 1032), (4096, 48), (512, 16)])
+@pytest.mark.parametrize("M", [1, 33, 64, 100])
+def test_a8_tiled_k_split_inside_workgroup(w2, M, K, N, G, kw):
+    # 64-row tiles, 128-column workgroups whose 2 or 4 groups of waves take K ranges of their own and add up in
+    # LDS (K = 512 with four groups: the ranges cannot be equal, the plain kernel runs); with and without the
+    # split across workgroups on top
+    tune = {"tiled_bm": 64, "tiled_bn": 128, "tiled_kw": kw}
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G + kw, tune=tune)
+    if K >= 2048:
+        codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + N)
+        packed = w2.prepack(dev(codes), dev(scales), G, 0)
+        xq, sx, _ = w2.quantize_rows(dev(X), G)
+        ws = torch.empty(4 * M * N * 4, dtype=torch.uint8, device="cuda")
+        Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED, workspace=ws, tune=dict(tune, splitk=2))
+        oq, osx, _ = oracle.quantize_rows(X, G)
+        Yo, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+        mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+        check_y(bf16_bits(Y), Yo, y64, mag, f"a8 tiled kw={kw} split-K 2 M={M} K={K} N={N} G={G}")
+
+
 @pytest.mark.parametrize("bn", [128, 256])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (512, 1032), (4608, 48)])
 @pytest.mark.parametrize("M", [1, 17, 127, 128, 129, 300])
