@@ -473,7 +473,7 @@ a8_gemv_kernel(Args a)
 //     bytes in flight than about 10 MB over the chip does not pay); 8 was never better.
 struct Cfg { int cbw, ks, window; };
 
-static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_cbw, int min_threads, int max_w, int rows)
+static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_cbw, int min_threads, int max_w, int rows, int xt)
 {
     Cfg c;
     if (tune.small_waves || tune.small_cbw) {                // forced shape (tests, sweeps)
@@ -497,6 +497,15 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
         while (ks < max_w && (n_kt + ks - 1) / ks > MAX_RUN) ks <<= 1;
         c.ks = ks;
         c.cbw = ks >= 8 ? 1 : 8 / ks;                        // eight waves; sixteen when ks = 16
+        if (xt != 0 && ks == 8 && n_kt <= 32 && (n_cb >= 320 || rows <= 2) && 4 * (n_cb >= 320 ? 2 : 1) * 64 >= min_threads) {
+            // rows quantised in the kernel, narrow projection: every workgroup re-reads and re-quantises the
+            // row, so half as many k-ranges (runs of four or five tiles) and, from 320 column blocks on, two
+            // column blocks per workgroup (4096 x 6144 4.5 against 4.9 us, 5120 x 5120 4.9 against 5.5;
+            // 4096 x 4096 keeps one column block, in workgroups of four waves, for one or two rows: 3.5
+            // against 3.9; at three and four rows it loses), where that many threads can hold the rows
+            c.ks = 4;
+            c.cbw = n_cb >= 320 ? 2 : 1;
+        }
     }
     if (even_cbw && (c.cbw & 1)) c.cbw = 2;                  // the gated epilogue pairs adjacent column blocks
     while (c.cbw * c.ks > max_w) {                           // at most 16 waves (8 in the wide form)
@@ -512,7 +521,7 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
     while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw * c.ks < max_w) c.ks <<= 1;
     const int64_t run = (n_kt + c.ks - 1) / c.ks;
     const int64_t wgs = (n_cb + c.cbw - 1) / c.cbw;
-    c.window = tune.gemv_window ? tune.gemv_window : run > 4 && (wgs > 768 || wgs <= 256) ? 4 : 2;
+    c.window = tune.gemv_window ? tune.gemv_window : (run > 4 && (wgs > 768 || wgs <= 256)) || c.cbw * c.ks == 4 ? 4 : 2;
     return c;
 }
 
@@ -567,7 +576,7 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
         set_error(too_large);
         return W2_ERR_UNSUPPORTED_SHAPE;
     }
-    const Cfg c = pick(a8.tune, a8.n_cb, a8.n_kt, a8.epi.act == ACT_SILU_MUL, min_threads, max_w, (int)M);
+    const Cfg c = pick(a8.tune, a8.n_cb, a8.n_kt, a8.epi.act == ACT_SILU_MUL, min_threads, max_w, (int)M, xt);
     const int waves = c.cbw * c.ks;
     // local memory: header, rows, reduction scratch, the waves' scale slices; a CU has 160 KiB
     const size_t lds_need = HDR + xs_bytes + (size_t)waves * rl * 16 * sizeof(float) +
