@@ -160,6 +160,7 @@ static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
     else if (!one_of(t->tiled_bm, 64, 128)) bad = "tiled_bm";
     else if (!one_of(t->tiled_bn, 128, 256)) bad = "tiled_bn";
     else if (!one_of(t->tiled_kw, 1, 2, 4)) bad = "tiled_kw";
+    else if (!one_of(t->tiled_wd, 2, 8)) bad = "tiled_wd";
     else if (!in(t->tiled_group_m, 1, 1024)) bad = "tiled_group_m";
     else if (!in(t->splitk, 1, 16)) bad = "splitk";
     else if (!in(t->splitk_min_tiles, 1, 1024)) bad = "splitk_min_tiles";
@@ -268,13 +269,17 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         const int midm_min = tn.midm_min_m ? tn.midm_min_m : (a.n_cb >= 384 || a.n_kt > 64) ? 4 : 9;
         // Upper end.  Two bands of 64 rows (up to M = 128) on the narrowest projections only (up to 4096
         // columns, where the tiled kernel has too few tiles: 4096 x 4096 at M = 128 10 against 14.7 us; with room
-        // for split-K partial results the tiled kernel is the faster one there once K passes 16384).  Wider:
+        // for split-K partial results the tiled kernel is the faster one there once K reaches 14336).  Wider:
         // 8192 x 8192 at M = 128 runs 23.5 us through the tiled kernel with K split inside its workgroups
         // against 33 in two bands, 4096 x 6144 15.0 against 18.7.  On wide projections (24576 columns and more)
         // the tiled kernel takes over at M = 33, where the mid-M kernel goes to four row tiles per wave and its
         // LDS operand reads bound it (4096 x 28672 at M = 48: 15.8 against 19.0 us; 5120 x 34816: 27 against 40).
+        // Deep K (56 tiles and more) with room for split-K partial results: the tiled kernel, its K cut across
+        // and inside workgroups, takes over at M = 33 (28672 x 8192 at M = 64: 31 against 34 us; 17408 x 5120 at
+        // M = 33: 18.0 against 19.2), on the narrowest projections at M = 65 (14336 x 4096: 19.2 against 21.2).
+        const bool deep_ws = a.part_bytes && a.n_kt >= 56;
         const int midm_max = tn.midm_max_m ? tn.midm_max_m
-                           : a.n_cb <= 256 ? (a.part_bytes && a.n_kt > 64 ? 64 : 128) : a.n_cb >= 1536 ? 32 : 64;
+                           : a.n_cb <= 256 ? (deep_ws ? 64 : 128) : a.n_cb >= 1536 || deep_ws ? 32 : 64;
         fallback = M >= midm_min && M <= midm_max && a8_midm_supports(a) ? W2_VARIANT_MIDM
                  : a8_smallm_supports(a)                                   ? W2_VARIANT_SMALLM
                                                                            : W2_VARIANT_TILED;

@@ -60,7 +60,16 @@ constexpr int A_STRIDE = BK + 32;
 constexpr int A_BUF = BM * A_STRIDE;              // bytes per stage
 constexpr int WM = BM, WN = 16 * CJ;                // wave tile
 constexpr int E_STRIDE = WN * 2 + 16;             // epilogue: bytes per LDS row of a wave's result
-constexpr int wgs_per_cu(int threads) { return threads > 512 ? 1 : threads <= 256 && RI * CJ <= 8 ? 4 : ((RI * CJ <= 16 && threads <= 256) || (RI * CJ <= 8) ? 2 : 1); }
+constexpr int P_STRIDE = WN * 4 + 16;             // split-K: bytes per LDS row of a wave's fp32 partial result
+// LDS layout after the main loop: [epilogue regions | partial results of the groups 1..KW-1 | fp32 staging]
+constexpr int exch_off(int waves) { return waves * BM * E_STRIDE; }
+constexpr int pstage_off(int waves, int kw) { return kw > 1 ? exch_off(waves) + (kw - 1) * waves * BM * WN * 4 : 0; }
+constexpr int wgs_per_cu(int threads, int wd = 2)
+{
+    // a weight window deeper than two stages needs more than 128 registers: two waves per SIMD
+    if (wd > 2) return threads > 256 ? 1 : 2;
+    return threads > 512 ? 1 : threads <= 256 && RI * CJ <= 8 ? 4 : ((RI * CJ <= 16 && threads <= 256) || (RI * CJ <= 8) ? 2 : 1);
+}
 constexpr int BIAS = 1 << 21;                     // > 64 * 127 * 2 * 128 = 2 080 768
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
@@ -112,8 +121,13 @@ __device__ __forceinline__ void load_w(const char* const (&wb)[CJ], const char* 
 // group index extends the split coordinate; the host guarantees equal ranges, so every group meets
 // the same barriers) with activation buffers of their own; the partial results meet in LDS, group 0
 // adds them in a fixed order and stores.
-template <int G, bool DBG, int BN, int KW>
-__global__ void __launch_bounds__(64 * waves_of(BN) * KW, wgs_per_cu(64 * waves_of(BN) * KW))
+//
+// WD: weight stages in flight per wave (the one being multiplied included).  Two are enough when the
+// weights come out of L2 (many row tiles share them); a problem of one or two row tiles streams them
+// from HBM once, and a stage's arithmetic is far shorter than a memory round trip: there every wave
+// keeps WD - 1 = 7 stages (7 KiB) on their way.
+template <int G, bool DBG, int BN, int KW, int WD>
+__global__ void __launch_bounds__(64 * waves_of(BN) * KW, wgs_per_cu(64 * waves_of(BN) * KW, WD))
 a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
 {
     constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;      // per group
@@ -196,13 +210,25 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
         r0 = *reinterpret_cast<const uint4*>(p + cp_lane);
         if constexpr (CPB == 32) r1 = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
     };
-    uint4 ar0, ar1 = make_uint4(0, 0, 0, 0);
-    WStage w0, w1;
-    load_a(it_b, ar0, ar1);
-    load_w<G>(wb, sb, w_lane, s_lane, it_b, w0);
-    *reinterpret_cast<uint4*>(smem + cp_dst) = ar0;
-    if constexpr (CPB == 32) *reinterpret_cast<uint4*>(smem + cp_dst + 16) = ar1;
-    load_a(it_b + 1, ar0, ar1);
+    // Vector memory loads complete in order, so a wait for an activation load also waits for every weight
+    // load issued before it: with a deep weight window the activations need the same lead, or each
+    // stage would still wait for the weights of the stage before.  AQ register sets hold them on
+    // their way (stage s in set (s - it_b) % AQ); LEAD = stages between a load and its LDS store + 1.
+    constexpr int AQ = WD > 2 ? WD : 1, LEAD = WD > 2 ? WD : 2;
+    uint4 aq[AQ][2];
+#pragma unroll
+    for (int i = 0; i < AQ; ++i) aq[i][1] = make_uint4(0, 0, 0, 0);
+    WStage wq[WD];
+    load_a(it_b, aq[0][0], aq[0][1]);
+#pragma unroll
+    for (int i = 0; i < WD - 1; ++i) {
+        load_w<G>(wb, sb, w_lane, s_lane, min(it_b + i, n_it - 1), wq[i]);
+        if constexpr (WD > 2) load_a(min(it_b + i + 1, n_it - 1), aq[(i + 1) % AQ][0], aq[(i + 1) % AQ][1]);
+    }
+    if constexpr (WD > 2) __builtin_amdgcn_sched_barrier(0);
+    *reinterpret_cast<uint4*>(smem + cp_dst) = aq[0][0];     // (waits for the oldest load only)
+    if constexpr (CPB == 32) *reinterpret_cast<uint4*>(smem + cp_dst + 16) = aq[0][1];
+    if constexpr (WD == 2) load_a(it_b + 1, aq[0][0], aq[0][1]);
     __syncthreads();
 
     const int8_t* a_base = smem + (wm * WM + l16) * A_STRIDE + q * 16;
@@ -230,20 +256,21 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
     float pend_sw = 0.f;                                     // nothing pending yet: adds BIAS * 0
     int64_t pend_g = 0;
 
-    // One stage: wc holds this stage's weights, wnx receives the next stage's.
-    auto stage = [&](int64_t it, int buf, int buf_next, const WStage& wc, WStage& wnx) {
+    // One stage: wc holds this stage's weights, wnx (the set the stage before has just used up)
+    // receives those of stage it + WD - 1.
+    auto stage = [&](int64_t it, int buf, int buf_next, const WStage& wc, WStage& wnx, uint4 (&ast)[2], uint4 (&ald)[2]) {
         // No branch around the loads: past the end they re-read the last stage (and the last
         // LDS write lands in a buffer nobody reads any more).  With loads under a condition the
         // compiler cannot count how many are in flight and its waits for the previous stage's
         // registers also wait for the loads just issued, i.e. a full memory round trip per stage.
         {
             int8_t* dst = smem + buf_next * A_BUF + cp_dst;
-            *reinterpret_cast<uint4*>(dst) = ar0;            // activations of stage it+1
-            if constexpr (CPB == 32) *reinterpret_cast<uint4*>(dst + 16) = ar1;
+            *reinterpret_cast<uint4*>(dst) = ast[0];         // activations of stage it+1
+            if constexpr (CPB == 32) *reinterpret_cast<uint4*>(dst + 16) = ast[1];
             asm volatile("" : "+v"(w_lane), "+v"(s_lane));
-            load_w<G>(wb, sb, w_lane, s_lane, min(it + 1, n_it - 1), wnx);
+            load_w<G>(wb, sb, w_lane, s_lane, min(it + (WD - 1), n_it - 1), wnx);
         }
-        load_a(min(it + 2, n_it - 1), ar0, ar1);
+        load_a(min(it + LEAD, n_it - 1), ald[0], ald[1]);
         // keep the loads up here: the scheduler otherwise sinks them to their first use, one stage on
         __builtin_amdgcn_sched_barrier(0);
         const int8_t* ab = a_base + buf * A_BUF;
@@ -290,36 +317,42 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
         }
     };
 
-    int buf = 0;
-    for (int64_t it = it_b; it < n_it; it += 2) {
-        const int b1 = buf == 2 ? 0 : buf + 1;
-        const int b2 = b1 == 2 ? 0 : b1 + 1;
-        stage(it, buf, b1, w0, w1);
-        __syncthreads();
-        stage(it + 1, b1, b2, w1, w0);
-        buf = b2;
-        if ((it & 7) == 6) {
-            // take the accumulated bias term out every 8 stages, so that the running sums
-            // never carry more than 8 stages of it (keeps the rounding error near 2^-15 of
-            // the result, whatever K is)
+    // take the accumulated bias term out every 8 stages, so that the running sums never carry more
+    // than 8 stages of it (keeps the rounding error near 2^-15 of the result, whatever K is)
+    auto settle = [&]() {
 #pragma unroll
-            for (int j = 0; j < CJ; ++j) {
-                const float corr = ssum[j] * 0x1p-128f;     // BIAS * 2^-149 = 2^-128
-                ssum[j] = 0.f;
+        for (int j = 0; j < CJ; ++j) {
+            const float corr = ssum[j] * 0x1p-128f;         // BIAS * 2^-149 = 2^-128
+            ssum[j] = 0.f;
 #pragma unroll
-                for (int i = 0; i < RI; ++i)
+            for (int i = 0; i < RI; ++i)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) y[i][j][r] -= corr;
-            }
+                for (int r = 0; r < 4; ++r) y[i][j][r] -= corr;
         }
-        __syncthreads();
+    };
+    int buf = 0;
+    for (int64_t it = it_b; it < n_it; it += WD) {
+#pragma unroll
+        for (int i = 0; i < WD; i += 2) {
+            if constexpr (WD > 2) {
+                if (i > 0 && it + i >= n_it) break;          // (stages come in pairs; uniform over the workgroup)
+            }
+            const int b1 = buf == 2 ? 0 : buf + 1;
+            const int b2 = b1 == 2 ? 0 : b1 + 1;
+            stage(it + i, buf, b1, wq[i], wq[(i + WD - 1) % WD], aq[(i + 1) % AQ], aq[(i + LEAD) % AQ]);
+            __syncthreads();
+            stage(it + i + 1, b1, b2, wq[i + 1], wq[i], aq[(i + 2) % AQ], aq[(i + 1 + LEAD) % AQ]);
+            buf = b2;
+            if (((it + i) & 7) == 6) settle();
+            __syncthreads();
+        }
     }
     if constexpr (CJ > 1) dequant_col(CJ - 1, pend_sw, pend_g);   // the very last group's last column
     if constexpr (DBG) return;
     if constexpr (KW > 1) {
         // the groups' partial results (bias term taken out) meet in LDS, behind the epilogue's regions;
         // element e of a wave's 64 x 32 tile sits at [e][lane]: conflict-free both ways
-        float* pr = reinterpret_cast<float*>(smem_all + WAVES * BM * E_STRIDE) + (int64_t)wn * (RI * 4 * CJ * 64) + lane;
+        float* pr = reinterpret_cast<float*>(smem_all + exch_off(WAVES)) + (int64_t)wn * (RI * 4 * CJ * 64) + lane;
 #pragma unroll
         for (int i = 0; i < RI; ++i)
 #pragma unroll
@@ -348,21 +381,37 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
     // region; the barrier at the end of the last stage freed the activation buffers) and leaves
     // as 16-byte stores, eight lanes per 128-byte row piece.
     if (a.part) {
-        // split-K: this range's results, dequantised, go to the workspace as fp32
+        // split-K: this range's results, dequantised, go to the workspace as fp32 rows.  A lane holds single
+        // columns of four rows per tile (4-byte stores in 64-byte runs: measured, 5 us of a 29 us launch on
+        // 28672 x 8192 at M = 64); the wave's 64 x 32 tile goes through LDS (a region of its own, rows padded
+        // by 16 bytes: conflict-free both ways) and leaves as 16-byte stores in 128-byte runs.
         float* dst = a.part + (int64_t)blockIdx.y * a.M * a.N;
+        int8_t* pbase = smem_all + pstage_off(WAVES, KW) + wn * (BM * P_STRIDE);
+        const int prow = lane >> 3, pcol = (lane & 7) * 4;   // eight lanes per row piece
+        float sxr[BM / 8];
+#pragma unroll
+        for (int p = 0; p < BM / 8; ++p) {
+            const int64_t m = m0 + p * 8 + prow;
+            sxr[p] = a.sx[m < a.M ? m : a.M - 1];
+        }
 #pragma unroll
         for (int i = 0; i < RI; ++i)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int64_t m = m0 + i * 16 + 4 * q + r;
-                const float s = a.sx[m < a.M ? m : a.M - 1];
+            for (int r = 0; r < 4; ++r)
 #pragma unroll
-                for (int j = 0; j < CJ; ++j) {
-                    const int64_t n = n0 + wn * WN + j * 16 + l16;
-                    const float v = (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f;
-                    if (m < a.M && n < a.N) dst[m * a.N + n] = v * s;
-                }
-            }
+                for (int j = 0; j < CJ; ++j)
+                    *reinterpret_cast<float*>(pbase + (i * 16 + 4 * q + r) * P_STRIDE + (j * 16 + l16) * 4) =
+                        (y[i][j][r] - ssum[j] * 0x1p-128f) * 0x1p79f;
+        // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
+        const int64_t n = n0 + wn * WN + pcol;
+#pragma unroll
+        for (int p = 0; p < BM / 8; ++p) {
+            const int row = p * 8 + prow;
+            const int64_t m = m0 + row;
+            float4 v = *reinterpret_cast<const float4*>(pbase + row * P_STRIDE + pcol * 4);
+            v.x *= sxr[p]; v.y *= sxr[p]; v.z *= sxr[p]; v.w *= sxr[p];
+            if (m < a.M && n < a.N) *reinterpret_cast<float4*>(dst + m * a.N + n) = v;   // N % 8 == 0: all 4 or none
+        }
         return;
     }
     int8_t* ebase = smem_all + wn * (BM * E_STRIDE);
@@ -422,7 +471,7 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
 
 }  // namespace tiled
 
-template <int G, bool DBG, int BN, int KW = 1>
+template <int G, bool DBG, int BN, int KW = 1, int WD = 2>
 static int launch_tiled(const A8Args& a_in, int splits, hipStream_t stream)
 {
     using namespace tiled;
@@ -434,10 +483,11 @@ static int launch_tiled(const A8Args& a_in, int splits, hipStream_t stream)
     // three activation stages per group; the epilogue regions (and behind them the groups' partial results) reuse them
     const size_t act = (size_t)KW * 3 * A_BUF;
     const size_t epi = (size_t)WAVES * BM * E_STRIDE + (size_t)(KW - 1) * WAVES * BM * WN * sizeof(float);
-    const size_t lds = act > epi ? act : epi;
+    const size_t pst = a.part ? (size_t)pstage_off(WAVES, KW) + (size_t)WAVES * BM * P_STRIDE : 0;
+    const size_t lds = max(max(act, epi), pst);
     const int group_m = a.tune.tiled_group_m ? a.tune.tiled_group_m : 8;
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)splits), block(THREADS);
-    auto kern = a8_tiled_kernel<G, DBG, BN, KW>;
+    auto kern = a8_tiled_kernel<G, DBG, BN, KW, WD>;
     if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, "w2_matmul_a8[tiled]")) return rc;
     hipLaunchKernelGGL(kern, grid, block, lds, stream, a, tiles_m, tiles_n, group_m, splits);
     int rc = check_launch("w2_matmul_a8[tiled]");
@@ -454,39 +504,89 @@ static int tiled_bn(int64_t M, int64_t N, const w2_tuning_t& tune)
     return bn;
 }
 
-static int tiled_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap, const w2_tuning_t& tune)
+// How a problem's K is cut: `splits` ranges across workgroups (partial results in the workspace, summed
+// by a second launch) times `kw` ranges inside a workgroup (128-column workgroups only).
+struct TiledPlan { int bn, splits, kw; };
+
+static TiledPlan tiled_plan(int64_t M, int64_t N, int64_t n_kt, int64_t cap, const w2_tuning_t& tune)
 {
-    const int bn = tiled_bn(M, N, tune);
-    const int forced = tune.splitk;                          // tuning and tests: 1 = never, n = n parts if they fit
-    if (forced > 0) return (int)min((int64_t)forced, min(cap, n_kt));
-    // four 128-column workgroups fit a CU, two 256-column ones: count in units of half a CU's worth
-    const int64_t wgs = ((M + tiled::BM - 1) / tiled::BM) * ((N + bn - 1) / bn);
-    return splitk_plan(bn == 128 ? (wgs + 1) / 2 : wgs, n_kt, tune.splitk_min_tiles ? tune.splitk_min_tiles : 12, M, N, cap);
+    TiledPlan p;
+    p.bn = tiled_bn(M, N, tune);
+    const int64_t tiles_m = (M + tiled::BM - 1) / tiled::BM;
+    const int64_t wgs_n = tiles_m * ((N + p.bn - 1) / p.bn);
+    const int forced_s = tune.splitk;                        // tuning and tests: 1 = never, n = n parts if they fit
+    const int forced_kw = p.bn == 128 ? tune.tiled_kw : 1;
+    if (p.bn == 256 || tiles_m > 2) {
+        // many output tiles: split only to fill the chip (splitk_plan), K ranges inside a workgroup while
+        // the workgroups are few
+        if (forced_s > 0) p.splits = (int)min((int64_t)forced_s, min(max(cap, (int64_t)1), n_kt));
+        else p.splits = splitk_plan(p.bn == 128 ? (wgs_n + 1) / 2 : wgs_n, n_kt,
+                                    tune.splitk_min_tiles ? tune.splitk_min_tiles : 12, M, N, cap);
+        const int64_t wgs = wgs_n * p.splits;
+        p.kw = p.bn == 256 ? 1 : forced_kw ? forced_kw : wgs <= 256 ? 4 : wgs <= 512 ? 2 : 1;
+        while (p.kw > 1 && n_kt % (p.kw * p.splits) != 0) p.kw >>= 1;
+        return p;
+    }
+    // One or two row tiles of 128-column workgroups: a few dozen workgroups against 256 CUs, so K is cut
+    // both ways.  Every (splits, kw) that divides the tiles evenly is priced with a model fitted to
+    // sweeps over 28672 x 8192, 14336 x 4096, 17408 x 5120, 4096 x 28672 and 8192 x 8192 at M = 32..128:
+    //   loop  = matrix work at 1600 TOP/s, divided by the share of the CUs that get a workgroup (an
+    //           under-filled chip runs at 0.85 of that share: the busy CUs queue more stages) and by 0.55
+    //           with one wave per SIMD (4 waves per CU), 1 from two per SIMD on (measured: 8 and 16 waves
+    //           per CU run a stage in the same time);
+    //   parts = 6 us for the second launch and both kernels' ends + the partial results written and read once at 3 TB/s;
+    //           workgroups beyond what the chip holds at once (one 16-wave workgroup per CU, two of 8
+    //           waves, four of 4) run in rounds.
+    const double work_us = 2.0 * (double)(tiles_m * tiled::BM) * (double)N * (double)(n_kt * TILE_K) / 1600e6;
+    const int64_t room = max(cap, (int64_t)1);
+    int64_t s_lo = 1, s_hi = min(min((int64_t)16, room), max((int64_t)1, ((int64_t)16 << 20) / (M * N * (int64_t)sizeof(float))));
+    if (forced_s > 0) s_lo = s_hi = min((int64_t)forced_s, min(room, n_kt));
+    double best = 1e30;
+    p.splits = (int)s_lo;
+    p.kw = 1;
+    for (int kw = 4; kw >= 1; kw >>= 1) {
+        if (forced_kw && kw > forced_kw) continue;           // (a forced kw that does not divide the tiles falls back to the next smaller)
+        for (int64_t sp = s_lo; sp <= s_hi && sp <= n_kt; ++sp) {
+            if (kw > 1 && n_kt % (kw * sp) != 0) continue;
+            if (forced_s <= 0 && sp > 1 && n_kt / (sp * kw) < 2) continue;
+            const double wgs = (double)(wgs_n * sp);
+            const double slots = 256.0 * (kw == 4 ? 1 : kw == 2 ? 2 : 4);
+            const double rounds = wgs <= slots ? 1.0 : (double)((int64_t)((wgs + slots - 1) / slots));
+            const double fill = wgs < 256.0 ? 0.85 * wgs / 256.0 : rounds == 1.0 ? 1.0 : wgs / (rounds * slots);
+            const double waves_per_cu = rounds > 1.0 ? 16.0 : wgs * 4.0 * kw / (wgs < 256.0 ? wgs : 256.0);
+            const double rate = waves_per_cu >= 8.0 ? 1.0 : 0.55 + 0.45 * (waves_per_cu - 4.0) / 4.0;
+            const double parts = sp > 1 ? 6.0 + 2.0 * (double)sp * (double)M * (double)N * 4.0 / 3e6 : 0.0;
+            const double t = work_us / (fill * rate) + parts;
+            if (t < best) { best = t; p.splits = (int)sp; p.kw = kw; }
+        }
+        if (forced_kw && best < 1e30) break;
+    }
+    return p;
 }
 
 size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune)
 {
-    const int s = tiled_splits(M, N, n_kt, 16, tune);
+    const int s = tiled_plan(M, N, n_kt, 16, tune).splits;
     return s < 2 ? 0 : (size_t)s * M * N * sizeof(float);
 }
 
 template <int G, bool DBG>
 static int launch_tiled_bn(const A8Args& a, hipStream_t stream)
 {
-    const int bn = tiled_bn(a.M, a.N, a.tune);
     const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
-    const int splits = DBG ? 1 : tiled_splits(a.M, a.N, a.n_kt, cap, a.tune);
-    if (bn == 128 && !DBG) {
-        // K split inside the workgroup, only where every group gets the same number of 256-k tiles: four
-        // groups (16 waves, one workgroup per CU) while the workgroups fit the chip in one round, two (two
-        // workgroups per CU) up to two per CU.  Measured at M = 64: 4096 x 28672 16.1 us against 19.6 unsplit
-        // (and 20.4 through the mid-M kernel), 5120 x 34816 (272 workgroups) 27.4 with two groups, 33.3 with four.
-        const int64_t wgs = (a.M + tiled::BM - 1) / tiled::BM * ((a.N + 127) / 128) * (splits < 2 ? 1 : splits);
-        const int kw = a.tune.tiled_kw ? a.tune.tiled_kw : wgs <= 256 ? 4 : wgs <= 512 ? 2 : 1;
-        if (kw == 4 && a.n_kt % (4 * (splits < 2 ? 1 : splits)) == 0) return launch_tiled<G, DBG, 128, 4>(a, splits, stream);
-        if (kw >= 2 && a.n_kt % (2 * (splits < 2 ? 1 : splits)) == 0) return launch_tiled<G, DBG, 128, 2>(a, splits, stream);
+    TiledPlan p = tiled_plan(a.M, a.N, a.n_kt, cap, a.tune);
+    if (DBG) { p.splits = 1; p.kw = 1; }
+    const int splits = p.splits;
+    if constexpr (!DBG) {
+        if (a.tune.tiled_wd == 8) {
+            if (p.bn == 256) return launch_tiled<G, DBG, 256, 1, 8>(a, splits, stream);
+            if (p.kw >= 2) return launch_tiled<G, DBG, 128, 2, 8>(a, splits, stream);
+            return launch_tiled<G, DBG, 128, 1, 8>(a, splits, stream);
+        }
+        if (p.bn == 128 && p.kw == 4) return launch_tiled<G, DBG, 128, 4>(a, splits, stream);
+        if (p.bn == 128 && p.kw == 2) return launch_tiled<G, DBG, 128, 2>(a, splits, stream);
     }
-    return bn == 128 ? launch_tiled<G, DBG, 128>(a, splits, stream) : launch_tiled<G, DBG, 256>(a, splits, stream);
+    return p.bn == 128 ? launch_tiled<G, DBG, 128>(a, splits, stream) : launch_tiled<G, DBG, 256>(a, splits, stream);
 }
 
 int launch_a8_tiled(const A8Args& a, hipStream_t stream)
@@ -494,10 +594,8 @@ int launch_a8_tiled(const A8Args& a, hipStream_t stream)
     // 128-row tiles (half the up-convert work per matrix instruction) where the problem has the rows for
     // them and K is not split across workgroups
     {
-        const int bn = tiled_bn(a.M, a.N, a.tune);
         const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
-        const int splits = a.acc_out ? 1 : tiled_splits(a.M, a.N, a.n_kt, cap, a.tune);
-        (void)bn;
+        const int splits = a.acc_out ? 1 : tiled_plan(a.M, a.N, a.n_kt, cap, a.tune).splits;
         // 128-row tiles run one workgroup per CU, so a last round of workgroups that fills less than half the
         // chip costs a whole round (64-row workgroups share a CU in pairs and speed up when alone); with 224
         // tiles and more and a last round at least half full they win from M = 128 on (8192 x 57344 at M = 128:

@@ -271,6 +271,48 @@ def test_a8_tiled_k_split_inside_workgroup(w2, M, K, N, G, kw):
         check_y(bf16_bits(Y), Yo, y64, mag, f"a8 tiled kw={kw} split-K 2 M={M} K={K} N={N} G={G}")
 
 
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("M,K,N", [(40, 14336, 272), (100, 7168, 1032), (64, 4352, 48), (128, 3072, 528), (33, 2048, 2064)])
+def test_a8_tiled_planned_k_split(w2, M, K, N, G):
+    # one or two row tiles with a workspace for 16 parts: the library's own choice of K ranges across and
+    # inside workgroups (tile counts with many divisors, a prime one, few and many column tiles); a second
+    # call with room for fewer parts must still be correct (another plan), and so must one without a workspace
+    codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + N + G)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    oq, osx, _ = oracle.quantize_rows(X, G)
+    Yo, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+    for parts in (16, 3, 0):
+        ws = torch.empty(parts * M * N * 4, dtype=torch.uint8, device="cuda") if parts else None
+        Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED, workspace=ws, tune={"tiled_bm": 64})
+        Y2 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED, workspace=ws, tune={"tiled_bm": 64})
+        assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "not deterministic"
+        check_y(bf16_bits(Y), Yo, y64, mag, f"a8 tiled planned split, room for {parts} parts, M={M} K={K} N={N} G={G}")
+
+
+@pytest.mark.parametrize("bn,kw", [(128, 1), (128, 2), (256, 1)])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (2560, 1032), (4608, 48)])
+@pytest.mark.parametrize("M", [1, 33, 64, 100])
+def test_a8_tiled_deep_weight_window(w2, M, K, N, G, bn, kw):
+    # 64-row tiles with eight weight stages (and as many activation register sets) in flight per wave: fewer
+    # stages than the window (K = 256), exactly one window (1024), a last window cut short (2560: 20 stages,
+    # 4608: 36), with the K split across workgroups on top
+    tune = {"tiled_bm": 64, "tiled_bn": bn, "tiled_kw": kw, "tiled_wd": 8}
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G + kw, tune=tune)
+    if K >= 2048:
+        codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + N)
+        packed = w2.prepack(dev(codes), dev(scales), G, 0)
+        xq, sx, _ = w2.quantize_rows(dev(X), G)
+        ws = torch.empty(4 * M * N * 4, dtype=torch.uint8, device="cuda")
+        Y = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_TILED, workspace=ws, tune=dict(tune, splitk=3))
+        oq, osx, _ = oracle.quantize_rows(X, G)
+        Yo, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+        mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+        check_y(bf16_bits(Y), Yo, y64, mag, f"a8 tiled wd=8 bn={bn} kw={kw} split-K 3 M={M} K={K} N={N} G={G}")
+
+
 @pytest.mark.parametrize("bn", [128, 256])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (512, 1032), (4608, 48)])
 @pytest.mark.parametrize("M", [1, 17, 127, 128, 129, 300])
