@@ -172,7 +172,7 @@ W2_API int w2_quantize_rows(const void* X, w2_dtype_t x_dtype, int64_t M, int64_
  * Y       dev, bf16 bit patterns [M][N], row stride ldy
  * workspace  optional (NULL / 0: none), dev, 16-byte aligned, contents
  *            undefined before and after: on shapes with few output tiles
- *            and a deep K (M > 64: the tiled kernel; 4 <= M <= 128 and
+ *            and a deep K (M > 32: the tiled kernel; 4 <= M <= 128 and
  *            K >= 13568: the mid-M kernel) K is split across workgroups
  *            (Sec. II-D, K-splitting for the smaller GEMM shapes) if there
  *            is room for the fp32 partial results (w2_workspace_size; less

@@ -319,19 +319,35 @@ a16_fold_tiled_kernel(A16Args a, int tiles_m, int tiles_n, int group_m, int spli
     }
 
     if (a.part) {
-        // split-K: this range's fp32 partial results go to the workspace as they sit in the registers
+        // split-K: this range's fp32 partial results go to the workspace.  A lane holds single columns of
+        // four rows per tile (4-byte stores in 64-byte runs: measured on the w2a8 kernel, 5 us of a 29 us
+        // launch); the wave's tile goes through LDS, 64 rows at a time (a region of its own: the barrier at
+        // the end of the last stage freed the activation buffers; rows padded by 16 bytes, conflict-free both
+        // ways), and leaves as 16-byte stores in 128-byte runs.
+        constexpr int P_STRIDE = WN * 4 + 16;
+        static_assert(WAVES * 64 * P_STRIDE <= lds_bytes(BN, BM), "partial-result staging fits the activation buffers");
         float* dst = a.part + (int64_t)blockIdx.y * a.M * a.N;
+        int8_t* pbase = smem + wn * (64 * P_STRIDE);
+        const int prow = lane >> 3, pcol = (lane & 7) * 4;   // eight lanes per row piece
+        const int64_t n = n0 + wn * WN + pcol;
 #pragma unroll
-        for (int i = 0; i < RI; ++i)
+        for (int h = 0; h < RI / 4; ++h) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int64_t m = m0 + i * 16 + 4 * q + r;
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < CJ; ++j) {
-                    const int64_t n = n0 + wn * WN + j * 16 + l16;
-                    if (m < a.M && n < a.N) dst[m * a.N + n] = acc[i][j][r];
-                }
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int j = 0; j < CJ; ++j)
+                        *reinterpret_cast<float*>(pbase + (i * 16 + 4 * q + r) * P_STRIDE + (j * 16 + l16) * 4) = acc[h * 4 + i][j][r];
+            // the wave reads back only what it wrote itself: LDS operations of one wave complete in order
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int row = p * 8 + prow;
+                const int64_t m = m0 + h * 64 + row;
+                const float4 v = *reinterpret_cast<const float4*>(pbase + row * P_STRIDE + pcol * 4);
+                if (m < a.M && n < a.N) *reinterpret_cast<float4*>(dst + m * a.N + n) = v;   // N % 8 == 0: all 4 or none
             }
+        }
         return;
     }
 
