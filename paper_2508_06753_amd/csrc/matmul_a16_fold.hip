@@ -440,7 +440,11 @@ static int fold_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap, const w2
     if (forced > 0) return (int)min((int64_t)forced, min(cap, n_kt));
     // two 128-column workgroups fit a CU, one 256-column one: count in CUs' worth
     const int64_t wgs = ((M + 127) / 128) * ((N + bn - 1) / bn);
-    return splitk_plan(bn == 128 ? (wgs + 1) / 2 : wgs, n_kt, tune.splitk_min_tiles ? tune.splitk_min_tiles : 4, M, N, cap);
+    // deep K (56 tiles and more): up to 32 MiB of partial results (28672 x 8192 at M = 128: 8 parts 74 us,
+    // 4 parts 81; M = 256: 4 parts 128, 2 parts 144); on shallow K more parts lose (4096 x 28672 at M = 65:
+    // 2 parts 40 us, 4 parts 46)
+    return splitk_plan(bn == 128 ? (wgs + 1) / 2 : wgs, n_kt, tune.splitk_min_tiles ? tune.splitk_min_tiles : 4, M, N, cap,
+                       (int64_t)(n_kt >= 56 ? 32 : 16) << 20);
 }
 
 size_t a16_fold_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune)

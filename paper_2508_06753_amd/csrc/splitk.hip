@@ -10,16 +10,17 @@
 
 namespace w2 {
 
-int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t N, int64_t cap)
+int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t N, int64_t cap, int64_t max_bytes)
 {
     // enough parts for about 1.5 workgroups per CU; a part spans at least min_tiles 256-k tiles (below
     // that the partial results and the second launch cost more than the idle CUs); at most 16 parts
-    // and at most 16 MiB of partial results (the second launch reads them all)
+    // and at most max_bytes (16 MiB unless the caller says otherwise) of partial results (the second launch
+    // reads them all)
     if (wgs >= 192 || cap < 2) return 1;
     int64_t s = (384 + wgs - 1) / wgs;
     s = min(s, n_kt / min_tiles);
     s = min(s, (int64_t)16);
-    s = min(s, ((int64_t)16 << 20) / (M * N * (int64_t)sizeof(float)));
+    s = min(s, max_bytes / (M * N * (int64_t)sizeof(float)));
     s = min(s, cap);
     return s < 2 ? 1 : (int)s;
 }

@@ -94,7 +94,8 @@ int launch_a16_midm(const A16Args& a, hipStream_t stream);
 // K-splitting for smaller GEMM shapes).  splitk_plan: number of K ranges for `wgs` output tiles of a
 // kernel whose K loop has `n_kt` 256-k tiles (a part spans at least `min_tiles` of them), given room
 // for `cap` fp32 copies of the M x N output.
-int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t N, int64_t cap);
+int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t N, int64_t cap,
+                int64_t max_bytes = (int64_t)16 << 20);
 // Bytes of workspace with which the tiled kernels would split K for this problem (0: they would not).
 size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune);
 size_t a8_midm_splitk_bytes(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, const w2_tuning_t& tune);
