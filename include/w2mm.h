@@ -104,7 +104,7 @@ typedef struct {
     int small_cbw;        /* ... column blocks per workgroup: 1, 2, 4, 8 or 16, at most the waves */
     int small_kc;         /* ... k per local-memory chunk of the activations: a multiple of 256 */
     int gemv_window;      /* GEMV: weight tiles a wave keeps in flight: 2, 4 or 8 */
-    int gemv_max_m;       /* w2a8 AUTO: largest M given to GEMV (1..16) */
+    int gemv_max_m;       /* w2a8 AUTO: largest M given to GEMV (1..32) */
     int midm_cbw;         /* MIDM: column blocks per workgroup: 2, 4 or 8 */
     int tiled_bm;         /* w2a8 TILED: rows per workgroup: 64 or 128 (128: G = 128, K not split) */
     int tiled_bn;         /* TILED / SCALED16 tiled kernels: columns per workgroup: 128 or 256 */

@@ -155,7 +155,7 @@ static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
     else if (!one_of(t->small_cbw, 1, 2, 4, 8, 16)) bad = "small_cbw";
     else if (t->small_kc < 0 || t->small_kc % TILE_K) bad = "small_kc";
     else if (!one_of(t->gemv_window, 2, 4, 8)) bad = "gemv_window";
-    else if (!in(t->gemv_max_m, 1, 16)) bad = "gemv_max_m";
+    else if (!in(t->gemv_max_m, 1, 32)) bad = "gemv_max_m";
     else if (!one_of(t->midm_cbw, 2, 4, 8)) bad = "midm_cbw";
     else if (!one_of(t->tiled_bm, 64, 128)) bad = "tiled_bm";
     else if (!one_of(t->tiled_bn, 128, 256)) bad = "tiled_bn";
@@ -302,7 +302,12 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
                            : !one_round                                  ? 4
                            : M <= 8                                      ? 8
                            : M <= 12 && (row_bytes <= 64 * 1024 || a.n_cb <= 512) ? 12
-                           : row_bytes <= 68 * 1024 || a.n_cb <= 512     ? 16
+                           : M <= 16 ? (row_bytes <= 68 * 1024 || a.n_cb <= 512 ? 16 : 8)
+                           // 17 to 32 rows (two row tiles per wave, one workgroup per CU): K up to 4096 in a grid of
+                           // one round (4096 x 4096 at M = 17..32: 5.9 against 6.9 to 7.3 us through the mid-M
+                           // kernel; 4096 x 6144 6.8 against 7.2; 4096 x 28672 12.5 to 13.9 against 13.0 to 14.3;
+                           // K = 5120 gains nothing, 4096 x 57344, two rounds, loses 10 %)
+                           : M <= 32 && a.n_kt <= 16 && row_bytes <= 133 * 1024 ? 32
                                                                          : 8;
         variant = M <= dot4_max && a8_dot4_supports(a)     ? W2_VARIANT_DOT4
                 : M <= gemv_max && a8_gemv_supports(M)     ? W2_VARIANT_GEMV
@@ -311,7 +316,7 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
     hipStream_t s = (hipStream_t)stream;
     switch (variant) {
     case W2_VARIANT_GEMV: {
-        if (!a8_gemv_supports(M)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: GEMV needs M <= 16", fn);
+        if (!a8_gemv_supports(M)) return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: GEMV needs M <= 32", fn);
         rc = launch_a8_gemv(a, xq, 0, K, s);
         // rows too long for one workgroup's local memory: the kernels that stage them in chunks
         if (rc != W2_ERR_UNSUPPORTED_SHAPE || tn.variant == W2_VARIANT_GEMV) return rc;

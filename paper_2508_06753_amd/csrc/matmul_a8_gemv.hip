@@ -108,8 +108,9 @@ __device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, ui
 }
 
 // RL: rows staged (M <= RL).  Up to four rows sit in accumulator rows 0..3, which the lanes of the first
-// quarter of a wave hold (one, two or four values each); the wide form (RL = 8 or 16, int8 rows only) uses
-// every accumulator row: lane (q, l) holds rows 4q..4q+3 of column l.
+// quarter of a wave hold (one, two or four values each); the wide form (RL = 8, 16 or 32, int8 rows only)
+// uses every accumulator row: lane (q, l) holds rows 4q..4q+3 of column l, for one row tile or, at RL = 32,
+// two (the up-converted operand then feeds two matrix instructions).
 // NP: 16-byte pieces per row and thread (a launch-time choice: the row's pieces / the workgroup's threads, rounded up)
 template <int G, int RL, int XT, int W, int NP, bool DBG>
 __global__ void __launch_bounds__(64 * max_waves(RL))
@@ -117,6 +118,7 @@ a8_gemv_kernel(Args a)
 {
     constexpr bool WIDE = RL > 4;
     constexpr int RA = WIDE ? 4 : RL;                        // accumulator rows a lane folds into y
+    constexpr int RT = RL > 16 ? RL / 16 : 1;                // 16-row tiles
     static_assert(!WIDE || XT == 0, "the wide form takes int8 rows");
     extern __shared__ __align__(16) int8_t smem[];
     constexpr int GPT = TILE_K / G;
@@ -275,34 +277,47 @@ a8_gemv_kernel(Args a)
     W2_GEMV_MARK(2);
 
     // ---- 4. the stream: up-convert and compute
-    float y[RA];
+    float y[RT][RA];
 #pragma unroll
-    for (int r = 0; r < RA; ++r) y[r] = 0.f;
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int r = 0; r < RA; ++r) y[rt][r] = 0.f;
     // Two accumulators alternate between groups; a finished group is dequantised after the next
     // group's first matrix instruction has been issued, so its int -> float conversion does not wait
     // for the matrix pipe.
-    v4i acc[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    v4i acc[2][RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) acc[0][rt] = acc[1][rt] = v4i{0, 0, 0, 0};
     float pend_sw = 0.f;                                     // scale of the group waiting in acc[1]: none yet
     int pend_g = -1;                                         // its index (debug export)
     auto dequant = [&](int b) {
 #pragma unroll
-        for (int r = 0; r < RA; ++r) {
-            if constexpr (DBG) {
-                const int64_t n = (int64_t)cb * TILE_N + l16;
-                const int row = WIDE ? 4 * q + r : r;
-                if (pend_g >= 0 && (WIDE || q == 0) && cb_ok && n < a.N && row < a.M)
-                    a.acc_out[((int64_t)row * (a.K / G) + pend_g) * a.N + n] = acc[b][r] >> 6;
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int r = 0; r < RA; ++r) {
+                if constexpr (DBG) {
+                    const int64_t n = (int64_t)cb * TILE_N + l16;
+                    const int row = WIDE ? rt * 16 + 4 * q + r : r;
+                    if (pend_g >= 0 && (WIDE || q == 0) && cb_ok && n < a.N && row < a.M)
+                        a.acc_out[((int64_t)row * (a.K / G) + pend_g) * a.N + n] = acc[b][rt][r] >> 6;
+                }
+                y[rt][r] = fmaf(pend_sw, (float)acc[b][rt][r], y[rt][r]);
             }
-            y[r] = fmaf(pend_sw, (float)acc[b][r], y[r]);
-        }
     };
     // LDS address of this lane's A operand: row (lane & 15, padded rows repeat the last), 16-byte piece lane >> 4
-    const int arow = l16 < a.M ? l16 : a.M - 1;
-    const uint32_t a_lane = (uint32_t)(HDR + arow * row_stride + q * 16);
-    auto read_aop = [&](int kt, v4i (&aop)[4]) {
-        const int8_t* p = smem + a_lane + (uint32_t)kt * TILE_K;
+    uint32_t a_lane[RT];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) aop[t] = *reinterpret_cast<const v4i*>(p + t * 64);
+    for (int rt = 0; rt < RT; ++rt) {
+        const int arow = rt * 16 + l16 < a.M ? rt * 16 + l16 : a.M - 1;
+        a_lane[rt] = (uint32_t)(HDR + arow * row_stride + q * 16);
+    }
+    auto read_aop = [&](int kt, v4i (&aop)[RT][4]) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const int8_t* p = smem + a_lane[rt] + (uint32_t)kt * TILE_K;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) aop[rt][t] = *reinterpret_cast<const v4i*>(p + t * 64);
+        }
     };
     const int8_t* sc_lane = sc_lds + l16 * (GPT * 2);
     auto read_scales = [&](int i, uint32_t (&sc)[2]) {       // tile i of the run
@@ -314,7 +329,7 @@ a8_gemv_kernel(Args a)
             sc[0] = t.x; sc[1] = t.y;
         }
     };
-    auto compute = [&](int kt, const u32x4& cur, const uint32_t (&sc)[2], const v4i (&aop)[4]) {
+    auto compute = [&](int kt, const u32x4& cur, const uint32_t (&sc)[2], const v4i (&aop)[RT][4]) {
         const uint32_t wd[4] = {cur[0], cur[1], cur[2], cur[3]};
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -325,7 +340,9 @@ a8_gemv_kernel(Args a)
             const int b = gi & 1;                            // its accumulator (groups per tile are even)
             const bool first = G == 64 || !(t & 1);
             const v4i zero = {0, 0, 0, 0};
-            acc[b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[t], bop, first ? zero : acc[b], 0, 0, 0);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+                acc[b][rt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[rt][t], bop, first ? zero : acc[b][rt], 0, 0, 0);
             if (first) dequant(b ^ 1);                       // the group before this one
             if (G == 64 || (t & 1)) {
                 const uint32_t pair = (G == 128 || gi < 2) ? sc[0] : sc[1];
@@ -334,7 +351,7 @@ a8_gemv_kernel(Args a)
             }
         }
     };
-    v4i aop[2][4];
+    v4i aop[2][RT][4];
     uint32_t scl[2][2];
     read_aop(kt_b, aop[0]);
     read_scales(0, scl[0]);
@@ -362,7 +379,9 @@ a8_gemv_kernel(Args a)
     float* red = reinterpret_cast<float*>(smem + a.red_off);   // [waves][RL][16]; its own region: no barrier before the writes
     if (WIDE ? 4 * q < RL : q == 0) {
 #pragma unroll
-        for (int r = 0; r < RA; ++r) red[(wave * RL + (WIDE ? 4 * q : 0) + r) * 16 + l16] = y[r];
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int r = 0; r < RA; ++r) red[(wave * RL + rt * 16 + (WIDE ? 4 * q : 0) + r) * 16 + l16] = y[rt][r];
     }
     __syncthreads();
     W2_GEMV_MARK(5);
@@ -551,8 +570,8 @@ static int launch_np(const Args& a, const Cfg& c, size_t lds, int np, hipStream_
 
 }  // namespace gemv
 
-// int8 rows: up to 16 (the wide form from five rows on); rows quantised in the kernel: up to four
-bool a8_gemv_supports(int64_t M) { return M >= 1 && M <= 16; }
+// int8 rows: up to 32 (the wide form from five rows on); rows quantised in the kernel: up to four
+bool a8_gemv_supports(int64_t M) { return M >= 1 && M <= 32; }
 
 // xt: 0 = int8 rows (X = xq, sx given), 1 = fp32 rows, 2 = bf16 rows.  Returns W2_ERR_UNSUPPORTED_SHAPE
 // (with a message, nothing launched) when the rows do not fit a workgroup.
@@ -561,10 +580,10 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
     using namespace gemv;
     const int64_t M = a8.M, K = a8.K;
     if (!a8_gemv_supports(M) || (xt != 0 && M > 4)) {
-        set_error("w2_matmul_a8[gemv]: M must be 1..16 (1..4 for rows quantised in the kernel)");
+        set_error("w2_matmul_a8[gemv]: M must be 1..32 (1..4 for rows quantised in the kernel)");
         return W2_ERR_UNSUPPORTED_SHAPE;
     }
-    const int rl = M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : M <= 8 ? 8 : 16;
+    const int rl = M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : M <= 8 ? 8 : M <= 16 ? 16 : 32;
     const int max_w = rl > 4 ? 8 : 16;                       // max_waves(rl)
     const int es = xt == 1 ? 4 : xt == 2 ? 2 : 1;
     const int64_t ppr = K * es / 16;                         // 16-byte pieces per row
@@ -624,13 +643,15 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
         if (rl == 2) W2_GEMV(128, 2);
         if (rl == 4) W2_GEMV(128, 4);
         if (rl == 8) W2_GEMV_WIDE(128, 8);
-        W2_GEMV_WIDE(128, 16);
+        if (rl == 16) W2_GEMV_WIDE(128, 16);
+        W2_GEMV_WIDE(128, 32);
     }
     if (rl == 1) W2_GEMV(64, 1);
     if (rl == 2) W2_GEMV(64, 2);
     if (rl == 4) W2_GEMV(64, 4);
     if (rl == 8) W2_GEMV_WIDE(64, 8);
-    W2_GEMV_WIDE(64, 16);
+    if (rl == 16) W2_GEMV_WIDE(64, 16);
+    W2_GEMV_WIDE(64, 32);
 #undef W2_GEMV_WIDE
 #undef W2_GEMV
 }
