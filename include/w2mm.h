@@ -67,10 +67,14 @@ typedef enum {
 } w2_status_t;
 
 /* Kernel families, for w2_matmul_a8_ex / w2_matmul_a16_ex and the debug export.
- * AUTO picks by M (w2a8: SMALLM for M <= 8 (M <= 3 when N >= 6144 or K > 16384), MIDM up to
- * M = 64 (M = 128 when N <= 8192, M = 48 when N >= 32768), else TILED;
+ * AUTO picks by shape.  w2a8: GEMV up to M = 8 wherever the rows fit a workgroup's local memory (up to 16
+ * while two workgroups share a CU or the projection is narrow, up to 32 for K <= 4096), MIDM above it up to
+ * M = 64 (128 when N <= 4096; 32 when N >= 24576 or, with a workspace, K >= 14336), else TILED (64-row
+ * tiles; 128-row tiles from M = 1024, or from M = 128 where they fill the chip).
  * w2a16: SMALLM for M <= 8, MIDM up to M = 64 (M = 128 when N <= 4096, M = 40 when N >= 32768), else the
- * SCALED16 tiled kernel).
+ * SCALED16 tiled kernel.
+ * GEMV (w2a8): the decode kernel: whole rows in local memory, a wave streams a contiguous run of a column
+ * block's tiles through a rolling register window into int8 MFMA (M <= 32).
  * DOT4: per-lane v_dot4_i32_i8
  * with split-K across the waves of a workgroup (M <= 4; kept as the dot-product form of the microkernel,
  * selectable here).  SMALLM: one 16-row int8 (bf16 for a16) MFMA tile per
