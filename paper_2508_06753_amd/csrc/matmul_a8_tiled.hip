@@ -516,27 +516,24 @@ static TiledPlan tiled_plan(int64_t M, int64_t N, int64_t n_kt, int64_t cap, con
     const int64_t wgs_n = tiles_m * ((N + p.bn - 1) / p.bn);
     const int forced_s = tune.splitk;                        // tuning and tests: 1 = never, n = n parts if they fit
     const int forced_kw = p.bn == 128 ? tune.tiled_kw : 1;
-    if (p.bn == 256 || tiles_m > 2) {
-        // many output tiles: split only to fill the chip (splitk_plan), K ranges inside a workgroup while
-        // the workgroups are few
+    if (p.bn == 256) {
+        // many output tiles: split only to fill the chip (splitk_plan)
         if (forced_s > 0) p.splits = (int)min((int64_t)forced_s, min(max(cap, (int64_t)1), n_kt));
-        else p.splits = splitk_plan(p.bn == 128 ? (wgs_n + 1) / 2 : wgs_n, n_kt,
-                                    tune.splitk_min_tiles ? tune.splitk_min_tiles : 12, M, N, cap);
-        const int64_t wgs = wgs_n * p.splits;
-        p.kw = p.bn == 256 ? 1 : forced_kw ? forced_kw : wgs <= 256 ? 4 : wgs <= 512 ? 2 : 1;
-        while (p.kw > 1 && n_kt % (p.kw * p.splits) != 0) p.kw >>= 1;
+        else p.splits = splitk_plan(wgs_n, n_kt, tune.splitk_min_tiles ? tune.splitk_min_tiles : 12, M, N, cap);
+        p.kw = 1;
         return p;
     }
-    // One or two row tiles of 128-column workgroups: a few dozen workgroups against 256 CUs, so K is cut
-    // both ways.  Every (splits, kw) that divides the tiles evenly is priced with a model fitted to
-    // sweeps over 28672 x 8192, 14336 x 4096, 17408 x 5120, 4096 x 28672 and 8192 x 8192 at M = 32..128:
-    //   loop  = matrix work at 1600 TOP/s, divided by the share of the CUs that get a workgroup (an
-    //           under-filled chip runs at 0.85 of that share: the busy CUs queue more stages) and by 0.55
-    //           with one wave per SIMD (4 waves per CU), 1 from two per SIMD on (measured: 8 and 16 waves
-    //           per CU run a stage in the same time);
-    //   parts = 6 us for the second launch and both kernels' ends + the partial results written and read once at 3 TB/s;
-    //           workgroups beyond what the chip holds at once (one 16-wave workgroup per CU, two of 8
-    //           waves, four of 4) run in rounds.
+    // 128-column workgroups (fewer than 400 tiles of 64 x 256): from a few dozen to a few hundred workgroups
+    // against 256 CUs, so K is cut both ways.  Every (splits, kw) that divides the tiles evenly is priced with
+    // a model fitted to sweeps over 28672 x 8192, 14336 x 4096, 17408 x 5120, 4096 x 28672, 8192 x 8192,
+    // 4096 x 4096 and 4096 x 6144 at M = 32..512:
+    //   loop  = the work of the busiest CU at 1600 TOP/s: it gets ceil(workgroups / 256) workgroups (a CU holds
+    //           one of 16 waves, two of 8, four of 4 at a time; more run in rounds, +10 %); with one wave per
+    //           SIMD (4 waves on the CU) it runs at 0.55 of that rate, from two per SIMD on at the full rate
+    //           (measured: 8 and 16 waves per CU run a stage in the same time); fewer workgroups than CUs
+    //           cost another 15 % (the busy CUs queue more stages each);
+    //   parts = 6 us for the second launch and both kernels' ends + the partial results written and read once
+    //           at 3 TB/s.
     const double work_us = 2.0 * (double)(tiles_m * tiled::BM) * (double)N * (double)(n_kt * TILE_K) / 1600e6;
     const int64_t room = max(cap, (int64_t)1);
     int64_t s_lo = 1, s_hi = min(min((int64_t)16, room), max((int64_t)1, ((int64_t)16 << 20) / (M * N * (int64_t)sizeof(float))));
@@ -549,14 +546,16 @@ static TiledPlan tiled_plan(int64_t M, int64_t N, int64_t n_kt, int64_t cap, con
         for (int64_t sp = s_lo; sp <= s_hi && sp <= n_kt; ++sp) {
             if (kw > 1 && n_kt % (kw * sp) != 0) continue;
             if (forced_s <= 0 && sp > 1 && n_kt / (sp * kw) < 2) continue;
-            const double wgs = (double)(wgs_n * sp);
-            const double slots = 256.0 * (kw == 4 ? 1 : kw == 2 ? 2 : 4);
-            const double rounds = wgs <= slots ? 1.0 : (double)((int64_t)((wgs + slots - 1) / slots));
-            const double fill = wgs < 256.0 ? 0.85 * wgs / 256.0 : rounds == 1.0 ? 1.0 : wgs / (rounds * slots);
-            const double waves_per_cu = rounds > 1.0 ? 16.0 : wgs * 4.0 * kw / (wgs < 256.0 ? wgs : 256.0);
-            const double rate = waves_per_cu >= 8.0 ? 1.0 : 0.55 + 0.45 * (waves_per_cu - 4.0) / 4.0;
+            const int64_t wgs = wgs_n * sp;
+            const int64_t per_cu = (wgs + 255) / 256;                    // workgroups on the busiest CU
+            const int64_t at_once = min(per_cu, (int64_t)(kw == 4 ? 1 : kw == 2 ? 2 : 4));
+            const double waves = (double)(at_once * 4 * kw);
+            const double rate = waves >= 8.0 ? 1.0 : 0.55;
+            double loop = (double)per_cu * work_us * 256.0 / (double)wgs / rate;
+            if (wgs < 256) loop /= 0.85;
+            if (per_cu > at_once) loop *= 1.1;
             const double parts = sp > 1 ? 6.0 + 2.0 * (double)sp * (double)M * (double)N * 4.0 / 3e6 : 0.0;
-            const double t = work_us / (fill * rate) + parts;
+            const double t = loop + parts;
             if (t < best) { best = t; p.splits = (int)sp; p.kw = kw; }
         }
         if (forced_kw && best < 1e30) break;
