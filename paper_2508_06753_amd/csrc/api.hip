@@ -158,7 +158,7 @@ static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
     else if (!in(t->gemv_max_m, 1, 32)) bad = "gemv_max_m";
     else if (!one_of(t->midm_cbw, 2, 4, 8)) bad = "midm_cbw";
     else if (!one_of(t->tiled_bm, 64, 128)) bad = "tiled_bm";
-    else if (!one_of(t->tiled_bn, 128, 256)) bad = "tiled_bn";
+    else if (!one_of(t->tiled_bn, 64, 128, 256)) bad = "tiled_bn";
     else if (!one_of(t->tiled_kw, 1, 2, 4)) bad = "tiled_kw";
     else if (!one_of(t->tiled_wd, 2, 8)) bad = "tiled_wd";
     else if (!in(t->tiled_group_m, 1, 1024)) bad = "tiled_group_m";

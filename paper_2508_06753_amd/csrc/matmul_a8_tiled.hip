@@ -170,10 +170,11 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
     uint32_t w_lane = (uint32_t)lane * 16u;
     uint32_t s_lane = (uint32_t)l16 * (uint32_t)(TILE_K / G) * 2u;
 
-    // global -> LDS copy: 4 threads per 128-byte row piece, 32 bytes each.  Rows past M repeat
-    // the last row; the lane offset (< 64 K) fits 32 bits.
-    constexpr int CPT = THREADS / BM, CPB = BK / CPT;        // threads per row, bytes each: 4 x 32 or 8 x 16
-    static_assert(CPB == 32 || CPB == 16, "copy geometry");
+    // global -> LDS copy: CPT threads per 128-byte row piece, CPB bytes (NV 16-byte pieces) each.  Rows past
+    // M repeat the last row; the lane offset (< 64 K) fits 32 bits.
+    constexpr int CPT = THREADS / BM, CPB = BK / CPT;        // threads per row, bytes each: 2 x 64, 4 x 32 or 8 x 16
+    constexpr int NV = CPB / 16;
+    static_assert(CPB == 64 || CPB == 32 || CPB == 16, "copy geometry");
     const int cp_row = tid / CPT, cp_seg = tid % CPT;
     int64_t cp_m = m0 + cp_row;
     if (cp_m >= a.M) cp_m = a.M - 1;
@@ -204,31 +205,46 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
     const int64_t n_it = a.n_kt * (sy + 1) / ns * 2;               // stages [it_b, n_it): an even number, >= 2
     // The empty asm statements keep the zero-extension of a lane offset next to its load, which is
     // what lets the compiler pick the "scalar base + 32-bit vector offset" addressing mode.
-    auto load_a = [&](int64_t it, uint4& r0, uint4& r1) {
+    // (pieces passed one by one: with the array handed over as a whole the compiler kept it in scratch memory)
+    auto load_a4 = [&](int64_t it, uint4& r0, uint4& r1, uint4& r2, uint4& r3) {
         const char* p = cp_base + it * BK;                   // uniform
         asm volatile("" : "+v"(cp_lane));
         r0 = *reinterpret_cast<const uint4*>(p + cp_lane);
-        if constexpr (CPB == 32) r1 = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
+        if constexpr (NV > 1) r1 = *reinterpret_cast<const uint4*>(p + cp_lane + 16);
+        if constexpr (NV > 2) {
+            r2 = *reinterpret_cast<const uint4*>(p + cp_lane + 32);
+            r3 = *reinterpret_cast<const uint4*>(p + cp_lane + 48);
+        }
     };
+    auto store_a4 = [&](int8_t* dst, const uint4& r0, const uint4& r1, const uint4& r2, const uint4& r3) {
+        *reinterpret_cast<uint4*>(dst) = r0;
+        if constexpr (NV > 1) *reinterpret_cast<uint4*>(dst + 16) = r1;
+        if constexpr (NV > 2) {
+            *reinterpret_cast<uint4*>(dst + 32) = r2;
+            *reinterpret_cast<uint4*>(dst + 48) = r3;
+        }
+    };
+#define W2_PIECES(x) x[0], x[NV > 1 ? 1 : 0], x[NV > 2 ? 2 : 0], x[NV > 2 ? 3 : 0]
     // Vector memory loads complete in order, so a wait for an activation load also waits for every weight
     // load issued before it: with a deep weight window the activations need the same lead, or each
     // stage would still wait for the weights of the stage before.  AQ register sets hold them on
     // their way (stage s in set (s - it_b) % AQ); LEAD = stages between a load and its LDS store + 1.
     constexpr int AQ = WD > 2 ? WD : 1, LEAD = WD > 2 ? WD : 2;
-    uint4 aq[AQ][2];
+    uint4 aq[AQ][NV];
 #pragma unroll
-    for (int i = 0; i < AQ; ++i) aq[i][1] = make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < AQ; ++i)
+#pragma unroll
+        for (int v = 1; v < NV; ++v) aq[i][v] = make_uint4(0, 0, 0, 0);   // (dead stores that keep the array in registers)
     WStage wq[WD];
-    load_a(it_b, aq[0][0], aq[0][1]);
+    load_a4(it_b, W2_PIECES(aq[0]));
 #pragma unroll
     for (int i = 0; i < WD - 1; ++i) {
         load_w<G>(wb, sb, w_lane, s_lane, min(it_b + i, n_it - 1), wq[i]);
-        if constexpr (WD > 2) load_a(min(it_b + i + 1, n_it - 1), aq[(i + 1) % AQ][0], aq[(i + 1) % AQ][1]);
+        if constexpr (WD > 2) load_a4(min(it_b + i + 1, n_it - 1), W2_PIECES(aq[(i + 1) % AQ]));
     }
     if constexpr (WD > 2) __builtin_amdgcn_sched_barrier(0);
-    *reinterpret_cast<uint4*>(smem + cp_dst) = aq[0][0];     // (waits for the oldest load only)
-    if constexpr (CPB == 32) *reinterpret_cast<uint4*>(smem + cp_dst + 16) = aq[0][1];
-    if constexpr (WD == 2) load_a(it_b + 1, aq[0][0], aq[0][1]);
+    store_a4(smem + cp_dst, W2_PIECES(aq[0]));               // (waits for the oldest load only)
+    if constexpr (WD == 2) load_a4(it_b + 1, W2_PIECES(aq[0]));
     __syncthreads();
 
     const int8_t* a_base = smem + (wm * WM + l16) * A_STRIDE + q * 16;
@@ -258,19 +274,17 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
 
     // One stage: wc holds this stage's weights, wnx (the set the stage before has just used up)
     // receives those of stage it + WD - 1.
-    auto stage = [&](int64_t it, int buf, int buf_next, const WStage& wc, WStage& wnx, uint4 (&ast)[2], uint4 (&ald)[2]) {
+    auto stage = [&](int64_t it, int buf, int buf_next, const WStage& wc, WStage& wnx, uint4 (&ast)[NV], uint4 (&ald)[NV]) {
         // No branch around the loads: past the end they re-read the last stage (and the last
         // LDS write lands in a buffer nobody reads any more).  With loads under a condition the
         // compiler cannot count how many are in flight and its waits for the previous stage's
         // registers also wait for the loads just issued, i.e. a full memory round trip per stage.
         {
-            int8_t* dst = smem + buf_next * A_BUF + cp_dst;
-            *reinterpret_cast<uint4*>(dst) = ast[0];         // activations of stage it+1
-            if constexpr (CPB == 32) *reinterpret_cast<uint4*>(dst + 16) = ast[1];
+            store_a4(smem + buf_next * A_BUF + cp_dst, W2_PIECES(ast));  // activations of stage it+1
             asm volatile("" : "+v"(w_lane), "+v"(s_lane));
             load_w<G>(wb, sb, w_lane, s_lane, min(it + (WD - 1), n_it - 1), wnx);
         }
-        load_a(min(it + LEAD, n_it - 1), ald[0], ald[1]);
+        load_a4(min(it + LEAD, n_it - 1), W2_PIECES(ald));
         // keep the loads up here: the scheduler otherwise sinks them to their first use, one stage on
         __builtin_amdgcn_sched_barrier(0);
         const int8_t* ab = a_base + buf * A_BUF;
@@ -469,6 +483,8 @@ a8_tiled_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int splits)
     }
 }
 
+#undef W2_PIECES
+
 }  // namespace tiled
 
 template <int G, bool DBG, int BN, int KW = 1, int WD = 2>
@@ -500,7 +516,7 @@ static int tiled_bn(int64_t M, int64_t N, const w2_tuning_t& tune)
 {
     const int64_t wgs256 = ((M + tiled::BM - 1) / tiled::BM) * ((N + 255) / 256);
     int bn = tune.tiled_bn;
-    if (bn != 128 && bn != 256) bn = wgs256 < 400 ? 128 : 256;
+    if (bn != 64 && bn != 128 && bn != 256) bn = wgs256 < 400 ? 128 : 256;
     return bn;
 }
 
@@ -513,52 +529,71 @@ static TiledPlan tiled_plan(int64_t M, int64_t N, int64_t n_kt, int64_t cap, con
     TiledPlan p;
     p.bn = tiled_bn(M, N, tune);
     const int64_t tiles_m = (M + tiled::BM - 1) / tiled::BM;
-    const int64_t wgs_n = tiles_m * ((N + p.bn - 1) / p.bn);
     const int forced_s = tune.splitk;                        // tuning and tests: 1 = never, n = n parts if they fit
-    const int forced_kw = p.bn == 128 ? tune.tiled_kw : 1;
     if (p.bn == 256) {
         // many output tiles: split only to fill the chip (splitk_plan)
+        const int64_t wgs_n = tiles_m * ((N + 255) / 256);
         if (forced_s > 0) p.splits = (int)min((int64_t)forced_s, min(max(cap, (int64_t)1), n_kt));
         else p.splits = splitk_plan(wgs_n, n_kt, tune.splitk_min_tiles ? tune.splitk_min_tiles : 12, M, N, cap);
         p.kw = 1;
         return p;
     }
-    // 128-column workgroups (fewer than 400 tiles of 64 x 256): from a few dozen to a few hundred workgroups
-    // against 256 CUs, so K is cut both ways.  Every (splits, kw) that divides the tiles evenly is priced with
-    // a model fitted to sweeps over 28672 x 8192, 14336 x 4096, 17408 x 5120, 4096 x 28672, 8192 x 8192,
-    // 4096 x 4096 and 4096 x 6144 at M = 32..512:
+    // Fewer than 400 tiles of 64 x 256: from a few dozen to a few hundred workgroups against 256 CUs, so K is
+    // cut both ways.  Every (splits, kw) that divides the tiles evenly is priced with a model fitted to sweeps
+    // over 28672 x 8192, 14336 x 4096, 17408 x 5120, 4096 x 28672, 8192 x 8192, 4096 x 4096, 4096 x 6144,
+    // 5120 x 7168 and 2048 x 2048 at M = 32..768:
     //   loop  = the work of the busiest CU at 1600 TOP/s: it gets ceil(workgroups / 256) workgroups (a CU holds
-    //           one of 16 waves, two of 8, four of 4 at a time; more run in rounds, +10 %); with one wave per
-    //           SIMD (4 waves on the CU) it runs at 0.55 of that rate, from two per SIMD on at the full rate
-    //           (measured: 8 and 16 waves per CU run a stage in the same time); fewer workgroups than CUs
-    //           cost another 15 % (the busy CUs queue more stages each);
+    //           one of 16 waves, two of 8, four of 4 at a time; more run in rounds, +10 %); with fewer than 8
+    //           waves on the CU it runs at 0.55 of that rate (measured: 8 and 16 waves per CU run a stage in the
+    //           same time); fewer workgroups than CUs cost another 15 % (the busy CUs queue more stages each);
     //   parts = 6 us for the second launch and both kernels' ends + the partial results written and read once
     //           at 3 TB/s.
+    // 64-column workgroups (two waves per group, four groups) are priced too where they still fit the chip in
+    // one round and K is not split across workgroups, at 30 % more per unit of work (every workgroup stages
+    // the whole 64-row panel of activations for half the columns; fitted: 13.4 / 20.8 / 54.2 us at 6.3 / 10.7 /
+    // 37.6 us of work): 4096 x 6144 at M = 65..128 13.1 against 15.5 us, 8192 x 8192 19.3 against 21.4, 4096 x
+    // 4096 at M = 256 13.3 against 15.7.  In more than one round, or with K split on top, they lost everywhere
+    // (14336 x 4096 at M = 384: 62 against 38 us).
     const double work_us = 2.0 * (double)(tiles_m * tiled::BM) * (double)N * (double)(n_kt * TILE_K) / 1600e6;
     const int64_t room = max(cap, (int64_t)1);
     int64_t s_lo = 1, s_hi = min(min((int64_t)16, room), max((int64_t)1, ((int64_t)16 << 20) / (M * N * (int64_t)sizeof(float))));
     if (forced_s > 0) s_lo = s_hi = min((int64_t)forced_s, min(room, n_kt));
+    const int forced_kw = tune.tiled_kw;
     double best = 1e30;
     p.splits = (int)s_lo;
     p.kw = 1;
+    auto price = [&](int bn, int kw, int64_t sp) {
+        const int64_t wgs = tiles_m * ((N + bn - 1) / bn) * sp;
+        const int64_t per_cu = (wgs + 255) / 256;                        // workgroups on the busiest CU
+        const int64_t at_once = min(per_cu, (int64_t)(kw == 4 ? 1 : kw == 2 ? 2 : 4));
+        const double waves = (double)(at_once * (bn / 32) * kw);
+        const double rate = waves >= 8.0 ? 1.0 : 0.55;
+        double loop = (double)per_cu * work_us * 256.0 / (double)wgs / rate;
+        if (wgs < 256) loop /= 0.85;
+        if (per_cu > at_once) loop *= 1.1;
+        if (bn == 64) loop *= 1.3;
+        const double parts = sp > 1 ? 6.0 + 2.0 * (double)sp * (double)M * (double)N * 4.0 / 3e6 : 0.0;
+        return loop + parts;
+    };
+    bool found = false;
     for (int kw = 4; kw >= 1; kw >>= 1) {
         if (forced_kw && kw > forced_kw) continue;           // (a forced kw that does not divide the tiles falls back to the next smaller)
         for (int64_t sp = s_lo; sp <= s_hi && sp <= n_kt; ++sp) {
             if (kw > 1 && n_kt % (kw * sp) != 0) continue;
             if (forced_s <= 0 && sp > 1 && n_kt / (sp * kw) < 2) continue;
-            const int64_t wgs = wgs_n * sp;
-            const int64_t per_cu = (wgs + 255) / 256;                    // workgroups on the busiest CU
-            const int64_t at_once = min(per_cu, (int64_t)(kw == 4 ? 1 : kw == 2 ? 2 : 4));
-            const double waves = (double)(at_once * 4 * kw);
-            const double rate = waves >= 8.0 ? 1.0 : 0.55;
-            double loop = (double)per_cu * work_us * 256.0 / (double)wgs / rate;
-            if (wgs < 256) loop /= 0.85;
-            if (per_cu > at_once) loop *= 1.1;
-            const double parts = sp > 1 ? 6.0 + 2.0 * (double)sp * (double)M * (double)N * 4.0 / 3e6 : 0.0;
-            const double t = loop + parts;
+            const double t = price(p.bn, kw, sp);
+            found = true;
             if (t < best) { best = t; p.splits = (int)sp; p.kw = kw; }
         }
-        if (forced_kw && best < 1e30) break;
+        if (forced_kw && found) break;
+    }
+    // (an unsplit launch carries about 4 us of first loads and epilogue that the split launches' 6 us include;
+    // the narrow workgroups one more; and they must win by 10 %: the model is that good and no better)
+    if (tune.tiled_bn == 0 && forced_s <= 1 && (forced_kw == 0 || forced_kw == 4) && n_kt % 4 == 0 &&
+        tiles_m * ((N + 63) / 64) <= 256 && price(64, 4, 1) + 5.0 < 0.9 * (best + (p.splits > 1 ? 0.0 : 4.0))) {
+        p.bn = 64;
+        p.splits = 1;
+        p.kw = 4;
     }
     return p;
 }
@@ -584,7 +619,10 @@ static int launch_tiled_bn(const A8Args& a, hipStream_t stream)
         }
         if (p.bn == 128 && p.kw == 4) return launch_tiled<G, DBG, 128, 4>(a, splits, stream);
         if (p.bn == 128 && p.kw == 2) return launch_tiled<G, DBG, 128, 2>(a, splits, stream);
+        if (p.bn == 64 && p.kw == 4) return launch_tiled<G, DBG, 64, 4>(a, splits, stream);
+        if (p.bn == 64 && p.kw == 2) return launch_tiled<G, DBG, 64, 2>(a, splits, stream);
     }
+    if (p.bn == 64) return launch_tiled<G, DBG, 64>(a, splits, stream);
     return p.bn == 128 ? launch_tiled<G, DBG, 128>(a, splits, stream) : launch_tiled<G, DBG, 256>(a, splits, stream);
 }
 

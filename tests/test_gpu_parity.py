@@ -243,24 +243,25 @@ def test_a8_midm_long_k_and_limits(w2):
         w2.matmul_a8(packed, 256, 16, 128, xq, sx, variant=w2.VARIANT_MIDM)
 
 
-@pytest.mark.parametrize("bn", [128, 256])
+@pytest.mark.parametrize("bn", [64, 128, 256])
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (512, 1032)])
 @pytest.mark.parametrize("M", [1, 17, 127, 128, 200])
 def test_a8_tiled(w2, M, K, N, G, bn):
-    # both workgroup widths (four and eight waves); ragged M, N; one to four stages of K
+    # the three workgroup widths (two, four and eight waves); ragged M, N; one to four stages of K
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G, tune={"tiled_bn": bn})
 
 
+@pytest.mark.parametrize("bn", [64, 128])
 @pytest.mark.parametrize("kw", [2, 4])
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", [(1024, 272), (2048, 1032), (4096, 48), (512, 16)])
 @pytest.mark.parametrize("M", [1, 33, 64, 100])
-def test_a8_tiled_k_split_inside_workgroup(w2, M, K, N, G, kw):
-    # 64-row tiles, 128-column workgroups whose 2 or 4 groups of waves take K ranges of their own and add up in
-    # LDS (K = 512 with four groups: the ranges cannot be equal, the plain kernel runs); with and without the
-    # split across workgroups on top
-    tune = {"tiled_bm": 64, "tiled_bn": 128, "tiled_kw": kw}
+def test_a8_tiled_k_split_inside_workgroup(w2, M, K, N, G, kw, bn):
+    # 64-row tiles, 128- and 64-column workgroups whose 2 or 4 groups of waves take K ranges of their own and
+    # add up in LDS (K = 512 with four groups: the ranges cannot be equal, the plain kernel runs); with and
+    # without the split across workgroups on top
+    tune = {"tiled_bm": 64, "tiled_bn": bn, "tiled_kw": kw}
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N + G + kw, tune=tune)
     if K >= 2048:
         codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + N)
@@ -796,7 +797,7 @@ def test_argument_errors_write_nothing(w2):
     assert lib.w2_matmul_a8(p(packed), 256, 64, 128, None, p(sx), 1, p(Y), 64, None, 0, s) == w2.ERR_INVALID_ARG
     # overrides outside what the header allows are refused, field by field, before anything is launched
     for field, value in (("variant", 9), ("variant", w2.VARIANT_SCALED16), ("small_waves", 17), ("small_cbw", 3),
-                         ("small_kc", 100), ("midm_cbw", 3), ("tiled_bn", 64), ("splitk", 17), ("stream_unroll", 1),
+                         ("small_kc", 100), ("midm_cbw", 3), ("tiled_bn", 32), ("splitk", 17), ("stream_unroll", 1),
                          ("tiled_group_m", -1)):
         t = w2.Tuning()
         setattr(t, field, value)
