@@ -244,6 +244,8 @@ def sweep_mode(torch, w2, synth, dev):
           "kernels may split K)")
     for name, (K, N) in synth.SHAPES_8B.items():
         decode_case("mid", name, K, N, 128, (16, 32, 64, 128, 256), ("a8", "a16"))
+    print("# the same between decode and prefill on the deepest projection (70B-class down, 28672 x 8192)")
+    decode_case("deep", "down", 28672, 8192, 128, (16, 32, 64, 128, 256), ("a8", "a16"))
     print("# prefill: 40 launches to warm the clock up, 20 timed")
     for name, (K, N) in synth.SHAPES_70B.items():
         nb = w2.packed_size(K, N, G)
