@@ -350,6 +350,44 @@ def test_a8_auto_dispatch(w2, M):
     run_a8_case(w2, M, 1024, 528, 128, 0, w2.VARIANT_AUTO, seed=M)
 
 
+def _auto_cases():
+    # seeded draws over the shape space AUTO decides on: M on both sides of every switch between kernel families,
+    # shallow and deep K, narrow and wide N (multiples of 8, mostly not of 64), both group sizes
+    rng = np.random.default_rng(20250811)
+    ms = [1, 3, 5, 8, 9, 12, 16, 17, 24, 32, 33, 40, 64, 65, 96, 128, 129, 192, 256, 300]
+    cases = []
+    for i in range(48):
+        M = int(ms[i % len(ms)])
+        K = int(rng.choice([256, 512, 1024, 2048, 3072, 4096, 7168, 14336]))
+        n_max = max(16, min(4096, (3 << 20) // K))
+        N = int(rng.integers(2, n_max // 8 + 1)) * 8
+        cases.append((M, K, N, int(rng.choice([64, 128])), i))
+    return cases
+
+
+@pytest.mark.parametrize("M,K,N,G,seed", _auto_cases())
+def test_auto_dispatch_over_random_shapes(w2, M, K, N, G, seed):
+    # the library's own choice of kernel, launch shape and K split, with the workspace w2_workspace_size asks
+    # for and without one, w2a8 and w2a16, against the oracle
+    codes, scales, X = synth.make_problem(M, K, N, G, seed % 2, 1000 + seed)
+    packed = w2.prepack(dev(codes), dev(scales), G, seed % 2)
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    oq, osx, _ = oracle.quantize_rows(X, G)
+    assert np.array_equal(xq.cpu().numpy(), oq)
+    Yo, y64 = oracle.matmul_a8(codes, scales, G, seed % 2, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, G, seed % 2, oq, osx)
+    Xb = synth.f32_to_bf16_bits(X)
+    Yo16, y64_16, mag16 = oracle.matmul_a16(codes, scales, G, seed % 2, Xb)
+    for with_ws in (True, False):
+        n8, n16 = w2.workspace_size(M, K, N, G), w2.workspace_size(M, K, N, G, a16=True)
+        ws8 = torch.empty(n8, dtype=torch.uint8, device="cuda") if with_ws and n8 else None
+        ws16 = torch.empty(n16, dtype=torch.uint8, device="cuda") if with_ws and n16 else None
+        Y = w2.matmul_a8(packed, K, N, G, xq, sx, workspace=ws8)
+        check_y(bf16_bits(Y), Yo, y64, mag, f"a8 auto M={M} K={K} N={N} G={G} workspace={with_ws}")
+        Y16 = w2.matmul_a16(packed, K, N, G, dev(Xb).view(torch.bfloat16), workspace=ws16)
+        check_y(bf16_bits(Y16), Yo16, y64_16, mag16, f"a16 auto M={M} K={K} N={N} G={G} workspace={with_ws}")
+
+
 @pytest.mark.parametrize("codec", [0, 1])
 def test_config0_gemv_2048(w2, codec):
     """The single-GEMV configuration: M=1, K=N=2048, G=128, seed 0."""
