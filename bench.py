@@ -169,7 +169,7 @@ def gamma_mode(torch, w2, synth, dev, timing):
     torch.cuda.synchronize()
 
 
-def sweep_mode(torch, w2, synth, dev):
+def sweep_mode(torch, w2, synth, dev, sections=None):
     """One line per (configuration, projection, M, call): microseconds per launch, the method's own
     bytes / time (GB/s, % of 8 TB/s) for M <= 64, ops / time (TOP/s, % of the MFMA peak) above."""
     def pool_for(K, N, g):
@@ -208,6 +208,8 @@ def sweep_mode(torch, w2, synth, dev):
         print("%-6s %-8s K=%5d N=%5d G=%3d M=%4d %-17s %9.2f us  %s" % (cfg, name, K, N, g, M, call, us, rate), flush=True)
 
     def decode_case(cfg, name, K, N, g, Ms, calls):
+        if sections and cfg not in sections:
+            return
         pool = pool_for(K, N, g)
         sink = torch.zeros(1, dtype=torch.int32, device=dev)
         if "stream read" in calls:
@@ -246,6 +248,8 @@ def sweep_mode(torch, w2, synth, dev):
         decode_case("mid", name, K, N, 128, (16, 32, 64, 128, 256), ("a8", "a16"))
     print("# the same between decode and prefill on the deepest projection (70B-class down, 28672 x 8192)")
     decode_case("deep", "down", 28672, 8192, 128, (16, 32, 64, 128, 256), ("a8", "a16"))
+    if sections and "cfg4" not in sections:
+        return
     print("# prefill: 40 launches to warm the clock up, 20 timed")
     for name, (K, N) in synth.SHAPES_70B.items():
         nb = w2.packed_size(K, N, G)
@@ -293,6 +297,8 @@ def main():
                     help="time every configuration BASELINE.json lists (decode shapes from HIP graphs over a pool "
                          "of distinct weight copies, prefill shapes under sustained launches) and print a table "
                          "instead of the bench line")
+    ap.add_argument("--sections", default="",
+                    help="with --sweep: only these sections of the table (comma-separated: cfg0..cfg4, mid, deep)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -306,7 +312,7 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     if args.sweep:
-        return sweep_mode(torch, w2, synth, dev)
+        return sweep_mode(torch, w2, synth, dev, set(args.sections.split(",")) - {""} or None)
     if args.probe_sweep:
         return probe_sweep_mode(torch, w2, synth, dev)
     if args.gamma:
