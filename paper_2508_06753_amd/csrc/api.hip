@@ -629,7 +629,7 @@ int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* b
     else {
         // split-K partial results: the tiled kernel's above 64 rows, the mid-M kernel's on deep projections
         // (whichever of the two the call would pick, the larger need covers it)
-        const size_t tiled = M > 32 ? a8_tiled_splitk_bytes(M, N, L.n_kt, dflt) : 0;
+        const size_t tiled = M > 32 ? a8_tiled_splitk_bytes(M, N, L.n_kt, G, dflt) : 0;
         const size_t midm = M >= 4 && M <= 128 ? a8_midm_splitk_bytes(M, N, L.n_cb, L.n_kt, dflt) : 0;
         *bytes = (single ? 0 : fused_workspace_bytes(M, K)) + (tiled > midm ? tiled : midm);
     }

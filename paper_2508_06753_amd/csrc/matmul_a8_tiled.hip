@@ -598,9 +598,22 @@ static TiledPlan tiled_plan(int64_t M, int64_t N, int64_t n_kt, int64_t cap, con
     return p;
 }
 
-size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune)
+// Deep K with room for partial results: the 128-row kernel with its own K ranges (half the up-convert work per
+// matrix instruction) instead of 64-row tiles.  Measured against the priced 64-row plan: 28672 x 8192 at
+// M = 128 / 256 / 512 / 768 44 / 70 / 125 / 193 against 48 / 80 / 145 / 215 us, 17408 x 5120 at M = 256 / 512 / 768
+// 36 / 56 / 77 against 40 / 77 / 88; at K = 14336 and below the 64-row plan holds its own (14336 x 4096 at
+// M = 256: 27.5 against 29.4), and so it does below 256 rows at K = 17408.
+static int deep128_splits(int64_t M, int64_t N, int64_t n_kt, int64_t G, int64_t cap, const w2_tuning_t& tune)
 {
-    const int s = tiled_plan(M, N, n_kt, 16, tune).splits;
+    if (tune.tiled_bm || G != 128 || !((n_kt >= 100 && M >= 128) || (n_kt >= 64 && M >= 256))) return 1;
+    const int s = a8_tiled128_splits(M, N, n_kt, cap, tune);
+    const int64_t t256 = ((M + 127) / 128) * ((N + 255) / 256);
+    return s >= 2 && t256 * s >= 192 ? s : 1;
+}
+
+size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, int G, const w2_tuning_t& tune)
+{
+    const int s = max(tiled_plan(M, N, n_kt, 16, tune).splits, deep128_splits(M, N, n_kt, G, 16, tune));
     return s < 2 ? 0 : (size_t)s * M * N * sizeof(float);
 }
 
@@ -641,7 +654,13 @@ int launch_a8_tiled(const A8Args& a, hipStream_t stream)
         const bool fill_ok = t128 >= 768 || t128 % 256 == 0 || t128 % 256 >= 128;
         const bool want128 = a.tune.tiled_bm ? a.tune.tiled_bm == 128
                                              : a.M >= 1024 || (a.M >= 128 && t128 >= 224 && fill_ok);
-        if (want128 && splits < 2 && a8_tiled128_supports(a)) return launch_a8_tiled128(a, stream);
+        const int s_deep = a.acc_out ? 1 : deep128_splits(a.M, a.N, a.n_kt, a.G, cap, a.tune);
+        if (a8_tiled128_supports(a)) {
+            // forced 128-row tiles: that kernel's own rule for K ranges (or the forced count)
+            if (a.tune.tiled_bm == 128) return launch_a8_tiled128(a, a8_tiled128_splits(a.M, a.N, a.n_kt, cap, a.tune), stream);
+            if (s_deep >= 2) return launch_a8_tiled128(a, s_deep, stream);
+            if (want128 && splits < 2) return launch_a8_tiled128(a, 1, stream);
+        }
     }
     if (a.G == 128)
         return a.acc_out ? launch_tiled_bn<128, true>(a, stream) : launch_tiled_bn<128, false>(a, stream);

@@ -84,9 +84,13 @@ struct WTile {
     uint32_t s[CJ][G == 128 ? 1 : 2];              // the lane's column: 2 (G=128) or 4 (G=64) bf16 group scales
 };
 
-template <int G, bool DBG, int BN>
+// SPLIT: K cut into gridDim.y near-equal ranges of whole 256-k tiles (c_lo tiles each, one more for the first
+// c_rem ranges), one grid slice each; a range is entered by moving the base pointers, its fp32 results go to the
+// workspace and a second launch sums them (Sec. II-D, K-splitting for the smaller shapes).  An instantiation of
+// its own: the unsplit kernel is compiled exactly as before.
+template <int G, bool DBG, int BN, bool SPLIT = false>
 __global__ void __launch_bounds__(64 * waves_of(BN), BN >= 256 ? 1 : 2)
-a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
+a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m, int c_lo, int c_rem)
 {
     constexpr int WAVES = waves_of(BN), THREADS = 64 * WAVES;
     constexpr int GPT = TILE_K / G;
@@ -127,13 +131,25 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     }
     uint32_t w_lane = (uint32_t)lane * 16u;
     uint32_t s_lane = (uint32_t)l16 * (GPT * 2u);
+    int64_t nkt = a.n_kt;                                    // tiles this workgroup multiplies
+    int64_t kt0 = 0;                                         // the first of them
+    if constexpr (SPLIT) {
+        const int z = (int)blockIdx.y;
+        kt0 = (int64_t)z * c_lo + min(z, c_rem);
+        nkt = c_lo + (z < c_rem ? 1 : 0);
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) {
+            wb[j] += kt0 * 1024;
+            sb[j] += kt0 * (TILE_N * GPT * 2);
+        }
+    }
 
     // global -> LDS copy: CPT threads per row, NV 16-byte pieces each; rows past M repeat the last row.
     // Lane offsets stay below 128 * K <= 2^31.
     const int cp_row = tid / CPT, cp_seg = tid % CPT;
     int64_t cp_m = m0 + cp_row;
     if (cp_m >= a.M) cp_m = a.M - 1;
-    const char* cp_base = reinterpret_cast<const char*>(a.xq) + m0 * a.K;                 // uniform
+    const char* cp_base = reinterpret_cast<const char*>(a.xq) + m0 * a.K + kt0 * TILE_K;  // uniform
     // piece v of a thread is the row's 16-byte piece v * CPT + cp_seg: the CPT threads of a row store CPT
     // consecutive pieces per instruction, so eight lanes (two or four rows) never share an LDS bank
     // (with NV consecutive pieces per thread a row's last piece fell on the next row's first bank)
@@ -154,7 +170,7 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
             for (int r = 0; r < 4; ++r) y[i][j][r] = 0.0f;
         }
 
-    const int64_t n_st = a.n_kt * 2;                         // stages of 128 k
+    const int64_t n_st = nkt * 2;                            // stages of 128 k
     // plain named registers (arrays and structs of them ended up in scratch memory)
     uint4 p00, p01, p02 = make_uint4(0, 0, 0, 0), p03 = p02;         // set 0
     uint4 p10 = p02, p11 = p02;                                      // set 1 (eight-wave workgroups)
@@ -179,7 +195,7 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
         }
     };
     auto load_w = [&](int64_t kt, WTile<G>& r) {
-        kt = min(kt, a.n_kt - 1);
+        kt = min(kt, nkt - 1);
         const int64_t w_off = kt * 1024;
         const int64_t s_off = kt * (TILE_N * GPT * 2);
         asm volatile("" : "+v"(w_lane), "+v"(s_lane));
@@ -338,7 +354,7 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     // one 256-k tile (two stages) per iteration; the next tile's weights arrive in w1 meanwhile and move
     // to w0 at the end (every load and every register write is unconditional: registers written under a
     // condition end up in scratch memory)
-    for (int64_t kt = 0; kt < a.n_kt; ++kt) {
+    for (int64_t kt = 0; kt < nkt; ++kt) {
         stage(kt * 2, std::integral_constant<int, 0>{}, w0, w1);
         stage(kt * 2 + 1, std::integral_constant<int, 1>{}, w0, w1);
         w0 = w1;
@@ -380,6 +396,39 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     float cj[CJ];
 #pragma unroll
     for (int j = 0; j < CJ; ++j) cj[j] = ssum[j] * BIAS_F;
+    if constexpr (SPLIT) {
+        // this range's results, dequantised, as fp32 rows of the workspace: the wave's 128 x 32 tile goes
+        // through LDS 64 rows at a time (rows padded by 16 bytes: conflict-free both ways; the wave reads
+        // back only what it wrote) and leaves as 16-byte stores in 128-byte runs
+        constexpr int P_STRIDE = WN * 4 + 16;
+        static_assert(waves_of(BN) * 64 * P_STRIDE <= lds_bytes(BN), "partial-result staging fits the activation buffers");
+        float* dst = a.part + (int64_t)blockIdx.y * a.M * a.N;
+        int8_t* pbase = smem + wn * (64 * P_STRIDE);
+        const int prow = lane >> 3, pcol = (lane & 7) * 4;   // eight lanes per row piece
+        const int64_t n = n0 + wn * WN + pcol;
+#pragma unroll
+        for (int h = 0; h < RI / 4; ++h) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float4 s4 = *reinterpret_cast<const float4*>(sx_lds + (h * 4 + i) * 16 + 4 * q);
+                const float sr[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int j = 0; j < CJ; ++j)
+                        *reinterpret_cast<float*>(pbase + (i * 16 + 4 * q + r) * P_STRIDE + (j * 16 + l16) * 4) =
+                            (y[h * 4 + i][j][r] - cj[j]) * (sr[r] * 0x1p79f);
+            }
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int row = p * 8 + prow;
+                const int64_t m = m0 + h * 64 + row;
+                const float4 v = *reinterpret_cast<const float4*>(pbase + row * P_STRIDE + pcol * 4);
+                if (m < a.M && n < a.N) *reinterpret_cast<float4*>(dst + m * a.N + n) = v;   // N % 8 == 0: all 4 or none
+            }
+        }
+        return;
+    }
     auto emit = [&](auto mode_c) {
         constexpr int MODE = decltype(mode_c)::value;        // ACT_NONE, ACT_SILU, ACT_SILU_MUL
 #pragma unroll
@@ -421,8 +470,8 @@ a8_tiled128_kernel(A8Args a, int tiles_m, int tiles_n, int group_m)
     }
 }
 
-template <bool DBG, int BN>
-static int launch(const A8Args& a, hipStream_t stream)
+template <bool DBG, int BN, bool SPLIT = false>
+static int launch(const A8Args& a, int splits, hipStream_t stream)
 {
     constexpr int WAVES = waves_of(BN);
     const int tiles_m = (int)((a.M + BM - 1) / BM);
@@ -432,24 +481,50 @@ static int launch(const A8Args& a, hipStream_t stream)
     // moves the least through the XCD's L2 (measured as fast as 8 at M = 2048, 2 % faster at M = 4096).
     const int group_m = a.tune.tiled_group_m ? a.tune.tiled_group_m : 4;
     constexpr int lds = lds_bytes(BN) + SX_BYTES;
-    auto kern = a8_tiled128_kernel<128, DBG, BN>;
+    auto kern = a8_tiled128_kernel<128, DBG, BN, SPLIT>;
     if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, "w2_matmul_a8[tiled 128]")) return rc;
-    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(64 * WAVES);
-    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, tiles_m, tiles_n, group_m);
-    return check_launch("w2_matmul_a8[tiled 128]");
+    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)(SPLIT ? splits : 1)), block(64 * WAVES);
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, a, tiles_m, tiles_n, group_m, (int)(a.n_kt / (SPLIT ? splits : 1)),
+                       (int)(a.n_kt % (SPLIT ? splits : 1)));
+    int rc = check_launch("w2_matmul_a8[tiled 128]");
+    if (rc || !SPLIT) return rc;
+    return launch_splitk_reduce(a.part, splits, a.M, a.N, a.Y, a.ldy, a.epi, stream);
 }
 
 }  // namespace t128
 
-// G = 128 only (a stage is one group); K splitting across workgroups stays with the 64-row kernel.
+// G = 128 only (a stage is one group).
 bool a8_tiled128_supports(const A8Args& a) { return a.G == 128; }
 
-int launch_a8_tiled128(const A8Args& a, hipStream_t stream)
+// K ranges across workgroups for the 128-row kernel: with room for partial results, 256-column workgroups
+// (one per CU) times floor(256 / tiles) ranges -- one round, never more -- up to 8, at least two 256-k tiles
+// each, at most 64 MiB of partial results (the rule that came out of the w2a16 kernel's sweeps, which has
+// the same tiling).
+int a8_tiled128_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap, const w2_tuning_t& tune)
+{
+    if (tune.splitk > 0) return (int)max((int64_t)1, min((int64_t)tune.splitk, min(cap, n_kt)));
+    const int64_t t256 = ((M + 127) / 128) * ((N + 255) / 256);
+    int64_t s = 256 / max(t256, (int64_t)1);
+    s = min(s, (int64_t)8);
+    s = min(s, n_kt / 2);
+    s = min(s, ((int64_t)64 << 20) / (M * N * (int64_t)sizeof(float)));
+    s = min(s, cap);
+    return s < 2 ? 1 : (int)s;
+}
+
+// splits: K ranges across workgroups (1 = none); the caller decides (a8_tiled128_splits is the rule).
+int launch_a8_tiled128(const A8Args& a, int splits, hipStream_t stream)
 {
     const int64_t wgs256 = ((a.M + 127) / 128) * ((a.N + 255) / 256);
-    const int bn = a.tune.tiled_bn ? a.tune.tiled_bn : wgs256 <= 128 ? 128 : 256;
-    if (a.acc_out) return bn == 128 ? t128::launch<true, 128>(a, stream) : t128::launch<true, 256>(a, stream);
-    return bn == 128 ? t128::launch<false, 128>(a, stream) : t128::launch<false, 256>(a, stream);
+    const int64_t cap = a.part ? (int64_t)(a.part_bytes / ((size_t)a.M * a.N * sizeof(float))) : 0;
+    if (a.acc_out || splits > cap || splits > a.n_kt) splits = 1;
+    if (splits >= 2) {
+        if (a.tune.tiled_bn == 128) return t128::launch<false, 128, true>(a, splits, stream);
+        return t128::launch<false, 256, true>(a, splits, stream);
+    }
+    const int bn = a.tune.tiled_bn == 128 || a.tune.tiled_bn == 256 ? a.tune.tiled_bn : wgs256 <= 128 ? 128 : 256;
+    if (a.acc_out) return bn == 128 ? t128::launch<true, 128>(a, 1, stream) : t128::launch<true, 256>(a, 1, stream);
+    return bn == 128 ? t128::launch<false, 128>(a, 1, stream) : t128::launch<false, 256>(a, 1, stream);
 }
 
 }  // namespace w2

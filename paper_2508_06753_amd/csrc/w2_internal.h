@@ -61,7 +61,8 @@ bool a8_midm_supports(const A8Args& a);
 int launch_a8_midm(const A8Args& a, hipStream_t stream);
 int launch_a8_tiled(const A8Args& a, hipStream_t stream);
 bool a8_tiled128_supports(const A8Args& a);
-int launch_a8_tiled128(const A8Args& a, hipStream_t stream);
+int launch_a8_tiled128(const A8Args& a, int splits, hipStream_t stream);
+int a8_tiled128_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap, const w2_tuning_t& tune);
 
 // The decode kernel (M <= 4): xt 0 = int8 rows (a.xq / a.sx), 1 = fp32 rows, 2 = bf16 rows quantised in the kernel.
 bool a8_gemv_supports(int64_t M);
@@ -97,7 +98,7 @@ int launch_a16_midm(const A16Args& a, hipStream_t stream);
 int splitk_plan(int64_t wgs, int64_t n_kt, int64_t min_tiles, int64_t M, int64_t N, int64_t cap,
                 int64_t max_bytes = (int64_t)16 << 20);
 // Bytes of workspace with which the tiled kernels would split K for this problem (0: they would not).
-size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, const w2_tuning_t& tune);
+size_t a8_tiled_splitk_bytes(int64_t M, int64_t N, int64_t n_kt, int G, const w2_tuning_t& tune);
 size_t a8_midm_splitk_bytes(int64_t M, int64_t N, int64_t n_cb, int64_t n_kt, const w2_tuning_t& tune);
 // The mid-M kernels' launch shape (both activation types): column blocks per workgroup and K ranges.
 struct MidmPlan { int cbw, splits; };

@@ -326,6 +326,32 @@ def test_a8_tiled_128_row_tiles(w2, M, K, N, bn):
     run_a8_case(w2, M, K, N, 128, (M + K) % 2, w2.VARIANT_TILED, seed=M + K + N, tune={"tiled_bm": 128, "tiled_bn": bn})
 
 
+@pytest.mark.parametrize("act", [0, 2])
+@pytest.mark.parametrize("bn", [128, 256])
+@pytest.mark.parametrize("splitk", [0, 2, 3, 8])
+@pytest.mark.parametrize("M,K,N", [(129, 4608, 288), (300, 2048, 544), (128, 7168, 64), (256, 1024, 1056)])
+def test_a8_tiled_128_row_tiles_split_k(w2, M, K, N, splitk, bn, act):
+    # the 128-row kernel with K cut into ranges across workgroups (its own rule, or forced part counts: uneven
+    # ranges, more parts than the workspace holds), partial results summed by the second launch; both widths;
+    # plain and gated epilogue; against the oracle and, for the plain epilogue, bit for bit against ... the
+    # unsplit kernel is NOT expected to match bit for bit (another order of additions)
+    codes, scales, X = synth.make_problem(M, K, N, 128, 0, M + K + N + splitk)
+    packed = w2.prepack(dev(codes), dev(scales), 128, 0)
+    xq, sx, _ = w2.quantize_rows(dev(X), 128)
+    ws = torch.empty(5 * M * N * 4, dtype=torch.uint8, device="cuda")
+    tune = {"tiled_bm": 128, "tiled_bn": bn, "splitk": splitk}
+    Y = w2.matmul_a8_epi(packed, K, N, 128, xq, sx, act=act, variant=w2.VARIANT_TILED, workspace=ws, tune=tune)
+    Y2 = w2.matmul_a8_epi(packed, K, N, 128, xq, sx, act=act, variant=w2.VARIANT_TILED, workspace=ws, tune=tune)
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "not deterministic"
+    oq, osx, _ = oracle.quantize_rows(X, 128)
+    Yo, y64 = oracle.matmul_a8(codes, scales, 128, 0, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, 128, 0, oq, osx)
+    if act == 0:
+        check_y(bf16_bits(Y), Yo, y64, mag, f"a8 128-row tiles split-K {splitk} bn={bn} M={M} K={K} N={N}")
+    else:
+        check_epilogue(bf16_bits(Y), y64, mag, None, act, f"a8 128-row tiles split-K {splitk} gated bn={bn} M={M} K={K} N={N}")
+
+
 @pytest.mark.parametrize("M", [20, 100, 300])
 def test_a8_one_fma_dequant_keeps_denormals(w2, M):
     # the mid-M and prefill kernels read BIAS + 64*sum as an fp32 denormal and multiply by sw * 2^64: a build
