@@ -250,7 +250,7 @@ def sweep_mode(torch, w2, synth, dev, sections=None):
     decode_case("deep", "down", 28672, 8192, 128, (16, 32, 64, 128, 256), ("a8", "a16"))
     if sections and "cfg4" not in sections:
         return
-    print("# prefill: 40 launches to warm the clock up, 20 timed")
+    print("# prefill: 40 launches to warm the clock up, 20 timed; workspaces of w2_workspace_size bytes (none needed at M = 2048)")
     for name, (K, N) in synth.SHAPES_70B.items():
         nb = w2.packed_size(K, N, G)
         pk = torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev)
@@ -261,8 +261,11 @@ def sweep_mode(torch, w2, synth, dev, sections=None):
             Xb = X.to(torch.bfloat16)
             del X
             Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-            for call, fn in (("a8", lambda: w2.matmul_a8(pk, K, N, G, xq, sx, out=Y)),
-                             ("a16", lambda: w2.matmul_a16(pk, K, N, G, Xb, out=Y))):
+            nws, nws16 = w2.workspace_size(M, K, N, G), w2.workspace_size(M, K, N, G, a16=True)
+            ws = torch.empty(nws, dtype=torch.uint8, device=dev) if nws else None
+            ws16 = torch.empty(nws16, dtype=torch.uint8, device=dev) if nws16 else None
+            for call, fn in (("a8", lambda: w2.matmul_a8(pk, K, N, G, xq, sx, out=Y, workspace=ws)),
+                             ("a16", lambda: w2.matmul_a16(pk, K, N, G, Xb, out=Y, workspace=ws16))):
                 for _ in range(40 if call == "a8" else 15):
                     fn()
                 torch.cuda.synchronize()
