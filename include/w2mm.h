@@ -110,7 +110,7 @@ typedef struct {
     int gemv_window;      /* GEMV: weight tiles a wave keeps in flight: 2, 4 or 8 */
     int gemv_max_m;       /* w2a8 AUTO: largest M given to GEMV (1..32) */
     int midm_cbw;         /* MIDM: column blocks per workgroup: 2, 4 or 8 */
-    int tiled_bm;         /* w2a8 TILED: rows per workgroup: 64 or 128 (128: G = 128, K not split) */
+    int tiled_bm;         /* w2a8 TILED: rows per workgroup: 64 or 128 (128: G = 128) */
     int tiled_bn;         /* TILED / SCALED16 tiled kernels: columns per workgroup: 128 or 256 (w2a8, 64-row tiles: also 64) */
     int tiled_kw;         /* w2a8 TILED, 128-column workgroups: K ranges inside a workgroup: 1, 2 or 4 */
     int tiled_wd;         /* w2a8 TILED, 64-row tiles: weight stages in flight per wave: 2 or 8 */

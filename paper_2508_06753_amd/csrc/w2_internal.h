@@ -64,7 +64,8 @@ bool a8_tiled128_supports(const A8Args& a);
 int launch_a8_tiled128(const A8Args& a, int splits, hipStream_t stream);
 int a8_tiled128_splits(int64_t M, int64_t N, int64_t n_kt, int64_t cap, const w2_tuning_t& tune);
 
-// The decode kernel (M <= 4): xt 0 = int8 rows (a.xq / a.sx), 1 = fp32 rows, 2 = bf16 rows quantised in the kernel.
+// The decode kernel (M <= 32; rows quantised in the kernel: M <= 4): xt 0 = int8 rows (a.xq / a.sx), 1 = fp32 rows,
+// 2 = bf16 rows quantised in the kernel.
 bool a8_gemv_supports(int64_t M);
 int launch_a8_gemv(const A8Args& a, const void* X, int xt, int64_t ldx, hipStream_t stream);
 
