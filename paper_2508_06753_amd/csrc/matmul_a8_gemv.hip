@@ -225,9 +225,7 @@ a8_gemv_kernel(Args a)
                     }
                 }
             }
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-            amax[r] = m;
+            amax[r] = wave_max_f32(m);
         }
         if (lane == 0) {
 #pragma unroll

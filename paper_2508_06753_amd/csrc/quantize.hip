@@ -87,8 +87,7 @@ quantize_rows_kernel(const void* __restrict__ X, int64_t K, int64_t ldx, int G,
 #pragma unroll
         for (int i = 0; i < EPT; ++i) amax = fmaxf(amax, fabsf(v[i]));
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    amax = wave_max_f32(amax);
     if (lane == 0) s_red[wave] = amax;
     __syncthreads();
     amax = s_red[lane & 15];                                 // every wave reduces the (at most 16) partial maxima itself

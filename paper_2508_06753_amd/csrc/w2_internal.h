@@ -9,6 +9,28 @@
 
 namespace w2 {
 
+// Maximum of a value over the 64 lanes of a wave, the same in every lane.  Cross-lane moves inside a row of 16
+// lanes ride on the vector instruction itself (DPP), the four rows meet through scalar registers: no trip
+// through local memory per step, which is what a generic lane shuffle costs here.  fmaxf semantics (a NaN
+// operand is ignored).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move_f32(float v)      // lanes with no source read 0
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+__device__ __forceinline__ float wave_max_f32(float m)
+{
+    m = fmaxf(m, dpp_move_f32<0xB1>(m));                     // quad_perm [1,0,3,2]
+    m = fmaxf(m, dpp_move_f32<0x4E>(m));                     // quad_perm [2,3,0,1]
+    m = fmaxf(m, dpp_move_f32<0x141>(m));                    // row_half_mirror
+    m = fmaxf(m, dpp_move_f32<0x140>(m));                    // row_mirror: every lane holds its row's maximum
+    const int b = __float_as_int(m);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
 // Records `what` + the HIP error string as this thread's last error if the
 // preceding launches failed; returns a w2_status_t.
 int check_launch(const char* what);
