@@ -54,18 +54,23 @@ constexpr int xslots(int RL) { return RL > 4 ? 32 : 8; }
 constexpr int max_waves(int RL) { return RL > 4 ? 8 : 16; }
 
 struct Args {
+    // What a wave needs before it can issue its first loads comes first, 64 bytes that one scalar load fetches:
+    // the kernel's first memory request waits for these and for nothing else.
+    const void* X;                // XT 0: int8 [M][K] dense; 1: fp32 rows; 2: bf16 rows (row stride ldx elements)
+    int64_t ldx;
     const uint32_t* codes;
     const uint16_t* scales;
-    const void* X;                // XT 0: int8 [M][K] dense; 1: fp32 rows; 2: bf16 rows (row stride ldx elements)
+    int K, M, n_cb, n_kt;
+    int cbw_shift, cbw;           // waves of a workgroup = cbw column blocks x ks k-ranges
+    int t_lo, t_rem;              // tiles per k-range: t_lo, and one more for the first t_rem ranges
+    // ... the rest
+    int ks;
+    int red_off;                  // LDS offset of the reduction scratch
+    int sc_off;                   // LDS offset of the waves' scale slices
     const float* sx;              // XT 0: activation scales [M]
     uint16_t* Y;
     int32_t* acc_out;             // debug export (XT 0)
-    int64_t ldx, ldy, N;
-    int K, M, n_cb, n_kt;
-    int cbw_shift, cbw, ks;       // waves of a workgroup = cbw column blocks x ks k-ranges
-    int t_lo, t_rem;              // tiles per k-range: t_lo, and one more for the first t_rem ranges
-    int red_off;                  // LDS offset of the reduction scratch
-    int sc_off;                   // LDS offset of the waves' scale slices
+    int64_t ldy, N;
     Epilogue epi;
 };
 
@@ -227,11 +232,13 @@ a8_gemv_kernel(Args a)
             }
             amax[r] = wave_max_f32(m);
         }
+        W2_GEMV_MARK(8);
         if (lane == 0) {
 #pragma unroll
             for (int r = 0; r < RL; ++r) s_red[wave * 4 + r] = amax[r];
         }
         __syncthreads();
+        W2_GEMV_MARK(9);
         float inv[RL];
 #pragma unroll
         for (int r = 0; r < RL; ++r) {
@@ -243,6 +250,7 @@ a8_gemv_kernel(Args a)
             if constexpr (SX_IN_REGS) sxv[r] = sxr;
             else if (tid == 0) s_red[SX_SLOT + r] = sxr;
         }
+        W2_GEMV_MARK(10);
 #pragma unroll
         for (int r = 0; r < RL; ++r)
 #pragma unroll
