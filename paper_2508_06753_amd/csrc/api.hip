@@ -166,6 +166,8 @@ static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
     else if (!in(t->splitk_min_tiles, 1, 1024)) bad = "splitk_min_tiles";
     else if (!one_of(t->stream_unroll, 4, 8, 16)) bad = "stream_unroll";
     else if (!in(t->stream_blocks, 1, 65536)) bad = "stream_blocks";
+    else if (!in(t->gemv_cbw, 1, 16)) bad = "gemv_cbw";
+    else if (!in(t->gemv_ks, 1, 16)) bad = "gemv_ks";
     if (bad) return fail(W2_ERR_INVALID_ARG, "%s: w2_tuning_t.%s is out of range", fn, bad);
     *out = *t;
     return W2_OK;

@@ -61,10 +61,12 @@ struct Args {
     const uint32_t* codes;
     const uint16_t* scales;
     int K, M, n_cb, n_kt;
-    int cbw_shift, cbw;           // waves of a workgroup = cbw column blocks x ks k-ranges
+    int cbw_rcp, cbw;             // waves of a workgroup = cbw column blocks x ks k-ranges (cbw: any number up to 16);
+                                  // cbw_rcp = ceil(256 / cbw): wave / cbw = (wave * cbw_rcp) >> 8, exact for waves below 16
     int t_lo, t_rem;              // tiles per k-range: t_lo, and one more for the first t_rem ranges
     // ... the rest
     int ks;
+    int outs_magic;               // ceil(2^20 / outputs per row of a workgroup): item / outputs for items below 4096
     int red_off;                  // LDS offset of the reduction scratch
     int sc_off;                   // LDS offset of the waves' scale slices
     const float* sx;              // XT 0: activation scales [M]
@@ -132,7 +134,7 @@ a8_gemv_kernel(Args a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n_waves = __builtin_amdgcn_readfirstlane((int)blockDim.x >> 6);
     const int threads = n_waves * 64;
-    const int cbi = wave & (a.cbw - 1), ksi = wave >> a.cbw_shift;
+    const int ksi = (wave * a.cbw_rcp) >> 8, cbi = wave - ksi * a.cbw;
     const int q = lane >> 4, l16 = lane & 15;
     const int cb = (int)blockIdx.x * a.cbw + cbi;
     const bool cb_ok = cb < a.n_cb;
@@ -397,7 +399,7 @@ a8_gemv_kernel(Args a)
         // one or two rows: a thread per output column, the rows in turn
         if (tid < outs) {
             const int nl = tid & 15, ci = tid >> 4;
-            const int kstride = (RL * 16) << a.cbw_shift;    // floats between two k-ranges' partial sums
+            const int kstride = RL * 16 * a.cbw;             // floats between two k-ranges' partial sums
             auto z = [&](int c, int r) {                     // finished fp32 result of column block c, row r
                 const float* p0 = red + (c * RL + r) * 16 + nl;
                 float s = 0.f;
@@ -444,10 +446,12 @@ a8_gemv_kernel(Args a)
     }
     // one output per thread and step: column `item % outs` (a power of two), row `item / outs`; the k-ranges'
     // partial sums are fetched four at a time, then added in a fixed order
-    const int outs_shift = a.cbw_shift + (gated ? 3 : 4);
-    const int kstride = (RL * 16) << a.cbw_shift;            // floats between two k-ranges' partial sums
-    for (int item = tid; item < (a.M << outs_shift); item += threads) {
-        const int r = item >> outs_shift, col = item & (outs - 1);
+    const int kstride = RL * 16 * a.cbw;                     // floats between two k-ranges' partial sums
+    for (int item = tid; item < a.M * outs; item += threads) {
+        int r;
+        if constexpr (WIDE) r = item >> (31 - __clz(outs));  // the wide form's workgroups hold a power of two of column blocks
+        else r = (int)(((uint32_t)item * (uint32_t)a.outs_magic) >> 20);
+        const int col = item - r * outs;
         const int nl = col & 15, ci = col >> 4;
         const float sxr = s_red[SX_SLOT + r] * 0.015625f;
         auto z = [&](int c) {                                // finished fp32 result of column block c, row r
@@ -501,6 +505,14 @@ struct Cfg { int cbw, ks, window; };
 static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_cbw, int min_threads, int max_w, int rows, int xt)
 {
     Cfg c;
+    if (tune.gemv_cbw || tune.gemv_ks) {                     // forced shape, any numbers: the caller of pick checks it
+        c.cbw = tune.gemv_cbw ? tune.gemv_cbw : 1;
+        c.ks = tune.gemv_ks ? tune.gemv_ks : (8 / c.cbw > 0 ? 8 / c.cbw : 1);
+        if (c.ks > n_kt) c.ks = (int)n_kt;
+        const int64_t run = (n_kt + c.ks - 1) / c.ks;
+        c.window = tune.gemv_window ? tune.gemv_window : run > 4 ? 4 : 2;
+        return c;
+    }
     if (tune.small_waves || tune.small_cbw) {                // forced shape (tests, sweeps)
         int waves = tune.small_waves ? tune.small_waves : 8;
         int p = 1;
@@ -536,14 +548,36 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
     while (c.cbw * c.ks > max_w) {                           // at most 16 waves (8 in the wide form)
         if (c.ks > 1) c.ks >>= 1; else c.cbw >>= 1;
     }
-    while (c.cbw * c.ks * 64 < min_threads && c.cbw * c.ks < max_w) c.cbw <<= 1;   // the rows need the threads
+    if (rows <= 4) {
+        // Up to four rows the workgroup may hold any number of column blocks.
+        // (a) The chip's time follows the CU that holds the most column blocks: with every workgroup resident,
+        //     ceil(workgroups / 256) of them share the busiest CU.  Where another width cuts that by a fifth or
+        //     more, take it (5120 x 34816: three column blocks, 726 workgroups, at most 9 blocks on a CU against 12
+        //     with four: 9.9 against 10.9 us at M = 1; smaller differences do not show: 4096 x 28672 with 7 x 256).
+        auto busiest = [&](int cb) { const int64_t w = (n_cb + cb - 1) / cb; return ((w + 255) / 256) * cb; };
+        if (rows == 1 && !tune.small_waves && !tune.small_cbw && n_cb >= 1024) {
+            int best = c.cbw;
+            for (int cb = 8; cb >= 1; --cb) {
+                if ((even_cbw && (cb & 1)) || cb * c.ks > max_w || cb * c.ks * 64 < min_threads) continue;
+                if (busiest(cb) * 5 <= busiest(c.cbw) * 4 && busiest(cb) < busiest(best)) best = cb;
+            }
+            c.cbw = best;
+        }
+    }
     if (c.ks > n_kt) {
         c.ks = 1;
         while (c.ks * 2 <= n_kt) c.ks <<= 1;
     }
     // a run is at most MAX_RUN tiles: split K further (fewer column blocks per workgroup, then more waves)
-    while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw > 1 && !(even_cbw && c.cbw == 2)) { c.cbw >>= 1; c.ks <<= 1; }
-    while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw * c.ks < max_w) c.ks <<= 1;
+    while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw > 1 && !(c.cbw & 1) && !(even_cbw && c.cbw == 2)) { c.cbw >>= 1; c.ks <<= 1; }
+    while ((n_kt + c.ks - 1) / c.ks > MAX_RUN && c.cbw * c.ks * 2 <= max_w) c.ks <<= 1;
+    // The rows need the threads.  Up to four rows: one column block more at a time, not the next power of two
+    // (5120 x 34816 with four fp32 rows quantised in the kernel: ten waves 14.8 us, sixteen 20.5).
+    if (rows <= 4) {
+        const int step = even_cbw ? 2 : 1;
+        while (c.cbw * c.ks * 64 < min_threads && (c.cbw + step) * c.ks <= max_w) c.cbw += step;
+    }
+    while (c.cbw * c.ks * 64 < min_threads && c.cbw * c.ks * 2 <= max_w) c.cbw <<= 1;
     const int64_t run = (n_kt + c.ks - 1) / c.ks;
     const int64_t wgs = (n_cb + c.cbw - 1) / c.cbw;
     c.window = tune.gemv_window ? tune.gemv_window : (run > 4 && (wgs > 768 || wgs <= 256)) || c.cbw * c.ks == 4 ? 4 : 2;
@@ -603,6 +637,10 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
     }
     const Cfg c = pick(a8.tune, a8.n_cb, a8.n_kt, a8.epi.act == ACT_SILU_MUL, min_threads, max_w, (int)M, xt);
     const int waves = c.cbw * c.ks;
+    if (waves > max_w || (rl > 4 && (c.cbw & (c.cbw - 1))) || (a8.epi.act == ACT_SILU_MUL && (c.cbw & 1))) {
+        set_error("w2_matmul_a8[gemv]: workgroup shape %d x %d: at most %d waves, a power of two of column blocks from five rows on, an even number for the gated epilogue", c.cbw, c.ks, max_w);
+        return W2_ERR_INVALID_ARG;
+    }
     // local memory: header, rows, reduction scratch, the waves' scale slices; a CU has 160 KiB
     const size_t lds_need = HDR + xs_bytes + (size_t)waves * rl * 16 * sizeof(float) +
                             (size_t)waves * MAX_RUN * (TILE_N * (TILE_K / a8.G) * 2);
@@ -623,8 +661,11 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
     a.ldx = ldx; a.ldy = a8.ldy; a.N = a8.N; a.K = (int)K; a.M = (int)M;
     a.n_cb = (int)a8.n_cb; a.n_kt = (int)a8.n_kt;
     a.cbw = c.cbw; a.ks = c.ks;
-    a.cbw_shift = 0;
-    while ((1 << a.cbw_shift) < c.cbw) ++a.cbw_shift;
+    a.cbw_rcp = (256 + c.cbw - 1) / c.cbw;
+    {
+        const int outs = (a8.epi.act == ACT_SILU_MUL ? c.cbw / 2 : c.cbw) * 16;
+        a.outs_magic = ((1 << 20) + outs - 1) / outs;
+    }
     a.t_lo = (int)(a8.n_kt / c.ks); a.t_rem = (int)(a8.n_kt % c.ks);
     a.red_off = (int)(HDR + xs_bytes);
     a.sc_off = a.red_off + waves * rl * 16 * (int)sizeof(float);

@@ -180,6 +180,47 @@ def test_a8_gemv(w2, M, K, N, G, shape):
     run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_GEMV, seed=M + K + N + G, tune=tune)
 
 
+@pytest.mark.parametrize("cbw,ks", [(3, 1), (3, 4), (5, 2), (7, 2), (6, 2), (1, 3), (2, 5), (9, 1), (15, 1)])
+@pytest.mark.parametrize("K,N,G", [(1024, 272, 128), (2048, 1032, 64), (5120, 48, 128), (768, 8, 64)])
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+def test_a8_gemv_any_workgroup_width(w2, M, K, N, G, cbw, ks):
+    # up to four rows a workgroup of the decode kernel holds any number of column blocks (not only powers of
+    # two) times any number of K ranges: int32 accumulators, Y, the fused entry (same bits as quantise + matmul
+    # in the same shape) and, for even widths, the gated epilogue; a last workgroup with missing column blocks
+    if -(-(K // 256) // min(ks, K // 256)) > 16:
+        pytest.skip("a wave's run is limited to 16 tiles")
+    tune = {"gemv_cbw": cbw, "gemv_ks": ks}
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_GEMV, seed=M + K + N + G + cbw, tune=tune)
+    codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + cbw)
+    packed = w2.prepack(dev(codes), dev(scales), G, 0)
+    xq, sx, _ = w2.quantize_rows(dev(X), G)
+    Y2 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_GEMV, tune=tune)
+    if cbw * min(ks, K // 256) * 64 * 32 >= K * (1 if M == 1 else 2 if M == 2 else 4):      # the threads can hold the fp32 rows
+        Yf = w2.matmul_a8_fused_epi(packed, K, N, G, dev(X), tune=tune)
+        assert torch.equal(Yf.view(torch.int16), Y2.view(torch.int16))
+    if cbw % 2 == 0 and N % 32 == 0:
+        oq, osx, _ = oracle.quantize_rows(X, G)
+        _, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+        mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+        Yg = w2.matmul_a8_epi(packed, K, N, G, xq, sx, act=2, variant=w2.VARIANT_GEMV, tune=tune)
+        check_epilogue(bf16_bits(Yg), y64, mag, None, 2, f"gated, cbw={cbw} ks={ks} M={M}")
+
+
+def test_a8_gemv_workgroup_shape_limits(w2):
+    # shapes the kernel cannot run are refused before anything is launched
+    codes, scales, X = synth.make_problem(8, 512, 64, 128, 0, 3)
+    packed = w2.prepack(dev(codes), dev(scales), 128, 0)
+    xq, sx, _ = w2.quantize_rows(dev(X), 128)
+    for M, tune, act in ((1, {"gemv_cbw": 9, "gemv_ks": 2}, 0),        # more than 16 waves
+                         (8, {"gemv_cbw": 3, "gemv_ks": 2}, 0),        # the wide form: a power of two of column blocks
+                         (8, {"gemv_cbw": 8, "gemv_ks": 2}, 0),        # ... and at most 8 waves
+                         (1, {"gemv_cbw": 3, "gemv_ks": 2}, 2)):       # the gated epilogue pairs column blocks
+        Y = torch.full((M, 64), 7.0, dtype=torch.bfloat16, device="cuda")
+        with pytest.raises(w2.W2Error):
+            w2.matmul_a8_epi(packed, 512, 64, 128, xq[:M], sx[:M], act=act, out=Y, variant=w2.VARIANT_GEMV, tune=tune)
+        assert torch.all(Y == 7.0)
+
+
 @pytest.mark.parametrize("bf16_in", [False, True])
 @pytest.mark.parametrize("M", [1, 2, 4, 8])
 def test_production_kernels_hold_exact_group_sums(w2, M, bf16_in):
@@ -861,6 +902,7 @@ def test_argument_errors_write_nothing(w2):
     assert lib.w2_matmul_a8(p(packed), 256, 64, 128, None, p(sx), 1, p(Y), 64, None, 0, s) == w2.ERR_INVALID_ARG
     # overrides outside what the header allows are refused, field by field, before anything is launched
     for field, value in (("variant", 9), ("variant", w2.VARIANT_SCALED16), ("small_waves", 17), ("small_cbw", 3),
+                         ("gemv_cbw", 17), ("gemv_ks", -1),
                          ("small_kc", 100), ("midm_cbw", 3), ("tiled_bn", 32), ("splitk", 17), ("stream_unroll", 1),
                          ("tiled_group_m", -1)):
         t = w2.Tuning()
