@@ -532,7 +532,7 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     int variant = tn.variant;
     const int64_t n_out = epi.act == ACT_SILU_MUL ? N / 2 : N;
     if (variant != W2_VARIANT_AUTO && variant != W2_VARIANT_SMALLM && variant != W2_VARIANT_TILED &&
-        variant != W2_VARIANT_SCALED16 && variant != W2_VARIANT_MIDM)
+        variant != W2_VARIANT_SCALED16 && variant != W2_VARIANT_MIDM && variant != W2_VARIANT_GEMV)
         return fail(W2_ERR_INVALID_ARG, "%s: variant %d not available for w2a16", fn, variant);
     if (M == 0) return W2_OK;
     if (!packed || !X || !Y) return fail(W2_ERR_INVALID_ARG, "%s: NULL pointer", fn);
@@ -556,6 +556,7 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
     a.epi = epi;
     a.tune = tn;
     a.fold = variant == W2_VARIANT_SCALED16;
+    if (variant == W2_VARIANT_GEMV) return launch_a16_gemv(a, (hipStream_t)stream);
     if (variant == W2_VARIANT_SCALED16) {
         // the scale-folded construction: the small-M kernel with it, or the kernels built on it
         if (!a16_smallm_supports(a))
@@ -575,6 +576,7 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         const int midm_max = tn.midm_max_m ? tn.midm_max_m
                            : a.n_cb <= 256 ? (a.part_bytes && a.n_kt > 32 ? 64 : 128) : a.n_cb >= 2048 ? 40 : 64;
         if (M >= midm_min && M <= midm_max && a16_midm_supports(a)) return launch_a16_midm(a, (hipStream_t)stream);
+        if (a16_gemv_supports(a)) return launch_a16_gemv(a, (hipStream_t)stream);      // up to four rows: the decode kernel
         if (!a16_smallm_supports(a)) return launch_a16_fold_tiled(a, (hipStream_t)stream);
         variant = W2_VARIANT_SMALLM;
     }

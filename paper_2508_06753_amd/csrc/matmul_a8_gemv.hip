@@ -50,8 +50,44 @@ constexpr int HDR = 512;          // LDS: abs-max partials [16 waves][4 rows] fp
 constexpr int SX_SLOT = 64;       // ... the scales' first float
 // most 16-byte pieces of the activation rows a thread holds in registers: 8 for up to four rows (workgroups of
 // up to 16 waves, 128 registers a lane), 32 for the wide form (up to 8 waves, 256 registers)
-constexpr int xslots(int RL) { return RL > 4 ? 32 : 8; }
-constexpr int max_waves(int RL) { return RL > 4 ? 8 : 16; }
+// (bf16 rows left unquantised, XT 3: 16 slots, up to 8 waves of up to 256 registers)
+constexpr int xslots(int RL, int XT = 0) { return RL > 4 ? 32 : XT == 3 ? 16 : 8; }
+constexpr int max_waves(int RL, int XT = 0) { return RL > 4 || XT == 3 ? 8 : 16; }
+
+// ---- w2a16 in the same kernel (XT 3; Sec. II-D, "Alternative implementation": the activations stay bf16, the
+// weights become 16-bit values in registers and go to the 16-bit matrix instruction, fp32 accumulation).
+// The up-convert is the one of the other w2a16 kernels: XOR 0xAAAAAAAA turns every field into s = q + 2, OR-ing a
+// field into the mantissa of the bf16 constant 128 gives 130 + q, two weights per (shift, and-or); the matrix
+// instruction then sums x * (130 + q) and a group's accumulator STARTS from -130 * (sum of the group's x), which
+// the staging pass leaves in local memory, so that the group ends as sum x * q and the dequant is one fma.
+// Operand dwords 0..3 take their two weights from bytes 0 and 2 of the code word (even k of the lane's 16-k
+// block), dwords 4..7 from bytes 1 and 3 (odd k); the rows are staged de-interleaved the same way.
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+constexpr float ZP16 = 130.0f;
+struct Bf16Consts { uint32_t mask, base; };
+__device__ __forceinline__ Bf16Consts bf16_consts()
+{
+    Bf16Consts c = {0x00030003u, 0x43004300u};
+    asm volatile("" : "+v"(c.mask), "+v"(c.base));           // in vector registers: (x & mask) | base is one instruction
+    return c;
+}
+__device__ __forceinline__ void upconvert_bf16(uint32_t w, const Bf16Consts& c, v4i& b0, v4i& b1)
+{
+    const uint32_t x = w ^ 0xAAAAAAAAu;
+    b0[0] = (int)((x & c.mask) | c.base);
+    b0[1] = (int)(((x >> 2) & c.mask) | c.base);
+    b0[2] = (int)(((x >> 4) & c.mask) | c.base);
+    b0[3] = (int)(((x >> 6) & c.mask) | c.base);
+    b1[0] = (int)(((x >> 8) & c.mask) | c.base);
+    b1[1] = (int)(((x >> 10) & c.mask) | c.base);
+    b1[2] = (int)(((x >> 12) & c.mask) | c.base);
+    b1[3] = (int)(((x >> 14) & c.mask) | c.base);
+}
+__device__ __forceinline__ v4f mfma_bf16(const v4i& a, const v4i& b, const v4f& c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+}
 
 struct Args {
     // What a wave needs before it can issue its first loads comes first, 64 bytes that one scalar load fetches:
@@ -69,6 +105,7 @@ struct Args {
     int outs_magic;               // ceil(2^20 / outputs per row of a workgroup): item / outputs for items below 4096
     int red_off;                  // LDS offset of the reduction scratch
     int sc_off;                   // LDS offset of the waves' scale slices
+    int xg_off;                   // XT 3: LDS offset of -130 * (group sums of the rows), [K / G][4 rows] fp32
     const float* sx;              // XT 0: activation scales [M]
     uint16_t* Y;
     int32_t* acc_out;             // debug export (XT 0)
@@ -120,10 +157,12 @@ __device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, ui
 // two (the up-converted operand then feeds two matrix instructions).
 // NP: 16-byte pieces per row and thread (a launch-time choice: the row's pieces / the workgroup's threads, rounded up)
 template <int G, int RL, int XT, int W, int NP, bool DBG>
-__global__ void __launch_bounds__(64 * max_waves(RL))
+__global__ void __launch_bounds__(64 * max_waves(RL, XT))
 a8_gemv_kernel(Args a)
 {
     constexpr bool WIDE = RL > 4;
+    constexpr bool A16 = XT == 3;                            // bf16 rows, bf16 matrix instruction
+    static_assert(!A16 || (RL <= 4 && !DBG), "the w2a16 form: up to four rows");
     constexpr int RA = WIDE ? 4 : RL;                        // accumulator rows a lane folds into y
     constexpr int RT = RL > 16 ? RL / 16 : 1;                // 16-row tiles
     static_assert(!WIDE || XT == 0, "the wide form takes int8 rows");
@@ -141,16 +180,16 @@ a8_gemv_kernel(Args a)
     const int cbc = cb_ok ? cb : a.n_cb - 1;                 // clamp: keeps loads in bounds
     const int kt_b = ksi * a.t_lo + min(ksi, a.t_rem);       // this wave's run of tiles
     const int T = a.t_lo + (ksi < a.t_rem ? 1 : 0);
-    const int row_stride = a.K + XS_PAD;
+    const int row_stride = a.K * (A16 ? 2 : 1) + XS_PAD;
     float* s_red = reinterpret_cast<float*>(smem);           // [16 waves][4 rows]
     int8_t* xs = smem + HDR;                                 // int8 rows
 
     W2_GEMV_MARK_DECL;
     W2_GEMV_MARK(0);
     // ---- 1. the activation rows: unconditional vector loads, issued before the weight loads
-    constexpr int ES = XT == 1 ? 4 : XT == 2 ? 2 : 1;        // bytes per source element
+    constexpr int ES = XT == 1 ? 4 : XT >= 2 ? 2 : 1;        // bytes per source element
     constexpr int PR = NP;                                   // register slots per row
-    static_assert(NP * RL <= xslots(RL), "too many register slots");
+    static_assert(NP * RL <= xslots(RL, XT), "too many register slots");
     const int ppr = a.K * ES / 16;                           // 16-byte pieces per row
     uint4 pc[RL][PR];
 #pragma unroll
@@ -214,6 +253,39 @@ a8_gemv_kernel(Args a)
             }
         // (here, not at the load: a store right behind it would hold up the weight loads)
         if (!DBG && !SX_IN_REGS && tid < a.M) s_red[SX_SLOT + tid] = sx_mine;
+    } else if constexpr (A16) {
+        // bf16 rows as they are, de-interleaved per 16-k block ([8 even k | 8 odd k]: the two matrix operands of
+        // a lane are then one 16-byte read each), and -130 x the sum of every group of every row.  A piece
+        // is 8 values; the G / 8 pieces of a group sit in consecutive lanes of one row of 16 lanes.
+        constexpr int PPG = G / 8;
+        float* xg = reinterpret_cast<float*>(smem + a.xg_off);
+#pragma unroll
+        for (int r = 0; r < RL; ++r)
+#pragma unroll
+            for (int j = 0; j < PR; ++j) {
+                const int i = tid + j * threads;
+                const uint32_t d[4] = {pc[r][j].x, pc[r][j].y, pc[r][j].z, pc[r][j].w};
+                float sum = 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sum += __uint_as_float(d[e] << 16) + __uint_as_float(d[e] & 0xffff0000u);
+                sum += dpp_move_f32<0xB1>(sum);              // pairs, quads, eights, (sixteen) lanes: every lane
+                sum += dpp_move_f32<0x4E>(sum);              // ends with its group's sum, added in one fixed order
+                sum += dpp_move_f32<0x141>(sum);
+                if constexpr (PPG == 16) sum += dpp_move_f32<0x140>(sum);
+                if (i < ppr && r < a.M) {
+                    const uint2 ev = make_uint2(__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u));
+                    const uint2 od = make_uint2(__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u));
+                    int8_t* blk = xs + r * row_stride + (i >> 1) * 32 + (i & 1) * 8;
+                    *reinterpret_cast<uint2*>(blk) = ev;
+                    *reinterpret_cast<uint2*>(blk + 16) = od;
+                    if ((i & (PPG - 1)) == 0) xg[(i / PPG) * 4 + r] = -ZP16 * sum;
+                }
+            }
+        // no activation scale: the epilogue's sx * 2^-6 is exactly 1
+        if constexpr (SX_IN_REGS) {
+#pragma unroll
+            for (int r = 0; r < RL; ++r) sxv[r] = 64.0f;
+        } else if (tid < 4) s_red[SX_SLOT + tid] = 64.0f;
     } else {
         float amax[RL];
 #pragma unroll
@@ -294,6 +366,9 @@ a8_gemv_kernel(Args a)
     // group's first matrix instruction has been issued, so its int -> float conversion does not wait
     // for the matrix pipe.
     v4i acc[2][RT];
+    v4f accf[2] = {v4f{0.f, 0.f, 0.f, 0.f}, v4f{0.f, 0.f, 0.f, 0.f}};      // the w2a16 form's
+    const Bf16Consts kc = bf16_consts();
+    (void)kc; (void)accf;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) acc[0][rt] = acc[1][rt] = v4i{0, 0, 0, 0};
     float pend_sw = 0.f;                                     // scale of the group waiting in acc[1]: none yet
@@ -309,7 +384,8 @@ a8_gemv_kernel(Args a)
                     if (pend_g >= 0 && (WIDE || q == 0) && cb_ok && n < a.N && row < a.M)
                         a.acc_out[((int64_t)row * (a.K / G) + pend_g) * a.N + n] = acc[b][rt][r] >> 6;
                 }
-                y[rt][r] = fmaf(pend_sw, (float)acc[b][rt][r], y[rt][r]);
+                if constexpr (A16) y[rt][r] = fmaf(pend_sw, accf[b][r], y[rt][r]);
+                else y[rt][r] = fmaf(pend_sw, (float)acc[b][rt][r], y[rt][r]);
             }
     };
     // LDS address of this lane's A operand: row (lane & 15, padded rows repeat the last), 16-byte piece lane >> 4
@@ -317,14 +393,30 @@ a8_gemv_kernel(Args a)
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         const int arow = rt * 16 + l16 < a.M ? rt * 16 + l16 : a.M - 1;
-        a_lane[rt] = (uint32_t)(HDR + arow * row_stride + q * 16);
+        a_lane[rt] = (uint32_t)(HDR + arow * row_stride + q * (A16 ? 32 : 16));
     }
-    auto read_aop = [&](int kt, v4i (&aop)[RT][4]) {
+    constexpr int NA = A16 ? 8 : 4;                          // A operands per tile and row tile
+    auto read_aop = [&](int kt, v4i (&aop)[RT][NA]) {
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-            const int8_t* p = smem + a_lane[rt] + (uint32_t)kt * TILE_K;
+            const int8_t* p = smem + a_lane[rt] + (uint32_t)kt * (TILE_K * (A16 ? 2 : 1));
 #pragma unroll
-            for (int t = 0; t < 4; ++t) aop[rt][t] = *reinterpret_cast<const v4i*>(p + t * 64);
+            for (int t = 0; t < 4; ++t) {
+                if constexpr (A16) {
+                    aop[rt][2 * t] = *reinterpret_cast<const v4i*>(p + t * 128);            // even k of the lane's block
+                    aop[rt][2 * t + 1] = *reinterpret_cast<const v4i*>(p + t * 128 + 16);   // odd k
+                } else {
+                    aop[rt][t] = *reinterpret_cast<const v4i*>(p + t * 64);
+                }
+            }
+        }
+    };
+    // w2a16: what a group's accumulator starts from, rows 0..3 of the tile's groups (every lane reads the same)
+    auto read_cinit = [&](int kt, v4f (&ci)[GPT]) {
+        if constexpr (A16) {
+            const float* xg = reinterpret_cast<const float*>(smem + a.xg_off) + kt * (GPT * 4);
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) ci[g] = *reinterpret_cast<const v4f*>(xg + g * 4);
         }
     };
     const int8_t* sc_lane = sc_lds + l16 * (GPT * 2);
@@ -337,20 +429,27 @@ a8_gemv_kernel(Args a)
             sc[0] = t.x; sc[1] = t.y;
         }
     };
-    auto compute = [&](int kt, const u32x4& cur, const uint32_t (&sc)[2], const v4i (&aop)[RT][4]) {
+    auto compute = [&](int kt, const u32x4& cur, const uint32_t (&sc)[2], const v4i (&aop)[RT][NA], const v4f (&ci)[GPT]) {
         const uint32_t wd[4] = {cur[0], cur[1], cur[2], cur[3]};
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            int u[4];
-            upconvert(wd[t], u);
-            const v4i bop = {u[0], u[1], u[2], u[3]};
             const int gi = G == 64 ? t : t >> 1;             // group inside the tile
             const int b = gi & 1;                            // its accumulator (groups per tile are even)
             const bool first = G == 64 || !(t & 1);
-            const v4i zero = {0, 0, 0, 0};
+            if constexpr (A16) {
+                v4i b0, b1;
+                upconvert_bf16(wd[t], kc, b0, b1);
+                accf[b] = mfma_bf16(aop[0][2 * t], b0, first ? ci[gi] : accf[b]);
+                accf[b] = mfma_bf16(aop[0][2 * t + 1], b1, accf[b]);
+            } else {
+                int u[4];
+                upconvert(wd[t], u);
+                const v4i bop = {u[0], u[1], u[2], u[3]};
+                const v4i zero = {0, 0, 0, 0};
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
-                acc[b][rt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[rt][t], bop, first ? zero : acc[b][rt], 0, 0, 0);
+                for (int rt = 0; rt < RT; ++rt)
+                    acc[b][rt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[rt][t], bop, first ? zero : acc[b][rt], 0, 0, 0);
+            }
             if (first) dequant(b ^ 1);                       // the group before this one
             if (G == 64 || (t & 1)) {
                 const uint32_t pair = (G == 128 || gi < 2) ? sc[0] : sc[1];
@@ -359,10 +458,12 @@ a8_gemv_kernel(Args a)
             }
         }
     };
-    v4i aop[2][RT][4];
+    v4i aop[2][RT][NA];
     uint32_t scl[2][2];
+    v4f cin[2][GPT];
     read_aop(kt_b, aop[0]);
     read_scales(0, scl[0]);
+    read_cinit(kt_b, cin[0]);
     for (int base = 0; base < T; base += W) {
 #pragma unroll
         for (int u = 0; u < W; ++u) {
@@ -374,7 +475,8 @@ a8_gemv_kernel(Args a)
             if (i < T) {                                     // uniform
                 read_aop(kt_b + min(i + 1, T - 1), aop[(u + 1) & 1]);     // a tile ahead; clamped: stays inside the rows
                 read_scales(min(i + 1, T - 1), scl[(u + 1) & 1]);
-                compute(kt_b + i, cur, scl[u & 1], aop[u & 1]);
+                read_cinit(kt_b + min(i + 1, T - 1), cin[(u + 1) & 1]);
+                compute(kt_b + i, cur, scl[u & 1], aop[u & 1], cin[u & 1]);
                 if (i == 0) { W2_GEMV_MARK(3); }
             }
         }
@@ -534,7 +636,7 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
         while (ks < max_w && (n_kt + ks - 1) / ks > MAX_RUN) ks <<= 1;
         c.ks = ks;
         c.cbw = ks >= 8 ? 1 : 8 / ks;                        // eight waves; sixteen when ks = 16
-        if (xt != 0 && ks == 8 && n_kt <= 32 && (n_cb >= 320 || rows <= 2) && 4 * (n_cb >= 320 ? 2 : 1) * 64 >= min_threads) {
+        if ((xt == 1 || xt == 2) && ks == 8 && n_kt <= 32 && (n_cb >= 320 || rows <= 2) && 4 * (n_cb >= 320 ? 2 : 1) * 64 >= min_threads) {
             // rows quantised in the kernel, narrow projection: every workgroup re-reads and re-quantises the
             // row, so half as many k-ranges (runs of four or five tiles) and, from 320 column blocks on, two
             // column blocks per workgroup (4096 x 6144 4.5 against 4.9 us, 5120 x 5120 4.9 against 5.5;
@@ -543,6 +645,12 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
             c.ks = 4;
             c.cbw = n_cb >= 320 ? 2 : 1;
         }
+    }
+    if (xt == 3 && rows == 1 && n_cb >= 1024 && n_kt >= 4 && n_kt <= 4 * MAX_RUN && !tune.small_waves && !tune.small_cbw && !even_cbw) {
+        // w2a16 (twice the vector work per code word), one row, wide projection: small workgroups of four waves
+        // spread evenly over the CUs (4096 x 28672: 9.4 us against 10.0 with 4 x 2 waves; 5120 x 34816: 13.7 against 14.7)
+        c.cbw = 1;
+        c.ks = 4;
     }
     if (even_cbw && (c.cbw & 1)) c.cbw = 2;                  // the gated epilogue pairs adjacent column blocks
     while (c.cbw * c.ks > max_w) {                           // at most 16 waves (8 in the wide form)
@@ -580,7 +688,8 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
     while (c.cbw * c.ks * 64 < min_threads && c.cbw * c.ks * 2 <= max_w) c.cbw <<= 1;
     const int64_t run = (n_kt + c.ks - 1) / c.ks;
     const int64_t wgs = (n_cb + c.cbw - 1) / c.cbw;
-    c.window = tune.gemv_window ? tune.gemv_window : (run > 4 && (wgs > 768 || wgs <= 256)) || c.cbw * c.ks == 4 ? 4 : 2;
+    // (w2a16: a window of two everywhere; deeper ones lost on every shape of the sweep)
+    c.window = tune.gemv_window ? tune.gemv_window : xt == 3 ? 2 : (run > 4 && (wgs > 768 || wgs <= 256)) || c.cbw * c.ks == 4 ? 4 : 2;
     return c;
 }
 
@@ -601,10 +710,11 @@ static int launch_w(const Args& a, const Cfg& c, size_t lds, hipStream_t stream)
 template <int G, int RL, int XT, bool DBG>
 static int launch_np(const Args& a, const Cfg& c, size_t lds, int np, hipStream_t stream)
 {
-    constexpr int MAXNP = xslots(RL) / RL;
+    constexpr int MAXNP = xslots(RL, XT) / RL;
     if (np <= 1) return launch_w<G, RL, XT, 1, DBG>(a, c, lds, stream);
     if constexpr (MAXNP >= 2) { if (np <= 2) return launch_w<G, RL, XT, 2, DBG>(a, c, lds, stream); }
     if constexpr (MAXNP >= 4) { if (np <= 4) return launch_w<G, RL, XT, 4, DBG>(a, c, lds, stream); }
+    if constexpr (MAXNP >= 8) { if (np <= 8) return launch_w<G, RL, XT, 8, DBG>(a, c, lds, stream); }
     return launch_w<G, RL, XT, MAXNP, DBG>(a, c, lds, stream);
 }
 
@@ -701,6 +811,73 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
     W2_GEMV_WIDE(64, 32);
 #undef W2_GEMV_WIDE
 #undef W2_GEMV
+}
+
+// w2a16 through the same kernel: bf16 rows as they are, up to four of them, where a workgroup of eight waves
+// can hold them (local memory and registers); false: the caller takes another kernel.
+bool a16_gemv_supports(const A16Args& a)
+{
+    using namespace gemv;
+    if (a.M < 1 || a.M > 4) return false;
+    const int rl = a.M <= 1 ? 1 : a.M <= 2 ? 2 : 4;
+    const int64_t ppr = a.K * 2 / 16;
+    const int pr = xslots(rl, 3) / rl;
+    const size_t lds = HDR + (size_t)a.M * (a.K * 2 + XS_PAD) + 16 + 8 * (size_t)rl * 16 * sizeof(float) +
+                       8 * (size_t)MAX_RUN * (TILE_N * (TILE_K / a.G) * 2) + (size_t)(a.K / a.G) * 16;
+    return (ppr + pr - 1) / pr <= 64 * 8 && lds <= 160 * 1024 && (a.n_kt + 7) / 8 <= MAX_RUN;
+}
+
+int launch_a16_gemv(const A16Args& a16, hipStream_t stream)
+{
+    using namespace gemv;
+    if (!a16_gemv_supports(a16)) {
+        set_error("w2_matmul_a16[gemv]: M must be 1..4 and the rows must fit one workgroup");
+        return W2_ERR_UNSUPPORTED_SHAPE;
+    }
+    const int64_t M = a16.M, K = a16.K;
+    const int rl = M <= 1 ? 1 : M <= 2 ? 2 : 4;
+    const int max_w = max_waves(rl, 3);
+    const int64_t ppr = K * 2 / 16;
+    const int pr = xslots(rl, 3) / rl;
+    const int min_threads = (int)((ppr + pr - 1) / pr);
+    const size_t xs_bytes = ((size_t)M * (K * 2 + XS_PAD) + 15) & ~(size_t)15;
+    const Cfg c = pick(a16.tune, a16.n_cb, a16.n_kt, a16.epi.act == ACT_SILU_MUL, min_threads, max_w, (int)M, 3);
+    const int waves = c.cbw * c.ks;
+    if (waves > max_w || waves * 64 < min_threads || (a16.epi.act == ACT_SILU_MUL && (c.cbw & 1)) ||
+        (a16.n_kt + c.ks - 1) / c.ks > MAX_RUN) {
+        set_error("w2_matmul_a16[gemv]: workgroup shape %d x %d cannot run this problem (at most %d waves, %d threads for the rows, runs of %d tiles)",
+                  c.cbw, c.ks, max_w, min_threads, MAX_RUN);
+        return a16.tune.gemv_cbw || a16.tune.gemv_ks ? W2_ERR_INVALID_ARG : W2_ERR_UNSUPPORTED_SHAPE;
+    }
+    Args a;
+    a.codes = a16.codes; a.scales = a16.scales; a.X = a16.X; a.sx = nullptr; a.Y = a16.Y; a.acc_out = nullptr;
+    a.ldx = a16.ldx; a.ldy = a16.ldy; a.N = a16.N; a.K = (int)K; a.M = (int)M;
+    a.n_cb = (int)a16.n_cb; a.n_kt = (int)a16.n_kt;
+    a.cbw = c.cbw; a.ks = c.ks;
+    a.cbw_rcp = (256 + c.cbw - 1) / c.cbw;
+    {
+        const int outs = (a16.epi.act == ACT_SILU_MUL ? c.cbw / 2 : c.cbw) * 16;
+        a.outs_magic = ((1 << 20) + outs - 1) / outs;
+    }
+    a.t_lo = (int)(a16.n_kt / c.ks); a.t_rem = (int)(a16.n_kt % c.ks);
+    a.red_off = (int)(HDR + xs_bytes);
+    a.sc_off = a.red_off + waves * rl * 16 * (int)sizeof(float);
+    a.xg_off = a.sc_off + waves * MAX_RUN * (TILE_N * (TILE_K / a16.G) * 2);
+    a.epi = a16.epi;
+    const size_t lds = (size_t)a.xg_off + (size_t)(K / a16.G) * 16;
+    if (lds > 160 * 1024) {
+        set_error("w2_matmul_a16[gemv]: the rows do not fit a workgroup's local memory");
+        return W2_ERR_UNSUPPORTED_SHAPE;
+    }
+    const int np = (int)((ppr + waves * 64 - 1) / (waves * 64));
+    if (a16.G == 128) {
+        if (rl == 1) return launch_np<128, 1, 3, false>(a, c, lds, np, stream);
+        if (rl == 2) return launch_np<128, 2, 3, false>(a, c, lds, np, stream);
+        return launch_np<128, 4, 3, false>(a, c, lds, np, stream);
+    }
+    if (rl == 1) return launch_np<64, 1, 3, false>(a, c, lds, np, stream);
+    if (rl == 2) return launch_np<64, 2, 3, false>(a, c, lds, np, stream);
+    return launch_np<64, 4, 3, false>(a, c, lds, np, stream);
 }
 
 }  // namespace w2

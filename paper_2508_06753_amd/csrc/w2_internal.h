@@ -111,6 +111,9 @@ bool a16_smallm_supports(const A16Args& a);
 int launch_a16_smallm(const A16Args& a, hipStream_t stream);
 int launch_a16_tiled(const A16Args& a, hipStream_t stream);
 int launch_a16_fold_tiled(const A16Args& a, hipStream_t stream);
+// w2a16 through the decode kernel (bf16 rows as they are, M <= 4, rows that fit one workgroup)
+bool a16_gemv_supports(const A16Args& a);
+int launch_a16_gemv(const A16Args& a, hipStream_t stream);
 bool a16_midm_supports(const A16Args& a);
 int launch_a16_midm(const A16Args& a, hipStream_t stream);
 

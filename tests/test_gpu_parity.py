@@ -708,7 +708,7 @@ def test_a8_fused_entry_with_epilogue_and_split_k(w2, M, act):
     check_epilogue(bf16_bits(Y), y64, mag, bias, act, f"fused entry + epilogue M={M} act={act}")
 
 
-A16_EPI_VARIANTS = [("SMALLM", 2, [1, 5, 16]), ("SCALED16 small", 5, [3]), ("MIDM", 4, [9, 40, 100]),
+A16_EPI_VARIANTS = [("GEMV", 6, [1, 2, 3]), ("SMALLM", 2, [1, 5, 16]), ("SCALED16 small", 5, [3]), ("MIDM", 4, [9, 40, 100]),
                     ("SCALED16 tiled", 5, [130]), ("TILED", 3, [70])]
 
 
@@ -765,6 +765,52 @@ def run_a16_case(w2, M, K, N, G, codec, variant, seed, tune=None):
 @pytest.mark.parametrize("M", [1, 4, 7, 16])
 def test_a16_smallm(w2, M, K, N, G):
     run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_SMALLM, seed=M + K + N + G)
+
+
+@pytest.mark.parametrize("shape", [None, (1, 1, 2), (3, 2, 2), (8, 1, 4), (2, 4, 8), (5, 1, 2), (1, 8, 2)])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", SMALL_SHAPES + [(5120, 48), (14336, 40)])
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+def test_a16_gemv(w2, M, K, N, G, shape):
+    # w2a16 through the decode kernel (bf16 rows as they are, bf16 matrix instruction, the group's accumulator
+    # started from -130 x the group's row sum): the library's workgroup shape and forced ones (column blocks,
+    # K ranges, window), runs of one tile and runs longer than the window, long rows, ragged N
+    tune = None
+    if shape is not None:
+        cbw, ks, win = shape
+        ks = min(ks, K // 256)
+        rl = 1 if M == 1 else 2 if M == 2 else 4
+        if -(-(K // 256) // ks) > 16 or cbw * ks * 64 * (16 // rl) < K // 8:
+            pytest.skip("a run is limited to 16 tiles / the threads must hold the rows")
+        tune = {"gemv_cbw": cbw, "gemv_ks": ks, "gemv_window": win}
+    run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_GEMV, seed=M + K + N + G, tune=tune)
+
+
+def test_a16_gemv_exact_integers_and_limits(w2):
+    # unit scales, small-integer activations: every product and sum is exact whatever the order
+    K, N, G = 4096, 80, 128
+    codes, _, _ = synth.make_problem(1, K, N, G, 0, 5)
+    ones = np.full((K // G, N), 0x3F80, np.uint16)
+    packed = w2.prepack(dev(codes), dev(ones), G, 0)
+    rng = np.random.default_rng(1)
+    Xi = (rng.integers(-1, 2, size=(4, K)) * (rng.random((4, K)) < 0.05)).astype(np.float32)
+    ref = Xi.astype(np.int64) @ (codes.astype(np.int64) - 2)
+    assert np.abs(ref).max() < 256
+    for M in (1, 2, 4):
+        Y = w2.matmul_a16(packed, K, N, G, dev(synth.f32_to_bf16_bits(Xi[:M])).view(torch.bfloat16), variant=w2.VARIANT_GEMV)
+        assert np.array_equal(bits_to_f64(bf16_bits(Y)), ref[:M].astype(np.float64))
+    # five rows, or rows that do not fit a workgroup: refused when forced (AUTO takes another kernel)
+    X5 = torch.zeros((5, K), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(w2.W2Error):
+        w2.matmul_a16(packed, K, N, G, X5, variant=w2.VARIANT_GEMV)
+    Kb = 28672
+    codes, scales, X = synth.make_problem(4, Kb, 16, 128, 0, 6)
+    pk = w2.prepack(dev(codes), dev(scales), 128, 0)
+    Xd = dev(synth.f32_to_bf16_bits(X)).view(torch.bfloat16)
+    with pytest.raises(w2.W2Error):
+        w2.matmul_a16(pk, Kb, 16, 128, Xd, variant=w2.VARIANT_GEMV)
+    run_a16_case(w2, 4, Kb, 16, 128, 0, w2.VARIANT_AUTO, seed=6)       # ... and AUTO still answers
+    run_a16_case(w2, 1, Kb, 16, 128, 0, w2.VARIANT_GEMV, seed=7)       # one such row fits
 
 
 @pytest.mark.parametrize("G", [64, 128])
