@@ -25,6 +25,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# per-file additions: the decode kernel asks for its first sixteen dwords of scalar kernel arguments to be
+# handed over in registers at wave launch (the compiled entry still fetches them itself where the machine does not)
+EXTRA_FLAGS = {"matmul_a8_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"]}
+
+
 def _newer(target, deps):
     if not os.path.exists(target):
         return False
@@ -42,7 +47,7 @@ def build(force=False, verbose=True):
         obj = os.path.join(OBJDIR, s.replace(".hip", ".o"))
         objs.append(obj)
         if force or not _newer(obj, [src] + hdrs):
-            jobs.append([HIPCC] + FLAGS + ["-c", src, "-o", obj])
+            jobs.append([HIPCC] + FLAGS + EXTRA_FLAGS.get(s, []) + ["-c", src, "-o", obj])
 
     def run(cmd):
         if verbose:

@@ -156,10 +156,31 @@ __device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, ui
 // uses every accumulator row: lane (q, l) holds rows 4q..4q+3 of column l, for one row tile or, at RL = 32,
 // two (the up-converted operand then feeds two matrix instructions).
 // NP: 16-byte pieces per row and thread (a launch-time choice: the row's pieces / the workgroup's threads, rounded up)
+// The kernel takes the head of Args as scalar parameters, fourteen dwords, and the rest as a structure: the
+// first fourteen dwords of scalar kernel arguments can be handed to a wave in registers at its launch (the build
+// asks for that, for this file only), so the first loads wait for no argument fetch at all; where the machine
+// does not preload, the compiled entry fetches them with one scalar load as before.
+struct ArgsRest {
+    int ks, outs_magic, red_off, sc_off, xg_off;
+    const float* sx;
+    uint16_t* Y;
+    int32_t* acc_out;
+    int64_t ldy, N;
+    Epilogue epi;
+};
+
 template <int G, int RL, int XT, int W, int NP, bool DBG>
 __global__ void __launch_bounds__(64 * max_waves(RL, XT))
-a8_gemv_kernel(Args a)
+a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const uint16_t* p_scales, int p_K, int p_M,
+               int p_n_cb, int p_n_kt, int p_cbw_rcp, int p_shape, ArgsRest rest)
 {
+    Args a;
+    a.X = p_X; a.ldx = p_ldx; a.codes = p_codes; a.scales = p_scales; a.K = p_K; a.M = p_M; a.n_cb = p_n_cb;
+    a.n_kt = p_n_kt; a.cbw_rcp = p_cbw_rcp;
+    // fourteen dwords fit the registers: the workgroup's shape and the K ranges travel in one of them
+    a.cbw = p_shape & 0xff; a.ks = (p_shape >> 8) & 0xff; a.t_lo = (p_shape >> 16) & 0xff; a.t_rem = (p_shape >> 24) & 0xff; a.outs_magic = rest.outs_magic; a.red_off = rest.red_off; a.sc_off = rest.sc_off;
+    a.xg_off = rest.xg_off; a.sx = rest.sx; a.Y = rest.Y; a.acc_out = rest.acc_out; a.ldy = rest.ldy; a.N = rest.N;
+    a.epi = rest.epi;
     constexpr bool WIDE = RL > 4;
     constexpr bool A16 = XT == 3;                            // bf16 rows, bf16 matrix instruction
     static_assert(!A16 || (RL <= 4 && !DBG), "the w2a16 form: up to four rows");
@@ -171,7 +192,7 @@ a8_gemv_kernel(Args a)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n_waves = __builtin_amdgcn_readfirstlane((int)blockDim.x >> 6);
+    const int n_waves = a.cbw * a.ks;                        // = blockDim.x / 64
     const int threads = n_waves * 64;
     const int ksi = (wave * a.cbw_rcp) >> 8, cbi = wave - ksi * a.cbw;
     const int q = lane >> 4, l16 = lane & 15;
@@ -699,7 +720,11 @@ static int launch_w(const Args& a, const Cfg& c, size_t lds, hipStream_t stream)
     const dim3 grid((unsigned)((a.n_cb + c.cbw - 1) / c.cbw)), block(64 * c.cbw * c.ks);
     auto go = [&](auto kern) {
         if (int rc = ensure_dynamic_lds((const void*)kern, lds, "w2_matmul_a8[gemv]")) return rc;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
+        ArgsRest r;
+        r.ks = a.ks; r.outs_magic = a.outs_magic; r.red_off = a.red_off; r.sc_off = a.sc_off; r.xg_off = a.xg_off;
+        r.sx = a.sx; r.Y = a.Y; r.acc_out = a.acc_out; r.ldy = a.ldy; r.N = a.N; r.epi = a.epi;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, a.X, a.ldx, a.codes, a.scales, a.K, a.M, a.n_cb, a.n_kt,
+                           a.cbw_rcp, a.cbw | (a.ks << 8) | (a.t_lo << 16) | (a.t_rem << 24), r);
         return check_launch("w2_matmul_a8[gemv]");
     };
     if (c.window >= 8) return go(a8_gemv_kernel<G, RL, XT, 8, NP, DBG>);
@@ -766,7 +791,7 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
         set_error("w2_matmul_a8[gemv]: K too deep for this workgroup shape (a wave's run is limited to %d tiles)", MAX_RUN);
         return W2_ERR_UNSUPPORTED_SHAPE;
     }
-    Args a;
+    Args a = {};
     a.codes = a8.codes; a.scales = a8.scales; a.X = X; a.sx = a8.sx; a.Y = a8.Y; a.acc_out = a8.acc_out;
     a.ldx = ldx; a.ldy = a8.ldy; a.N = a8.N; a.K = (int)K; a.M = (int)M;
     a.n_cb = (int)a8.n_cb; a.n_kt = (int)a8.n_kt;
