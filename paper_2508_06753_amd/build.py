@@ -25,9 +25,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-# per-file additions: the decode kernel asks for its first sixteen dwords of scalar kernel arguments to be
+# per-file additions: the decode kernel asks for the first dwords of its scalar kernel arguments to be
 # handed over in registers at wave launch (the compiled entry still fetches them itself where the machine does not)
-EXTRA_FLAGS = {"matmul_a8_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"]}
+_PRELOAD = ["-mllvm", "-amdgpu-kernarg-preload-count=16"]
+# (also the row quantiser and the streaming-read probe the decode kernel is compared with: scalar parameters already)
+EXTRA_FLAGS = {"matmul_a8_gemv.hip": _PRELOAD, "quantize.hip": _PRELOAD, "api.hip": _PRELOAD}
 
 
 def _newer(target, deps):
