@@ -262,6 +262,10 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
 #pragma unroll
     for (int u = 0; u < W; ++u) issue(u, tr[u]);
     W2_GEMV_MARK(1);
+    // The rest of the arguments, fetched here, under the latency of the loads just issued: left to the compiler
+    // their scalar loads sit right in front of the first barrier and in the epilogue, where a wave waits them out.
+    asm volatile("" ::"s"(a.red_off), "s"(a.sc_off), "s"(a.xg_off), "s"(a.outs_magic), "s"(a.sx), "s"(a.Y), "s"(a.acc_out),
+                 "s"(a.ldy), "s"(a.N), "s"(a.epi.bias), "s"(a.epi.act));
 
     // ---- 3. quantise (or copy) the rows into LDS
     if constexpr (XT == 0) {
