@@ -694,9 +694,8 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
                 if ((even_cbw && (cb & 1)) || cb * c.ks > max_w || cb * c.ks * 64 < min_threads) continue;
                 if (busiest(cb) * 5 <= busiest(c.cbw) * 4 && busiest(cb) < busiest(best)) best = cb;
             }
-            // (where no width does: 4096 x 28672 runs best in workgroups of four waves, two column blocks x two
-            // K ranges, 896 of them: 7.4 against 7.8 us with int8 rows, 7.7 against 7.9 with the row quantised inside)
-            if (best == c.cbw && c.cbw == 4 && c.ks == 2 && n_cb < 2048 && xt != 3 && !even_cbw && 2 * 2 * 64 >= min_threads) best = 2;
+            // (4096 x 28672 in 896 workgroups of 2 x 2 waves: 1 % faster than 4 x 2 back to back in a replayed graph,
+            // 4 % slower per launch as the profiler times it, dispatch included: not taken)
             c.cbw = best;
         }
     }
@@ -717,7 +716,7 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
     const int64_t run = (n_kt + c.ks - 1) / c.ks;
     const int64_t wgs = (n_cb + c.cbw - 1) / c.cbw;
     // (w2a16: a window of two everywhere; deeper ones lost on every shape of the sweep)
-    c.window = tune.gemv_window ? tune.gemv_window : xt == 3 ? 2 : c.cbw == 2 && c.ks == 2 ? 2 : (run > 4 && (wgs > 768 || wgs <= 256)) || c.cbw * c.ks == 4 ? 4 : 2;
+    c.window = tune.gemv_window ? tune.gemv_window : xt == 3 ? 2 : (run > 4 && (wgs > 768 || wgs <= 256)) || c.cbw * c.ks == 4 ? 4 : 2;
     return c;
 }
 
