@@ -121,8 +121,8 @@ typedef struct {
     int splitk_min_tiles; /* ... planner: fewest 256-k tiles per part, 1..1024 */
     int stream_unroll;    /* w2_debug_stream_read: 1 KiB chunks in flight per wave: 4, 8 or 16 */
     int stream_blocks;    /* ... most workgroups launched: 1..65536 */
-    int gemv_cbw;         /* GEMV: column blocks per workgroup, any number 1..16 (a power of two from five rows on; even for */
-    int gemv_ks;          /* ... the gated epilogue) x K ranges per workgroup, 1..16: at most 16 waves (8 from five rows on) */
+    int gemv_cbw;         /* GEMV: column blocks per workgroup, any number 1..16 (even for the gated epilogue) */
+    int gemv_ks;          /* ... x K ranges per workgroup, 1..16: at most 16 waves (8 from five rows on, and for w2a16) */
 } w2_tuning_t;
 
 /* ------------------------------------------------------------------------

@@ -576,7 +576,9 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
     const int kstride = RL * 16 * a.cbw;                     // floats between two k-ranges' partial sums
     for (int item = tid; item < a.M * outs; item += threads) {
         int r;
-        if constexpr (WIDE) r = item >> (31 - __clz(outs));  // the wide form's workgroups hold a power of two of column blocks
+        // item / outs: by the magic multiplier below 4096 items; the wide form (up to 32 x 256 items) in fp32, exact
+        // for these sizes (item + 0.5 keeps the quotient clear of an integer by more than the rounding error)
+        if constexpr (WIDE) r = (int)(((float)item + 0.5f) * __frcp_rn((float)outs));
         else r = (int)(((uint32_t)item * (uint32_t)a.outs_magic) >> 20);
         const int col = item - r * outs;
         const int nl = col & 15, ci = col >> 4;
@@ -653,6 +655,18 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
         // 8 from 13 rows on) as leave about 192 workgroups; eight waves
         int cbw = rows > 12 ? 8 : 4;
         while (cbw > 1 && n_cb / cbw < 192) cbw >>= 1;
+        // ... unless another width unloads the busiest CU by a fifth or more (the rule of the narrow form below:
+        // 5120 x 34816 at M = 8 in 726 workgroups of 3 x 2 waves 11.8 us, in 544 of 4 x 2 13.9)
+        if (n_cb >= 1024) {
+            auto busiest = [&](int cb) { const int64_t w = (n_cb + cb - 1) / cb; return ((w + 255) / 256) * cb; };
+            int best = cbw;
+            for (int cb = 8; cb >= 1; --cb) {
+                const int ks = 8 / cb;
+                if ((even_cbw && (cb & 1)) || cb * ks * 64 < min_threads || (n_kt + ks - 1) / ks > MAX_RUN || n_cb / cb < 192) continue;
+                if (busiest(cb) * 5 <= busiest(cbw) * 4 && busiest(cb) < busiest(best)) best = cb;
+            }
+            cbw = best;
+        }
         c.cbw = cbw;
         c.ks = 8 / cbw;
     } else {
@@ -778,8 +792,8 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
     }
     const Cfg c = pick(a8.tune, a8.n_cb, a8.n_kt, a8.epi.act == ACT_SILU_MUL, min_threads, max_w, (int)M, xt);
     const int waves = c.cbw * c.ks;
-    if (waves > max_w || (rl > 4 && (c.cbw & (c.cbw - 1))) || (a8.epi.act == ACT_SILU_MUL && (c.cbw & 1))) {
-        set_error("w2_matmul_a8[gemv]: workgroup shape %d x %d: at most %d waves, a power of two of column blocks from five rows on, an even number for the gated epilogue", c.cbw, c.ks, max_w);
+    if (waves > max_w || (a8.epi.act == ACT_SILU_MUL && (c.cbw & 1))) {
+        set_error("w2_matmul_a8[gemv]: workgroup shape %d x %d: at most %d waves, an even number of column blocks for the gated epilogue", c.cbw, c.ks, max_w);
         return W2_ERR_INVALID_ARG;
     }
     // local memory: header, rows, reduction scratch, the waves' scale slices; a CU has 160 KiB

@@ -206,14 +206,32 @@ def test_a8_gemv_any_workgroup_width(w2, M, K, N, G, cbw, ks):
         check_epilogue(bf16_bits(Yg), y64, mag, None, 2, f"gated, cbw={cbw} ks={ks} M={M}")
 
 
+@pytest.mark.parametrize("cbw,ks", [(3, 2), (5, 1), (7, 1), (6, 1), (1, 5), (3, 1)])
+@pytest.mark.parametrize("K,N,G", [(1024, 272, 128), (2048, 1032, 64), (768, 40, 128)])
+@pytest.mark.parametrize("M", [5, 8, 13, 16, 17, 32])
+def test_a8_gemv_wide_form_any_workgroup_width(w2, M, K, N, G, cbw, ks):
+    # from five rows on (every accumulator row in use; two row tiles from seventeen): the same freedom of width,
+    # the epilogue's (row, column) split by an exact fp32 quotient; plain and, for even widths, gated
+    tune = {"gemv_cbw": cbw, "gemv_ks": ks}
+    run_a8_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_GEMV, seed=M + K + N + G + cbw, tune=tune)
+    if cbw % 2 == 0 and N % 32 == 0:
+        codes, scales, X = synth.make_problem(M, K, N, G, 0, M + K + cbw)
+        packed = w2.prepack(dev(codes), dev(scales), G, 0)
+        xq, sx, _ = w2.quantize_rows(dev(X), G)
+        oq, osx, _ = oracle.quantize_rows(X, G)
+        _, y64 = oracle.matmul_a8(codes, scales, G, 0, oq, osx)
+        mag = oracle.a8_term_magnitude(codes, scales, G, 0, oq, osx)
+        Yg = w2.matmul_a8_epi(packed, K, N, G, xq, sx, act=2, variant=w2.VARIANT_GEMV, tune=tune)
+        check_epilogue(bf16_bits(Yg), y64, mag, None, 2, f"wide, gated, cbw={cbw} ks={ks} M={M}")
+
+
 def test_a8_gemv_workgroup_shape_limits(w2):
     # shapes the kernel cannot run are refused before anything is launched
     codes, scales, X = synth.make_problem(8, 512, 64, 128, 0, 3)
     packed = w2.prepack(dev(codes), dev(scales), 128, 0)
     xq, sx, _ = w2.quantize_rows(dev(X), 128)
     for M, tune, act in ((1, {"gemv_cbw": 9, "gemv_ks": 2}, 0),        # more than 16 waves
-                         (8, {"gemv_cbw": 3, "gemv_ks": 2}, 0),        # the wide form: a power of two of column blocks
-                         (8, {"gemv_cbw": 8, "gemv_ks": 2}, 0),        # ... and at most 8 waves
+                         (8, {"gemv_cbw": 8, "gemv_ks": 2}, 0),        # the wide form: at most 8 waves
                          (1, {"gemv_cbw": 3, "gemv_ks": 2}, 2)):       # the gated epilogue pairs column blocks
         Y = torch.full((M, 64), 7.0, dtype=torch.bfloat16, device="cuda")
         with pytest.raises(w2.W2Error):
