@@ -338,16 +338,36 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
         }
         __syncthreads();
         W2_GEMV_MARK(9);
-        float inv[RL];
+        // The rows' maxima: one read per wave brings all its rows' partial maxima.  Only 127 / amax stands between a
+        // wave and its quantising; the row's scale amax / 127, the other correctly rounded division, is wanted in the
+        // epilogue only: for one or two rows the threads that store results divide there (sxv holds amax until
+        // then), for more the first threads of the workgroup do it here, one row each, the other waves pass by.
+        float inv[RL], mrow[RL];
+#pragma unroll
+        for (int r = 0; r < RL; ++r) mrow[r] = 0.f;
+        for (int w = 0; w < n_waves; ++w) {
+            typedef float vrow __attribute__((ext_vector_type(RL == 3 ? 4 : RL)));
+            if constexpr (RL == 1) {
+                mrow[0] = fmaxf(mrow[0], s_red[w * 4]);
+            } else {
+                const vrow v = *reinterpret_cast<const vrow*>(s_red + w * 4);
+#pragma unroll
+                for (int r = 0; r < RL; ++r) mrow[r] = fmaxf(mrow[r], v[r]);
+            }
+        }
 #pragma unroll
         for (int r = 0; r < RL; ++r) {
-            float m = 0.f;
-            for (int w = 0; w < n_waves; ++w) m = fmaxf(m, s_red[w * 4 + r]);
-            inv[r] = m > 0.f ? __fdiv_rn(127.0f, m) : 0.f;
-            // the row's scale, for the epilogue (LDS: another slot of the header than the partial maxima being read)
-            const float sxr = m > 0.f ? __fdiv_rn(m, 127.0f) : 0.f;
-            if constexpr (SX_IN_REGS) sxv[r] = sxr;
-            else if (tid == 0) s_red[SX_SLOT + r] = sxr;
+            inv[r] = mrow[r] > 0.f ? __fdiv_rn(127.0f, mrow[r]) : 0.f;
+            if constexpr (SX_IN_REGS) sxv[r] = mrow[r];
+        }
+        if constexpr (!SX_IN_REGS) {
+            // (LDS: another slot of the header than the partial maxima being read)
+            if (tid < RL) {
+                float m = mrow[0];
+#pragma unroll
+                for (int r = 1; r < RL; ++r) m = tid == r ? mrow[r] : m;
+                s_red[SX_SLOT + tid] = m > 0.f ? __fdiv_rn(m, 127.0f) : 0.f;
+            }
         }
         W2_GEMV_MARK(10);
 #pragma unroll
@@ -525,6 +545,10 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
     if constexpr (SX_IN_REGS) {
         // one or two rows: a thread per output column, the rows in turn
         if (tid < outs) {
+            if constexpr (XT == 1 || XT == 2) {
+#pragma unroll
+                for (int r = 0; r < RL; ++r) sxv[r] = sxv[r] > 0.f ? __fdiv_rn(sxv[r], 127.0f) : 0.f;   // amax until here
+            }
             const int nl = tid & 15, ci = tid >> 4;
             const int kstride = RL * 16 * a.cbw;             // floats between two k-ranges' partial sums
             auto z = [&](int c, int r) {                     // finished fp32 result of column block c, row r
