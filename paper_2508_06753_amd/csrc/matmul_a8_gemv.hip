@@ -355,10 +355,20 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
                 for (int r = 0; r < RL; ++r) mrow[r] = fmaxf(mrow[r], v[r]);
             }
         }
+        if constexpr (RL == 1) {
+            inv[0] = mrow[0] > 0.f ? __fdiv_rn(127.0f, mrow[0]) : 0.f;
+        } else {
+            // one division for all rows: lane r divides for row r, the quotients come back through scalar registers
+            float mm = mrow[0];
 #pragma unroll
-        for (int r = 0; r < RL; ++r) {
-            inv[r] = mrow[r] > 0.f ? __fdiv_rn(127.0f, mrow[r]) : 0.f;
-            if constexpr (SX_IN_REGS) sxv[r] = mrow[r];
+            for (int r = 1; r < RL; ++r) mm = lane == r ? mrow[r] : mm;
+            const float iv = mm > 0.f ? __fdiv_rn(127.0f, mm) : 0.f;
+#pragma unroll
+            for (int r = 0; r < RL; ++r) inv[r] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(iv), r));
+        }
+        if constexpr (SX_IN_REGS) {
+#pragma unroll
+            for (int r = 0; r < RL; ++r) sxv[r] = mrow[r];
         }
         if constexpr (!SX_IN_REGS) {
             // (LDS: another slot of the header than the partial maxima being read)
