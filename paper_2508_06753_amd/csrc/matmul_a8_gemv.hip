@@ -161,7 +161,7 @@ __device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, ui
 // asks for that, for this file only), so the first loads wait for no argument fetch at all; where the machine
 // does not preload, the compiled entry fetches them with one scalar load as before.
 struct ArgsRest {
-    int ks, outs_magic, red_off, sc_off, xg_off;
+    int outs_magic, red_off, sc_off, xg_off;
     const float* sx;
     uint16_t* Y;
     int32_t* acc_out;
@@ -178,9 +178,10 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
     a.X = p_X; a.ldx = p_ldx; a.codes = p_codes; a.scales = p_scales; a.K = p_K; a.M = p_M; a.n_cb = p_n_cb;
     a.n_kt = p_n_kt; a.cbw_rcp = p_cbw_rcp;
     // fourteen dwords fit the registers: the workgroup's shape and the K ranges travel in one of them
-    a.cbw = p_shape & 0xff; a.ks = (p_shape >> 8) & 0xff; a.t_lo = (p_shape >> 16) & 0xff; a.t_rem = (p_shape >> 24) & 0xff; a.outs_magic = rest.outs_magic; a.red_off = rest.red_off; a.sc_off = rest.sc_off;
-    a.xg_off = rest.xg_off; a.sx = rest.sx; a.Y = rest.Y; a.acc_out = rest.acc_out; a.ldy = rest.ldy; a.N = rest.N;
-    a.epi = rest.epi;
+    a.cbw = p_shape & 0xff; a.ks = (p_shape >> 8) & 0xff; a.t_lo = (p_shape >> 16) & 0xff;
+    a.t_rem = (p_shape >> 24) & 0xff;
+    a.outs_magic = rest.outs_magic; a.red_off = rest.red_off; a.sc_off = rest.sc_off; a.xg_off = rest.xg_off;
+    a.sx = rest.sx; a.Y = rest.Y; a.acc_out = rest.acc_out; a.ldy = rest.ldy; a.N = rest.N; a.epi = rest.epi;
     constexpr bool WIDE = RL > 4;
     constexpr bool A16 = XT == 3;                            // bf16 rows, bf16 matrix instruction
     static_assert(!A16 || (RL <= 4 && !DBG), "the w2a16 form: up to four rows");
@@ -775,7 +776,7 @@ static int launch_w(const Args& a, const Cfg& c, size_t lds, hipStream_t stream)
     auto go = [&](auto kern) {
         if (int rc = ensure_dynamic_lds((const void*)kern, lds, "w2_matmul_a8[gemv]")) return rc;
         ArgsRest r;
-        r.ks = a.ks; r.outs_magic = a.outs_magic; r.red_off = a.red_off; r.sc_off = a.sc_off; r.xg_off = a.xg_off;
+        r.outs_magic = a.outs_magic; r.red_off = a.red_off; r.sc_off = a.sc_off; r.xg_off = a.xg_off;
         r.sx = a.sx; r.Y = a.Y; r.acc_out = a.acc_out; r.ldy = a.ldy; r.N = a.N; r.epi = a.epi;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, a.X, a.ldx, a.codes, a.scales, a.K, a.M, a.n_cb, a.n_kt,
                            a.cbw_rcp, a.cbw | (a.ks << 8) | (a.t_lo << 16) | (a.t_rem << 24), r);
