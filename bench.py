@@ -250,7 +250,7 @@ def sweep_mode(torch, w2, synth, dev, sections=None):
     decode_case("deep", "down", 28672, 8192, 128, (16, 32, 64, 128, 256), ("a8", "a16"))
     if sections and "cfg4" not in sections:
         return
-    print("# prefill: 40 launches to warm the clock up, 20 timed; workspaces of w2_workspace_size bytes (none needed at M = 2048)")
+    print("# prefill: 40 launches and 0.15 s to warm the clock up, 20 timed; workspaces of w2_workspace_size bytes (none needed at M = 2048)")
     for name, (K, N) in synth.SHAPES_70B.items():
         nb = w2.packed_size(K, N, G)
         pk = torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev)
@@ -269,6 +269,10 @@ def sweep_mode(torch, w2, synth, dev, sections=None):
                 for _ in range(40 if call == "a8" else 15):
                     fn()
                 torch.cuda.synchronize()
+                t_end = time.perf_counter() + 0.15            # ... and until the chip has been busy for a while: the
+                while time.perf_counter() < t_end:           # first case of a cold chip otherwise reads 10 % slow
+                    fn()
+                    torch.cuda.synchronize()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 n = 20 if call == "a8" else 8
                 e0.record()
