@@ -576,7 +576,10 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         const int midm_max = tn.midm_max_m ? tn.midm_max_m
                            : a.n_cb <= 256 ? (a.part_bytes && a.n_kt > 32 ? 64 : 128) : a.n_cb >= 2048 ? 40 : 64;
         if (M >= midm_min && M <= midm_max && a16_midm_supports(a)) return launch_a16_midm(a, (hipStream_t)stream);
-        if (a16_gemv_supports(a)) return launch_a16_gemv(a, (hipStream_t)stream);      // up to four rows: the decode kernel
+        if (a16_gemv_supports(a)) {                          // up to four rows: the decode kernel
+            rc = launch_a16_gemv(a, (hipStream_t)stream);
+            if (rc != W2_ERR_UNSUPPORTED_SHAPE) return rc;   // (a shape it turns down after all goes on to the small-M kernel)
+        }
         if (!a16_smallm_supports(a)) return launch_a16_fold_tiled(a, (hipStream_t)stream);
         variant = W2_VARIANT_SMALLM;
     }
