@@ -829,6 +829,8 @@ def test_a16_gemv_exact_integers_and_limits(w2):
         w2.matmul_a16(pk, Kb, 16, 128, Xd, variant=w2.VARIANT_GEMV)
     run_a16_case(w2, 4, Kb, 16, 128, 0, w2.VARIANT_AUTO, seed=6)       # ... and AUTO still answers
     run_a16_case(w2, 1, Kb, 16, 128, 0, w2.VARIANT_GEMV, seed=7)       # one such row fits
+    run_a16_case(w2, 2, Kb, 24, 64, 1, w2.VARIANT_GEMV, seed=8)        # two rows, G = 64: local memory nearly full
+    run_a16_case(w2, 2, 32768, 16, 64, 0, w2.VARIANT_AUTO, seed=9)     # ... and the longest K whose runs fit
 
 
 @pytest.mark.parametrize("G", [64, 128])
