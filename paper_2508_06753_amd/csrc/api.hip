@@ -564,19 +564,28 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         variant = W2_VARIANT_SMALLM;
     }
     if (variant == W2_VARIANT_AUTO) {
-        // M <= 8: zero-point construction in the small-M kernel; up to 64 rows the mid-M kernel (the
-        // weight stream is still read once; measured faster from M = 9 on every projection shape);
-        // above, 128-row tiles.  Both of the latter fold the scale into the weights: fewest vector
-        // instructions per matrix instruction.
-        const int midm_min = tn.midm_min_m ? tn.midm_min_m : 9;
+        // Few rows: the decode kernel (below), else the zero-point construction in the small-M kernel; up to
+        // 64 rows the mid-M kernel (the weight stream is still read once; measured faster than the small-M
+        // kernel from M = 9 on every projection shape); above, 128-row tiles.  Both of the latter fold the
+        // scale into the weights: fewest vector instructions per matrix instruction.
+        // (K beyond 16384: from M = 5; 17408 x 5120 at M = 8 19.9 us against 33.7 in the small-M kernel)
+        const int midm_min = tn.midm_min_m ? tn.midm_min_m : a.n_kt > 64 ? 5 : 9;
         // two bands on small projections; on very wide ones (32768 columns and more) the tiled kernel
         // takes over at M = 41 (8192 x 57344 at M = 48: 94 against 104 us)
         // (and with room for split-K partial results the tiled kernel wins above 64 rows once K passes 8192:
         // 28 against 35 us on 14336 x 4096 at M = 128)
         const int midm_max = tn.midm_max_m ? tn.midm_max_m
                            : a.n_cb <= 256 ? (a.part_bytes && a.n_kt > 32 ? 64 : 128) : a.n_cb >= 2048 ? 40 : 64;
+        // The decode kernel wherever a workgroup can hold the rows: up to 8 of them, and up to 16 while a thread
+        // stages one piece per row (K <= 4096: 4096 x 28672 at M = 12 14.0 us against 15.9 in the mid-M kernel,
+        // 4096 x 4096 6.4 against 7.6; 5120 x 34816 31 against 29)
+        const bool gemv_rows = tn.midm_min_m ? M < midm_min : M <= 8 || (M <= 16 && K <= 4096);
+        if (gemv_rows && a16_gemv_supports(a)) {
+            rc = launch_a16_gemv(a, (hipStream_t)stream);
+            if (rc != W2_ERR_UNSUPPORTED_SHAPE) return rc;   // (a shape it turns down after all goes on to the other kernels)
+        }
         if (M >= midm_min && M <= midm_max && a16_midm_supports(a)) return launch_a16_midm(a, (hipStream_t)stream);
-        if (a16_gemv_supports(a)) {                          // up to four rows: the decode kernel
+        if (a16_gemv_supports(a)) {
             rc = launch_a16_gemv(a, (hipStream_t)stream);
             if (rc != W2_ERR_UNSUPPORTED_SHAPE) return rc;   // (a shape it turns down after all goes on to the small-M kernel)
         }

@@ -184,10 +184,11 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
     a.sx = rest.sx; a.Y = rest.Y; a.acc_out = rest.acc_out; a.ldy = rest.ldy; a.N = rest.N; a.epi = rest.epi;
     constexpr bool WIDE = RL > 4;
     constexpr bool A16 = XT == 3;                            // bf16 rows, bf16 matrix instruction
-    static_assert(!A16 || (RL <= 4 && !DBG), "the w2a16 form: up to four rows");
+    static_assert(!A16 || (RL <= 16 && !DBG), "the w2a16 form: up to sixteen rows");
     constexpr int RA = WIDE ? 4 : RL;                        // accumulator rows a lane folds into y
     constexpr int RT = RL > 16 ? RL / 16 : 1;                // 16-row tiles
-    static_assert(!WIDE || XT == 0, "the wide form takes int8 rows");
+    static_assert(!WIDE || XT == 0 || XT == 3, "the wide form takes int8 rows or unquantised bf16 rows");
+    constexpr int XGS = WIDE ? 16 : 4;                       // w2a16: rows per group in the table of group sums
     extern __shared__ __align__(16) int8_t smem[];
     constexpr int GPT = TILE_K / G;
     const int tid = threadIdx.x;
@@ -304,14 +305,14 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
                     int8_t* blk = xs + r * row_stride + (i >> 1) * 32 + (i & 1) * 8;
                     *reinterpret_cast<uint2*>(blk) = ev;
                     *reinterpret_cast<uint2*>(blk + 16) = od;
-                    if ((i & (PPG - 1)) == 0) xg[(i / PPG) * 4 + r] = -ZP16 * sum;
+                    if ((i & (PPG - 1)) == 0) xg[(i / PPG) * XGS + r] = -ZP16 * sum;
                 }
             }
         // no activation scale: the epilogue's sx * 2^-6 is exactly 1
         if constexpr (SX_IN_REGS) {
 #pragma unroll
             for (int r = 0; r < RL; ++r) sxv[r] = 64.0f;
-        } else if (tid < 4) s_red[SX_SLOT + tid] = 64.0f;
+        } else if (tid < (WIDE ? RL : 4)) s_red[SX_SLOT + tid] = 64.0f;
     } else {
         float amax[RL];
 #pragma unroll
@@ -467,12 +468,13 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
             }
         }
     };
-    // w2a16: what a group's accumulator starts from, rows 0..3 of the tile's groups (every lane reads the same)
+    // w2a16: what a group's accumulator starts from, the lane's four rows of the tile's groups (rows 0..3 in
+    // every lane; the wide form: rows 4q..4q+3)
     auto read_cinit = [&](int kt, v4f (&ci)[GPT]) {
         if constexpr (A16) {
-            const float* xg = reinterpret_cast<const float*>(smem + a.xg_off) + kt * (GPT * 4);
+            const float* xg = reinterpret_cast<const float*>(smem + a.xg_off) + kt * (GPT * XGS) + (WIDE ? 4 * q : 0);
 #pragma unroll
-            for (int g = 0; g < GPT; ++g) ci[g] = *reinterpret_cast<const v4f*>(xg + g * 4);
+            for (int g = 0; g < GPT; ++g) ci[g] = *reinterpret_cast<const v4f*>(xg + g * XGS);
         }
     };
     const int8_t* sc_lane = sc_lds + l16 * (GPT * 2);
@@ -688,7 +690,8 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
     } else if (rows > 4) {
         // the wide form: every workgroup stages all rows, so as many column blocks per workgroup (up to 4;
         // 8 from 13 rows on) as leave about 192 workgroups; eight waves
-        int cbw = rows > 12 ? 8 : 4;
+        // (w2a16: 8 from 9 rows on: 4096 x 28672 at M = 9 13.1 us with 8 x 1 waves, 17.0 with 4 x 2)
+        int cbw = rows > (xt == 3 ? 8 : 12) ? 8 : 4;
         while (cbw > 1 && n_cb / cbw < 192) cbw >>= 1;
         // ... unless another width unloads the busiest CU by a fifth or more (the rule of the narrow form below:
         // 5120 x 34816 at M = 8 in 726 workgroups of 3 x 2 waves 11.8 us, in 544 of 4 x 2 13.9)
@@ -702,6 +705,11 @@ static Cfg pick(const w2_tuning_t& tune, int64_t n_cb, int64_t n_kt, bool even_c
             }
             cbw = best;
         }
+        // w2a16 rows that leave room for one workgroup on a CU, narrow projection, more workgroups than CUs: twice
+        // as wide, one round of workgroups that stage the rows once (5120 x 5120 at M = 8)
+        if (xt == 3 && (int64_t)rows * (n_kt * 512 + XS_PAD) > 78 * 1024 && n_cb <= 512 && n_cb / cbw > 256 && cbw < 8 &&
+            (n_kt + 8 / (cbw * 2) - 1) / (8 / (cbw * 2)) <= MAX_RUN)
+            cbw <<= 1;
         c.cbw = cbw;
         c.ks = 8 / cbw;
     } else {
@@ -893,17 +901,20 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
 #undef W2_GEMV
 }
 
-// w2a16 through the same kernel: bf16 rows as they are, up to four of them, where a workgroup of eight waves
-// can hold them (local memory and registers); false: the caller takes another kernel.
+// w2a16 through the same kernel: bf16 rows as they are, up to sixteen of them (the wide form from five on),
+// where a workgroup of eight waves can hold them (local memory and registers); false: the caller takes
+// another kernel.
+static int a16_rl(int64_t M) { return M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : M <= 8 ? 8 : 16; }
+
 bool a16_gemv_supports(const A16Args& a)
 {
     using namespace gemv;
-    if (a.M < 1 || a.M > 4) return false;
-    const int rl = a.M <= 1 ? 1 : a.M <= 2 ? 2 : 4;
+    if (a.M < 1 || a.M > 16) return false;
+    const int rl = a16_rl(a.M);
     const int64_t ppr = a.K * 2 / 16;
     const int pr = xslots(rl, 3) / rl;
     const size_t lds = HDR + (size_t)a.M * (a.K * 2 + XS_PAD) + 16 + 8 * (size_t)rl * 16 * sizeof(float) +
-                       8 * (size_t)MAX_RUN * (TILE_N * (TILE_K / a.G) * 2) + (size_t)(a.K / a.G) * 16;
+                       8 * (size_t)MAX_RUN * (TILE_N * (TILE_K / a.G) * 2) + (size_t)(a.K / a.G) * (rl > 4 ? 64 : 16);
     return (ppr + pr - 1) / pr <= 64 * 8 && lds <= 160 * 1024 && (a.n_kt + 7) / 8 <= MAX_RUN;
 }
 
@@ -911,11 +922,11 @@ int launch_a16_gemv(const A16Args& a16, hipStream_t stream)
 {
     using namespace gemv;
     if (!a16_gemv_supports(a16)) {
-        set_error("w2_matmul_a16[gemv]: M must be 1..4 and the rows must fit one workgroup");
+        set_error("w2_matmul_a16[gemv]: M must be 1..16 and the rows must fit one workgroup");
         return W2_ERR_UNSUPPORTED_SHAPE;
     }
     const int64_t M = a16.M, K = a16.K;
-    const int rl = M <= 1 ? 1 : M <= 2 ? 2 : 4;
+    const int rl = a16_rl(M);
     const int max_w = max_waves(rl, 3);
     const int64_t ppr = K * 2 / 16;
     const int pr = xslots(rl, 3) / rl;
@@ -944,7 +955,7 @@ int launch_a16_gemv(const A16Args& a16, hipStream_t stream)
     a.sc_off = a.red_off + waves * rl * 16 * (int)sizeof(float);
     a.xg_off = a.sc_off + waves * MAX_RUN * (TILE_N * (TILE_K / a16.G) * 2);
     a.epi = a16.epi;
-    const size_t lds = (size_t)a.xg_off + (size_t)(K / a16.G) * 16;
+    const size_t lds = (size_t)a.xg_off + (size_t)(K / a16.G) * (rl > 4 ? 64 : 16);
     if (lds > 160 * 1024) {
         set_error("w2_matmul_a16[gemv]: the rows do not fit a workgroup's local memory");
         return W2_ERR_UNSUPPORTED_SHAPE;
@@ -953,11 +964,15 @@ int launch_a16_gemv(const A16Args& a16, hipStream_t stream)
     if (a16.G == 128) {
         if (rl == 1) return launch_np<128, 1, 3, false>(a, c, lds, np, stream);
         if (rl == 2) return launch_np<128, 2, 3, false>(a, c, lds, np, stream);
-        return launch_np<128, 4, 3, false>(a, c, lds, np, stream);
+        if (rl == 4) return launch_np<128, 4, 3, false>(a, c, lds, np, stream);
+        if (rl == 8) return launch_np<128, 8, 3, false>(a, c, lds, np, stream);
+        return launch_np<128, 16, 3, false>(a, c, lds, np, stream);
     }
     if (rl == 1) return launch_np<64, 1, 3, false>(a, c, lds, np, stream);
     if (rl == 2) return launch_np<64, 2, 3, false>(a, c, lds, np, stream);
-    return launch_np<64, 4, 3, false>(a, c, lds, np, stream);
+    if (rl == 4) return launch_np<64, 4, 3, false>(a, c, lds, np, stream);
+    if (rl == 8) return launch_np<64, 8, 3, false>(a, c, lds, np, stream);
+    return launch_np<64, 16, 3, false>(a, c, lds, np, stream);
 }
 
 }  // namespace w2

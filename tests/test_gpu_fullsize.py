@@ -90,6 +90,15 @@ def test_8b_decode_layer(w2, name):
 
 
 @pytest.mark.parametrize("name", list(synth.SHAPES_8B))
+def test_8b_small_batch_a16(w2, name):
+    """w2a16 at M = 5 .. 16 on the 8B-class projections: AUTO takes the decode kernel's wide form where a
+    workgroup can hold the rows (K = 4096), the small-M and mid-M kernels on the down projection."""
+    K, N = synth.SHAPES_8B[name]
+    for M in (5, 8, 11, 16):
+        check_a16(w2, M, K, N, 128, 0, seed=1, ncols=64)
+
+
+@pytest.mark.parametrize("name", list(synth.SHAPES_8B))
 def test_8b_decode_layer_fused_quantise(w2, name):
     """The benchmark's step at M=1: fp32 row in, one fused launch, against the oracle."""
     K, N = synth.SHAPES_8B[name]

@@ -788,17 +788,22 @@ def test_a16_smallm(w2, M, K, N, G):
 @pytest.mark.parametrize("shape", [None, (1, 1, 2), (3, 2, 2), (8, 1, 4), (2, 4, 8), (5, 1, 2), (1, 8, 2)])
 @pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("K,N", SMALL_SHAPES + [(5120, 48), (14336, 40)])
-@pytest.mark.parametrize("M", [1, 2, 3, 4])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 11, 16])
 def test_a16_gemv(w2, M, K, N, G, shape):
     # w2a16 through the decode kernel (bf16 rows as they are, bf16 matrix instruction, the group's accumulator
     # started from -130 x the group's row sum): the library's workgroup shape and forced ones (column blocks,
-    # K ranges, window), runs of one tile and runs longer than the window, long rows, ragged N
+    # K ranges, window), runs of one tile and runs longer than the window, long rows, ragged N; five rows and
+    # more: the wide form (every accumulator row in use)
     tune = None
+    rl = 1 if M == 1 else 2 if M == 2 else 4 if M <= 4 else 8 if M <= 8 else 16
+    slots = 32 if rl > 4 else 16
+    lds = 512 + M * (2 * K + 32) + 16 + 8 * rl * 64 + 8 * 16 * (16 * (256 // G) * 2) + (K // G) * (64 if rl > 4 else 16)
+    if lds > 160 * 1024 or 512 * (slots // rl) < K // 8:
+        pytest.skip("the rows do not fit a workgroup (local memory, registers)")
     if shape is not None:
         cbw, ks, win = shape
         ks = min(ks, K // 256)
-        rl = 1 if M == 1 else 2 if M == 2 else 4
-        if -(-(K // 256) // ks) > 16 or cbw * ks * 64 * (16 // rl) < K // 8:
+        if -(-(K // 256) // ks) > 16 or cbw * ks * 64 * (slots // rl) < K // 8:
             pytest.skip("a run is limited to 16 tiles / the threads must hold the rows")
         tune = {"gemv_cbw": cbw, "gemv_ks": ks, "gemv_window": win}
     run_a16_case(w2, M, K, N, G, (M + K) % 2, w2.VARIANT_GEMV, seed=M + K + N + G, tune=tune)
@@ -811,14 +816,14 @@ def test_a16_gemv_exact_integers_and_limits(w2):
     ones = np.full((K // G, N), 0x3F80, np.uint16)
     packed = w2.prepack(dev(codes), dev(ones), G, 0)
     rng = np.random.default_rng(1)
-    Xi = (rng.integers(-1, 2, size=(4, K)) * (rng.random((4, K)) < 0.05)).astype(np.float32)
+    Xi = (rng.integers(-1, 2, size=(16, K)) * (rng.random((16, K)) < 0.05)).astype(np.float32)
     ref = Xi.astype(np.int64) @ (codes.astype(np.int64) - 2)
     assert np.abs(ref).max() < 256
-    for M in (1, 2, 4):
+    for M in (1, 2, 4, 6, 8, 13, 16):
         Y = w2.matmul_a16(packed, K, N, G, dev(synth.f32_to_bf16_bits(Xi[:M])).view(torch.bfloat16), variant=w2.VARIANT_GEMV)
         assert np.array_equal(bits_to_f64(bf16_bits(Y)), ref[:M].astype(np.float64))
-    # five rows, or rows that do not fit a workgroup: refused when forced (AUTO takes another kernel)
-    X5 = torch.zeros((5, K), dtype=torch.bfloat16, device="cuda")
+    # seventeen rows, or rows that do not fit a workgroup: refused when forced (AUTO takes another kernel)
+    X5 = torch.zeros((17, K), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(w2.W2Error):
         w2.matmul_a16(packed, K, N, G, X5, variant=w2.VARIANT_GEMV)
     Kb = 28672
