@@ -152,7 +152,7 @@ __device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, ui
 }
 
 // RL: rows staged (M <= RL).  Up to four rows sit in accumulator rows 0..3, which the lanes of the first
-// quarter of a wave hold (one, two or four values each); the wide form (RL = 8, 16 or 32, int8 rows only)
+// quarter of a wave hold (one, two or four values each); the wide form (RL = 8, 16 or 32 for int8 rows, 8 or 16 for unquantised bf16 rows)
 // uses every accumulator row: lane (q, l) holds rows 4q..4q+3 of column l, for one row tile or, at RL = 32,
 // two (the up-converted operand then feeds two matrix instructions).
 // NP: 16-byte pieces per row and thread (a launch-time choice: the row's pieces / the workgroup's threads, rounded up)
