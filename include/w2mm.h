@@ -124,6 +124,7 @@ typedef struct {
     int stream_blocks;    /* ... most workgroups launched: 1..65536 */
     int gemv_cbw;         /* GEMV: column blocks per workgroup, any number 1..16 (even for the gated epilogue) */
     int gemv_ks;          /* ... x K ranges per workgroup, 1..16: at most 16 waves (8 from five rows on, and for w2a16) */
+    int fused_rows;       /* w2_matmul_a8_fused*: largest M quantised inside the matmul kernel, one launch (1..8) */
 } w2_tuning_t;
 
 /* ------------------------------------------------------------------------
@@ -201,16 +202,19 @@ W2_API int w2_matmul_a8_ex(const void* packed, int64_t K, int64_t N, int G, cons
 /* The int2 x {fp32, bf16} -> bf16 call (Sec. II-D: activation quantisation
  * fused into the GEMM; Sec. III-C: fusing wins for matrix-vector shapes, a
  * separate abs-max pass for multi-row activations).  Takes the unquantised
- * activations (fp32 or bf16, row stride ldx) and produces exactly what
- * w2_quantize_rows followed by w2_matmul_a8 produces, bit for bit (where a
- * kernel splits K, see w2_matmul_a8's workspace, with room in the workspace
- * beyond the int8 rows, the fp32 sums are taken in another order and the two
- * agree to the tolerance of the result contract instead).
- *   M <= 4: one launch where a workgroup can hold the rows (M', M rounded up
- *           to a power of two: M'*K*elem_size up to 128 KiB in registers and
- *           M*K up to about 150 KB of int8 rows in local memory): the abs-max
- *           is reduced per workgroup, redundantly, and the rows are quantised
- *           into local memory.
+ * activations (fp32 or bf16, row stride ldx) and produces what
+ * w2_quantize_rows followed by w2_matmul_a8 produces: the same int8 rows and
+ * scales, and the same bf16 result bit for bit wherever the two calls cut K
+ * into the same ranges (the fp32 partial sums of a column are then added in
+ * the same order); where they do not (another workgroup shape for the same
+ * M, or K split across workgroups, see w2_matmul_a8's workspace) the two
+ * agree to the tolerance of the result contract.
+ *   M <= 4 (M <= 8 when K <= 4096): one launch where a workgroup can hold the
+ *           rows (M', M rounded up to a power of two: M'*K*elem_size up to
+ *           128 KiB in registers and M*K up to about 150 KB of int8 rows in
+ *           local memory): the abs-max is reduced per workgroup, redundantly,
+ *           and the rows are quantised into local memory.  (M > 4 still asks
+ *           for the workspace below, used or not.)
  *   Otherwise, with a workspace of w2_workspace_size(M, K, N, G, 0) bytes (dev,
  *           16-byte aligned; holds the int8 rows and their scales, contents
  *           undefined afterwards) two launches: quantise, then the kernel family

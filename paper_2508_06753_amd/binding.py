@@ -149,7 +149,7 @@ class Tuning(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in (
         "variant", "dot4_max_m", "midm_min_m", "midm_max_m", "small_waves", "small_cbw", "small_kc", "gemv_window",
         "gemv_max_m", "midm_cbw", "tiled_bm", "tiled_bn", "tiled_kw", "tiled_wd", "tiled_group_m", "splitk", "splitk_min_tiles", "stream_unroll", "stream_blocks",
-        "gemv_cbw", "gemv_ks")]
+        "gemv_cbw", "gemv_ks", "fused_rows")]
 
 
 def _tune(variant=VARIANT_AUTO, tune=None):

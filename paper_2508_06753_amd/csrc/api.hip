@@ -168,6 +168,7 @@ static int check_tuning(const char* fn, const w2_tuning_t* t, w2_tuning_t* out)
     else if (!in(t->stream_blocks, 1, 65536)) bad = "stream_blocks";
     else if (!in(t->gemv_cbw, 1, 16)) bad = "gemv_cbw";
     else if (!in(t->gemv_ks, 1, 16)) bad = "gemv_ks";
+    else if (!in(t->fused_rows, 1, 8)) bad = "fused_rows";
     if (bad) return fail(W2_ERR_INVALID_ARG, "%s: w2_tuning_t.%s is out of range", fn, bad);
     *out = *t;
     return W2_OK;
@@ -389,13 +390,20 @@ static int a8_fused_common(const char* fn, const void* packed, int64_t K, int64_
     const Layout L = make_layout(K, N, G);
     // Measured: one launch with the abs-max reduced per workgroup is at least as fast as quantise + matmul
     // up to four rows wherever a workgroup can hold the rows (4096 x 28672 at M = 4: 10.2 against 11.0 us,
-    // 4096 x 4096: 5.3 against 6.3); beyond, every workgroup re-reading and re-quantising all rows costs
-    // more than a separate quantise launch (the paper's finding for multi-row activations, Sec. III-C).
+    // 4096 x 4096: 5.3 against 6.3), and up to eight rows (the wide form) while a thread stages one piece per
+    // row, K <= 4096 (M = 8, bf16 rows: 4096 x 28672 10.7 against 11.8 us, 4096 x 4096 5.0 against 6.6; at
+    // K = 5120 5120 x 34816 23.8 against 14.1); beyond, every workgroup re-reading and re-quantising all rows
+    // costs more than a separate quantise launch (the paper's finding for multi-row activations, Sec. III-C:
+    // twelve rows of 4096 x 6144 8.2 against 7.7 us).
     const bool ws_ok = workspace && workspace_bytes >= fused_workspace_bytes(M, K);
-    if (M <= 4 || !ws_ok) {
-        if (M > 4 && workspace)
+    const int one_launch_rows = tn.fused_rows ? tn.fused_rows : K <= 4096 ? 8 : 4;
+    if (M > 4 && !ws_ok) {
+        if (workspace)
             return fail(W2_ERR_BUFFER_TOO_SMALL, "%s: M = %lld needs a workspace of %zu bytes (w2_workspace_size)",
                         fn, (long long)M, fused_workspace_bytes(M, K));
+        return fail(W2_ERR_UNSUPPORTED_SHAPE, "%s: M = %lld needs a workspace (w2_workspace_size)", fn, (long long)M);
+    }
+    if (M <= one_launch_rows || !ws_ok) {
         A8Args a;
         a.codes = (const uint32_t*)packed;
         a.scales = (const uint16_t*)((const char*)packed + L.codes_bytes);

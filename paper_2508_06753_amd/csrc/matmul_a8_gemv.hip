@@ -187,7 +187,7 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
     static_assert(!A16 || (RL <= 16 && !DBG), "the w2a16 form: up to sixteen rows");
     constexpr int RA = WIDE ? 4 : RL;                        // accumulator rows a lane folds into y
     constexpr int RT = RL > 16 ? RL / 16 : 1;                // 16-row tiles
-    static_assert(!WIDE || XT == 0 || XT == 3, "the wide form takes int8 rows or unquantised bf16 rows");
+    static_assert(!WIDE || XT == 0 || XT == 3 || RL == 8, "the wide form: rows quantised in the kernel up to eight");
     constexpr int XGS = WIDE ? 16 : 4;                       // w2a16: rows per group in the table of group sums
     extern __shared__ __align__(16) int8_t smem[];
     constexpr int GPT = TILE_K / G;
@@ -334,9 +334,13 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
             amax[r] = wave_max_f32(m);
         }
         W2_GEMV_MARK(8);
+        // the waves' partial maxima: [wave][4] floats in the header; the wide form's [wave][RL] in the scratch of
+        // the final reduction, which nothing touches before the stream is over
+        float* s_max = WIDE ? reinterpret_cast<float*>(smem + a.red_off) : s_red;
+        constexpr int MS = WIDE ? RL : 4;
         if (lane == 0) {
 #pragma unroll
-            for (int r = 0; r < RL; ++r) s_red[wave * 4 + r] = amax[r];
+            for (int r = 0; r < RL; ++r) s_max[wave * MS + r] = amax[r];
         }
         __syncthreads();
         W2_GEMV_MARK(9);
@@ -348,9 +352,16 @@ a8_gemv_kernel(const void* p_X, int64_t p_ldx, const uint32_t* p_codes, const ui
 #pragma unroll
         for (int r = 0; r < RL; ++r) mrow[r] = 0.f;
         for (int w = 0; w < n_waves; ++w) {
-            typedef float vrow __attribute__((ext_vector_type(RL == 3 ? 4 : RL)));
+            typedef float vrow __attribute__((ext_vector_type(RL == 3 || WIDE ? 4 : RL)));
             if constexpr (RL == 1) {
                 mrow[0] = fmaxf(mrow[0], s_red[w * 4]);
+            } else if constexpr (WIDE) {
+#pragma unroll
+                for (int r4 = 0; r4 < RL / 4; ++r4) {
+                    const v4f v = *reinterpret_cast<const v4f*>(s_max + w * MS + 4 * r4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) mrow[4 * r4 + e] = fmaxf(mrow[4 * r4 + e], v[e]);
+                }
             } else {
                 const vrow v = *reinterpret_cast<const vrow*>(s_red + w * 4);
 #pragma unroll
@@ -808,7 +819,7 @@ static int launch_np(const Args& a, const Cfg& c, size_t lds, int np, hipStream_
 
 }  // namespace gemv
 
-// int8 rows: up to 32 (the wide form from five rows on); rows quantised in the kernel: up to four
+// int8 rows: up to 32 (the wide form from five rows on); rows quantised in the kernel: up to eight
 bool a8_gemv_supports(int64_t M) { return M >= 1 && M <= 32; }
 
 // xt: 0 = int8 rows (X = xq, sx given), 1 = fp32 rows, 2 = bf16 rows.  Returns W2_ERR_UNSUPPORTED_SHAPE
@@ -817,8 +828,8 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
 {
     using namespace gemv;
     const int64_t M = a8.M, K = a8.K;
-    if (!a8_gemv_supports(M) || (xt != 0 && M > 4)) {
-        set_error("w2_matmul_a8[gemv]: M must be 1..32 (1..4 for rows quantised in the kernel)");
+    if (!a8_gemv_supports(M) || (xt != 0 && M > 8)) {
+        set_error("w2_matmul_a8[gemv]: M must be 1..32 (1..8 for rows quantised in the kernel)");
         return W2_ERR_UNSUPPORTED_SHAPE;
     }
     const int rl = M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : M <= 8 ? 8 : M <= 16 ? 16 : 32;
@@ -881,6 +892,10 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
 #define W2_GEMV_WIDE(GG, RLL)                                                                          \
     do {                                                                                               \
         if (dbg) return launch_np<GG, RLL, 0, true>(a, c, lds, np, stream);                            \
+        if constexpr (RLL == 8) {                                                                      \
+            if (xt == 1) return launch_np<GG, RLL, 1, false>(a, c, lds, np, stream);                   \
+            if (xt == 2) return launch_np<GG, RLL, 2, false>(a, c, lds, np, stream);                   \
+        }                                                                                              \
         return launch_np<GG, RLL, 0, false>(a, c, lds, np, stream);                                    \
     } while (0)
     if (a8.G == 128) {

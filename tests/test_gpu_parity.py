@@ -550,6 +550,38 @@ def test_a8_fused_equals_two_call_path(w2, M, K, N, G, bf16_in):
     check_y(bf16_bits(Yf), Yo, y64, mag, f"a8 fused M={M} K={K} N={N} G={G} bf16_in={bf16_in}")
 
 
+@pytest.mark.parametrize("bf16_in", [False, True])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("K,N", [(256, 16), (1024, 272), (4096, 512), (5120, 48), (14336, 40)])
+@pytest.mark.parametrize("M", [5, 6, 8])
+def test_a8_fused_wide_one_launch(w2, M, K, N, G, bf16_in):
+    # five to eight rows quantised inside the decode kernel's wide form (tuning field fused_rows), against the
+    # oracle and, with the same workgroup shape forced on both, bit for bit against quantise + matmul; rows too
+    # long for a workgroup's registers take the two launches after all
+    codes, scales, X = synth.make_problem(M, K, N, G, M % 2, seed=M + K + N)
+    X[1] = 0.0                                                # all-zero row
+    packed = w2.prepack(dev(codes), dev(scales), G, M % 2)
+    if bf16_in:
+        Xb = synth.f32_to_bf16_bits(X)
+        Xd = dev(Xb).view(torch.bfloat16)
+        oq, osx, _ = oracle.quantize_rows(Xb, G, x_is_bf16=True)
+    else:
+        Xd = dev(X)
+        oq, osx, _ = oracle.quantize_rows(X, G)
+    ks = min(4, K // 256)
+    shape = {"gemv_cbw": 2, "gemv_ks": ks}
+    ws = torch.empty(w2.workspace_size(M, K, N, G), dtype=torch.uint8, device="cuda")
+    Yf = w2.matmul_a8_fused_epi(packed, K, N, G, Xd, workspace=ws, tune=dict(shape, fused_rows=8))
+    Yo, y64 = oracle.matmul_a8(codes, scales, G, M % 2, oq, osx)
+    mag = oracle.a8_term_magnitude(codes, scales, G, M % 2, oq, osx)
+    check_y(bf16_bits(Yf), Yo, y64, mag, f"a8 fused wide M={M} K={K} N={N} G={G} bf16_in={bf16_in}")
+    pieces = K * (2 if bf16_in else 4) // 16
+    if -(-pieces // 4) <= 512:                       # one launch: the same sums in the same order
+        xq, sx, _ = w2.quantize_rows(Xd, G)
+        Y2 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_GEMV, tune=shape)
+        assert torch.equal(Yf.view(torch.int16), Y2.view(torch.int16)), "fused and two-call results differ"
+
+
 def test_a8_fused_rejects_large_m(w2):
     codes, scales, X = synth.make_problem(5, 256, 16, 128, 0, 1)
     packed = w2.prepack(dev(codes), dev(scales), 128, 0)
