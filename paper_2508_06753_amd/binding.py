@@ -275,7 +275,7 @@ def matmul_a16_epi(packed, K, N, G, X, bias=None, act=ACT_NONE, out=None, varian
 
 def matmul_a8_fused(packed, K, N, G, X, out=None, workspace=None):
     """Y bf16 [M,N] from unquantised X (fp32 or bf16); `workspace`: a uint8 device tensor of
-    workspace_size(M, K, N, G) bytes, needed for M > 4 and faster from M = 3 on."""
+    workspace_size(M, K, N, G) bytes, needed for M > 4."""
     if X.dtype == torch.float32:
         dt = DT_F32
     elif X.dtype == torch.bfloat16:
