@@ -741,7 +741,7 @@ def test_a8_fused_epilogues(w2, K, N, G, with_bias, act):
 
 
 @pytest.mark.parametrize("act", [1, 2])
-@pytest.mark.parametrize("M", [1, 2, 4, 40, 130])
+@pytest.mark.parametrize("M", [1, 2, 4, 5, 8, 40, 130])
 def test_a8_fused_entry_with_epilogue_and_split_k(w2, M, act):
     # the one-call entry point (quantisation fused or through the workspace) with bias + activation; for the large M
     # the tiled kernel splits K and the epilogue runs in the reduce launch
@@ -758,7 +758,7 @@ def test_a8_fused_entry_with_epilogue_and_split_k(w2, M, act):
     check_epilogue(bf16_bits(Y), y64, mag, bias, act, f"fused entry + epilogue M={M} act={act}")
 
 
-A16_EPI_VARIANTS = [("GEMV", 6, [1, 2, 3]), ("SMALLM", 2, [1, 5, 16]), ("SCALED16 small", 5, [3]), ("MIDM", 4, [9, 40, 100]),
+A16_EPI_VARIANTS = [("GEMV", 6, [1, 2, 3, 6, 13]), ("SMALLM", 2, [1, 5, 16]), ("SCALED16 small", 5, [3]), ("MIDM", 4, [9, 40, 100]),
                     ("SCALED16 tiled", 5, [130]), ("TILED", 3, [70])]
 
 
