@@ -50,8 +50,9 @@ constexpr int HDR = 512;          // LDS: abs-max partials [16 waves][4 rows] fp
 constexpr int SX_SLOT = 64;       // ... the scales' first float
 // most 16-byte pieces of the activation rows a thread holds in registers: 8 for up to four rows (workgroups of
 // up to 16 waves, 128 registers a lane), 32 for the wide form (up to 8 waves, 256 registers)
-// (bf16 rows left unquantised, XT 3: 16 slots, up to 8 waves of up to 256 registers)
-constexpr int xslots(int RL, int XT = 0) { return RL > 4 ? 32 : XT == 3 ? 16 : 8; }
+// (bf16 rows left unquantised, XT 3: 16 slots, up to 8 waves of up to 256 registers; bf16 rows quantised in the wide
+// form: 16, a piece is eight values in flight through the quantiser and 32 slots spilled)
+constexpr int xslots(int RL, int XT = 0) { return RL > 4 ? (XT == 2 ? 16 : 32) : XT == 3 ? 16 : 8; }
 constexpr int max_waves(int RL, int XT = 0) { return RL > 4 || XT == 3 ? 8 : 16; }
 
 // ---- w2a16 in the same kernel (XT 3; Sec. II-D, "Alternative implementation": the activations stay bf16, the
@@ -836,7 +837,7 @@ int launch_a8_gemv(const A8Args& a8, const void* X, int xt, int64_t ldx, hipStre
     const int max_w = rl > 4 ? 8 : 16;                       // max_waves(rl)
     const int es = xt == 1 ? 4 : xt == 2 ? 2 : 1;
     const int64_t ppr = K * es / 16;                         // 16-byte pieces per row
-    const int pr = (rl > 4 ? 32 : 8) / rl;                   // register slots per row and thread: xslots(rl) / rl
+    const int pr = xslots(rl, xt) / rl;                      // register slots per row and thread
     const int min_threads = (int)((ppr + pr - 1) / pr);
     const size_t xs_bytes = ((size_t)(M < rl ? M : rl) * (K + XS_PAD) + 15) & ~(size_t)15;
     const char* too_large = "w2_matmul_a8[gemv]: M*K too large for one workgroup (use w2_quantize_rows + w2_matmul_a8)";

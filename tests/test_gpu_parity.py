@@ -576,7 +576,7 @@ def test_a8_fused_wide_one_launch(w2, M, K, N, G, bf16_in):
     mag = oracle.a8_term_magnitude(codes, scales, G, M % 2, oq, osx)
     check_y(bf16_bits(Yf), Yo, y64, mag, f"a8 fused wide M={M} K={K} N={N} G={G} bf16_in={bf16_in}")
     pieces = K * (2 if bf16_in else 4) // 16
-    if -(-pieces // 4) <= 512:                       # one launch: the same sums in the same order
+    if -(-pieces // (2 if bf16_in else 4)) <= 512:   # one launch: the same sums in the same order
         xq, sx, _ = w2.quantize_rows(Xd, G)
         Y2 = w2.matmul_a8(packed, K, N, G, xq, sx, variant=w2.VARIANT_GEMV, tune=shape)
         assert torch.equal(Yf.view(torch.int16), Y2.view(torch.int16)), "fused and two-call results differ"
