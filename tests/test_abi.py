@@ -23,6 +23,18 @@ def test_library_exports_every_declared_symbol():
     assert sorted(binding.EXPORTED) == names
 
 
+def test_tuning_structure_matches_the_header():
+    # the binding's ctypes mirror of w2_tuning_t: the header's fields, all int, in the header's order
+    text = open(os.path.join(ROOT, "include", "w2mm.h")).read()
+    body = re.search(r"typedef struct \{(.*?)\} w2_tuning_t;", text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\bint\s+(\w+)\s*;", body)
+    assert len(fields) >= 20 and len(re.findall(r";", body)) == len(fields), "a field that is not a plain int"
+    assert [n for n, _ in binding.Tuning._fields_] == fields
+    assert all(t is ctypes.c_int for _, t in binding.Tuning._fields_)
+    assert ctypes.sizeof(binding.Tuning) == 4 * len(fields)
+
+
 def test_sizes_and_shape_rules_on_host():
     lib = binding.raw()
     assert binding.packed_size(4096, 4096, 128) == 4096 * 4096 // 4 + (4096 // 128) * 4096 * 2

@@ -1005,7 +1005,7 @@ def test_argument_errors_write_nothing(w2):
     assert lib.w2_matmul_a8(p(packed), 256, 64, 128, None, p(sx), 1, p(Y), 64, None, 0, s) == w2.ERR_INVALID_ARG
     # overrides outside what the header allows are refused, field by field, before anything is launched
     for field, value in (("variant", 9), ("variant", w2.VARIANT_SCALED16), ("small_waves", 17), ("small_cbw", 3),
-                         ("gemv_cbw", 17), ("gemv_ks", -1),
+                         ("gemv_cbw", 17), ("gemv_ks", -1), ("fused_rows", 9),
                          ("small_kc", 100), ("midm_cbw", 3), ("tiled_bn", 32), ("splitk", 17), ("stream_unroll", 1),
                          ("tiled_group_m", -1)):
         t = w2.Tuning()
