@@ -237,7 +237,7 @@ def sweep_mode(torch, w2, synth, dev, sections=None):
           "inside a replayed HIP graph, gaps between launches included")
     decode_case("cfg0", "single", 2048, 2048, 128, (1,), ("a8", "fused", "stream read"))
     for name, (K, N) in synth.SHAPES_8B.items():
-        decode_case("cfg1", name, K, N, 128, (1, 4), ("a8", "fused", "a16", "stream read"))
+        decode_case("cfg1", name, K, N, 128, (1, 4, 8), ("a8", "fused", "a16", "stream read"))
     for g in (128, 64):
         decode_case("cfg2", "gate_up", 4096, 28672, g, (1, 2, 4, 8, 16, 32, 64), ("a8",))
     for name, (K, N) in synth.SHAPES_27B.items():
