@@ -71,9 +71,10 @@ typedef enum {
  * while two workgroups share a CU or the projection is narrow, up to 32 for K <= 4096), MIDM above it up to
  * M = 64 (128 when N <= 4096; 32 when N >= 24576 or, with a workspace, K >= 14336), else TILED (64-row
  * tiles; 128-row tiles from M = 1024, or from M = 128 where they fill the chip).
- * w2a16: GEMV up to M = 8 (up to 16 for K <= 4096) wherever the bf16 rows fit a workgroup's local memory,
- * SMALLM for the rest up to M = 8 (M = 4 for K > 16384), MIDM up to M = 64 (M = 128 when N <= 4096, M = 40
- * when N >= 32768), else the SCALED16 tiled kernel.
+ * w2a16: GEMV up to M = 8 (up to 16 for K <= 4096; up to 4 for K > 5120 with N >= 32768) wherever the bf16
+ * rows fit a workgroup's local memory, SMALLM for the rest up to M = 8 (M = 2 for K > 16384; M = 4 for
+ * K > 8192 with a workspace), MIDM up to M = 64 (M = 128 when N <= 4096, M = 40 when N >= 32768), else the
+ * SCALED16 tiled kernel.
  * GEMV: the decode kernel: whole rows in local memory, a wave streams a contiguous run of a column
  * block's tiles through a rolling register window into int8 MFMA (w2a8, M <= 32) or, with bf16 rows left as they
  * are and the zero-point weight construction, into bf16 MFMA (w2a16, M <= 16; W2_ERR_UNSUPPORTED_SHAPE when the

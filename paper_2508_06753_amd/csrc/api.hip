@@ -576,8 +576,14 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         // 64 rows the mid-M kernel (the weight stream is still read once; measured faster than the small-M
         // kernel from M = 9 on every projection shape); above, 128-row tiles.  Both of the latter fold the
         // scale into the weights: fewest vector instructions per matrix instruction.
-        // (K beyond 16384: from M = 5; 17408 x 5120 at M = 8 19.9 us against 33.7 in the small-M kernel)
-        const int midm_min = tn.midm_min_m ? tn.midm_min_m : a.n_kt > 64 ? 5 : 9;
+        // (K beyond 16384: from M = 3, for the rows the decode kernel cannot hold; 17408 x 5120 at M = 8 19.9 us
+        // against 33.7 in the small-M kernel, at M = 4 19.2 against 25.5)
+        // (with room for split-K partial results already from K = 8448 on: 14336 x 4096 at M = 8 13.8 us against 15.4)
+        // (and on the widest projections once K passes 5120, where five to eight rows leave the decode kernel one
+        // workgroup per CU: 8192 x 57344 at M = 5 / 8 42.3 / 43.1 us against 43.7 / 45.8)
+        const bool wide_deep = K > 5120 && a.n_cb >= 2048;
+        const int midm_min = tn.midm_min_m ? tn.midm_min_m
+                           : a.n_kt > 64 ? 3 : (a.n_kt > 32 && a.part_bytes) || wide_deep ? 5 : 9;
         // two bands on small projections; on very wide ones (32768 columns and more) the tiled kernel
         // takes over at M = 41 (8192 x 57344 at M = 48: 94 against 104 us)
         // (and with room for split-K partial results the tiled kernel wins above 64 rows once K passes 8192:
@@ -587,7 +593,7 @@ static int a16_common(const char* fn, const void* packed, int64_t K, int64_t N, 
         // The decode kernel wherever a workgroup can hold the rows: up to 8 of them, and up to 16 while a thread
         // stages one piece per row (K <= 4096: 4096 x 28672 at M = 12 14.0 us against 15.9 in the mid-M kernel,
         // 4096 x 4096 6.4 against 7.6; 5120 x 34816 31 against 29)
-        const bool gemv_rows = tn.midm_min_m ? M < midm_min : M <= 8 || (M <= 16 && K <= 4096);
+        const bool gemv_rows = tn.midm_min_m ? M < midm_min : M <= 4 || (M <= 8 && !wide_deep) || (M <= 16 && K <= 4096);
         if (gemv_rows && a16_gemv_supports(a)) {
             rc = launch_a16_gemv(a, (hipStream_t)stream);
             if (rc != W2_ERR_UNSUPPORTED_SHAPE) return rc;   // (a shape it turns down after all goes on to the other kernels)
