@@ -653,7 +653,7 @@ int w2_workspace_size(int64_t M, int64_t K, int64_t N, int G, int a16, size_t* b
     if (M == 0) *bytes = 0;
     else if (a16) {
         const size_t tiled = M > 64 ? a16_fold_splitk_bytes(M, N, L.n_kt, dflt) : 0;
-        const size_t midm = M >= 9 && M <= 128 ? a16_midm_splitk_bytes(M, N, L.n_cb, L.n_kt, dflt) : 0;
+        const size_t midm = M >= 3 && M <= 128 ? a16_midm_splitk_bytes(M, N, L.n_cb, L.n_kt, dflt) : 0;
         *bytes = tiled > midm ? tiled : midm;
     }
     else {
