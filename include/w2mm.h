@@ -68,7 +68,8 @@ typedef enum {
 
 /* Kernel families, for w2_matmul_a8_ex / w2_matmul_a16_ex and the debug export.
  * AUTO picks by shape.  w2a8: GEMV up to M = 8 wherever the rows fit a workgroup's local memory (up to 16
- * while two workgroups share a CU or the projection is narrow, up to 32 for K <= 4096), MIDM above it up to
+ * while two workgroups share a CU or the projection is narrow: N <= 10240 or at most 256 workgroups; up to 32
+ * for K <= 4096), MIDM above it up to
  * M = 64 (128 when N <= 4096; 32 when N >= 24576 or, with a workspace, K >= 14336), else TILED (64-row
  * tiles; 128-row tiles from M = 1024, or from M = 128 where they fill the chip).
  * w2a16: GEMV up to M = 8 (up to 16 for K <= 4096; up to 4 for K > 5120 with N >= 32768) wherever the bf16

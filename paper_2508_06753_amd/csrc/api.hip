@@ -291,7 +291,8 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         // rows fit (4096 x 28672 at M = 8: 7.4 against 10.1 us; 8192 x 8192: 5.9 against 7.8), and up to 16 rows
         // while two workgroups share a CU (rows of at most 64 to 68 KiB: 4096 x 28672 at M = 16 10.1 against
         // 10.5 us, 4096 x 6144 5.2 against 6.0) or the projection is narrow (8192 x 8192 at M = 16: 7.5 against
-        // 9.4 us); wide projections with long rows lose (8192 x 57344 at M = 12: 33 against 28 us).
+        // 9.4 us; 8192 x 10240 at M = 12 / 16: 11.6 / 11.7 against 12.6 / 12.8); wide projections with long rows
+        // lose (8192 x 57344 at M = 12: 33 against 28 us).
         // Rows of more than 72 KiB leave room for one workgroup per CU only: then the grid must fit the chip
         // in one round (17408 x 5120 at M = 8, 320 workgroups: 15.3 against 10.4 us through the mid-M kernel;
         // 14336 x 4096, 256 workgroups: 6.4 against 8.1).
@@ -299,13 +300,17 @@ static int a8_common(const char* fn, const void* packed, int64_t K, int64_t N, i
         int gcbw = M > 12 ? 8 : 4;                              // (the decode kernel's rule for five rows and more)
         while (gcbw > 1 && (a.n_cb / gcbw < 192 || (a.n_kt + 8 / gcbw - 1) / (8 / gcbw) > 16)) gcbw >>= 1;
         const int64_t gemv_wgs = (a.n_cb + gcbw - 1) / gcbw;
-        const bool one_round = row_bytes <= 72 * 1024 || gemv_wgs <= 256;
+        // (up to K = 8192 two rounds still win: 8192 x 10240 at M = 9 .. 16, 320 workgroups, 11.6 to 11.8 against 12.4 to 12.9)
+        const bool one_round = row_bytes <= 72 * 1024 || gemv_wgs <= 256 || a.n_kt <= 32;
+        // narrow: few column blocks, or a grid of one round (8192 x 12288 at M = 9 .. 16, 192 workgroups: 9.1 to 9.3
+        // against 12.8 to 13.2)
+        const bool narrow = a.n_cb <= 640 || gemv_wgs <= 256;
         const int gemv_max = tn.gemv_max_m                               ? tn.gemv_max_m
                            : M <= 4                                      ? 4
                            : !one_round                                  ? 4
                            : M <= 8                                      ? 8
-                           : M <= 12 && (row_bytes <= 64 * 1024 || a.n_cb <= 512) ? 12
-                           : M <= 16 ? (row_bytes <= 68 * 1024 || a.n_cb <= 512 ? 16 : 8)
+                           : M <= 12 && (row_bytes <= 64 * 1024 || narrow) ? 12
+                           : M <= 16 ? (row_bytes <= 68 * 1024 || narrow ? 16 : 8)
                            // 17 to 32 rows (two row tiles per wave, one workgroup per CU): K up to 4096 in a grid of
                            // one round (4096 x 4096 at M = 17..32: 5.9 against 6.9 to 7.3 us through the mid-M
                            // kernel; 4096 x 6144 6.8 against 7.2; 4096 x 28672 12.5 to 13.9 against 13.0 to 14.3;
